@@ -1,0 +1,168 @@
+/*
+ * asap.h -- C ABI of the MI355X (gfx950) visual-token pruning stage of ASAP
+ * ("Attention-Shift-Aware Pruning", Sec. 4: salience-guided selection, Sec. 4.2:
+ * salience-weighted consolidation).  Plain C: pointers, sizes, enums; no C++ or
+ * framework types.  Every data pointer is a DEVICE pointer unless marked [host].
+ *
+ * One pruning stage = four calls on one stream, no host synchronisation between:
+ *   asap_score      Eq. 2-5  -> raw mass s, salience s_hat, selection score r
+ *   asap_select     top-k of r                                  (Fig. 3, stage 1)
+ *   asap_merge      cosine routing + Eq. 6 + output sequence    (Sec. 4.2)
+ *   asap_compact_kv K/V rows of the surviving positions         (KV-cache compatibility)
+ *
+ * Sequence layout of one image: P prefix tokens | V visual tokens | Tmax text slots
+ * (text_len[b] <= Tmax of them valid), N = P + V + Tmax.  Visual-local index j is
+ * sequence position P + j.  All index arrays are int32.
+ *
+ * Ownership: the caller owns every buffer including the workspace; the library
+ * allocates nothing on the device, never synchronises the stream and keeps no
+ * state between calls except the last error text of a context.
+ * Errors: shapes, dtypes, pointers and workspace size are checked on the host
+ * before anything is launched; a failed check launches nothing.  Contents of device
+ * buffers (NaNs, text_len outside [1, Tmax]) are not checked.
+ * Determinism: the same inputs give bit-identical outputs on every call.
+ */
+#ifndef ASAP_H
+#define ASAP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct asap_ctx asap_ctx;   /* opaque: device id + last error text */
+
+typedef enum {
+  ASAP_OK = 0,
+  ASAP_EINVAL = 1,        /* bad shape / pointer / alignment / parameter          */
+  ASAP_EUNSUPPORTED = 2,  /* legal request this build has no kernel for           */
+  ASAP_EWORKSPACE = 3,    /* workspace smaller than asap_workspace_bytes()        */
+  ASAP_EHIP = 4           /* the HIP runtime refused a launch or a query          */
+} asap_status;
+
+typedef enum { ASAP_F32 = 0, ASAP_BF16 = 1 } asap_dtype;
+
+/* How Eq. 4's discount enters the text->visual scores.
+ * OFF:     no discount (plain attention-received top-k, the ablation's starting point).
+ * KEYBIAS: ln(max(lambda_max * s_hat_j, eps)) is added to every text row's logit of key j,
+ *          i.e. the unnormalised weight is lambda_j * exp(W_tj) (the exponent rule below Eq. 5). */
+typedef enum { ASAP_MASK_OFF = 0, ASAP_MASK_KEYBIAS = 1 } asap_mask_mode;
+
+/* ABSORB: every pruned token is routed to its most similar kept token.
+ * PAPER:  Sec. 4.2 routing inside the kept set + budget reallocation (not built: EUNSUPPORTED). */
+typedef enum { ASAP_ROUTE_ABSORB = 0, ASAP_ROUTE_PAPER = 1 } asap_route;
+
+typedef struct {
+  int32_t B;        /* images in the batch                                   >= 1 */
+  int32_t H;        /* query heads                                                */
+  int32_t Hkv;      /* key/value heads, H % Hkv == 0; head h reads kv head h*Hkv/H */
+  int32_t d;        /* head dim, 64 or 128                                        */
+  int32_t D;        /* hidden size, multiple of 64                                */
+  int32_t P;        /* prefix tokens before the image                        >= 0 */
+  int32_t V;        /* visual tokens, 1 .. 16384                                  */
+  int32_t Tmax;     /* padded text length, 1 .. 128                               */
+  int32_t k;        /* visual tokens kept, 1 .. V                                 */
+  asap_dtype qk_dtype;   /* Q and K of the pruning layer                          */
+  asap_dtype h_dtype;    /* hidden states in and out                              */
+  asap_dtype kv_dtype;   /* K/V caches of the layers in front                     */
+  float lambda_max;      /* Eq. 4, (0, 1]; 1.0 when the paper gives none          */
+  float eps;             /* Eq. 3 and Eq. 4, > 0; the paper's 1e-6                */
+  float sim_threshold;   /* t of Sec. 4.2: route only if cosine > t; -INFINITY = always */
+  float merge_weight;    /* mu >= 0 on the source terms of Eq. 6; 1 = Eq. 6, 0 = no merging */
+  asap_mask_mode mask_mode;
+  asap_route route;
+} asap_params;
+
+/* Context for one device.  [host] pointers.  asap_create checks that `device` exists and
+ * is a gfx950 part.  A context may be used from one thread at a time. */
+asap_status asap_create(asap_ctx** out_ctx, int device);
+void        asap_destroy(asap_ctx* ctx);
+/* Text of the last error on this context ("" if none); valid until the next call on it. */
+const char* asap_last_error(const asap_ctx* ctx);
+
+/* Checks a parameter block on the host; msg (nullable, [host]) receives up to msg_len-1
+ * characters naming the offending field. */
+asap_status asap_check_params(const asap_params* p, char* msg, size_t msg_len);
+
+/* Bytes of device scratch any of the four calls may need for these parameters (one size
+ * serves all four).  0 if the parameters are invalid.  The workspace must be 256-byte
+ * aligned; its contents are undefined before and after each call. */
+size_t asap_workspace_bytes(const asap_params* p);
+
+/*
+ * asap_score -- Eq. 2, 3, 4, 5 and the selection score.
+ *   s[b,j]     = 1/(H sqrt(d)) * sum_h sum_{i<V} q_vis[b,h,i,:] . k_vis[b,g(h),j,:]        (Eq. 2, mean over heads)
+ *   s_hat[b,j] = (s - min_j s) / (max_j s - min_j s + eps)                                  (Eq. 3)
+ *   lam[b,j]   = max(lambda_max * s_hat, eps)   (KEYBIAS)   or 1   (OFF)                    (Eq. 4)
+ *   A[b,h,t,j] = lam_j exp(z_tj) / (sum_j' lam_j' exp(z_tj') + exp(lse_extra[b,h,t])),
+ *                z_tj = q_txt[b,h,t,:] . k_vis[b,g(h),j,:] / sqrt(d)                        (Eq. 5, text rows)
+ *   score[b,j] = 1/(H text_len[b]) * sum_h sum_{t<text_len[b]} A[b,h,t,j]
+ * q_vis [B,H,V,d], q_txt [B,H,Tmax,d], k_vis [B,Hkv,V,d] in qk_dtype; each *_stride[3] gives
+ * the element strides of the three outer dims (last dim contiguous) so that the three may be
+ * views into [B,heads,N,d] tensors.  Pointers 16-byte aligned, strides multiples of 8 elements.
+ * text_len [B] int32.  lse_extra: NULL, or [B,H,Tmax] f32 = log-sum-exp of each text row's
+ * logits over its NON-visual keys (then A is the full-row softmax of Eq. 5); NULL drops that term.
+ * Outputs s_raw, s_hat, score: [B,V] f32, contiguous.  Sums are carried in fp64 up to the
+ * final rounding of s_raw / s_hat, and per-row softmax terms in fp32.
+ */
+asap_status asap_score(asap_ctx* ctx, const asap_params* p,
+                       const void* q_vis, const int64_t q_vis_stride[3],
+                       const void* q_txt, const int64_t q_txt_stride[3],
+                       const void* k_vis, const int64_t k_vis_stride[3],
+                       const int32_t* text_len, const float* lse_extra,
+                       float* s_raw, float* s_hat, float* score,
+                       void* workspace, size_t workspace_bytes, void* stream /* hipStream_t */);
+
+/*
+ * asap_select -- the k largest score[b,:] per image, ties to the smaller index (Fig. 3:
+ * "retains top-k salient visual tokens").  score [B,V] f32, finite and >= 0.
+ * kept_idx [B,k] and pruned_idx [B,V-k]: visual-local indices, each ascending.
+ */
+asap_status asap_select(asap_ctx* ctx, const asap_params* p, const float* score,
+                        int32_t* kept_idx, int32_t* pruned_idx,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * asap_merge -- Sec. 4.2 with ABSORB routing, Eq. 6, and the output sequence.
+ *   c(j,i)    = x_j . x_i / (max(|x_j|,1e-8) max(|x_i|,1e-8))   for pruned j, kept i (hidden states)
+ *   assign[j] = slot (0..k-1, position in kept_idx) of the kept token with the largest c(j,.),
+ *               ties to the smaller slot; -1 if that c <= sim_threshold.  best_sim[j] = that c.
+ *   y_c       = (s_hat_i x_i + mu sum_{assign[j]=c} s_hat_j x_j) / wsum_c,
+ *   wsum_c    = s_hat_i + mu sum s_hat_j;  a slot that absorbs no weight keeps x_i bit-exactly.  (Eq. 6)
+ *   out_hidden[b] = prefix rows | y_0..y_{k-1} | text rows 0..text_len[b]-1   (Fig. 3: text and
+ *               system prompt preserved); rows past new_len[b] = P + k + text_len[b] are not written.
+ *   pos_out[b,n]  = original position id of output row n (n < new_len[b]), -1 beyond.
+ * hidden [B,N,D] h_dtype with element strides hidden_stride[2] for (b, row); out_hidden
+ * [B,P+k+Tmax,D] contiguous, h_dtype; must not overlap hidden.  s_hat [B,V] f32 from asap_score.
+ * Dot products run on the matrix cores in the input precision (bf16 x bf16 or f32 x f32) with fp32
+ * accumulation; Eq. 6 accumulates in fp32 and rounds once (nearest-even) to h_dtype.
+ * assign [B,V-k] int32, best_sim [B,V-k] f32, wsum [B,k] f32, final_idx [B,k] int32 (= kept_idx here).
+ */
+asap_status asap_merge(asap_ctx* ctx, const asap_params* p,
+                       const void* hidden, const int64_t hidden_stride[2],
+                       const float* s_hat, const int32_t* text_len,
+                       const int32_t* kept_idx, const int32_t* pruned_idx,
+                       void* out_hidden, int32_t* pos_out, int32_t* new_len,
+                       int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * asap_compact_kv -- drops the pruned tokens from the K/V caches of the n_layers layers in
+ * front of the pruning layer: for every layer, K and V, image b and kv head g,
+ *   dst[b,g,n,:] = src[b,g,pos_out[b,n],:]   for n < new_len[b]      (bit-exact copy)
+ * Rows of kept tokens are copied unchanged (only the hidden state is merged).
+ * k_src, v_src, k_dst, v_dst: [host] arrays of n_layers DEVICE pointers; src [B,Hkv,N,d],
+ * dst [B,Hkv,P+k+Tmax,d], kv_dtype, contiguous, 16-byte aligned; dst must not overlap src.
+ * pos_out [B,P+k+Tmax], new_len [B] from asap_merge.  1 <= n_layers <= 64.
+ */
+asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layers,
+                            const void* const* k_src, const void* const* v_src,
+                            void* const* k_dst, void* const* v_dst,
+                            const int32_t* pos_out, const int32_t* new_len, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASAP_H */

@@ -1,0 +1,226 @@
+"""ctypes binding of libasap.so: same names and arguments as include/asap.h.
+
+Argument marshalling only -- every step of the pruning stage runs in the library's HIP
+kernels.  torch tensors are used for device memory (data_ptr, strides) and for the current
+HIP stream; nothing here computes.  There is no CPU fallback: if the library is missing,
+load() raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libasap.so")
+
+ASAP_OK, ASAP_EINVAL, ASAP_EUNSUPPORTED, ASAP_EWORKSPACE, ASAP_EHIP = 0, 1, 2, 3, 4
+ASAP_F32, ASAP_BF16 = 0, 1
+ASAP_MASK_OFF, ASAP_MASK_KEYBIAS = 0, 1
+ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
+
+EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
+           "asap_score", "asap_select", "asap_merge", "asap_compact_kv"]
+
+_DTYPE_CODE = {"f32": ASAP_F32, "bf16": ASAP_BF16, torch.float32: ASAP_F32, torch.bfloat16: ASAP_BF16}
+_TORCH_DTYPE = {ASAP_F32: torch.float32, ASAP_BF16: torch.bfloat16}
+
+
+class asap_params(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("P", ctypes.c_int32), ("V", ctypes.c_int32), ("Tmax", ctypes.c_int32),
+                ("k", ctypes.c_int32),
+                ("qk_dtype", ctypes.c_int), ("h_dtype", ctypes.c_int), ("kv_dtype", ctypes.c_int),
+                ("lambda_max", ctypes.c_float), ("eps", ctypes.c_float), ("sim_threshold", ctypes.c_float),
+                ("merge_weight", ctypes.c_float),
+                ("mask_mode", ctypes.c_int), ("route", ctypes.c_int)]
+
+
+class AsapError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"asap status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Loads libasap.so (built by paper_2603_14549_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} not found: build it with `python -m paper_2603_14549_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32p, f32p, i64p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64)
+    pp = ctypes.POINTER(asap_params)
+    lib.asap_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int]
+    lib.asap_create.restype = ctypes.c_int
+    lib.asap_destroy.argtypes = [vp]
+    lib.asap_destroy.restype = None
+    lib.asap_last_error.argtypes = [vp]
+    lib.asap_last_error.restype = ctypes.c_char_p
+    lib.asap_check_params.argtypes = [pp, ctypes.c_char_p, ctypes.c_size_t]
+    lib.asap_check_params.restype = ctypes.c_int
+    lib.asap_workspace_bytes.argtypes = [pp]
+    lib.asap_workspace_bytes.restype = ctypes.c_size_t
+    lib.asap_score.argtypes = [vp, pp, vp, i64p, vp, i64p, vp, i64p, i32p, f32p, f32p, f32p, f32p, vp,
+                               ctypes.c_size_t, vp]
+    lib.asap_score.restype = ctypes.c_int
+    lib.asap_select.argtypes = [vp, pp, f32p, i32p, i32p, vp, ctypes.c_size_t, vp]
+    lib.asap_select.restype = ctypes.c_int
+    lib.asap_merge.argtypes = [vp, pp, vp, i64p, f32p, i32p, i32p, i32p, vp, i32p, i32p, i32p, f32p, f32p, i32p,
+                               vp, ctypes.c_size_t, vp]
+    lib.asap_merge.restype = ctypes.c_int
+    lib.asap_compact_kv.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                    ctypes.POINTER(vp), ctypes.POINTER(vp), i32p, i32p, vp]
+    lib.asap_compact_kv.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def make_params(B, H, Hkv, d, D, P, V, Tmax, k, qk_dtype, h_dtype, kv_dtype, lambda_max=1.0, eps=1e-6,
+                sim_threshold=float("-inf"), merge_weight=1.0, mask_mode=ASAP_MASK_KEYBIAS,
+                route=ASAP_ROUTE_ABSORB) -> asap_params:
+    return asap_params(B, H, Hkv, d, D, P, V, Tmax, k, _DTYPE_CODE[qk_dtype], _DTYPE_CODE[h_dtype],
+                       _DTYPE_CODE[kv_dtype], lambda_max, eps, sim_threshold, merge_weight, mask_mode, route)
+
+
+def params_from_config(cfg, **overrides) -> asap_params:
+    """asap_params for a synth.StageConfig."""
+    return make_params(cfg.B, cfg.H, cfg.Hkv, cfg.d, cfg.D, cfg.P, cfg.V, cfg.Tmax, cfg.k, cfg.qk_dtype,
+                       cfg.h_dtype, cfg.kv_dtype, **overrides)
+
+
+def asap_check_params(p: asap_params):
+    buf = ctypes.create_string_buffer(256)
+    st = load().asap_check_params(ctypes.byref(p), buf, 256)
+    return st, buf.value.decode()
+
+
+def asap_workspace_bytes(p: asap_params) -> int:
+    return int(load().asap_workspace_bytes(ctypes.byref(p)))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _strides(t: torch.Tensor, n: int):
+    assert t.stride(-1) == 1, "last dimension must be contiguous"
+    return (ctypes.c_int64 * n)(*[t.stride(i) for i in range(n)])
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class Context:
+    """asap_ctx for one device."""
+
+    def __init__(self, device: int = 0):
+        self._lib = load()
+        self._h = ctypes.c_void_p()
+        st = self._lib.asap_create(ctypes.byref(self._h), device)
+        if st != ASAP_OK:
+            raise AsapError(st, f"asap_create(device={device}) failed")
+        self.device = device
+
+    def close(self):
+        if self._h:
+            self._lib.asap_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_error(self) -> str:
+        return self._lib.asap_last_error(self._h).decode()
+
+    def _check(self, st: int):
+        if st != ASAP_OK:
+            raise AsapError(st, self.last_error())
+
+    # ---- the four calls, arguments as in asap.h -------------------------------------------
+    def asap_score(self, p, q_vis, q_txt, k_vis, text_len, lse_extra, s_raw, s_hat, score, workspace,
+                   stream=None):
+        self._check(self._lib.asap_score(
+            self._h, ctypes.byref(p), _ptr(q_vis), _strides(q_vis, 3), _ptr(q_txt), _strides(q_txt, 3),
+            _ptr(k_vis), _strides(k_vis, 3), _ptr(text_len), _ptr(lse_extra), _ptr(s_raw), _ptr(s_hat),
+            _ptr(score), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+    def asap_select(self, p, score, kept_idx, pruned_idx, workspace, stream=None):
+        self._check(self._lib.asap_select(
+            self._h, ctypes.byref(p), _ptr(score), _ptr(kept_idx), _ptr(pruned_idx), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream(stream)))
+
+    def asap_merge(self, p, hidden, s_hat, text_len, kept_idx, pruned_idx, out_hidden, pos_out, new_len,
+                   assign, best_sim, wsum, final_idx, workspace, stream=None):
+        self._check(self._lib.asap_merge(
+            self._h, ctypes.byref(p), _ptr(hidden), _strides(hidden, 2), _ptr(s_hat), _ptr(text_len),
+            _ptr(kept_idx), _ptr(pruned_idx), _ptr(out_hidden), _ptr(pos_out), _ptr(new_len), _ptr(assign),
+            _ptr(best_sim), _ptr(wsum), _ptr(final_idx), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream(stream)))
+
+    def asap_compact_kv(self, p, k_src: Sequence[torch.Tensor], v_src, k_dst, v_dst, pos_out, new_len,
+                        stream=None):
+        n = len(k_src)
+        arr = lambda ts: (ctypes.c_void_p * n)(*[t.data_ptr() for t in ts])
+        self._check(self._lib.asap_compact_kv(
+            self._h, ctypes.byref(p), n, arr(k_src), arr(v_src), arr(k_dst), arr(v_dst), _ptr(pos_out),
+            _ptr(new_len), _stream(stream)))
+
+
+class StageBuffers:
+    """Device buffers of one pruning stage (outputs + workspace), allocated once with torch."""
+
+    def __init__(self, p: asap_params, n_layers: int, device="cuda:0"):
+        B, V, k, D = p.B, p.V, p.k, p.D
+        Nout = p.P + p.k + p.Tmax
+        f32, i32 = torch.float32, torch.int32
+        dev = device
+        self.s_raw = torch.empty(B, V, dtype=f32, device=dev)
+        self.s_hat = torch.empty(B, V, dtype=f32, device=dev)
+        self.score = torch.empty(B, V, dtype=f32, device=dev)
+        self.kept_idx = torch.empty(B, k, dtype=i32, device=dev)
+        self.pruned_idx = torch.empty(B, max(V - k, 1), dtype=i32, device=dev)
+        self.out_hidden = torch.zeros(B, Nout, D, dtype=_TORCH_DTYPE[p.h_dtype], device=dev)
+        self.pos_out = torch.empty(B, Nout, dtype=i32, device=dev)
+        self.new_len = torch.empty(B, dtype=i32, device=dev)
+        self.assign = torch.empty(B, max(V - k, 1), dtype=i32, device=dev)
+        self.best_sim = torch.empty(B, max(V - k, 1), dtype=f32, device=dev)
+        self.wsum = torch.empty(B, k, dtype=f32, device=dev)
+        self.final_idx = torch.empty(B, k, dtype=i32, device=dev)
+        kvd = _TORCH_DTYPE[p.kv_dtype]
+        self.k_dst = [torch.zeros(B, p.Hkv, Nout, p.d, dtype=kvd, device=dev) for _ in range(n_layers)]
+        self.v_dst = [torch.zeros(B, p.Hkv, Nout, p.d, dtype=kvd, device=dev) for _ in range(n_layers)]
+        self.workspace = torch.empty(max(asap_workspace_bytes(p), 256), dtype=torch.uint8, device=dev)
+
+
+def run_stage(ctx: Context, p: asap_params, q: torch.Tensor, k: torch.Tensor, hidden: torch.Tensor,
+              text_len: torch.Tensor, k_cache: List[torch.Tensor], v_cache: List[torch.Tensor],
+              buf: StageBuffers, lse_extra: Optional[torch.Tensor] = None, stream=None) -> StageBuffers:
+    """The four calls of one stage, back to back on one stream.  q [B,H,N,d], k [B,Hkv,N,d],
+    hidden [B,N,D]; the visual / text blocks are passed to the library as strided views."""
+    P, V = p.P, p.V
+    q_vis, q_txt, k_vis = q[:, :, P:P + V], q[:, :, P + V:], k[:, :, P:P + V]
+    ctx.asap_score(p, q_vis, q_txt, k_vis, text_len, lse_extra, buf.s_raw, buf.s_hat, buf.score,
+                   buf.workspace, stream)
+    ctx.asap_select(p, buf.score, buf.kept_idx, buf.pruned_idx, buf.workspace, stream)
+    ctx.asap_merge(p, hidden, buf.s_hat, text_len, buf.kept_idx, buf.pruned_idx, buf.out_hidden, buf.pos_out,
+                   buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace, stream)
+    if k_cache:
+        ctx.asap_compact_kv(p, k_cache, v_cache, buf.k_dst, buf.v_dst, buf.pos_out, buf.new_len, stream)
+    return buf

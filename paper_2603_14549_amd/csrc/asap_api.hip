@@ -1,0 +1,242 @@
+// C ABI of the pruning stage (see include/asap.h): host-side validation and dispatch only.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "asap_launch.hpp"
+
+struct asap_ctx {
+  int device;
+  char err[512];
+};
+
+namespace {
+
+using namespace asap;
+
+asap_status fail(asap_ctx* ctx, asap_status st, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return st;
+}
+
+bool valid_dtype(asap_dtype t) { return t == ASAP_F32 || t == ASAP_BF16; }
+int dtype_size(asap_dtype t) { return t == ASAP_BF16 ? 2 : 4; }
+
+asap_status check_params(const asap_params* p, char* msg, size_t n) {
+#define BAD(cond, text)                                  \
+  if (cond) {                                            \
+    if (msg && n) snprintf(msg, n, "%s", text);          \
+    return ASAP_EINVAL;                                  \
+  }
+  BAD(p == nullptr, "params is NULL");
+  BAD(p->B < 1, "B must be >= 1");
+  BAD(p->H < 1 || p->Hkv < 1 || p->H % p->Hkv != 0, "H must be a positive multiple of Hkv");
+  BAD(p->d != 64 && p->d != 128, "d must be 64 or 128");
+  BAD((int64_t)p->Hkv * p->d > 8192, "Hkv * d must be <= 8192");
+  BAD(p->D < 64 || p->D % 64 != 0 || p->D > 8192, "D must be a multiple of 64 in [64, 8192]");
+  BAD(p->P < 0, "P must be >= 0");
+  BAD(p->V < 1 || p->V > 16384, "V must be in [1, 16384]");
+  BAD(p->Tmax < 1 || p->Tmax > 128, "Tmax must be in [1, 128]");
+  BAD(p->k < 1 || p->k > p->V, "k must be in [1, V]");
+  BAD(!valid_dtype(p->qk_dtype) || !valid_dtype(p->h_dtype) || !valid_dtype(p->kv_dtype), "unknown dtype");
+  BAD(!(p->lambda_max > 0.0f && p->lambda_max <= 1.0f), "lambda_max must be in (0, 1]");
+  BAD(!(p->eps > 0.0f) || !isfinite(p->eps), "eps must be positive and finite");
+  BAD(isnan(p->sim_threshold), "sim_threshold is NaN");
+  BAD(!(p->merge_weight >= 0.0f) || !isfinite(p->merge_weight), "merge_weight must be finite and >= 0");
+  BAD(p->mask_mode != ASAP_MASK_OFF && p->mask_mode != ASAP_MASK_KEYBIAS, "unknown mask_mode");
+  BAD(p->route != ASAP_ROUTE_ABSORB && p->route != ASAP_ROUTE_PAPER, "unknown route");
+  BAD((int64_t)p->B * p->Hkv > 65535 || (int64_t)p->B * p->H > 65535, "B * heads must be <= 65535");
+#undef BAD
+  if (msg && n) msg[0] = 0;
+  return ASAP_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+asap_status common_checks(asap_ctx* ctx, const asap_params* p) {
+  if (!ctx) return ASAP_EINVAL;
+  ctx->err[0] = 0;
+  char msg[128];
+  asap_status st = check_params(p, msg, sizeof(msg));
+  if (st != ASAP_OK) return fail(ctx, st, "invalid parameters: %s", msg);
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(ctx, ASAP_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev != ctx->device)
+    return fail(ctx, ASAP_EINVAL, "current device %d is not the context's device %d", dev, ctx->device);
+  return ASAP_OK;
+}
+
+asap_status check_strides(asap_ctx* ctx, const char* name, const int64_t* s, int n, int unit) {
+  if (!s) return fail(ctx, ASAP_EINVAL, "%s is NULL", name);
+  for (int i = 0; i < n; ++i)
+    if (s[i] < 0 || s[i] % unit != 0)
+      return fail(ctx, ASAP_EINVAL, "%s[%d] = %lld must be a non-negative multiple of %d elements", name, i,
+                  (long long)s[i], unit);
+  return ASAP_OK;
+}
+
+asap_status check_workspace(asap_ctx* ctx, const asap_params* p, const void* ws, size_t bytes) {
+  size_t need = asap_workspace_bytes(p);
+  if (need == 0) return ASAP_OK;
+  if (!ws) return fail(ctx, ASAP_EINVAL, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(ctx, ASAP_EINVAL, "workspace is not 256-byte aligned");
+  if (bytes < need)
+    return fail(ctx, ASAP_EWORKSPACE, "workspace of %zu bytes is smaller than the %zu required", bytes, need);
+  return ASAP_OK;
+}
+
+asap_status hip_result(asap_ctx* ctx, hipError_t e, const char* what) {
+  if (e == hipSuccess) return ASAP_OK;
+  return fail(ctx, ASAP_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+asap_status asap_create(asap_ctx** out_ctx, int device) {
+  if (!out_ctx) return ASAP_EINVAL;
+  *out_ctx = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return ASAP_EINVAL;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return ASAP_EHIP;
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return ASAP_EUNSUPPORTED;
+  asap_ctx* c = new (std::nothrow) asap_ctx;
+  if (!c) return ASAP_EHIP;
+  c->device = device;
+  c->err[0] = 0;
+  *out_ctx = c;
+  return ASAP_OK;
+}
+
+void asap_destroy(asap_ctx* ctx) { delete ctx; }
+
+const char* asap_last_error(const asap_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+asap_status asap_check_params(const asap_params* p, char* msg, size_t msg_len) {
+  return check_params(p, msg, msg_len);
+}
+
+size_t asap_workspace_bytes(const asap_params* p) {
+  if (check_params(p, nullptr, 0) != ASAP_OK) return 0;
+  return score_workspace(*p).total;
+}
+
+asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, const int64_t q_vis_stride[3],
+                       const void* q_txt, const int64_t q_txt_stride[3], const void* k_vis,
+                       const int64_t k_vis_stride[3], const int32_t* text_len, const float* lse_extra,
+                       float* s_raw, float* s_hat, float* score, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  asap_status st = common_checks(ctx, p);
+  if (st != ASAP_OK) return st;
+  if (!q_vis || !q_txt || !k_vis || !text_len || !s_raw || !s_hat || !score)
+    return fail(ctx, ASAP_EINVAL, "asap_score: a required pointer is NULL");
+  if (!aligned16(q_vis) || !aligned16(q_txt) || !aligned16(k_vis))
+    return fail(ctx, ASAP_EINVAL, "asap_score: q_vis, q_txt and k_vis must be 16-byte aligned");
+  if ((st = check_strides(ctx, "q_vis_stride", q_vis_stride, 3, 8)) != ASAP_OK) return st;
+  if ((st = check_strides(ctx, "q_txt_stride", q_txt_stride, 3, 8)) != ASAP_OK) return st;
+  if ((st = check_strides(ctx, "k_vis_stride", k_vis_stride, 3, 8)) != ASAP_OK) return st;
+  if (q_vis_stride[2] < p->d || q_txt_stride[2] < p->d || k_vis_stride[2] < p->d)
+    return fail(ctx, ASAP_EINVAL, "asap_score: row strides must be >= d");
+  if ((st = check_workspace(ctx, p, workspace, workspace_bytes)) != ASAP_OK) return st;
+  Strides3 qv{q_vis_stride[0], q_vis_stride[1], q_vis_stride[2]};
+  Strides3 qt{q_txt_stride[0], q_txt_stride[1], q_txt_stride[2]};
+  Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
+  return hip_result(ctx,
+                    launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
+                                 static_cast<char*>(workspace), static_cast<hipStream_t>(stream)),
+                    "asap_score launch");
+}
+
+asap_status asap_select(asap_ctx* ctx, const asap_params* p, const float* score, int32_t* kept_idx,
+                        int32_t* pruned_idx, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  asap_status st = common_checks(ctx, p);
+  if (st != ASAP_OK) return st;
+  if (!score || !kept_idx || (!pruned_idx && p->k < p->V))
+    return fail(ctx, ASAP_EINVAL, "asap_select: a required pointer is NULL");
+  return hip_result(ctx, launch_select(*p, score, kept_idx, pruned_idx, static_cast<hipStream_t>(stream)),
+                    "asap_select launch");
+}
+
+asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, const int64_t hidden_stride[2],
+                       const float* s_hat, const int32_t* text_len, const int32_t* kept_idx,
+                       const int32_t* pruned_idx, void* out_hidden, int32_t* pos_out, int32_t* new_len,
+                       int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  asap_status st = common_checks(ctx, p);
+  if (st != ASAP_OK) return st;
+  if (p->route != ASAP_ROUTE_ABSORB)
+    return fail(ctx, ASAP_EUNSUPPORTED, "asap_merge: only ASAP_ROUTE_ABSORB is built");
+  const bool has_pruned = p->k < p->V;
+  if (!hidden || !s_hat || !text_len || !kept_idx || !out_hidden || !pos_out || !new_len || !wsum ||
+      !final_idx || (has_pruned && (!pruned_idx || !assign || !best_sim)))
+    return fail(ctx, ASAP_EINVAL, "asap_merge: a required pointer is NULL");
+  if (!aligned16(hidden) || !aligned16(out_hidden))
+    return fail(ctx, ASAP_EINVAL, "asap_merge: hidden and out_hidden must be 16-byte aligned");
+  if ((st = check_strides(ctx, "hidden_stride", hidden_stride, 2, 8)) != ASAP_OK) return st;
+  if (hidden_stride[1] < p->D) return fail(ctx, ASAP_EINVAL, "asap_merge: hidden row stride must be >= D");
+  {
+    const int64_t esz = dtype_size(p->h_dtype);
+    const char* a0 = static_cast<const char*>(hidden);
+    const char* a1 = a0 + ((int64_t)(p->B - 1) * hidden_stride[0] +
+                           (int64_t)(p->P + p->V + p->Tmax - 1) * hidden_stride[1] + p->D) * esz;
+    const char* b0 = static_cast<const char*>(out_hidden);
+    const char* b1 = b0 + (int64_t)p->B * (p->P + p->k + p->Tmax) * p->D * esz;
+    if (a0 < b1 && b0 < a1) return fail(ctx, ASAP_EINVAL, "asap_merge: out_hidden overlaps hidden");
+  }
+  return hip_result(ctx,
+                    launch_merge(*p, hidden, hidden_stride[0], hidden_stride[1], s_hat, text_len, kept_idx,
+                                 pruned_idx, out_hidden, pos_out, new_len, assign, best_sim, wsum, final_idx,
+                                 static_cast<hipStream_t>(stream)),
+                    "asap_merge launch");
+}
+
+asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layers, const void* const* k_src,
+                            const void* const* v_src, void* const* k_dst, void* const* v_dst,
+                            const int32_t* pos_out, const int32_t* new_len, void* stream) {
+  asap_status st = common_checks(ctx, p);
+  if (st != ASAP_OK) return st;
+  if (n_layers < 1 || n_layers > 64) return fail(ctx, ASAP_EINVAL, "asap_compact_kv: n_layers must be in [1, 64]");
+  if (!k_src || !v_src || !k_dst || !v_dst || !pos_out || !new_len)
+    return fail(ctx, ASAP_EINVAL, "asap_compact_kv: a required pointer is NULL");
+  const int64_t esz = dtype_size(p->kv_dtype);
+  const int64_t src_bytes = (int64_t)p->B * p->Hkv * (p->P + p->V + p->Tmax) * p->d * esz;
+  const int64_t dst_bytes = (int64_t)p->B * p->Hkv * (p->P + p->k + p->Tmax) * p->d * esz;
+  for (int l = 0; l < n_layers; ++l) {
+    const void* ptrs[4] = {k_src[l], v_src[l], k_dst[l], v_dst[l]};
+    for (const void* q : ptrs) {
+      if (!q) return fail(ctx, ASAP_EINVAL, "asap_compact_kv: layer %d has a NULL pointer", l);
+      if (!aligned16(q)) return fail(ctx, ASAP_EINVAL, "asap_compact_kv: layer %d pointer not 16-byte aligned", l);
+    }
+  }
+  // no destination may overlap any source (a kernel that reads and writes one buffer would race)
+  for (int l = 0; l < n_layers; ++l)
+    for (int which = 0; which < 2; ++which) {
+      const char* d0 = static_cast<const char*>(which ? v_dst[l] : k_dst[l]);
+      const char* d1 = d0 + dst_bytes;
+      for (int m = 0; m < n_layers; ++m)
+        for (int w2 = 0; w2 < 2; ++w2) {
+          const char* s0 = static_cast<const char*>(w2 ? v_src[m] : k_src[m]);
+          if (d0 < s0 + src_bytes && s0 < d1)
+            return fail(ctx, ASAP_EINVAL, "asap_compact_kv: destination of layer %d overlaps a source", l);
+        }
+    }
+  return hip_result(ctx,
+                    launch_compact_kv(*p, n_layers, k_src, v_src, k_dst, v_dst, pos_out, new_len,
+                                      static_cast<hipStream_t>(stream)),
+                    "asap_compact_kv launch");
+}
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+// asap_compact_kv: gathers the K/V rows of the surviving positions of every cached layer
+// (KV-cache compatibility of the pruning stage).  Pure data movement, bit-exact.
+//
+// k_compact: grid (ceil(Nout / ROWS_PER_BLOCK), B * Hkv, 2 * layers_in_launch), 256 threads.
+// A row is d elements = LPR 16-byte pieces; LPR consecutive lanes move one row.
+#include "asap_device.hpp"
+#include "asap_launch.hpp"
+
+namespace asap {
+
+constexpr int KV_LAYERS_PER_LAUNCH = 16;
+constexpr int KV_ROWS_PER_THREAD = 4;
+
+struct KvPointers {
+  const char* src[2 * KV_LAYERS_PER_LAUNCH];   // K then V of each layer
+  char* dst[2 * KV_LAYERS_PER_LAUNCH];
+};
+
+__global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t* __restrict__ pos_out,
+                                                  const int32_t* __restrict__ new_len, int Hkv, int N, int Nout,
+                                                  int row_bytes) {
+  const int lpr = row_bytes >> 4, rpi = 256 / lpr;
+  const int tid = threadIdx.x, piece = tid % lpr, r0 = tid / lpr;
+  const int bg = blockIdx.y, b = bg / Hkv;
+  const int nl = new_len[b];
+  const char* src = ptrs.src[blockIdx.z] + (int64_t)bg * N * row_bytes + piece * 16;
+  char* dst = ptrs.dst[blockIdx.z] + (int64_t)bg * Nout * row_bytes + piece * 16;
+  const int32_t* pos = pos_out + (int64_t)b * Nout;
+  const int base = blockIdx.x * rpi * KV_ROWS_PER_THREAD + r0;
+  uint4 v[KV_ROWS_PER_THREAD];
+#pragma unroll
+  for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
+    int nrow = base + i * rpi;
+    if (nrow < nl) v[i] = ldg16(src + (int64_t)pos[nrow] * row_bytes);
+  }
+#pragma unroll
+  for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
+    int nrow = base + i * rpi;
+    if (nrow < nl) *reinterpret_cast<uint4*>(dst + (int64_t)nrow * row_bytes) = v[i];
+  }
+}
+
+hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* const* k_src,
+                             const void* const* v_src, void* const* k_dst, void* const* v_dst,
+                             const int32_t* pos_out, const int32_t* new_len, hipStream_t st) {
+  const int row_bytes = p.d * (p.kv_dtype == ASAP_BF16 ? 2 : 4);
+  const int N = p.P + p.V + p.Tmax, Nout = p.P + p.k + p.Tmax;
+  const int rows_per_block = (256 / (row_bytes / 16)) * KV_ROWS_PER_THREAD;
+  for (int l0 = 0; l0 < n_layers; l0 += KV_LAYERS_PER_LAUNCH) {
+    const int nl = n_layers - l0 < KV_LAYERS_PER_LAUNCH ? n_layers - l0 : KV_LAYERS_PER_LAUNCH;
+    KvPointers ptrs;
+    for (int l = 0; l < nl; ++l) {
+      ptrs.src[2 * l] = static_cast<const char*>(k_src[l0 + l]);
+      ptrs.src[2 * l + 1] = static_cast<const char*>(v_src[l0 + l]);
+      ptrs.dst[2 * l] = static_cast<char*>(k_dst[l0 + l]);
+      ptrs.dst[2 * l + 1] = static_cast<char*>(v_dst[l0 + l]);
+    }
+    for (int l = 2 * nl; l < 2 * KV_LAYERS_PER_LAUNCH; ++l) { ptrs.src[l] = nullptr; ptrs.dst[l] = nullptr; }
+    dim3 grid((Nout + rows_per_block - 1) / rows_per_block, p.B * p.Hkv, 2 * nl);
+    hipLaunchKernelGGL(k_compact, grid, dim3(256), 0, st, ptrs, pos_out, new_len, p.Hkv, N, Nout, row_bytes);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace asap

@@ -1,0 +1,82 @@
+// Device-side helpers shared by the gfx950 kernels of the pruning stage.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace asap {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+struct bf16_t { uint16_t bits; };   // storage type tag for bfloat16 tensors
+
+template <typename T> struct elem;
+template <> struct elem<float>  { static constexpr int per16 = 4; };   // elements in a 16-byte chunk
+template <> struct elem<bf16_t> { static constexpr int per16 = 8; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// round-to-nearest-even float -> bf16 bits (NaN kept quiet)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// Unpack a 16-byte chunk into floats: 4 for f32 storage, 8 for bf16 storage.
+template <typename T> __device__ __forceinline__ void unpack16(const uint4& c, float* out);
+template <> __device__ __forceinline__ void unpack16<float>(const uint4& c, float* out) {
+  out[0] = __uint_as_float(c.x); out[1] = __uint_as_float(c.y);
+  out[2] = __uint_as_float(c.z); out[3] = __uint_as_float(c.w);
+}
+template <> __device__ __forceinline__ void unpack16<bf16_t>(const uint4& c, float* out) {
+  out[0] = bf16_bits_to_f32(c.x & 0xffffu); out[1] = bf16_bits_to_f32(c.x >> 16);
+  out[2] = bf16_bits_to_f32(c.y & 0xffffu); out[3] = bf16_bits_to_f32(c.y >> 16);
+  out[4] = bf16_bits_to_f32(c.z & 0xffffu); out[5] = bf16_bits_to_f32(c.z >> 16);
+  out[6] = bf16_bits_to_f32(c.w & 0xffffu); out[7] = bf16_bits_to_f32(c.w >> 16);
+}
+
+template <typename T> __device__ __forceinline__ uint4 pack16(const float* in);
+template <> __device__ __forceinline__ uint4 pack16<float>(const float* in) {
+  return make_uint4(__float_as_uint(in[0]), __float_as_uint(in[1]), __float_as_uint(in[2]),
+                    __float_as_uint(in[3]));
+}
+template <> __device__ __forceinline__ uint4 pack16<bf16_t>(const float* in) {
+  return make_uint4(f32_to_bf16_bits(in[0]) | (f32_to_bf16_bits(in[1]) << 16),
+                    f32_to_bf16_bits(in[2]) | (f32_to_bf16_bits(in[3]) << 16),
+                    f32_to_bf16_bits(in[4]) | (f32_to_bf16_bits(in[5]) << 16),
+                    f32_to_bf16_bits(in[6]) | (f32_to_bf16_bits(in[7]) << 16));
+}
+
+// One 16-byte operand chunk per lane on each side -> 32x32 fp32 tile update on the matrix
+// cores.  Lane l supplies row (A) / column (B) l%32 and the contraction slice picked by l/32;
+// which slice of the contraction dimension a chunk holds is the caller's choice as long as the
+// A and B chunks of one call agree.  The 16 results of lane l are C[8*(v/4) + 4*(l/32) + v%4][l%32].
+template <typename T> __device__ __forceinline__ void mma32(f32x16_t& acc, const uint4& a, const uint4& b);
+template <> __device__ __forceinline__ void mma32<bf16_t>(f32x16_t& acc, const uint4& a, const uint4& b) {
+  bf16x8_t x, y;
+  __builtin_memcpy(&x, &a, 16);
+  __builtin_memcpy(&y, &b, 16);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ void mma32<float>(f32x16_t& acc, const uint4& a, const uint4& b) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+}
+
+// row of the 32x32 tile held in accumulator register v of lane l
+__device__ __forceinline__ int mma32_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+
+__device__ __forceinline__ double shfl_xor_f64(double x, int mask) {
+  int lo = __double2loint(x), hi = __double2hiint(x);
+  lo = __shfl_xor(lo, mask);
+  hi = __shfl_xor(hi, mask);
+  return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+
+}  // namespace asap

@@ -1,0 +1,46 @@
+// Host-side launch entry points of the kernel files (internal; the public ABI is asap.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "asap.h"
+
+namespace asap {
+
+// Carve-up of the caller's workspace for the score path.  All offsets 256-byte aligned.
+struct ScoreWorkspace {
+  int q_rows;        // visual query rows summed per partial block
+  int q_chunks;      // ceil(V / q_rows)
+  size_t off_qpart;  // double [B,H,q_chunks,d]  partial sums of visual queries
+  size_t off_qbar;   // double [B,Hkv,d]         summed visual queries per kv head
+  size_t off_s64;    // double [B,V]             raw attention mass before rounding
+  size_t off_mm;     // double [B,2]             min, max of s per image
+  size_t off_lam;    // float  [B,V]             discount lambda'_j (1 when the mask is off)
+  size_t off_upart;  // float  [B,H,V]           per-head column sums of normalised weights
+  size_t total;
+};
+ScoreWorkspace score_workspace(const asap_params& p);
+
+struct Strides3 { int64_t b, h, r; };
+
+hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
+                        const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
+                        float* s_raw, float* s_hat, float* score, char* ws, hipStream_t st);
+
+hipError_t launch_select(const asap_params& p, const float* score, int32_t* kept, int32_t* pruned,
+                         hipStream_t st);
+
+hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
+                        const float* s_hat, const int32_t* text_len, const int32_t* kept,
+                        const int32_t* pruned, void* out_hidden, int32_t* pos_out, int32_t* new_len,
+                        int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx,
+                        hipStream_t st);
+
+hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* const* k_src,
+                             const void* const* v_src, void* const* k_dst, void* const* v_dst,
+                             const int32_t* pos_out, const int32_t* new_len, hipStream_t st);
+
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+}  // namespace asap

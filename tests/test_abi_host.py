@@ -1,0 +1,86 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header declares,
+validates parameter blocks and sizes its workspace.  No kernel is launched here."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+from paper_2603_14549_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.lib_path()):
+        from paper_2603_14549_amd import build
+        build.build_library(verbose=False)
+    return binding.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "asap.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(asap_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_stage_calls():
+    names = declared_functions()
+    for n in ("asap_score", "asap_select", "asap_merge", "asap_compact_kv"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert sorted(names) == sorted(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def good():
+    return binding.params_from_config(synth.CONFIGS["C6"])
+
+
+def test_check_params_accepts_all_benchmark_configs(lib):
+    for cfg in synth.CONFIGS.values():
+        st, msg = binding.asap_check_params(binding.params_from_config(cfg))
+        assert st == binding.ASAP_OK, (cfg.name, msg)
+        assert binding.asap_workspace_bytes(binding.params_from_config(cfg)) > 0
+
+
+@pytest.mark.parametrize("field,value", [
+    ("B", 0), ("k", 0), ("k", 2305), ("Hkv", 5), ("d", 96), ("D", 4100), ("V", 0), ("V", 20000),
+    ("Tmax", 0), ("Tmax", 129), ("P", -1), ("lambda_max", 0.0), ("lambda_max", 1.5), ("eps", 0.0),
+    ("merge_weight", -1.0), ("sim_threshold", float("nan")), ("qk_dtype", 7), ("mask_mode", 3), ("route", 2),
+])
+def test_check_params_rejects(lib, field, value):
+    p = good()
+    setattr(p, field, value)
+    st, msg = binding.asap_check_params(p)
+    assert st == binding.ASAP_EINVAL and msg
+    assert binding.asap_workspace_bytes(p) == 0
+
+
+def test_k_equal_v_and_infinite_threshold_are_legal(lib):
+    p = good()
+    p.k = p.V
+    p.sim_threshold = -math.inf
+    assert binding.asap_check_params(p)[0] == binding.ASAP_OK
+
+
+def test_workspace_size_formula(lib):
+    # partial query sums + summed queries + fp64 mass + min/max + discount + per-head column sums
+    p = good()
+    B, H, Hkv, d, V = p.B, p.H, p.Hkv, p.d, p.V
+    chunks = -(-V // 256)
+    al = lambda x: (x + 255) // 256 * 256
+    want = (al(8 * B * H * chunks * d) + al(8 * B * Hkv * d) + al(8 * B * V) + al(16 * B) + al(4 * B * V)
+            + al(4 * B * H * V))
+    assert binding.asap_workspace_bytes(p) == want
+
+
+def test_struct_layout_matches_header(lib):
+    # 9 int32 + 3 enums + 4 floats + 2 enums, all 4 bytes, no padding
+    assert ctypes.sizeof(binding.asap_params) == 18 * 4

@@ -1,0 +1,186 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same
+seeded inputs.  Small cases are compared element by element on every image; the benchmark
+configurations run at full size in the launch configuration bench.py times."""
+import dataclasses
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_14549_amd import binding, synth
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    c = binding.Context(0)
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("name", ["S0", "S1", "S2", "S3", "S4"])
+def test_small_configs_every_image(ctx, name):
+    U.run_and_compare(synth.CONFIGS[name], ctx=ctx)
+
+
+@pytest.mark.parametrize("name,overrides", [
+    ("S1", dict(mask_mode=binding.ASAP_MASK_OFF)),
+    ("S1", dict(merge_weight=0.0)),
+    ("S2", dict(merge_weight=0.5, lambda_max=0.7)),
+    ("S2", dict(sim_threshold=0.9)),
+    ("S0", dict(eps=1e-3)),
+    ("S4", dict(mask_mode=binding.ASAP_MASK_OFF, merge_weight=0.0)),
+])
+def test_parameter_variants(ctx, name, overrides):
+    U.run_and_compare(synth.CONFIGS[name], ctx=ctx, **overrides)
+
+
+def test_full_row_softmax_with_lse_extra(ctx):
+    U.run_and_compare(synth.CONFIGS["S1"], ctx=ctx, lse=True)
+    U.run_and_compare(synth.CONFIGS["S2"], ctx=ctx, lse=True)
+
+
+def test_reduction_to_plain_topk_pruning(ctx):
+    """Mask off and merge weight 0: the output is a pure gather of the top-k rows."""
+    cfg = synth.CONFIGS["S2"]
+    inp, st = U.run_and_compare(cfg, ctx=ctx, mask_mode=binding.ASAP_MASK_OFF, merge_weight=0.0)
+    buf = st.buf
+    for b in range(cfg.B):
+        kept = buf.kept_idx[b].long()
+        rows = st.hidden[b, cfg.P + kept]
+        assert torch.equal(buf.out_hidden[b, cfg.P:cfg.P + cfg.k], rows)
+
+
+@pytest.mark.parametrize("k", [1, 2, 63, 64, 65, 199, 200])
+def test_budget_edges(ctx, k):
+    cfg = dataclasses.replace(synth.CONFIGS["S3"], k=k, name=f"S3k{k}")
+    U.run_and_compare(cfg, ctx=ctx)
+
+
+@pytest.mark.parametrize("V,k,Tmax", [(1, 1, 1), (5, 2, 3), (31, 7, 33), (32, 32, 64), (33, 1, 65), (127, 100, 97),
+                                      (1025, 300, 128)])
+def test_shape_edges(ctx, V, k, Tmax):
+    cfg = dataclasses.replace(synth.CONFIGS["S2"], V=V, k=k, Tmax=Tmax, B=2, ragged_text=True, text_lo=1,
+                              name=f"edge{V}_{k}_{Tmax}", n_clusters=3)
+    U.run_and_compare(cfg, ctx=ctx)
+
+
+def test_f32_long_text_and_gqa_d64(ctx):
+    cfg = dataclasses.replace(synth.CONFIGS["S0"], Tmax=128, V=150, k=40, H=8, Hkv=2, B=2, ragged_text=True,
+                              text_lo=100, name="f32T128")
+    U.run_and_compare(cfg, ctx=ctx)
+    cfg = dataclasses.replace(synth.CONFIGS["S0"], d=128, Tmax=100, V=140, k=35, H=4, Hkv=4, B=1, name="f32d128")
+    U.run_and_compare(cfg, ctx=ctx)
+
+
+def test_ties_all_equal_scores_and_duplicate_rows(ctx):
+    """Identical visual tokens: all scores tie (top-k must take the smallest indices) and every
+    cosine ties at 1 (routing must take the smallest slot)."""
+    cfg = dataclasses.replace(synth.CONFIGS["S0"], B=1, V=96, k=30, name="dups")
+    inp = synth.make_inputs(cfg)
+    P, V = cfg.P, cfg.V
+    inp["hidden"][0, P:P + V] = inp["hidden"][0, P]
+    inp["q"][0, :, P:P + V] = inp["q"][0, :, P:P + 1]
+    inp["k"][0, :, P:P + V] = inp["k"][0, :, P:P + 1]
+    st = U.GpuStage(inp, ctx=ctx)
+    buf = st.run()
+    assert buf.kept_idx[0].tolist() == list(range(cfg.k))
+    assert buf.pruned_idx[0].tolist() == list(range(cfg.k, V))
+    assert (buf.assign[0] == 0).all()
+    assert torch.allclose(buf.best_sim[0], torch.ones_like(buf.best_sim[0]), atol=1e-5)
+    # constant mass -> salience 0 everywhere -> nothing is absorbed -> rows copied bit-exactly
+    assert (buf.s_hat[0] == 0).all()
+    assert torch.equal(buf.out_hidden[0, P:P + cfg.k], st.hidden[0, P:P + cfg.k])
+
+
+def test_determinism(ctx):
+    cfg = synth.CONFIGS["S2"]
+    inp = synth.make_inputs(cfg)
+    st = U.GpuStage(inp, ctx=ctx)
+    buf = st.run()
+    first = {n: getattr(buf, n).clone() for n in ("score", "kept_idx", "assign", "best_sim", "out_hidden", "wsum")}
+    for _ in range(5):
+        buf = st.run()
+        for n, t in first.items():
+            got = getattr(buf, n)
+            assert torch.equal(got.view(torch.uint8) if got.is_floating_point() else got,
+                               t.view(torch.uint8) if t.is_floating_point() else t), n
+
+
+def test_strided_views_and_errors(ctx):
+    cfg = synth.CONFIGS["S0"]
+    inp = synth.make_inputs(cfg)
+    st = U.GpuStage(inp, ctx=ctx)
+    p, buf = st.p, st.buf
+    with pytest.raises(binding.AsapError) as e:       # workspace too small
+        small = torch.empty(256, dtype=torch.uint8, device="cuda")
+        ctx.asap_score(p, st.q[:, :, cfg.P:cfg.P + cfg.V], st.q[:, :, cfg.P + cfg.V:], st.k[:, :, cfg.P:cfg.P + cfg.V],
+                       st.text_len, None, buf.s_raw, buf.s_hat, buf.score, small)
+    assert e.value.status == binding.ASAP_EWORKSPACE
+    with pytest.raises(binding.AsapError) as e:       # out_hidden aliasing hidden
+        ctx.asap_merge(p, st.hidden, buf.s_hat, st.text_len, buf.kept_idx, buf.pruned_idx, st.hidden, buf.pos_out,
+                       buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace)
+    assert e.value.status == binding.ASAP_EINVAL
+    p2 = binding.params_from_config(cfg, route=binding.ASAP_ROUTE_PAPER)
+    with pytest.raises(binding.AsapError) as e:
+        ctx.asap_merge(p2, st.hidden, buf.s_hat, st.text_len, buf.kept_idx, buf.pruned_idx, buf.out_hidden,
+                       buf.pos_out, buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace)
+    assert e.value.status == binding.ASAP_EUNSUPPORTED
+    with pytest.raises(binding.AsapError) as e:       # K/V destination aliasing a source
+        ctx.asap_compact_kv(p, st.k_cache, st.v_cache, st.k_cache, buf.v_dst, buf.pos_out, buf.new_len)
+    assert e.value.status == binding.ASAP_EINVAL
+    st.run()                                           # the context still works afterwards
+
+
+# ------------------------------------------------------------------ benchmark configurations, full size
+def test_config1_llava15_single_image(ctx):
+    U.run_and_compare(synth.CONFIGS["C1"], ctx=ctx)
+
+
+def test_config2_llava_next_single_image(ctx):
+    U.run_and_compare(synth.CONFIGS["C2"], ctx=ctx)
+
+
+def test_config3_batch16_ragged_text(ctx):
+    rep = {}
+    U.run_and_compare(synth.CONFIGS["C3"], images=[0, 1, 7, 15], ctx=ctx, report=rep)
+    print("C3", rep)
+
+
+def test_config4_gqa_dynamic_resolution(ctx):
+    U.run_and_compare(synth.CONFIGS["C4"], images=[0, 3], ctx=ctx)
+
+
+def test_config6_target_2304_tokens_batch16(ctx):
+    rep = {}
+    U.run_and_compare(synth.CONFIGS["C6"], images=[0, 5, 15], ctx=ctx, report=rep)
+    print("C6", rep)
+
+
+def test_config5_two_stage(ctx):
+    """Stage 1 (2304 -> 576) then stage 2 (576 -> 160) on the GPU's stage-1 output, with Q/K of the
+    survivors rotated at their original position ids; stage 2 is judged stage-wise."""
+    c5a, c5b = synth.CONFIGS["C5a"], synth.CONFIGS["C5b"]
+    inp1 = synth.make_inputs(c5a)
+    st1 = U.GpuStage(inp1, ctx=ctx)
+    buf1 = st1.run()
+    for b in (0, 7):
+        U.compare_image(inp1, buf1, b, U.oracle_image(inp1, b))
+    hid = buf1.out_hidden.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+    pos = buf1.pos_out.cpu().numpy()
+    nl = buf1.new_len.cpu().numpy()
+    inp2 = synth.second_stage_inputs(c5b, hid, pos, nl, inp1["text_len"])
+    st2 = U.GpuStage(inp2, ctx=ctx)
+    buf2 = st2.run()
+    for b in (0, 7):
+        U.compare_image(inp2, buf2, b, U.oracle_image(inp2, b))
+    # original position ids survive both stages: compose the two maps
+    p2 = buf2.pos_out.cpu().numpy()
+    for b in range(c5b.B):
+        n2 = int(buf2.new_len[b])
+        orig = pos[b][p2[b][:n2]]
+        assert (np.diff(orig) > 0).all() and n2 == c5b.P + c5b.k + int(inp1["text_len"][b])
