@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the pruning stage on one MI355X.
+
+A step = one pass of the whole hot path (asap_score, asap_select, asap_merge, asap_compact_kv)
+over one batch of synthetic input already resident in HBM.  Default workload: C6, the
+2304-visual-token, batch-16, bf16 configuration (LLaVA-NeXT-7B shaped) the metric is quoted on.
+
+Prints ONE JSON line: whole-job images/s, ms per step, the roofline of the dominant kernel
+(per-kernel durations measured with HIP events recorded by the library on the launch stream,
+in a second pass of the same K steps right after the timed one, so that the events do not
+slow the timed region), the whole-stage HBM fraction, and the fp64 oracle timed on the host
+cores on a bounded sample of the same workload.
+
+    python bench.py [--steps K] [--warmup W] [--workload C6] [--no-cpu-baseline] [--copy-calibration]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12          # B/s, MI355X HBM3E
+MFMA_PEAK = {"bf16": 2.5e15, "f32": 157.3e12}
+
+# HBM bytes per launch read from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
+# (see profiles/); keyed by workload then kernel.  None = not measured for that workload.
+MEASURED_TRAFFIC = {}
+
+
+def esize(dt: str) -> int:
+    return 2 if dt == "bf16" else 4
+
+
+def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
+    """Compulsory bytes (each input read once, each output written once) per kernel and for the
+    whole stage, and the similarity flops."""
+    B, H, Hkv, d, D, P, V, k = cfg.B, cfg.H, cfg.Hkv, cfg.d, cfg.D, cfg.P, cfg.V, cfg.k
+    eq, eh, ek = esize(cfg.qk_dtype), esize(cfg.h_dtype), esize(cfg.kv_dtype)
+    T = mean_text
+    q_vis, k_vis, q_txt = B * H * V * d * eq, B * Hkv * V * d * eq, B * H * T * d * eq
+    vis_h = B * V * D * eh
+    out_rows = B * (P + k + T)
+    per_kernel = {
+        "k_qsum": q_vis,
+        "k_qbar": 8 * B * H * d * (-(-V // 256)) + 8 * B * Hkv * d,
+        "k_salience": 16 * B * V,
+        "k_mass": k_vis + 12 * B * V,
+        "k_text_attn": k_vis + q_txt + 4 * B * V + 4 * B * H * V,
+        "k_score": 4 * B * H * V + 12 * B * V,
+        "k_select": 12 * B * V,
+        "k_sim": vis_h + 8 * B * (V - k),
+        "k_merge": vis_h + B * (P + T) * D * eh + out_rows * D * eh,
+        "k_compact": 2 * 2 * n_layers * Hkv * out_rows * d * ek,
+    }
+    stage = (q_vis + k_vis + q_txt + 12 * B * V) + 12 * B * V + (vis_h + 8 * B * (V - k)) \
+        + (vis_h + B * (P + T) * D * eh + out_rows * D * eh) + per_kernel["k_compact"]
+    return {"per_kernel": per_kernel, "stage": stage, "sim_flops": 2.0 * B * (V - k) * k * D}
+
+
+def cpu_baseline(inp, cfg, budget_s: float = 12.0) -> dict:
+    """The oracle as it stands, timed on the host on the first few images of the batch."""
+    from oracle import asap_oracle as O          # only this leg touches the oracle
+    from paper_2603_14549_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    done, t_total = 0, 0.0
+    while done < cfg.B and done < 8 and t_total < budget_s:
+        t0 = time.perf_counter()
+        b = done
+        ref = O.stage(synth.to_f64(inp["q"][b], cfg.qk_dtype), synth.to_f64(inp["k"][b], cfg.qk_dtype),
+                      synth.to_f64(inp["hidden"][b], cfg.h_dtype), int(inp["text_len"][b]), cfg.P, cfg.V,
+                      cfg.Tmax, cfg.k, linear_mass=True)
+        for l in range(cfg.L_kv):
+            for cache in (inp["k_cache"][l], inp["v_cache"][l]):
+                O.gather_kv(cache[b], ref["pos_out"], ref["new_len"])
+        t_total += time.perf_counter() - t0
+        done += 1
+    return {"value": done / t_total, "unit": "images/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {done} of {cfg.B} images of workload {cfg.name} (fp64 NumPy oracle, "
+                      f"sum-of-queries form of Eq. 2, {t_total:.1f} s)",
+            "ms_per_image": 1e3 * t_total / done}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C6")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times (reference for HBM counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU (the pruning stage of one GPU's share of the batch); "
+              "images are independent, so N GPUs would each run this same stage on B/N images. "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2603_14549_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    binding.load()
+    cfg = synth.CONFIGS[args.workload]
+    t0 = time.perf_counter()
+    inp = synth.make_inputs(cfg)
+    gen_s = time.perf_counter() - t0
+    ctx = binding.Context(0)
+    stage = binding.DeviceStage(inp, ctx=ctx)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        stage.run_async()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        stage.run_async()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    images_per_s = cfg.B * args.steps / elapsed
+
+    # second pass of the same K steps with the library's per-kernel HIP events on
+    launches_per_step = 16
+    ctx.asap_timing_enable(min(8192, launches_per_step * args.steps))
+    for _ in range(args.steps):
+        stage.run_async()
+    torch.cuda.synchronize()
+    timing = ctx.asap_timing_collect()
+    ctx.asap_timing_enable(0)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    mean_text = float(np.mean(inp["text_len"]))
+    alg = algorithmic_bytes(cfg, mean_text, cfg.L_kv)
+    kernels = {}
+    for name, (ms, n) in timing.items():
+        avg_us = 1e3 * ms / n
+        per_launch_bytes = alg["per_kernel"][name] * args.steps / n      # several launches per step share it
+        kernels[name] = {"avg_us": round(avg_us, 2), "launches_per_step": n / args.steps,
+                         "alg_MB": round(per_launch_bytes / 1e6, 2),
+                         "GBps": round(per_launch_bytes / (avg_us * 1e-6) / 1e9, 1)}
+    step_kernel_us = sum(1e3 * ms / args.steps for ms, _ in timing.values())
+    dominant = max(timing, key=lambda k: timing[k][0])
+    d_ms, d_n = timing[dominant]
+    d_avg_s = 1e-3 * d_ms / d_n
+    traffic = MEASURED_TRAFFIC.get(cfg.name, {}).get(dominant)
+    if dominant == "k_sim" and cfg.V > cfg.k:
+        flops = alg["sim_flops"] * args.steps / d_n
+        peak = MFMA_PEAK[cfg.h_dtype]
+        roofline = {"kernel": dominant, "bound": "mfma", "achieved": flops / d_avg_s / 1e12, "peak": peak / 1e12,
+                    "unit": "TFLOP/s", "frac": flops / d_avg_s / peak, "traffic": traffic}
+    else:
+        nbytes = alg["per_kernel"][dominant] * args.steps / d_n
+        roofline = {"kernel": dominant, "bound": "hbm", "achieved": nbytes / d_avg_s / 1e9, "peak": HBM_PEAK / 1e9,
+                    "unit": "GB/s", "frac": nbytes / d_avg_s / HBM_PEAK, "traffic": traffic}
+    sim = timing.get("k_sim")
+    sim_roofline = None
+    if sim:
+        s_avg = 1e-3 * sim[0] / sim[1]
+        sim_roofline = {"bound": "mfma", "achieved": alg["sim_flops"] / s_avg / 1e12,
+                        "peak": MFMA_PEAK[cfg.h_dtype] / 1e12, "unit": "TFLOP/s",
+                        "frac": alg["sim_flops"] / s_avg / MFMA_PEAK[cfg.h_dtype]}
+    stage_roofline = {"bound": "hbm", "alg_MB": round(alg["stage"] / 1e6, 1),
+                      "achieved": alg["stage"] / (ms_per_step * 1e-3) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                      "frac": alg["stage"] / (ms_per_step * 1e-3) / HBM_PEAK,
+                      "sum_kernel_us": round(step_kernel_us, 1)}
+
+    out = {
+        "metric": "pruning-stage images/sec at %d visual tokens" % cfg.V,
+        "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "us_per_image": 1e3 * ms_per_step / cfg.B, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.h_dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B}, {cfg.P} prefix + {cfg.V} visual + {cfg.Tmax} text tokens, "
+                               f"hidden {cfg.D}, {cfg.H}/{cfg.Hkv} heads x {cfg.d}, keep {cfg.k}, "
+                               f"qk/hidden/kv dtypes {cfg.qk_dtype}/{cfg.h_dtype}/{cfg.kv_dtype}, "
+                               f"{cfg.L_kv} K/V layers, mask=keybias, route=absorb, mu=1",
+                   "input_generation_s": round(gen_s, 1)},
+        "roofline": roofline,
+        "stage_roofline": stage_roofline,
+        "similarity_gemm": sim_roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -162,6 +162,20 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
                             void* const* k_dst, void* const* v_dst,
                             const int32_t* pos_out, const int32_t* new_len, void* stream);
 
+/*
+ * Kernel timing for benchmarks (not part of the method).  asap_timing_enable(ctx, n) with n > 0
+ * creates a pool of n event pairs (n <= 8192); from then on each kernel the four calls launch
+ * is bracketed by two HIP events recorded on the call's own stream, until the pool is used up
+ * (later launches run untimed).  n <= 0 switches timing off and frees the pool.
+ * asap_timing_collect waits for the recorded events, adds the elapsed times up per kernel name
+ * and empties the pool for reuse: names [host] receives the kernel names, one per line;
+ * total_ms[i] / launches[i] [host] the summed milliseconds and launch count of the i-th name.
+ * Returns the number of distinct kernels (<= max_kernels, <= 64), or -1 on error.
+ */
+asap_status asap_timing_enable(asap_ctx* ctx, int32_t max_launches);
+int32_t     asap_timing_collect(asap_ctx* ctx, char* names, size_t names_len, double* total_ms,
+                                int32_t* launches, int32_t max_kernels);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,8 @@ ASAP_MASK_OFF, ASAP_MASK_KEYBIAS = 0, 1
 ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
 
 EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
-           "asap_score", "asap_select", "asap_merge", "asap_compact_kv"]
+           "asap_score", "asap_select", "asap_merge", "asap_compact_kv", "asap_timing_enable",
+           "asap_timing_collect"]
 
 _DTYPE_CODE = {"f32": ASAP_F32, "bf16": ASAP_BF16, torch.float32: ASAP_F32, torch.bfloat16: ASAP_BF16}
 _TORCH_DTYPE = {ASAP_F32: torch.float32, ASAP_BF16: torch.bfloat16}
@@ -83,6 +84,11 @@ def load() -> ctypes.CDLL:
     lib.asap_compact_kv.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                     ctypes.POINTER(vp), ctypes.POINTER(vp), i32p, i32p, vp]
     lib.asap_compact_kv.restype = ctypes.c_int
+    lib.asap_timing_enable.argtypes = [vp, ctypes.c_int32]
+    lib.asap_timing_enable.restype = ctypes.c_int
+    lib.asap_timing_collect.argtypes = [vp, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double),
+                                        ctypes.POINTER(ctypes.c_int32), ctypes.c_int32]
+    lib.asap_timing_collect.restype = ctypes.c_int32
     _lib = lib
     return lib
 
@@ -152,6 +158,20 @@ class Context:
     def _check(self, st: int):
         if st != ASAP_OK:
             raise AsapError(st, self.last_error())
+
+    def asap_timing_enable(self, max_launches: int):
+        self._check(self._lib.asap_timing_enable(self._h, max_launches))
+
+    def asap_timing_collect(self) -> dict:
+        """{kernel name: (total milliseconds, launches)} since the last collect."""
+        names = ctypes.create_string_buffer(4096)
+        ms = (ctypes.c_double * 64)()
+        cnt = (ctypes.c_int32 * 64)()
+        n = self._lib.asap_timing_collect(self._h, names, 4096, ms, cnt, 64)
+        if n < 0:
+            raise AsapError(ASAP_EHIP, "asap_timing_collect failed")
+        keys = names.value.decode().split("\n")[:n]
+        return {k: (ms[i], cnt[i]) for i, k in enumerate(keys)}
 
     # ---- the four calls, arguments as in asap.h -------------------------------------------
     def asap_score(self, p, q_vis, q_txt, k_vis, text_len, lse_extra, s_raw, s_hat, score, workspace,
@@ -224,3 +244,40 @@ def run_stage(ctx: Context, p: asap_params, q: torch.Tensor, k: torch.Tensor, hi
     if k_cache:
         ctx.asap_compact_kv(p, k_cache, v_cache, buf.k_dst, buf.v_dst, buf.pos_out, buf.new_len, stream)
     return buf
+
+
+def to_device(arr, dtype: str, device="cuda:0") -> torch.Tensor:
+    """Host array as stored by synth.quantise (float32, or uint16 bf16 bit patterns) -> device tensor."""
+    import numpy as np
+    if dtype == "bf16":
+        return torch.from_numpy(arr.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(arr).to(device)
+
+
+class DeviceStage:
+    """One batch from synth.make_inputs uploaded to the GPU, with output buffers; run() makes the
+    four library calls."""
+
+    def __init__(self, inp: dict, ctx: Optional[Context] = None, lse_extra=None, **param_overrides):
+        import numpy as np
+        cfg = inp["cfg"]
+        self.cfg = cfg
+        self.ctx = ctx or Context(0)
+        self.p = params_from_config(cfg, **param_overrides)
+        self.q = to_device(inp["q"], cfg.qk_dtype)
+        self.k = to_device(inp["k"], cfg.qk_dtype)
+        self.hidden = to_device(inp["hidden"], cfg.h_dtype)
+        self.text_len = torch.from_numpy(inp["text_len"].astype(np.int32)).cuda()
+        self.k_cache = [to_device(a, cfg.kv_dtype) for a in inp.get("k_cache", [])]
+        self.v_cache = [to_device(a, cfg.kv_dtype) for a in inp.get("v_cache", [])]
+        self.lse_extra = None if lse_extra is None else torch.from_numpy(lse_extra.astype(np.float32)).cuda()
+        self.buf = StageBuffers(self.p, len(self.k_cache))
+
+    def run_async(self) -> StageBuffers:
+        return run_stage(self.ctx, self.p, self.q, self.k, self.hidden, self.text_len, self.k_cache,
+                         self.v_cache, self.buf, self.lse_extra)
+
+    def run(self) -> StageBuffers:
+        self.run_async()
+        torch.cuda.synchronize()
+        return self.buf

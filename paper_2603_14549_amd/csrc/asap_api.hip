@@ -9,6 +9,7 @@
 struct asap_ctx {
   int device;
   char err[512];
+  asap::Timer* timer;   // non-null while kernel timing is on
 };
 
 namespace {
@@ -113,11 +114,84 @@ asap_status asap_create(asap_ctx** out_ctx, int device) {
   if (!c) return ASAP_EHIP;
   c->device = device;
   c->err[0] = 0;
+  c->timer = nullptr;
   *out_ctx = c;
   return ASAP_OK;
 }
 
-void asap_destroy(asap_ctx* ctx) { delete ctx; }
+static void drop_timer(asap_ctx* ctx) {
+  if (!ctx->timer) return;
+  for (int i = 0; i < ctx->timer->n_created; ++i) {
+    hipEventDestroy(ctx->timer->rec[i].start);
+    hipEventDestroy(ctx->timer->rec[i].stop);
+  }
+  delete ctx->timer;
+  ctx->timer = nullptr;
+}
+
+void asap_destroy(asap_ctx* ctx) {
+  if (!ctx) return;
+  drop_timer(ctx);
+  delete ctx;
+}
+
+asap_status asap_timing_enable(asap_ctx* ctx, int32_t max_launches) {
+  if (!ctx) return ASAP_EINVAL;
+  drop_timer(ctx);
+  if (max_launches <= 0) return ASAP_OK;
+  if (max_launches > asap::Timer::kMaxRecords) max_launches = asap::Timer::kMaxRecords;
+  asap::Timer* t = new (std::nothrow) asap::Timer;
+  if (!t) return fail(ctx, ASAP_EHIP, "asap_timing_enable: out of host memory");
+  ctx->timer = t;
+  for (int i = 0; i < max_launches; ++i) {
+    hipError_t e = hipEventCreate(&t->rec[i].start);
+    if (e == hipSuccess) {
+      e = hipEventCreate(&t->rec[i].stop);
+      if (e != hipSuccess) hipEventDestroy(t->rec[i].start);
+    }
+    if (e != hipSuccess) {
+      drop_timer(ctx);
+      return fail(ctx, ASAP_EHIP, "asap_timing_enable: hipEventCreate: %s", hipGetErrorString(e));
+    }
+    t->n_created = i + 1;
+  }
+  return ASAP_OK;
+}
+
+int32_t asap_timing_collect(asap_ctx* ctx, char* names, size_t names_len, double* total_ms, int32_t* launches,
+                            int32_t max_kernels) {
+  if (!ctx || !ctx->timer || !names || !total_ms || !launches || max_kernels < 1) return -1;
+  asap::Timer* t = ctx->timer;
+  const char* seen[64];
+  int n_seen = 0;
+  size_t used = 0;
+  if (names_len) names[0] = 0;
+  for (int i = 0; i < t->n_used; ++i) {
+    if (hipEventSynchronize(t->rec[i].stop) != hipSuccess) return -1;
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, t->rec[i].start, t->rec[i].stop) != hipSuccess) return -1;
+    int slot = -1;
+    for (int j = 0; j < n_seen; ++j)
+      if (seen[j] == t->rec[i].name || strcmp(seen[j], t->rec[i].name) == 0) { slot = j; break; }
+    if (slot < 0) {
+      if (n_seen >= max_kernels || n_seen >= 64) continue;
+      size_t len = strlen(t->rec[i].name);
+      if (used + len + 2 > names_len) continue;
+      memcpy(names + used, t->rec[i].name, len);
+      names[used + len] = '\n';
+      names[used + len + 1] = 0;
+      used += len + 1;
+      slot = n_seen++;
+      seen[slot] = t->rec[i].name;
+      total_ms[slot] = 0.0;
+      launches[slot] = 0;
+    }
+    total_ms[slot] += (double)ms;
+    launches[slot] += 1;
+  }
+  t->n_used = 0;
+  return n_seen;
+}
 
 const char* asap_last_error(const asap_ctx* ctx) { return ctx ? ctx->err : "null context"; }
 
@@ -152,7 +226,7 @@ asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, c
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
   return hip_result(ctx,
                     launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                                 static_cast<char*>(workspace), static_cast<hipStream_t>(stream)),
+                                 static_cast<char*>(workspace), static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_score launch");
 }
 
@@ -164,7 +238,7 @@ asap_status asap_select(asap_ctx* ctx, const asap_params* p, const float* score,
   if (st != ASAP_OK) return st;
   if (!score || !kept_idx || (!pruned_idx && p->k < p->V))
     return fail(ctx, ASAP_EINVAL, "asap_select: a required pointer is NULL");
-  return hip_result(ctx, launch_select(*p, score, kept_idx, pruned_idx, static_cast<hipStream_t>(stream)),
+  return hip_result(ctx, launch_select(*p, score, kept_idx, pruned_idx, static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_select launch");
 }
 
@@ -199,7 +273,7 @@ asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, 
   return hip_result(ctx,
                     launch_merge(*p, hidden, hidden_stride[0], hidden_stride[1], s_hat, text_len, kept_idx,
                                  pruned_idx, out_hidden, pos_out, new_len, assign, best_sim, wsum, final_idx,
-                                 static_cast<hipStream_t>(stream)),
+                                 static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_merge launch");
 }
 
@@ -235,7 +309,7 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
     }
   return hip_result(ctx,
                     launch_compact_kv(*p, n_layers, k_src, v_src, k_dst, v_dst, pos_out, new_len,
-                                      static_cast<hipStream_t>(stream)),
+                                      static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_compact_kv launch");
 }
 

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t*
 
 hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* const* k_src,
                              const void* const* v_src, void* const* k_dst, void* const* v_dst,
-                             const int32_t* pos_out, const int32_t* new_len, hipStream_t st) {
+                             const int32_t* pos_out, const int32_t* new_len, hipStream_t st, Timer* tm) {
   const int row_bytes = p.d * (p.kv_dtype == ASAP_BF16 ? 2 : 4);
   const int N = p.P + p.V + p.Tmax, Nout = p.P + p.k + p.Tmax;
   const int rows_per_block = (256 / (row_bytes / 16)) * KV_ROWS_PER_THREAD;
@@ -57,7 +57,7 @@ hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* con
     }
     for (int l = 2 * nl; l < 2 * KV_LAYERS_PER_LAUNCH; ++l) { ptrs.src[l] = nullptr; ptrs.dst[l] = nullptr; }
     dim3 grid((Nout + rows_per_block - 1) / rows_per_block, p.B * p.Hkv, 2 * nl);
-    hipLaunchKernelGGL(k_compact, grid, dim3(256), 0, st, ptrs, pos_out, new_len, p.Hkv, N, Nout, row_bytes);
+    ASAP_LAUNCH(tm, "k_compact", k_compact, grid, dim3(256), 0, st, ptrs, pos_out, new_len, p.Hkv, N, Nout, row_bytes);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -24,22 +24,51 @@ ScoreWorkspace score_workspace(const asap_params& p);
 
 struct Strides3 { int64_t b, h, r; };
 
+// Optional per-kernel timing: when a Timer is passed, every kernel launch is bracketed by two HIP
+// events recorded on the launch stream.  Events come from a fixed pool; when it is used up further
+// launches go untimed.
+struct Timer {
+  static constexpr int kMaxRecords = 8192;
+  struct Record { const char* name; hipEvent_t start, stop; };
+  Record rec[kMaxRecords];
+  int n_created = 0;
+  int n_used = 0;
+  Record* begin(const char* name, hipStream_t st) {
+    if (n_used >= n_created) return nullptr;
+    Record* r = &rec[n_used++];
+    r->name = name;
+    (void)hipEventRecord(r->start, st);
+    return r;
+  }
+  static void end(Record* r, hipStream_t st) {
+    if (r) (void)hipEventRecord(r->stop, st);
+  }
+};
+
+// Launches `kern` and, if `tm` is set, times it under `name`.
+#define ASAP_LAUNCH(tm, name, kern, grid, block, lds, st, ...)                  \
+  do {                                                                          \
+    ::asap::Timer::Record* asap_rec_ = (tm) ? (tm)->begin(name, st) : nullptr;  \
+    hipLaunchKernelGGL(kern, grid, block, lds, st, __VA_ARGS__);                \
+    ::asap::Timer::end(asap_rec_, st);                                          \
+  } while (0)
+
 hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
                         const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
-                        float* s_raw, float* s_hat, float* score, char* ws, hipStream_t st);
+                        float* s_raw, float* s_hat, float* score, char* ws, hipStream_t st, Timer* tm);
 
 hipError_t launch_select(const asap_params& p, const float* score, int32_t* kept, int32_t* pruned,
-                         hipStream_t st);
+                         hipStream_t st, Timer* tm);
 
 hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
                         const float* s_hat, const int32_t* text_len, const int32_t* kept,
                         const int32_t* pruned, void* out_hidden, int32_t* pos_out, int32_t* new_len,
                         int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx,
-                        hipStream_t st);
+                        hipStream_t st, Timer* tm);
 
 hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* const* k_src,
                              const void* const* v_src, void* const* k_dst, void* const* v_dst,
-                             const int32_t* pos_out, const int32_t* new_len, hipStream_t st);
+                             const int32_t* pos_out, const int32_t* new_len, hipStream_t st, Timer* tm);
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 

@@ -324,7 +324,7 @@ __global__ __launch_bounds__(256) void k_merge(const T* __restrict__ hidden, int
 // ------------------------------------------------------------------------------------------
 template <typename T, int NT>
 static hipError_t launch_sim(const asap_params& p, const T* xv, int64_t sb, int64_t sr, const int32_t* pruned,
-                             const int32_t* kept, int32_t* assign, float* best_sim, hipStream_t st) {
+                             const int32_t* kept, int32_t* assign, float* best_sim, hipStream_t st, Timer* tm) {
   constexpr int BN = 64 * NT, ROWS = SIM_BM + BN;
   const size_t lds = 2 * (size_t)ROWS * SIM_LDSROW + sizeof(float) * ROWS + 4 * sizeof(float) * SIM_BM;
   auto kern = k_sim<T, NT>;
@@ -334,8 +334,8 @@ static hipError_t launch_sim(const asap_params& p, const T* xv, int64_t sb, int6
     if (e != hipSuccess) return e;
   }
   const int M = p.V - p.k;
-  hipLaunchKernelGGL(kern, dim3((M + SIM_BM - 1) / SIM_BM, p.B), dim3(256), lds, st, xv, sb, sr, p.D, pruned,
-                     kept, M, p.k, p.sim_threshold, assign, best_sim);
+  ASAP_LAUNCH(tm, "k_sim", kern, dim3((M + SIM_BM - 1) / SIM_BM, p.B), dim3(256), lds, st, xv, sb, sr, p.D, pruned,
+              kept, M, p.k, p.sim_threshold, assign, best_sim);
   return hipGetLastError();
 }
 
@@ -356,17 +356,17 @@ static hipError_t merge_typed(const asap_params& p, const void* hidden, int64_t 
                               const float* s_hat, const int32_t* text_len, const int32_t* kept,
                               const int32_t* pruned, void* out_hidden, int32_t* pos_out, int32_t* new_len,
                               int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx,
-                              hipStream_t st) {
+                              hipStream_t st, Timer* tm) {
   const T* h = static_cast<const T*>(hidden);
   hipError_t e = hipSuccess;
   if (p.V > p.k) {
     const T* xv = h + (int64_t)p.P * hsr;
     switch (pick_nt(p.k)) {
-      case 1: e = launch_sim<T, 1>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st); break;
-      case 2: e = launch_sim<T, 2>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st); break;
-      case 3: e = launch_sim<T, 3>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st); break;
-      case 4: e = launch_sim<T, 4>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st); break;
-      default: e = launch_sim<T, 5>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st); break;
+      case 1: e = launch_sim<T, 1>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm); break;
+      case 2: e = launch_sim<T, 2>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm); break;
+      case 3: e = launch_sim<T, 3>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm); break;
+      case 4: e = launch_sim<T, 4>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm); break;
+      default: e = launch_sim<T, 5>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm); break;
     }
     if (e != hipSuccess) return e;
   }
@@ -375,9 +375,9 @@ static hipError_t merge_typed(const asap_params& p, const void* hidden, int64_t 
   const int cpt = (nchunks + 255) / 256;
   dim3 grid(p.P + p.k + p.Tmax, p.B);
 #define ASAP_MERGE(CPT)                                                                                    \
-  hipLaunchKernelGGL((k_merge<T, CPT>), grid, dim3(256), 0, st, h, hsb, hsr, p.D, p.P, p.V, p.k, p.Tmax,   \
-                     p.merge_weight, s_hat, text_len, kept, pruned, assign, static_cast<T*>(out_hidden),   \
-                     pos_out, new_len, wsum, final_idx)
+  ASAP_LAUNCH(tm, "k_merge", (k_merge<T, CPT>), grid, dim3(256), 0, st, h, hsb, hsr, p.D, p.P, p.V, p.k,   \
+              p.Tmax, p.merge_weight, s_hat, text_len, kept, pruned, assign, static_cast<T*>(out_hidden),  \
+              pos_out, new_len, wsum, final_idx)
   if (cpt <= 1) ASAP_MERGE(1);
   else if (cpt <= 2) ASAP_MERGE(2);
   else if (cpt <= 4) ASAP_MERGE(4);
@@ -391,12 +391,12 @@ hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, i
                         const float* s_hat, const int32_t* text_len, const int32_t* kept,
                         const int32_t* pruned, void* out_hidden, int32_t* pos_out, int32_t* new_len,
                         int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx,
-                        hipStream_t st) {
+                        hipStream_t st, Timer* tm) {
   if (p.h_dtype == ASAP_BF16)
     return merge_typed<bf16_t>(p, hidden, hsb, hsr, s_hat, text_len, kept, pruned, out_hidden, pos_out,
-                               new_len, assign, best_sim, wsum, final_idx, st);
+                               new_len, assign, best_sim, wsum, final_idx, st, tm);
   return merge_typed<float>(p, hidden, hsb, hsr, s_hat, text_len, kept, pruned, out_hidden, pos_out, new_len,
-                            assign, best_sim, wsum, final_idx, st);
+                            assign, best_sim, wsum, final_idx, st, tm);
 }
 
 }  // namespace asap

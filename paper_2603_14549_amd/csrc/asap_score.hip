@@ -375,7 +375,7 @@ ScoreWorkspace score_workspace(const asap_params& p) {
 template <typename T, int RB, int CH>
 static hipError_t launch_text_attn(const asap_params& p, const void* q_txt, Strides3 qt, const void* k_vis,
                                    Strides3 kv, const float* lam, const int32_t* text_len,
-                                   const float* lse_extra, float* upart, hipStream_t st) {
+                                   const float* lse_extra, float* upart, hipStream_t st, Timer* tm) {
   constexpr int NR = RB * 32;
   size_t lds = (size_t)NR * (CH * 32 + 16) + sizeof(float) * (10 * NR);
   auto kern = k_text_attn<T, RB, CH>;
@@ -386,21 +386,20 @@ static hipError_t launch_text_attn(const asap_params& p, const void* q_txt, Stri
   }
   const double sc = 1.4426950408889634 / sqrt((double)p.d);
   const float hi = (float)sc, lo = (float)(sc - (double)hi);
-  hipLaunchKernelGGL(kern, dim3(p.H, p.B), dim3(256), lds, st, static_cast<const T*>(q_txt), qt,
-                     static_cast<const T*>(k_vis), kv, lam, text_len, lse_extra, upart, p.H, p.Hkv, p.V,
-                     p.Tmax, hi, lo);
+  ASAP_LAUNCH(tm, "k_text_attn", kern, dim3(p.H, p.B), dim3(256), lds, st, static_cast<const T*>(q_txt), qt,
+              static_cast<const T*>(k_vis), kv, lam, text_len, lse_extra, upart, p.H, p.Hkv, p.V, p.Tmax, hi, lo);
   return hipGetLastError();
 }
 
 template <typename T, int CH>
 static hipError_t dispatch_rb(const asap_params& p, const void* q_txt, Strides3 qt, const void* k_vis,
                               Strides3 kv, const float* lam, const int32_t* text_len, const float* lse_extra,
-                              float* upart, hipStream_t st) {
+                              float* upart, hipStream_t st, Timer* tm) {
   switch ((p.Tmax + 31) / 32) {
-    case 1: return launch_text_attn<T, 1, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st);
-    case 2: return launch_text_attn<T, 2, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st);
-    case 3: return launch_text_attn<T, 3, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st);
-    case 4: return launch_text_attn<T, 4, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st);
+    case 1: return launch_text_attn<T, 1, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
+    case 2: return launch_text_attn<T, 2, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
+    case 3: return launch_text_attn<T, 3, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
+    case 4: return launch_text_attn<T, 4, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
   }
   return hipErrorInvalidValue;
 }
@@ -409,7 +408,7 @@ template <typename T>
 static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt,
                               Strides3 qt, const void* k_vis, Strides3 kv, const int32_t* text_len,
                               const float* lse_extra, float* s_raw, float* s_hat, float* score, char* ws,
-                              hipStream_t st) {
+                              hipStream_t st, Timer* tm) {
   const ScoreWorkspace w = score_workspace(p);
   double* qpart = reinterpret_cast<double*>(ws + w.off_qpart);
   double* qbar = reinterpret_cast<double*>(ws + w.off_qbar);
@@ -419,43 +418,43 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   float* upart = reinterpret_cast<float*>(ws + w.off_upart);
   const int mask_on = p.mask_mode == ASAP_MASK_KEYBIAS;
 
-  hipLaunchKernelGGL(k_qsum<T>, dim3(w.q_chunks, p.H, p.B), dim3(256), 0, st, static_cast<const T*>(q_vis), qv,
-                     p.V, p.d, w.q_rows, qpart);
-  hipLaunchKernelGGL(k_qbar, dim3(p.Hkv, p.B), dim3(p.d), 0, st, qpart, qbar, p.H, p.Hkv, w.q_chunks, p.d);
+  ASAP_LAUNCH(tm, "k_qsum", k_qsum<T>, dim3(w.q_chunks, p.H, p.B), dim3(256), 0, st, static_cast<const T*>(q_vis),
+              qv, p.V, p.d, w.q_rows, qpart);
+  ASAP_LAUNCH(tm, "k_qbar", k_qbar, dim3(p.Hkv, p.B), dim3(p.d), 0, st, qpart, qbar, p.H, p.Hkv, w.q_chunks, p.d);
   const double scale = 1.0 / ((double)p.H * sqrt((double)p.d));
-  hipLaunchKernelGGL(k_mass<T>, dim3((p.V + 31) / 32, p.B), dim3(256), sizeof(double) * p.Hkv * p.d, st,
-                     static_cast<const T*>(k_vis), kv, qbar, p.Hkv, p.V, p.d, scale, s64, s_raw);
-  hipLaunchKernelGGL(k_salience, dim3(p.B), dim3(1024), 0, st, s64, p.V, (double)p.lambda_max, (double)p.eps,
-                     mask_on, mm, s_hat, lam);
+  ASAP_LAUNCH(tm, "k_mass", k_mass<T>, dim3((p.V + 31) / 32, p.B), dim3(256), sizeof(double) * p.Hkv * p.d, st,
+              static_cast<const T*>(k_vis), kv, qbar, p.Hkv, p.V, p.d, scale, s64, s_raw);
+  ASAP_LAUNCH(tm, "k_salience", k_salience, dim3(p.B), dim3(1024), 0, st, s64, p.V, (double)p.lambda_max,
+              (double)p.eps, mask_on, mm, s_hat, lam);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   constexpr int E = elem<T>::per16;
   const int ch = p.d / E / 2;   // 16-byte chunks per half row
   if (ch == 4) {
-    if constexpr (E == 8) e = dispatch_rb<T, 4>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st);
+    if constexpr (E == 8) e = dispatch_rb<T, 4>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
     else e = hipErrorInvalidValue;
   } else if (ch == 8) {
-    e = dispatch_rb<T, 8>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st);
+    e = dispatch_rb<T, 8>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
   } else if (ch == 16) {
-    if constexpr (E == 4) e = dispatch_rb<T, 16>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st);
+    if constexpr (E == 4) e = dispatch_rb<T, 16>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
     else e = hipErrorInvalidValue;
   } else {
     e = hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_score, dim3((p.V + 255) / 256, p.B), dim3(256), 0, st, upart, s64, mm, text_len, p.H,
-                     p.V, (double)p.lambda_max, (double)p.eps, mask_on, score);
+  ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 255) / 256, p.B), dim3(256), 0, st, upart, s64, mm, text_len,
+              p.H, p.V, (double)p.lambda_max, (double)p.eps, mask_on, score);
   return hipGetLastError();
 }
 
 hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
                         const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
-                        float* s_raw, float* s_hat, float* score, char* ws, hipStream_t st) {
+                        float* s_raw, float* s_hat, float* score, char* ws, hipStream_t st, Timer* tm) {
   if (p.qk_dtype == ASAP_BF16)
     return score_typed<bf16_t>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                               ws, st);
+                               ws, st, tm);
   return score_typed<float>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score, ws,
-                            st);
+                            st, tm);
 }
 
 }  // namespace asap

@@ -124,8 +124,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
 }
 
 hipError_t launch_select(const asap_params& p, const float* score, int32_t* kept, int32_t* pruned,
-                         hipStream_t st) {
-  hipLaunchKernelGGL(k_select, dim3(p.B), dim3(SEL_THREADS), 0, st, score, p.V, p.k, kept, pruned);
+                         hipStream_t st, Timer* tm) {
+  ASAP_LAUNCH(tm, "k_select", k_select, dim3(p.B), dim3(SEL_THREADS), 0, st, score, p.V, p.k, kept, pruned);
   return hipGetLastError();
 }
 

@@ -28,10 +28,7 @@ TIE_REL = 1e-6
 ROUTE_GAP = 1e-5
 
 
-def to_device(arr: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
-    if dtype == "bf16":
-        return torch.from_numpy(arr.view(np.int16)).to(device).view(torch.bfloat16)
-    return torch.from_numpy(arr).to(device)
+to_device = binding.to_device
 
 
 def from_device(t: torch.Tensor) -> np.ndarray:
@@ -53,29 +50,7 @@ def raw_bits(t: torch.Tensor) -> np.ndarray:
     return t.numpy()
 
 
-class GpuStage:
-    """Uploads one batch and runs the four library calls."""
-
-    def __init__(self, inp: dict, ctx: Optional[binding.Context] = None, lse_extra: Optional[np.ndarray] = None,
-                 **param_overrides):
-        cfg = inp["cfg"]
-        self.cfg = cfg
-        self.ctx = ctx or binding.Context(0)
-        self.p = binding.params_from_config(cfg, **param_overrides)
-        self.q = to_device(inp["q"], cfg.qk_dtype)
-        self.k = to_device(inp["k"], cfg.qk_dtype)
-        self.hidden = to_device(inp["hidden"], cfg.h_dtype)
-        self.text_len = torch.from_numpy(inp["text_len"].astype(np.int32)).cuda()
-        self.k_cache = [to_device(a, cfg.kv_dtype) for a in inp.get("k_cache", [])]
-        self.v_cache = [to_device(a, cfg.kv_dtype) for a in inp.get("v_cache", [])]
-        self.lse_extra = None if lse_extra is None else torch.from_numpy(lse_extra.astype(np.float32)).cuda()
-        self.buf = binding.StageBuffers(self.p, len(self.k_cache))
-
-    def run(self):
-        binding.run_stage(self.ctx, self.p, self.q, self.k, self.hidden, self.text_len, self.k_cache,
-                          self.v_cache, self.buf, self.lse_extra)
-        torch.cuda.synchronize()
-        return self.buf
+GpuStage = binding.DeviceStage
 
 
 def oracle_image(inp: dict, b: int, lambda_max=1.0, eps=1e-6, mask_on=True, mu=1.0, threshold=None,
