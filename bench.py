@@ -54,6 +54,7 @@ def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
         "k_text_attn": k_vis + q_txt + 4 * B * V + 4 * B * H * V,
         "k_score": 4 * B * H * V + 12 * B * V,
         "k_select": 12 * B * V,
+        "k_knorm": B * k * D * eh,
         "k_sim": vis_h + 8 * B * (V - k),
         "k_merge": vis_h + B * (P + T) * D * eh + out_rows * D * eh,
         "k_compact": 2 * 2 * n_layers * Hkv * out_rows * d * ek,
@@ -152,7 +153,7 @@ def main():
     kernels = {}
     for name, (ms, n) in timing.items():
         avg_us = 1e3 * ms / n
-        per_launch_bytes = alg["per_kernel"][name] * args.steps / n      # several launches per step share it
+        per_launch_bytes = alg["per_kernel"].get(name, 0) * args.steps / n      # several launches per step share it
         kernels[name] = {"avg_us": round(avg_us, 2), "launches_per_step": n / args.steps,
                          "alg_MB": round(per_launch_bytes / 1e6, 2),
                          "GBps": round(per_launch_bytes / (avg_us * 1e-6) / 1e9, 1)}
@@ -167,7 +168,7 @@ def main():
         roofline = {"kernel": dominant, "bound": "mfma", "achieved": flops / d_avg_s / 1e12, "peak": peak / 1e12,
                     "unit": "TFLOP/s", "frac": flops / d_avg_s / peak, "traffic": traffic}
     else:
-        nbytes = alg["per_kernel"][dominant] * args.steps / d_n
+        nbytes = alg["per_kernel"].get(dominant, 0) * args.steps / d_n
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": nbytes / d_avg_s / 1e9, "peak": HBM_PEAK / 1e9,
                     "unit": "GB/s", "frac": nbytes / d_avg_s / HBM_PEAK, "traffic": traffic}
     sim = timing.get("k_sim")

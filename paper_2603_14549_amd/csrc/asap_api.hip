@@ -122,8 +122,8 @@ asap_status asap_create(asap_ctx** out_ctx, int device) {
 static void drop_timer(asap_ctx* ctx) {
   if (!ctx->timer) return;
   for (int i = 0; i < ctx->timer->n_created; ++i) {
-    hipEventDestroy(ctx->timer->rec[i].start);
-    hipEventDestroy(ctx->timer->rec[i].stop);
+    (void)hipEventDestroy(ctx->timer->rec[i].start);
+    (void)hipEventDestroy(ctx->timer->rec[i].stop);
   }
   delete ctx->timer;
   ctx->timer = nullptr;
@@ -147,7 +147,7 @@ asap_status asap_timing_enable(asap_ctx* ctx, int32_t max_launches) {
     hipError_t e = hipEventCreate(&t->rec[i].start);
     if (e == hipSuccess) {
       e = hipEventCreate(&t->rec[i].stop);
-      if (e != hipSuccess) hipEventDestroy(t->rec[i].start);
+      if (e != hipSuccess) (void)hipEventDestroy(t->rec[i].start);
     }
     if (e != hipSuccess) {
       drop_timer(ctx);
@@ -201,7 +201,8 @@ asap_status asap_check_params(const asap_params* p, char* msg, size_t msg_len) {
 
 size_t asap_workspace_bytes(const asap_params* p) {
   if (check_params(p, nullptr, 0) != ASAP_OK) return 0;
-  return score_workspace(*p).total;
+  size_t a = score_workspace(*p).total, b = sim_workspace_bytes(*p);
+  return a > b ? a : b;
 }
 
 asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, const int64_t q_vis_stride[3],
@@ -247,8 +248,6 @@ asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, 
                        const int32_t* pruned_idx, void* out_hidden, int32_t* pos_out, int32_t* new_len,
                        int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx, void* workspace,
                        size_t workspace_bytes, void* stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   asap_status st = common_checks(ctx, p);
   if (st != ASAP_OK) return st;
   if (p->route != ASAP_ROUTE_ABSORB)
@@ -270,10 +269,11 @@ asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, 
     const char* b1 = b0 + (int64_t)p->B * (p->P + p->k + p->Tmax) * p->D * esz;
     if (a0 < b1 && b0 < a1) return fail(ctx, ASAP_EINVAL, "asap_merge: out_hidden overlaps hidden");
   }
+  if ((st = check_workspace(ctx, p, workspace, workspace_bytes)) != ASAP_OK) return st;
   return hip_result(ctx,
                     launch_merge(*p, hidden, hidden_stride[0], hidden_stride[1], s_hat, text_len, kept_idx,
                                  pruned_idx, out_hidden, pos_out, new_len, assign, best_sim, wsum, final_idx,
-                                 static_cast<hipStream_t>(stream), ctx->timer),
+                                 static_cast<char*>(workspace), static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_merge launch");
 }
 

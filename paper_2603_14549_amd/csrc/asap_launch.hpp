@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "asap.h"
 
 namespace asap {
@@ -63,8 +65,14 @@ hipError_t launch_select(const asap_params& p, const float* score, int32_t* kept
 hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
                         const float* s_hat, const int32_t* text_len, const int32_t* kept,
                         const int32_t* pruned, void* out_hidden, int32_t* pos_out, int32_t* new_len,
-                        int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx,
+                        int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx, char* ws,
                         hipStream_t st, Timer* tm);
+
+// cosine routing (asap_sim.hip); ws needs sim_workspace_bytes(p)
+size_t sim_workspace_bytes(const asap_params& p);
+hipError_t launch_similarity(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
+                             const int32_t* kept, const int32_t* pruned, int32_t* assign, float* best_sim,
+                             char* ws, hipStream_t st, Timer* tm);
 
 hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* const* k_src,
                              const void* const* v_src, void* const* k_dst, void* const* v_dst,
