@@ -12,13 +12,15 @@ namespace asap {
 
 // Carve-up of the caller's workspace for the score path.  All offsets 256-byte aligned.
 struct ScoreWorkspace {
-  int q_rows;        // visual query rows summed per partial block
+  int q_rows;        // visual query rows summed per k_qsum block
   int q_chunks;      // ceil(V / q_rows)
+  int attn_splits;   // key-range splits of the text-row sweeps
   size_t off_qpart;  // double [B,H,q_chunks,d]  partial sums of visual queries
   size_t off_qbar;   // double [B,Hkv,d]         summed visual queries per kv head
+  size_t off_qsplit; // bf16   [B,Hkv,4,d]       the same, split into four bf16 pieces per component
   size_t off_s64;    // double [B,V]             raw attention mass before rounding
-  size_t off_mm;     // double [B,2]             min, max of s per image
-  size_t off_lam;    // float  [B,V]             discount lambda'_j (1 when the mask is off)
+  size_t off_mm;     // uint64 [B,2]             order-preserving keys of min, max of s per image
+  size_t off_pstat;  // float  [B,H,splits,2,NR] per-split (max, sum) of every text row
   size_t off_upart;  // float  [B,H,V]           per-head column sums of normalised weights
   size_t total;
 };

@@ -2,100 +2,189 @@
 // softmax of Eq. 5 reduced to one selection score per visual token.
 //
 // Kernels, in launch order:
-//   k_qsum      column sums of the visual queries, per (image, head, row chunk), fp64
-//   k_qbar      fixed-order sum of those partials per kv head
-//   k_mass      s_j = sum_g qbar_g . k_{g,j} / (H sqrt d)        (Eq. 2 by linearity), fp64
-//   k_salience  min / max per image, s_hat (Eq. 3), lambda' (Eq. 4)
-//   k_text_attn per (image, head): text-query x visual-key logits on the matrix cores, two
-//               sweeps over the keys (row statistics, then normalised column sums)
-//   k_score     fixed-order head reduction, times lambda', mean over heads and text rows, fp64
+//   k_qsum        column sums of the visual queries per (image, head[, row chunk]); rows are added
+//                 eight at a time in fp32, the eights in fp64
+//   k_qsplit      fixed-order sum of those partials per kv head (fp64), also split into four bf16
+//                 pieces per component (32 significant bits) for the matrix-core form of k_mass
+//   k_mass        s_j = sum_g qbar_g . k_{g,j} / (H sqrt d)  (Eq. 2 by linearity) and the per-image
+//                 min / max of s through order-preserving integer atomics.  bf16 keys: the four
+//                 pieces of qbar are four query rows of an MFMA tile, products are exact, one head's
+//                 128 products are added in fp32 and everything above that in fp64.  f32 keys: fp64
+//                 FMAs on the vector ALUs.
+//   k_attn_stats  per (image, head, key split): key x text-query logits on the matrix cores (keys as
+//                 tile rows, so a lane owns one text row), online (max, sum) of lambda'_j 2^z per row
+//   k_attn_colsum the sweep again with queries as tile rows and the merged row statistics:
+//                 normalised column sums per key
+//   k_score       fixed-order head reduction, times lambda' (Eq. 4) in fp64, mean over heads and
+//                 text rows; also writes s_hat (Eq. 3)
+// Logits stay in accumulator units; the factor log2(e)/sqrt(d) is applied to differences from the
+// row maximum only, so its rounding error scales with the distance from the maximum.
 #include "asap_device.hpp"
 #include "asap_launch.hpp"
 
 namespace asap {
 
+// order-preserving map double <-> uint64 (for atomic min / max)
+__device__ __forceinline__ unsigned long long f64_key(double x) {
+  unsigned long long u = (unsigned long long)__double_as_longlong(x);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+__device__ __forceinline__ double f64_unkey(unsigned long long k) {
+  unsigned long long u = (k >> 63) ? (k & 0x7fffffffffffffffull) : ~k;
+  return __longlong_as_double((long long)u);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // ------------------------------------------------------------------------------------------
-// k_qsum: grid (q_chunks, H, B), 256 threads.  Rows are d elements = LPR 16-byte pieces; a
-// thread keeps the piece tid % LPR of rows tid / LPR, tid / LPR + RPI, ...
+// k_qsum: grid (chunks, H, B), 1024 threads.  A row is d elements = LPR 16-byte pieces; thread t
+// keeps piece t % LPR of rows t / LPR + RPI * i.  Block (0, 0, b) also resets the min / max keys.
 // ------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void k_qsum(const T* __restrict__ q, Strides3 sq, int V, int d, int R,
-                                               double* __restrict__ qpart) {
+__global__ __launch_bounds__(1024) void k_qsum(const T* __restrict__ q, Strides3 sq, int V, int d, int R,
+                                                double* __restrict__ qpart, unsigned long long* __restrict__ mmkey) {
   constexpr int E = elem<T>::per16;
-  const int LPR = d / E, RPI = 256 / LPR;
+  const int LPR = d / E, RPI = 1024 / LPR;
   const int tid = threadIdx.x, piece = tid % LPR, r0 = tid / LPR;
   const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (c == 0 && h == 0 && tid == 0) { mmkey[2 * b] = ~0ull; mmkey[2 * b + 1] = 0ull; }
   const int lo = c * R, hi = min(V, lo + R);
-  const T* base = q + b * sq.b + h * sq.h + piece * E;
+  const char* base = reinterpret_cast<const char*>(q + b * sq.b + h * sq.h + piece * E);
+  const int64_t rowb = sq.r * (int64_t)sizeof(T);
   double acc[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) acc[e] = 0.0;
-#pragma unroll 4
-  for (int row = lo + r0; row < hi; row += RPI) {
-    uint4 ch = ldg16(base + (int64_t)row * sq.r);
-    float f[E];
-    unpack16<T>(ch, f);
+  int row = lo + r0;
+  for (; row + 7 * RPI < hi; row += 8 * RPI) {       // eight rows in flight, summed in fp32
+    uint4 ch[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) ch[u] = ldg16(base + (int64_t)(row + u * RPI) * rowb);
+    float f[E], g[E];
+    unpack16<T>(ch[0], f);
+#pragma unroll
+    for (int u = 1; u < 8; ++u) {
+      unpack16<T>(ch[u], g);
+#pragma unroll
+      for (int e = 0; e < E; ++e) f[e] += g[e];
+    }
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[e] += (double)f[e];
   }
-  __shared__ double red[256 * 8];
+  for (; row < hi; row += RPI) {
+    float f[E];
+    unpack16<T>(ldg16(base + (int64_t)row * rowb), f);
 #pragma unroll
-  for (int e = 0; e < E; ++e) red[r0 * d + piece * E + e] = acc[e];
+    for (int e = 0; e < E; ++e) acc[e] += (double)f[e];
+  }
+  // fixed-order reduction: row groups inside a wave by butterfly, then the 16 waves through LDS
+  __shared__ double red[16 * 128];
+  const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    double a = acc[e];
+    for (int off = LPR; off < 64; off <<= 1) a += shfl_xor_f64(a, off);
+    if (lane < LPR) red[wave * d + piece * E + e] = a;
+  }
   __syncthreads();
   if (tid < d) {
     double s = 0.0;
-    for (int r = 0; r < RPI; ++r) s += red[r * d + tid];
+    for (int w = 0; w < 16; ++w) s += red[w * d + tid];
     qpart[(((int64_t)b * gridDim.y + h) * gridDim.x + c) * d + tid] = s;
   }
 }
 
-// k_qbar: grid (Hkv, B), d threads.  qbar[b,g,:] = sum over the heads of group g and chunks.
-__global__ void k_qbar(const double* __restrict__ qpart, double* __restrict__ qbar, int H, int Hkv,
-                       int nchunk, int d) {
+// k_qsplit: grid (Hkv, B), d threads.  qbar[b,g,:] = sum over the heads of group g and the chunks;
+// qsplit[b,g,p,:] (p = 0..3) = successive bf16 roundings of what is left of qbar.
+__global__ void k_qsplit(const double* __restrict__ qpart, double* __restrict__ qbar, uint16_t* __restrict__ qsplit,
+                         int H, int Hkv, int nchunk, int d) {
   const int g = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
   const int G = H / Hkv;
   double s = 0.0;
   for (int h = g * G; h < (g + 1) * G; ++h)
     for (int ch = 0; ch < nchunk; ++ch) s += qpart[(((int64_t)b * H + h) * nchunk + ch) * d + c];
   qbar[((int64_t)b * Hkv + g) * d + c] = s;
+  double rest = s;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    uint32_t bits = f32_to_bf16_bits((float)rest);
+    qsplit[(((int64_t)b * Hkv + g) * 4 + p) * d + c] = (uint16_t)bits;
+    rest -= (double)bf16_bits_to_f32(bits);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
-// k_mass: grid (ceil(V/32), B), 256 threads, dynamic LDS = Hkv*d doubles (qbar of the image).
+// k_mass (vector-ALU form, f32 keys): grid (ceil(V/32), B), 256 threads, dynamic LDS = Hkv*d doubles
+// (qbar of the image, stored so that lanes with consecutive pieces read consecutive 16 bytes).
 // ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void publish_minmax(unsigned long long kmin, unsigned long long kmax, bool active,
+                                               unsigned long long* blk_mm, unsigned long long* mmkey, int b) {
+  if (active) {
+    atomicMin(&blk_mm[0], kmin);
+    atomicMax(&blk_mm[1], kmax);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    atomicMin(&mmkey[2 * b], blk_mm[0]);
+    atomicMax(&mmkey[2 * b + 1], blk_mm[1]);
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_mass(const T* __restrict__ kv, Strides3 sk, const double* __restrict__ qbar,
-                                               int Hkv, int V, int d, double scale,
-                                               double* __restrict__ s64, float* __restrict__ s_raw) {
+                                               int Hkv, int V, int d, double scale, double* __restrict__ s64,
+                                               float* __restrict__ s_raw, unsigned long long* __restrict__ mmkey) {
   constexpr int E = elem<T>::per16;
   constexpr int JT = 32;
-  extern __shared__ double qb_s[];
+  extern __shared__ __align__(16) double qb_s[];
+  __shared__ unsigned long long blk_mm[2];
   const int LPR = d / E, RPI = 256 / LPR, NP = JT / RPI;   // NP passes of RPI rows
   const int tid = threadIdx.x, piece = tid % LPR, r0 = tid / LPR;
   const int b = blockIdx.y, j0 = blockIdx.x * JT;
-  for (int i = tid; i < Hkv * d; i += 256) qb_s[i] = qbar[(int64_t)b * Hkv * d + i];
+  // qb_s[g][e / 2][piece][e % 2]: element e of piece `piece`
+  for (int i = tid; i < Hkv * d; i += 256) {
+    int g = i / d, col = i % d, pc = col / E, e = col % E;
+    qb_s[g * d + (e >> 1) * (LPR * 2) + pc * 2 + (e & 1)] = qbar[(int64_t)b * Hkv * d + i];
+  }
+  if (tid == 0) { blk_mm[0] = ~0ull; blk_mm[1] = 0ull; }
   __syncthreads();
   double acc[4] = {0.0, 0.0, 0.0, 0.0};
-  const T* base = kv + b * sk.b + piece * E;
-#pragma unroll 2
-  for (int g = 0; g < Hkv; ++g) {
-    double qb[E];
+  const char* base = reinterpret_cast<const char*>(kv + b * sk.b + piece * E);
+  const int64_t rowb = sk.r * (int64_t)sizeof(T), headb = sk.h * (int64_t)sizeof(T);
+  int rows[4];
 #pragma unroll
-    for (int e = 0; e < E; ++e) qb[e] = qb_s[g * d + piece * E + e];
+  for (int p = 0; p < 4; ++p) rows[p] = min(j0 + p * RPI + r0, V - 1);
+  constexpr int GU = 4;                                // kv heads in flight
+  for (int g0 = 0; g0 < Hkv; g0 += GU) {
+    uint4 ch[GU][4];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      if (p < NP) {
-        int row = j0 + p * RPI + r0;
-        if (row < V) {
-          uint4 ch = ldg16(base + g * sk.h + (int64_t)row * sk.r);
-          float f[E];
-          unpack16<T>(ch, f);
+    for (int u = 0; u < GU; ++u)
 #pragma unroll
-          for (int e = 0; e < E; ++e) acc[p] = fma(qb[e], (double)f[e], acc[p]);
+      for (int p = 0; p < 4; ++p)
+        if (p < NP && g0 + u < Hkv) ch[u][p] = ldg16(base + (g0 + u) * headb + rows[p] * rowb);
+#pragma unroll
+    for (int u = 0; u < GU; ++u) {
+      if (g0 + u < Hkv) {
+        double qb[E];
+        const double* qs = qb_s + (g0 + u) * d + piece * 2;
+#pragma unroll
+        for (int e = 0; e < E; e += 2) {
+          double2 t2 = *reinterpret_cast<const double2*>(qs + (e >> 1) * (LPR * 2));
+          qb[e] = t2.x;
+          qb[e + 1] = t2.y;
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          if (p < NP) {
+            float f[E];
+            unpack16<T>(ch[u][p], f);
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[p] = fma(qb[e], (double)f[e], acc[p]);
+          }
         }
       }
     }
   }
+  unsigned long long kmin = ~0ull, kmax = 0ull;
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     if (p < NP) {
@@ -106,300 +195,437 @@ __global__ __launch_bounds__(256) void k_mass(const T* __restrict__ kv, Strides3
         double s = a * scale;
         s64[(int64_t)b * V + row] = s;
         s_raw[(int64_t)b * V + row] = (float)s;
+        unsigned long long key = f64_key(s);
+        kmin = key < kmin ? key : kmin;
+        kmax = key > kmax ? key : kmax;
       }
     }
   }
+  publish_minmax(kmin, kmax, piece == 0, blk_mm, mmkey, b);
 }
 
 // ------------------------------------------------------------------------------------------
-// k_salience: grid (B), 1024 threads.
+// k_mass_mfma (bf16 keys): grid (ceil(V/32), B), 256 threads = 4 waves.  A workgroup owns one
+// 32-key tile; wave w walks the kv heads g = w, w + 4, ...  The four bf16 pieces of qbar_g are rows
+// 0..3 of the MFMA A tile (rows 4..31 are zero), the keys are the B tile, so lane n (< 32) finds
+// the four partial dot products of key n in its first four accumulator registers.
+// CH = 16-byte chunks of a row per lane half (d = 16*CH).
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_salience(const double* __restrict__ s64, int V, double lambda_max,
-                                                    double eps, int mask_on, double* __restrict__ mm,
-                                                    float* __restrict__ s_hat, float* __restrict__ lam) {
-  __shared__ double smin[16], smax[16];
-  const int b = blockIdx.x, tid = threadIdx.x;
-  const double* s = s64 + (int64_t)b * V;
-  double lo = INFINITY, hi = -INFINITY;
-  for (int j = tid; j < V; j += 1024) {
-    double v = s[j];
-    lo = fmin(lo, v);
-    hi = fmax(hi, v);
-  }
-  for (int off = 32; off > 0; off >>= 1) {
-    lo = fmin(lo, shfl_xor_f64(lo, off));
-    hi = fmax(hi, shfl_xor_f64(hi, off));
-  }
-  if ((tid & 63) == 0) { smin[tid >> 6] = lo; smax[tid >> 6] = hi; }
-  __syncthreads();
-  lo = smin[0]; hi = smax[0];
-  for (int w = 1; w < 16; ++w) { lo = fmin(lo, smin[w]); hi = fmax(hi, smax[w]); }
-  if (tid == 0) { mm[2 * b] = lo; mm[2 * b + 1] = hi; }
-  const double inv = 1.0 / (hi - lo + eps);
-  for (int j = tid; j < V; j += 1024) {
-    double sh = (s[j] - lo) * inv;
-    s_hat[(int64_t)b * V + j] = (float)sh;
-    lam[(int64_t)b * V + j] = mask_on ? (float)fmax(lambda_max * sh, eps) : 1.0f;
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// k_text_attn<T, RB, CH>: grid (H, B), 256 threads = 4 waves.
-//   RB = 32-row blocks of text queries (Tmax <= 32*RB), CH = 16-byte chunks of a row per lane
-//   half (row bytes = 32*CH).  The text queries sit in LDS as MFMA A operands; every wave
-//   streams its own 32-key tiles straight from global memory as B operands: lane (n, hf) of
-//   a tile reads the half row [hf*16*CH, +16*CH) bytes of key n, the A side reads the same
-//   half of its query row, so a chunk pair covers the same contraction slice.
-// Sweep 1 keeps, per lane and query row, an online (max, sum) of lambda'_j 2^(z) over the
-// keys that lane saw; they are merged across lanes and waves into row max m_t and 1/den_t.
-// Sweep 2 recomputes the logits and adds 2^(z - m_t)/den_t over the valid rows into
-// upart[b,h,j] (lambda'_j is applied later in fp64).  Logits are kept in log2 units.
-// ------------------------------------------------------------------------------------------
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
 template <int CH>
 __device__ __forceinline__ void load_key_tile(uint4 (&kb)[CH], const char* krow) {
 #pragma unroll
   for (int c = 0; c < CH; ++c) kb[c] = ldg16(krow + c * 16);
 }
 
-template <typename T, int RB, int CH>
-__global__ __launch_bounds__(256) void k_text_attn(const T* __restrict__ qt, Strides3 sq, const T* __restrict__ kv,
-                                                    Strides3 sk, const float* __restrict__ lam,
-                                                    const int32_t* __restrict__ text_len,
-                                                    const float* __restrict__ lse_extra, float* __restrict__ upart,
-                                                    int H, int Hkv, int V, int Tmax, float scale_hi, float scale_lo) {
-  constexpr int ROWB = CH * 32;        // bytes of one query / key row
-  constexpr int LDSROW = ROWB + 16;    // padded LDS row
-  constexpr int NR = RB * 32;
-  constexpr float NEG = -1e30f;
-  extern __shared__ __align__(16) char lds[];
-  char* q_s = lds;                                              // [NR][LDSROW]
-  float* st_m = reinterpret_cast<float*>(lds + NR * LDSROW);    // [4][NR]
-  float* st_s = st_m + 4 * NR;                                  // [4][NR]
-  float* fin_m = st_s + 4 * NR;                                 // [NR]
-  float* fin_i = fin_m + NR;                                    // [NR]
-
+template <int CH>
+__global__ __launch_bounds__(256) void k_mass_mfma(const bf16_t* __restrict__ kv, Strides3 sk,
+                                                    const uint16_t* __restrict__ qsplit, int Hkv, int V,
+                                                    double scale, double* __restrict__ s64, float* __restrict__ s_raw,
+                                                    unsigned long long* __restrict__ mmkey) {
+  constexpr int D = CH * 16;
+  __shared__ double part[4][32];
+  __shared__ unsigned long long blk_mm[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hf = lane >> 5;
-  const int h = blockIdx.x, b = blockIdx.y;
-  const int g = (h * Hkv) / H;
-  const int len = text_len[b];
+  const int b = blockIdx.y, j = blockIdx.x * 32 + n;
+  if (tid == 0) { blk_mm[0] = ~0ull; blk_mm[1] = 0ull; }
+  const char* kbase = reinterpret_cast<const char*>(kv + b * sk.b) + (int64_t)min(j, V - 1) * sk.r * 2 + hf * (CH * 16);
+  const int64_t headb = sk.h * 2;
+  // lane (m, hf) with m < 4 supplies piece m of qbar_g, half hf of the components
+  const char* qbase = reinterpret_cast<const char*>(qsplit + ((int64_t)b * Hkv * 4 + (n & 3)) * D) + hf * (CH * 16);
+  const int64_t qheadb = (int64_t)4 * D * 2;
+  const bool has_q = n < 4;
+  uint4 qa[CH], qn[CH], kb[CH], kn[CH];
+#pragma unroll
+  for (int c = 0; c < CH; ++c) qa[c] = qn[c] = make_uint4(0, 0, 0, 0);
+  int g = wave;
+  if (g < Hkv) {
+    load_key_tile<CH>(kb, kbase + g * headb);
+    if (has_q) load_key_tile<CH>(qa, qbase + g * qheadb);
+  }
+  double sum = 0.0;
+  for (; g < Hkv; g += 4) {
+    const int gn = g + 4;
+    if (gn < Hkv) {
+      load_key_tile<CH>(kn, kbase + gn * headb);
+      if (has_q) load_key_tile<CH>(qn, qbase + gn * qheadb);
+    }
+    f32x16_t acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) mma32<bf16_t>(acc, qa[c], kb[c]);
+    sum += ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);   // rows 0..3 (lanes < 32)
+    if (gn < Hkv) {
+#pragma unroll
+      for (int c = 0; c < CH; ++c) { kb[c] = kn[c]; qa[c] = qn[c]; }
+    }
+  }
+  if (hf == 0) part[wave][n] = sum;
+  __syncthreads();
+  unsigned long long kmin = ~0ull, kmax = 0ull;
+  const bool writer = tid < 32 && j < V;
+  if (writer) {
+    double s = (((part[0][n] + part[1][n]) + part[2][n]) + part[3][n]) * scale;
+    s64[(int64_t)b * V + j] = s;
+    s_raw[(int64_t)b * V + j] = (float)s;
+    kmin = kmax = f64_key(s);
+  }
+  publish_minmax(kmin, kmax, writer, blk_mm, mmkey, b);
+}
 
-  // stage the text queries (rows >= Tmax are zero)
-  {
-    const char* qbase = reinterpret_cast<const char*>(qt + b * sq.b + h * sq.h);
+// ------------------------------------------------------------------------------------------
+// Text-row attention sweeps.  grid (S, H, B), 256 threads = 4 waves.
+//   RB = 32-row blocks of text queries (Tmax <= 32*RB); CH = 16-byte chunks of a row per lane half
+//   (row bytes = 32*CH); QREG: the queries stay in registers as MFMA operands (else in LDS).
+// Every wave streams its own 32-key tiles of the split's key range straight from global memory:
+// lane (n, hf) of a tile reads the half row [hf*16*CH, +16*CH) bytes of key n, the query side holds
+// the same half of its row, so a chunk pair covers the same contraction slice.
+// ------------------------------------------------------------------------------------------
+struct AttnArgs {
+  const void* qt; Strides3 sq;          // [B,H,Tmax,d]
+  const void* kv; Strides3 sk;          // [B,Hkv,V,d]
+  const double* s64;                    // [B,V]
+  const unsigned long long* mmkey;      // [B,2]
+  const int32_t* text_len;              // [B]
+  const float* lse_extra;               // [B,H,Tmax] or null
+  float* pstat;                         // [B,H,S,2,NR]   partial (max, sum) per text row
+  float* upart;                         // [B,H,V]
+  int H, Hkv, V, Tmax, S, tiles_per_split;
+  float c2;                             // log2(e) / sqrt(d): accumulator units -> log2 units
+  double lambda_max, eps;
+  int mask_on;
+};
+
+// Query operands: registers or LDS.
+template <typename T, int RB, int CH, bool QREG> struct QueryOps;
+template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, true> {
+  uint4 qa[RB][CH];
+  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char*) {
+    const int m = lane & 31, hf = lane >> 5;
+    const char* qbase = reinterpret_cast<const char*>(static_cast<const T*>(a.qt) + b * a.sq.b + h * a.sq.h) +
+                        hf * (CH * 16);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const int row = rb * 32 + m;
+#pragma unroll
+      for (int c = 0; c < CH; ++c)
+        qa[rb][c] = row < a.Tmax ? ldg16(qbase + (int64_t)row * a.sq.r * sizeof(T) + c * 16) : make_uint4(0, 0, 0, 0);
+    }
+  }
+  __device__ __forceinline__ uint4 get(int rb, int c) const { return qa[rb][c]; }
+  static constexpr size_t lds_bytes() { return 0; }
+};
+template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, false> {
+  static constexpr int ROWB = CH * 32, LDSROW = ROWB + 16;
+  const char* qa;
+  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char* lds) {
+    const char* qbase = reinterpret_cast<const char*>(static_cast<const T*>(a.qt) + b * a.sq.b + h * a.sq.h);
     constexpr int PPR = ROWB / 16;
-    for (int i = tid; i < NR * PPR; i += 256) {
+    for (int i = threadIdx.x; i < RB * 32 * PPR; i += 256) {
       int row = i / PPR, pc = i % PPR;
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (row < Tmax) v = ldg16(qbase + (int64_t)row * sq.r * sizeof(T) + pc * 16);
-      *reinterpret_cast<uint4*>(q_s + row * LDSROW + pc * 16) = v;
+      if (row < a.Tmax) v = ldg16(qbase + (int64_t)row * a.sq.r * sizeof(T) + pc * 16);
+      *reinterpret_cast<uint4*>(lds + row * LDSROW + pc * 16) = v;
     }
+    __syncthreads();
+    qa = lds + (lane & 31) * LDSROW + (lane >> 5) * (CH * 16);
   }
-  __syncthreads();
+  __device__ __forceinline__ uint4 get(int rb, int c) const {
+    return *reinterpret_cast<const uint4*>(qa + rb * 32 * LDSROW + c * 16);
+  }
+  static constexpr size_t lds_bytes() { return (size_t)RB * 32 * LDSROW; }
+};
 
-  const char* kbase = reinterpret_cast<const char*>(kv + b * sk.b + g * sk.h) + hf * (CH * 16);
-  const int64_t krow_bytes = sk.r * (int64_t)sizeof(T);
-  const float* lam_b = lam + (int64_t)b * V;
-  const int ntiles = (V + 31) >> 5;
-  const char* qa = q_s + n * LDSROW + hf * (CH * 16);
+__device__ __forceinline__ float discount(const AttnArgs& a, int b, int j, double lo, double inv) {
+  if (!a.mask_on) return 1.0f;
+  return (float)fmax(a.lambda_max * ((a.s64[(int64_t)b * a.V + j] - lo) * inv), a.eps);
+}
 
-  float m_run[RB][16], s_run[RB][16];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) { m_run[rb][v] = NEG; s_run[rb][v] = 0.0f; }
+// merge of two (max, sum) pairs kept in accumulator units with scale c2
+__device__ __forceinline__ void merge_stat(float& m, float& s, float m2, float s2, float c2) {
+  float M = fmaxf(m, m2);
+  s = s * fast_exp2((m - M) * c2) + s2 * fast_exp2((m2 - M) * c2);
+  m = M;
+}
 
-  // ---------------- sweep 1: row statistics ----------------
-  {
-    uint4 kb[CH], kn[CH];
-    int tile = wave;
-    if (tile < ntiles) load_key_tile<CH>(kb, kbase + (int64_t)min(tile * 32 + n, V - 1) * krow_bytes);
-    for (; tile < ntiles; tile += 4) {
-      const int j = tile * 32 + n;
-      const int tnext = tile + 4;
-      if (tnext < ntiles) load_key_tile<CH>(kn, kbase + (int64_t)min(tnext * 32 + n, V - 1) * krow_bytes);
-      const bool valid = j < V;
-      const float lj = valid ? lam_b[j] : 0.0f;
-      f32x16_t acc[RB];
+// Keys are the tile rows here: lane (n, hf) owns text row rb*32 + n and finds, in accumulator
+// register v, its logit against key 8*(v/4) + 4*hf + v%4 of the tile.
+template <typename T, int RB, int CH, bool QREG>
+__global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_stats(AttnArgs a) {
+  constexpr int NR = RB * 32;
+  constexpr bool PREF = CH * RB <= 32;     // next key tile prefetched into a second register set
+  constexpr float NEG = -1e30f;
+  extern __shared__ __align__(16) char lds[];
+  using Q = QueryOps<T, RB, CH, QREG>;
+  float* st_m = reinterpret_cast<float*>(lds + Q::lds_bytes());   // [4][NR]
+  float* st_s = st_m + 4 * NR;                                     // [4][NR]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 31, hf = lane >> 5;
+  const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int g = (h * a.Hkv) / a.H;
+  Q q;
+  q.init(a, b, h, lane, lds);
+  const double mlo = f64_unkey(a.mmkey[2 * b]), mhi = f64_unkey(a.mmkey[2 * b + 1]);
+  const double minv = 1.0 / (mhi - mlo + a.eps);
+  const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.kv) + b * a.sk.b + g * a.sk.h) +
+                      hf * (CH * 16);
+  const int64_t krow_bytes = a.sk.r * (int64_t)sizeof(T);
+  const int ntiles = (a.V + 31) >> 5;
+  const int t_end = min(ntiles, (sp + 1) * a.tiles_per_split);
+  const float c2 = a.c2;
+
+  float m_run[RB], s_run[RB];
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
+  for (int rb = 0; rb < RB; ++rb) { m_run[rb] = NEG; s_run[rb] = 0.0f; }
+
+  uint4 kb[CH], kn[CH];
+  int tile = sp * a.tiles_per_split + wave;
+  if (tile < t_end) load_key_tile<CH>(kb, kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
+  for (; tile < t_end; tile += 4) {
+    const int j = tile * 32 + n;
+    const int tnext = tile + 4;
+    if (PREF && tnext < t_end) load_key_tile<CH>(kn, kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+    // discount of key n of the tile, then handed to the lanes in accumulator order
+    const float lj = j < a.V ? discount(a, b, j, mlo, minv) : 0.0f;
+    float lam[16];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[rb][v] = 0.0f;
+    for (int v = 0; v < 16; ++v) lam[v] = __shfl(lj, 8 * (v >> 2) + 4 * hf + (v & 3));
+    const bool ragged = tile * 32 + 32 > a.V;
 #pragma unroll
-        for (int c = 0; c < CH; ++c) {
-          uint4 a = *reinterpret_cast<const uint4*>(qa + rb * 32 * LDSROW + c * 16);
-          mma32<T>(acc[rb], a, kb[c]);
-        }
+    for (int rb = 0; rb < RB; ++rb) {
+      f32x16_t acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) mma32<T>(acc, kb[c], q.get(rb, c));
+      if (ragged) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (tile * 32 + 8 * (v >> 2) + 4 * hf + (v & 3) >= a.V) acc[v] = NEG;
       }
+      float mx = acc[0];
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
+      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, acc[v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));                  // both halves of the row's 32 keys
+      const float m_new = fmaxf(m_run[rb], mx);
+      float s = s_run[rb] * fast_exp2((m_run[rb] - m_new) * c2);
+      const float off = -m_new * c2;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float z = fmaf(acc[rb][v], scale_lo, acc[rb][v] * scale_hi);
-          z = valid ? z : NEG;
-          float dl = z - m_run[rb][v];
-          float e = fast_exp2(-fabsf(dl));
-          bool gt = dl > 0.0f;
-          s_run[rb][v] = fmaf(gt ? s_run[rb][v] : lj, e, gt ? lj : s_run[rb][v]);
-          m_run[rb][v] = fmaxf(m_run[rb][v], z);
-        }
-      if (tnext < ntiles) {
+      for (int v = 0; v < 16; ++v) s = fmaf(lam[v], fast_exp2(fmaf(acc[v], c2, off)), s);
+      s_run[rb] = s;
+      m_run[rb] = m_new;
+    }
+    if (tnext < t_end) {
+      if (PREF) {
 #pragma unroll
         for (int c = 0; c < CH; ++c) kb[c] = kn[c];
+      } else {
+        load_key_tile<CH>(kb, kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
       }
     }
   }
-  // merge the 32 lanes of a half (they hold the same rows, different keys)
+  // the two halves of a wave share the row maximum: their sums just add; then the 4 waves
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      float m = m_run[rb][v], s = s_run[rb][v];
-#pragma unroll
-      for (int off = 1; off < 32; off <<= 1) {
-        float m2 = __shfl_xor(m, off), s2 = __shfl_xor(s, off);
-        float M = fmaxf(m, m2);
-        s = s * fast_exp2(m - M) + s2 * fast_exp2(m2 - M);
-        m = M;
-      }
-      if (n == 0) {
-        int row = rb * 32 + mma32_row(v, lane);
-        st_m[wave * NR + row] = m;
-        st_s[wave * NR + row] = s;
-      }
+  for (int rb = 0; rb < RB; ++rb) {
+    float s = s_run[rb] + __shfl_xor(s_run[rb], 32);
+    if (hf == 0) {
+      st_m[wave * NR + rb * 32 + n] = m_run[rb];
+      st_s[wave * NR + rb * 32 + n] = s;
     }
+  }
   __syncthreads();
   if (tid < NR) {
     float m = st_m[tid], s = st_s[tid];
-    for (int w = 1; w < 4; ++w) {
-      float m2 = st_m[w * NR + tid], s2 = st_s[w * NR + tid];
-      float M = fmaxf(m, m2);
-      s = s * fast_exp2(m - M) + s2 * fast_exp2(m2 - M);
-      m = M;
-    }
-    if (lse_extra != nullptr && tid < Tmax) {
-      float l2 = lse_extra[((int64_t)b * H + h) * Tmax + tid] * 1.4426950408889634f;
-      float M = fmaxf(m, l2);
-      s = s * fast_exp2(m - M) + fast_exp2(l2 - M);
-      m = M;
+    for (int w = 1; w < 4; ++w) merge_stat(m, s, st_m[w * NR + tid], st_s[w * NR + tid], c2);
+    float* out = a.pstat + ((((int64_t)b * a.H + h) * a.S + sp) * 2) * NR;
+    out[tid] = m;
+    out[NR + tid] = s;
+  }
+}
+
+// Queries are the tile rows here: lane (n, hf) owns key n of the tile and finds, in accumulator
+// register v of row block rb, its logit against text row rb*32 + 8*(v/4) + 4*hf + v%4.
+template <typename T, int RB, int CH, bool QREG>
+__global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_colsum(AttnArgs a) {
+  constexpr int NR = RB * 32;
+  constexpr bool PREF = CH * RB <= 32;
+  extern __shared__ __align__(16) char lds[];
+  using Q = QueryOps<T, RB, CH, QREG>;
+  float* fin_o = reinterpret_cast<float*>(lds + Q::lds_bytes());   // [NR]  -max * c2
+  float* fin_i = fin_o + NR;                                       // [NR]  1 / denominator
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 31, hf = lane >> 5;
+  const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int g = (h * a.Hkv) / a.H;
+  const int len = a.text_len[b];
+  const float c2 = a.c2;
+  // merged row statistics of this (image, head): fixed order over the splits
+  if (tid < NR) {
+    const float* ps = a.pstat + (((int64_t)b * a.H + h) * a.S * 2) * NR;
+    float m = ps[tid], s = ps[NR + tid];
+    for (int w = 1; w < a.S; ++w) merge_stat(m, s, ps[(w * 2) * NR + tid], ps[(w * 2 + 1) * NR + tid], c2);
+    float m2 = m * c2;                                             // log2 units from here on
+    if (a.lse_extra != nullptr && tid < a.Tmax) {
+      float l2 = a.lse_extra[((int64_t)b * a.H + h) * a.Tmax + tid] * 1.4426950408889634f;
+      float M = fmaxf(m2, l2);
+      s = s * fast_exp2(m2 - M) + fast_exp2(l2 - M);
+      m2 = M;
     }
     const bool row_ok = tid < len;
-    fin_m[tid] = row_ok ? m : INFINITY;     // 2^(z - inf) = 0: padded rows add nothing
+    fin_o[tid] = row_ok ? -m2 : -INFINITY;   // 2^(z - inf) = 0: padded rows add nothing
     fin_i[tid] = row_ok ? 1.0f / s : 0.0f;
   }
+  Q q;
+  q.init(a, b, h, lane, lds);
   __syncthreads();
+  float off[RB][16], inv[RB][16];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       int row = rb * 32 + mma32_row(v, lane);
-      m_run[rb][v] = fin_m[row];
-      s_run[rb][v] = fin_i[row];
+      off[rb][v] = fin_o[row];
+      inv[rb][v] = fin_i[row];
     }
-
-  // ---------------- sweep 2: normalised column sums ----------------
-  {
-    float* out = upart + ((int64_t)b * H + h) * V;
-    uint4 kb[CH], kn[CH];
-    int tile = wave;
-    if (tile < ntiles) load_key_tile<CH>(kb, kbase + (int64_t)min(tile * 32 + n, V - 1) * krow_bytes);
-    for (; tile < ntiles; tile += 4) {
-      const int j = tile * 32 + n;
-      const int tnext = tile + 4;
-      if (tnext < ntiles) load_key_tile<CH>(kn, kbase + (int64_t)min(tnext * 32 + n, V - 1) * krow_bytes);
-      f32x16_t acc[RB];
-      float u = 0.0f;
+  const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.kv) + b * a.sk.b + g * a.sk.h) +
+                      hf * (CH * 16);
+  const int64_t krow_bytes = a.sk.r * (int64_t)sizeof(T);
+  const int ntiles = (a.V + 31) >> 5;
+  const int t_end = min(ntiles, (sp + 1) * a.tiles_per_split);
+  float* out = a.upart + ((int64_t)b * a.H + h) * a.V;
+  uint4 kb[CH], kn[CH];
+  int tile = sp * a.tiles_per_split + wave;
+  if (tile < t_end) load_key_tile<CH>(kb, kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
+  for (; tile < t_end; tile += 4) {
+    const int j = tile * 32 + n;
+    const int tnext = tile + 4;
+    if (PREF && tnext < t_end) load_key_tile<CH>(kn, kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+    float u = 0.0f;
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
+    for (int rb = 0; rb < RB; ++rb) {
+      f32x16_t acc;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[rb][v] = 0.0f;
+      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
-        for (int c = 0; c < CH; ++c) {
-          uint4 a = *reinterpret_cast<const uint4*>(qa + rb * 32 * LDSROW + c * 16);
-          mma32<T>(acc[rb], a, kb[c]);
-        }
+      for (int c = 0; c < CH; ++c) mma32<T>(acc, q.get(rb, c), kb[c]);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float z = fmaf(acc[rb][v], scale_lo, acc[rb][v] * scale_hi);
-          u = fmaf(fast_exp2(z - m_run[rb][v]), s_run[rb][v], u);
-        }
-      }
-      u += __shfl_xor(u, 32);
-      if (hf == 0 && j < V) out[j] = u;
-      if (tnext < ntiles) {
+      for (int v = 0; v < 16; ++v) u = fmaf(fast_exp2(fmaf(acc[v], c2, off[rb][v])), inv[rb][v], u);
+    }
+    u += __shfl_xor(u, 32);
+    if (hf == 0 && j < a.V) out[j] = u;
+    if (tnext < t_end) {
+      if (PREF) {
 #pragma unroll
         for (int c = 0; c < CH; ++c) kb[c] = kn[c];
+      } else {
+        load_key_tile<CH>(kb, kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
       }
     }
   }
 }
 
-// k_score: grid (ceil(V/256), B), 256 threads.
+// ------------------------------------------------------------------------------------------
+// k_score: grid (ceil(V/64), B), 256 threads: 64 keys x 4 head groups.
+// ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_score(const float* __restrict__ upart, const double* __restrict__ s64,
-                                                const double* __restrict__ mm, const int32_t* __restrict__ text_len,
-                                                int H, int V, double lambda_max, double eps, int mask_on,
-                                                float* __restrict__ score) {
-  const int b = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
-  if (j >= V) return;
+                                                const unsigned long long* __restrict__ mmkey,
+                                                const int32_t* __restrict__ text_len, int H, int V,
+                                                double lambda_max, double eps, int mask_on,
+                                                float* __restrict__ s_hat, float* __restrict__ score) {
+  __shared__ double part[4][64];
+  const int b = blockIdx.y, jl = threadIdx.x & 63, hq = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + jl;
   double u = 0.0;
-  for (int h = 0; h < H; ++h) u += (double)upart[((int64_t)b * H + h) * V + j];
-  double lam = 1.0;
-  if (mask_on) {
-    double lo = mm[2 * b], hi = mm[2 * b + 1];
-    lam = fmax(lambda_max * ((s64[(int64_t)b * V + j] - lo) / (hi - lo + eps)), eps);
+  if (j < V) {
+    const float* up = upart + (int64_t)b * H * V + j;
+    int h = hq;
+    for (; h + 12 < H; h += 16) {
+      float u0 = up[(int64_t)h * V], u1 = up[(int64_t)(h + 4) * V], u2 = up[(int64_t)(h + 8) * V],
+            u3 = up[(int64_t)(h + 12) * V];
+      u += (double)u0;
+      u += (double)u1;
+      u += (double)u2;
+      u += (double)u3;
+    }
+    for (; h < H; h += 4) u += (double)up[(int64_t)h * V];
   }
-  score[(int64_t)b * V + j] = (float)(lam * u / ((double)H * (double)text_len[b]));
+  part[hq][jl] = u;
+  __syncthreads();
+  if (hq == 0 && j < V) {
+    u = ((part[0][jl] + part[1][jl]) + part[2][jl]) + part[3][jl];
+    const double lo = f64_unkey(mmkey[2 * b]), hi = f64_unkey(mmkey[2 * b + 1]);
+    const double sh = (s64[(int64_t)b * V + j] - lo) * (1.0 / (hi - lo + eps));
+    const double lam = mask_on ? fmax(lambda_max * sh, eps) : 1.0;
+    s_hat[(int64_t)b * V + j] = (float)sh;
+    score[(int64_t)b * V + j] = (float)(lam * u / ((double)H * (double)text_len[b]));
+  }
 }
 
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+static int attn_splits(const asap_params& p) {
+  const int ntiles = (p.V + 31) / 32;
+  int s = (1024 + p.H * p.B - 1) / (p.H * p.B);
+  int smax = ntiles / 8;
+  if (s > smax) s = smax;
+  if (s > 16) s = 16;
+  if (s < 1) s = 1;
+  return s;
+}
+
 ScoreWorkspace score_workspace(const asap_params& p) {
   ScoreWorkspace w;
-  w.q_rows = 256;
-  if ((int64_t)p.B * p.H * ((p.V + 255) / 256) < 1024) w.q_rows = 64;
+  // rows per k_qsum block: whole image span unless that leaves the chip short of blocks
+  int chunks = (512 + p.B * p.H - 1) / (p.B * p.H);
+  if (chunks > (p.V + 255) / 256) chunks = (p.V + 255) / 256;
+  if (chunks < 1) chunks = 1;
+  w.q_rows = (p.V + chunks - 1) / chunks;
   w.q_chunks = (p.V + w.q_rows - 1) / w.q_rows;
+  w.attn_splits = attn_splits(p);
+  const int NR = ((p.Tmax + 31) / 32) * 32;
   size_t off = 0;
-  w.off_qpart = off; off = align256(off + sizeof(double) * p.B * p.H * w.q_chunks * p.d);
-  w.off_qbar = off;  off = align256(off + sizeof(double) * p.B * p.Hkv * p.d);
-  w.off_s64 = off;   off = align256(off + sizeof(double) * p.B * p.V);
-  w.off_mm = off;    off = align256(off + sizeof(double) * p.B * 2);
-  w.off_lam = off;   off = align256(off + sizeof(float) * p.B * p.V);
-  w.off_upart = off; off = align256(off + sizeof(float) * (size_t)p.B * p.H * p.V);
+  w.off_qpart = off;  off = align256(off + sizeof(double) * p.B * p.H * w.q_chunks * p.d);
+  w.off_qbar = off;   off = align256(off + sizeof(double) * p.B * p.Hkv * p.d);
+  w.off_qsplit = off; off = align256(off + sizeof(uint16_t) * p.B * p.Hkv * 4 * p.d);
+  w.off_s64 = off;    off = align256(off + sizeof(double) * p.B * p.V);
+  w.off_mm = off;     off = align256(off + sizeof(double) * p.B * 2);
+  w.off_pstat = off;  off = align256(off + sizeof(float) * (size_t)p.B * p.H * w.attn_splits * 2 * NR);
+  w.off_upart = off;  off = align256(off + sizeof(float) * (size_t)p.B * p.H * p.V);
   w.total = off;
   return w;
 }
 
-template <typename T, int RB, int CH>
-static hipError_t launch_text_attn(const asap_params& p, const void* q_txt, Strides3 qt, const void* k_vis,
-                                   Strides3 kv, const float* lam, const int32_t* text_len,
-                                   const float* lse_extra, float* upart, hipStream_t st, Timer* tm) {
+template <typename T, int RB, int CH, bool QREG>
+static hipError_t launch_attn(const asap_params& p, const AttnArgs& a, hipStream_t st, Timer* tm) {
   constexpr int NR = RB * 32;
-  size_t lds = (size_t)NR * (CH * 32 + 16) + sizeof(float) * (10 * NR);
-  auto kern = k_text_attn<T, RB, CH>;
+  using Q = QueryOps<T, RB, CH, QREG>;
+  const size_t lds = Q::lds_bytes() + sizeof(float) * 8 * NR;
+  auto k1 = k_attn_stats<T, RB, CH, QREG>;
+  auto k2 = k_attn_colsum<T, RB, CH, QREG>;
   if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds);
     if (e != hipSuccess) return e;
   }
-  const double sc = 1.4426950408889634 / sqrt((double)p.d);
-  const float hi = (float)sc, lo = (float)(sc - (double)hi);
-  ASAP_LAUNCH(tm, "k_text_attn", kern, dim3(p.H, p.B), dim3(256), lds, st, static_cast<const T*>(q_txt), qt,
-              static_cast<const T*>(k_vis), kv, lam, text_len, lse_extra, upart, p.H, p.Hkv, p.V, p.Tmax, hi, lo);
+  ASAP_LAUNCH(tm, "k_attn_stats", k1, dim3(a.S, p.H, p.B), dim3(256), lds, st, a);
+  ASAP_LAUNCH(tm, "k_attn_colsum", k2, dim3(a.S, p.H, p.B), dim3(256), lds, st, a);
   return hipGetLastError();
 }
 
 template <typename T, int CH>
-static hipError_t dispatch_rb(const asap_params& p, const void* q_txt, Strides3 qt, const void* k_vis,
-                              Strides3 kv, const float* lam, const int32_t* text_len, const float* lse_extra,
-                              float* upart, hipStream_t st, Timer* tm) {
+static hipError_t dispatch_rb(const asap_params& p, const AttnArgs& a, hipStream_t st, Timer* tm) {
+  // queries stay in registers while they need at most 64 VGPRs
+  constexpr bool R1 = CH * 4 <= 64, R2 = CH * 8 <= 64;
   switch ((p.Tmax + 31) / 32) {
-    case 1: return launch_text_attn<T, 1, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
-    case 2: return launch_text_attn<T, 2, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
-    case 3: return launch_text_attn<T, 3, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
-    case 4: return launch_text_attn<T, 4, CH>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
+    case 1: return launch_attn<T, 1, CH, R1>(p, a, st, tm);
+    case 2: return launch_attn<T, 2, CH, R2>(p, a, st, tm);
+    case 3: return launch_attn<T, 3, CH, false>(p, a, st, tm);
+    case 4: return launch_attn<T, 4, CH, false>(p, a, st, tm);
   }
   return hipErrorInvalidValue;
 }
@@ -412,38 +638,57 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   const ScoreWorkspace w = score_workspace(p);
   double* qpart = reinterpret_cast<double*>(ws + w.off_qpart);
   double* qbar = reinterpret_cast<double*>(ws + w.off_qbar);
+  uint16_t* qsplit = reinterpret_cast<uint16_t*>(ws + w.off_qsplit);
   double* s64 = reinterpret_cast<double*>(ws + w.off_s64);
-  double* mm = reinterpret_cast<double*>(ws + w.off_mm);
-  float* lam = reinterpret_cast<float*>(ws + w.off_lam);
+  unsigned long long* mmkey = reinterpret_cast<unsigned long long*>(ws + w.off_mm);
+  float* pstat = reinterpret_cast<float*>(ws + w.off_pstat);
   float* upart = reinterpret_cast<float*>(ws + w.off_upart);
   const int mask_on = p.mask_mode == ASAP_MASK_KEYBIAS;
-
-  ASAP_LAUNCH(tm, "k_qsum", k_qsum<T>, dim3(w.q_chunks, p.H, p.B), dim3(256), 0, st, static_cast<const T*>(q_vis),
-              qv, p.V, p.d, w.q_rows, qpart);
-  ASAP_LAUNCH(tm, "k_qbar", k_qbar, dim3(p.Hkv, p.B), dim3(p.d), 0, st, qpart, qbar, p.H, p.Hkv, w.q_chunks, p.d);
-  const double scale = 1.0 / ((double)p.H * sqrt((double)p.d));
-  ASAP_LAUNCH(tm, "k_mass", k_mass<T>, dim3((p.V + 31) / 32, p.B), dim3(256), sizeof(double) * p.Hkv * p.d, st,
-              static_cast<const T*>(k_vis), kv, qbar, p.Hkv, p.V, p.d, scale, s64, s_raw);
-  ASAP_LAUNCH(tm, "k_salience", k_salience, dim3(p.B), dim3(1024), 0, st, s64, p.V, (double)p.lambda_max,
-              (double)p.eps, mask_on, mm, s_hat, lam);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
   constexpr int E = elem<T>::per16;
   const int ch = p.d / E / 2;   // 16-byte chunks per half row
+  const int ktiles = (p.V + 31) / 32;
+
+  ASAP_LAUNCH(tm, "k_qsum", k_qsum<T>, dim3(w.q_chunks, p.H, p.B), dim3(1024), 0, st, static_cast<const T*>(q_vis),
+              qv, p.V, p.d, w.q_rows, qpart, mmkey);
+  ASAP_LAUNCH(tm, "k_qsplit", k_qsplit, dim3(p.Hkv, p.B), dim3(p.d), 0, st, qpart, qbar, qsplit, p.H, p.Hkv,
+              w.q_chunks, p.d);
+  const double scale = 1.0 / ((double)p.H * sqrt((double)p.d));
+  if constexpr (E == 8) {
+    const bf16_t* kp = static_cast<const bf16_t*>(k_vis);
+    if (ch == 8)
+      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<8>, dim3(ktiles, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
+                  s64, s_raw, mmkey);
+    else
+      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<4>, dim3(ktiles, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
+                  s64, s_raw, mmkey);
+  } else {
+    ASAP_LAUNCH(tm, "k_mass", k_mass<T>, dim3(ktiles, p.B), dim3(256), sizeof(double) * p.Hkv * p.d, st,
+                static_cast<const T*>(k_vis), kv, qbar, p.Hkv, p.V, p.d, scale, s64, s_raw, mmkey);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  AttnArgs a;
+  a.qt = q_txt; a.sq = qt; a.kv = k_vis; a.sk = kv; a.s64 = s64; a.mmkey = mmkey; a.text_len = text_len;
+  a.lse_extra = lse_extra; a.pstat = pstat; a.upart = upart;
+  a.H = p.H; a.Hkv = p.Hkv; a.V = p.V; a.Tmax = p.Tmax; a.S = w.attn_splits;
+  a.tiles_per_split = (ktiles + a.S - 1) / a.S;
+  a.c2 = (float)(1.4426950408889634 / sqrt((double)p.d));
+  a.lambda_max = (double)p.lambda_max; a.eps = (double)p.eps; a.mask_on = mask_on;
   if (ch == 4) {
-    if constexpr (E == 8) e = dispatch_rb<T, 4>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
+    if constexpr (E == 8) e = dispatch_rb<T, 4>(p, a, st, tm);
     else e = hipErrorInvalidValue;
   } else if (ch == 8) {
-    e = dispatch_rb<T, 8>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
+    e = dispatch_rb<T, 8>(p, a, st, tm);
   } else if (ch == 16) {
-    if constexpr (E == 4) e = dispatch_rb<T, 16>(p, q_txt, qt, k_vis, kv, lam, text_len, lse_extra, upart, st, tm);
+    if constexpr (E == 4) e = dispatch_rb<T, 16>(p, a, st, tm);
     else e = hipErrorInvalidValue;
   } else {
     e = hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;
-  ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 255) / 256, p.B), dim3(256), 0, st, upart, s64, mm, text_len,
-              p.H, p.V, (double)p.lambda_max, (double)p.eps, mask_on, score);
+  ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
+              p.H, p.V, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
   return hipGetLastError();
 }
 

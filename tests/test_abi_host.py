@@ -71,14 +71,15 @@ def test_k_equal_v_and_infinite_threshold_are_legal(lib):
 
 
 def test_workspace_size_formula(lib):
-    # partial query sums + summed queries + fp64 mass + min/max + discount + per-head column sums
+    # query sums + per-kv-head sums + fp64 mass + min/max keys + per-split row statistics
+    # + per-head column sums (C6: one query chunk, two key splits, 64 text rows)
     p = good()
     B, H, Hkv, d, V = p.B, p.H, p.Hkv, p.d, p.V
-    chunks = -(-V // 256)
     al = lambda x: (x + 255) // 256 * 256
-    want = (al(8 * B * H * chunks * d) + al(8 * B * Hkv * d) + al(8 * B * V) + al(16 * B) + al(4 * B * V)
-            + al(4 * B * H * V))
+    want = (al(8 * B * H * 1 * d) + al(8 * B * Hkv * d) + al(2 * B * Hkv * 4 * d) + al(8 * B * V) + al(16 * B)
+            + al(4 * B * H * 2 * 2 * 64) + al(4 * B * H * V))
     assert binding.asap_workspace_bytes(p) == want
+    assert want >= al(4 * B * p.k)          # also covers the kept-row norms of asap_merge
 
 
 def test_struct_layout_matches_header(lib):
