@@ -36,13 +36,27 @@ __device__ __forceinline__ double f64_unkey(unsigned long long k) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// successive bf16 roundings of what is left of x: x = p0 + p1 + p2 + p3 to 32 significant bits
+__device__ __forceinline__ void split_bf16x4(double x, uint16_t* out, int stride) {
+  double rest = x;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    uint32_t bits = f32_to_bf16_bits((float)rest);
+    out[p * stride] = (uint16_t)bits;
+    rest -= (double)bf16_bits_to_f32(bits);
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // k_qsum: grid (chunks, H, B), 1024 threads.  A row is d elements = LPR 16-byte pieces; thread t
 // keeps piece t % LPR of rows t / LPR + RPI * i.  Block (0, 0, b) also resets the min / max keys.
+// With one chunk and one query head per kv head the block's sums are final (`direct`): it writes
+// qbar and its bf16 split itself and k_qsplit is not needed.
 // ------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(1024) void k_qsum(const T* __restrict__ q, Strides3 sq, int V, int d, int R,
-                                                double* __restrict__ qpart, unsigned long long* __restrict__ mmkey) {
+                                                double* __restrict__ qpart, unsigned long long* __restrict__ mmkey,
+                                                double* __restrict__ qbar, uint16_t* __restrict__ qsplit, int direct) {
   constexpr int E = elem<T>::per16;
   const int LPR = d / E, RPI = 1024 / LPR;
   const int tid = threadIdx.x, piece = tid % LPR, r0 = tid / LPR;
@@ -90,6 +104,10 @@ __global__ __launch_bounds__(1024) void k_qsum(const T* __restrict__ q, Strides3
     double s = 0.0;
     for (int w = 0; w < 16; ++w) s += red[w * d + tid];
     qpart[(((int64_t)b * gridDim.y + h) * gridDim.x + c) * d + tid] = s;
+    if (direct) {
+      qbar[((int64_t)b * gridDim.y + h) * d + tid] = s;
+      split_bf16x4(s, qsplit + ((int64_t)b * gridDim.y + h) * 4 * d + tid, d);
+    }
   }
 }
 
@@ -103,13 +121,7 @@ __global__ void k_qsplit(const double* __restrict__ qpart, double* __restrict__ 
   for (int h = g * G; h < (g + 1) * G; ++h)
     for (int ch = 0; ch < nchunk; ++ch) s += qpart[(((int64_t)b * H + h) * nchunk + ch) * d + c];
   qbar[((int64_t)b * Hkv + g) * d + c] = s;
-  double rest = s;
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    uint32_t bits = f32_to_bf16_bits((float)rest);
-    qsplit[(((int64_t)b * Hkv + g) * 4 + p) * d + c] = (uint16_t)bits;
-    rest -= (double)bf16_bits_to_f32(bits);
-  }
+  split_bf16x4(s, qsplit + ((int64_t)b * Hkv + g) * 4 * d + c, d);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -648,10 +660,12 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   const int ch = p.d / E / 2;   // 16-byte chunks per half row
   const int ktiles = (p.V + 31) / 32;
 
+  const int direct = (w.q_chunks == 1 && p.H == p.Hkv) ? 1 : 0;
   ASAP_LAUNCH(tm, "k_qsum", k_qsum<T>, dim3(w.q_chunks, p.H, p.B), dim3(1024), 0, st, static_cast<const T*>(q_vis),
-              qv, p.V, p.d, w.q_rows, qpart, mmkey);
-  ASAP_LAUNCH(tm, "k_qsplit", k_qsplit, dim3(p.Hkv, p.B), dim3(p.d), 0, st, qpart, qbar, qsplit, p.H, p.Hkv,
-              w.q_chunks, p.d);
+              qv, p.V, p.d, w.q_rows, qpart, mmkey, qbar, qsplit, direct);
+  if (!direct)
+    ASAP_LAUNCH(tm, "k_qsplit", k_qsplit, dim3(p.Hkv, p.B), dim3(p.d), 0, st, qpart, qbar, qsplit, p.H, p.Hkv,
+                w.q_chunks, p.d);
   const double scale = 1.0 / ((double)p.H * sqrt((double)p.d));
   if constexpr (E == 8) {
     const bf16_t* kp = static_cast<const bf16_t*>(k_vis);

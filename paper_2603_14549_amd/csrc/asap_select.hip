@@ -41,8 +41,7 @@ __device__ __forceinline__ int block_scan_excl(int x, int* wave_sums /*[17]*/, i
 
 __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict__ score, int V, int k,
                                                          int32_t* __restrict__ kept, int32_t* __restrict__ pruned) {
-  __shared__ int hist[256];
-  __shared__ int suffix[257];
+  __shared__ int hist[512];   // two 256-bin histograms used alternately
   __shared__ int wave_sums[17];
   __shared__ int sel_bin, sel_remaining;
   const int b = blockIdx.x, tid = threadIdx.x;
@@ -58,36 +57,45 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
 
   uint32_t prefix = 0, mask = 0;
   int remaining = k;
+  if (tid < 512) hist[tid] = 0;
+  __syncthreads();
   for (int pass = 3; pass >= 0; --pass) {
     const int shift = 8 * pass;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
+    int* hcur = hist + (pass & 1) * 256;
 #pragma unroll
     for (int e = 0; e < SEL_IPT; ++e) {
       int i = i0 + e;
-      if (e < ipt && i < V && (key[e] & mask) == prefix) atomicAdd(&hist[(key[e] >> shift) & 255u], 1);
+      if (e < ipt && i < V && (key[e] & mask) == prefix) atomicAdd(&hcur[(key[e] >> shift) & 255u], 1);
     }
     __syncthreads();
-    // suffix[d] = number of candidates whose digit is >= d
-    if (tid < 256) suffix[tid] = hist[tid];
-    if (tid == 256) suffix[256] = 0;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-      int v = 0;
-      if (tid < 256) v = suffix[tid] + ((tid + off < 256) ? suffix[tid + off] : 0);
-      __syncthreads();
-      if (tid < 256) suffix[tid] = v;
-      __syncthreads();
-    }
-    if (tid < 256 && suffix[tid] >= remaining && suffix[tid + 1] < remaining) {
-      sel_bin = tid;
-      sel_remaining = remaining - suffix[tid + 1];
+    if (tid < 64) {
+      // one wave walks the digits from 255 down: lane l holds digits 255-4l .. 252-4l
+      int c[4], incl[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) c[q] = hcur[255 - (4 * tid + q)];
+      incl[0] = c[0]; incl[1] = incl[0] + c[1]; incl[2] = incl[1] + c[2]; incl[3] = incl[2] + c[3];
+      int run = incl[3];
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        int y = __shfl_up(run, off);
+        if (tid >= off) run += y;
+      }
+      const int before = run - incl[3];         // candidates with a digit above this lane's four
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int upto = before + incl[q], above = upto - c[q];
+        if (upto >= remaining && above < remaining) {
+          sel_bin = 255 - (4 * tid + q);
+          sel_remaining = remaining - above;
+        }
+      }
+    } else if (tid >= 256 && tid < 512) {
+      hist[((pass + 1) & 1) * 256 + (tid - 256)] = 0;    // the other histogram, for the next pass
     }
     __syncthreads();
     prefix |= (uint32_t)sel_bin << shift;
     mask |= 255u << shift;
     remaining = sel_remaining;
-    __syncthreads();
   }
   // prefix = the k-th largest key; `remaining` of the keys equal to it are kept, smallest index first
   const uint32_t thr = prefix;

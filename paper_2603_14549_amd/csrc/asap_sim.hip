@@ -2,13 +2,13 @@
 // stage, (pruned rows) x (kept rows)^T over the hidden dimension, on the matrix cores, with the
 // row arg-max fused into the epilogue.
 //
-//   k_knorm<T>    1 / max(|x_i|, 1e-8) of every kept row (one wave per row).
 //   k_sim<T, NT>  workgroup tile BM = 128 source rows x BN = 64*NT destination rows.  The hidden
 //                 dimension is walked in steps of 128 bytes per row; a step's (BM + BN) x 128 B
 //                 panel is staged through LDS (rows padded to 144 B), double buffered, one barrier
 //                 per step.  512 threads: 4 consumer waves (2 x 2 over the tile, each 64 x 32*NT =
 //                 2 x NT MFMA tiles of 32 x 32) and 4 producer waves that move global -> LDS with
-//                 three steps in flight in registers.
+//                 three steps in flight in registers and accumulate the squared norms of the
+//                 rows they move (sources once, kept rows every pass).
 //                 The grid is one-dimensional and XCD-aware: consecutive workgroup ids go to the 8
 //                 XCDs round-robin, so id % 8 picks the XCD and all tiles of one image are given
 //                 ids with the same id % 8 -- they then share that XCD's L2 for the kept panel.
@@ -41,32 +41,6 @@ template <> __device__ __forceinline__ float sumsq16<float>(const uint4& c, floa
   return acc;
 }
 
-// k_knorm: grid (ceil(B*k / 4)), 256 threads; wave w of a block handles kept row 4*blockIdx + w.
-template <typename T>
-__global__ __launch_bounds__(256) void k_knorm(const T* __restrict__ xv, int64_t sb, int64_t sr, int D,
-                                                const int32_t* __restrict__ kept, int k, int total,
-                                                float* __restrict__ invk) {
-  constexpr int E = elem<T>::per16;
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= total) return;
-  const int b = row / k;
-  const char* x = reinterpret_cast<const char*>(xv + b * sb + (int64_t)kept[row] * sr);
-  const int nchunks = D / E;
-  float acc0 = 0.0f, acc1 = 0.0f;
-  int c = lane;
-  for (; c + 64 < nchunks; c += 128) {
-    uint4 u = ldg16(x + c * 16), v = ldg16(x + (c + 64) * 16);
-    acc0 = sumsq16<T>(u, acc0);
-    acc1 = sumsq16<T>(v, acc1);
-  }
-  if (c < nchunks) acc0 = sumsq16<T>(ldg16(x + c * 16), acc0);
-  float a = acc0 + acc1;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off);
-  if (lane == 0) invk[row] = 1.0f / fmaxf(sqrtf(a), 1e-8f);
-}
-
 // k_sim: 512 threads = 4 consumer waves (MFMA, 2 x 2 over the tile) + 4 producer waves (global -> LDS).
 // A producer thread moves the 16-byte piece t % 8 of rows t / 8 + 32 i of every step's panel; it keeps
 // three steps in registers (issued at step s for step s + 3, written to LDS at step s + 2), so that
@@ -75,7 +49,7 @@ __global__ __launch_bounds__(256) void k_knorm(const T* __restrict__ xv, int64_t
 template <typename T, int NT>
 __global__ __launch_bounds__(512) void k_sim(const T* __restrict__ xv, int64_t sb, int64_t sr, int D,
                                               const int32_t* __restrict__ pruned, const int32_t* __restrict__ kept,
-                                              const float* __restrict__ invk_g, int B, int M, int k, int mtiles,
+                                              int B, int M, int k, int mtiles,
                                               float threshold, int32_t* __restrict__ assign,
                                               float* __restrict__ best_sim) {
   constexpr int BN = 64 * NT;
@@ -87,6 +61,7 @@ __global__ __launch_bounds__(512) void k_sim(const T* __restrict__ xv, int64_t s
   float* norm2 = reinterpret_cast<float*>(lds + 2 * STAGE);   // [BM]
   float* part_v = norm2 + SIM_BM;                             // [2][BM]
   int* part_c = reinterpret_cast<int*>(part_v + 2 * SIM_BM);  // [2][BM]
+  float* normk = reinterpret_cast<float*>(part_c + 2 * SIM_BM);  // [BN] squared norms of this pass's kept rows
 
   // XCD-aware decode of the linear workgroup id
   const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
@@ -118,15 +93,16 @@ __global__ __launch_bounds__(512) void k_sim(const T* __restrict__ xv, int64_t s
       int r = min(m0 + rbase + 32 * i, M - 1);
       off[i] = (uint32_t)(pruned[(int64_t)b * M + r] * rowb + piece * 16);
     }
-    float ss[PA];
+    float ss[PP];
 #pragma unroll
-    for (int i = 0; i < PA; ++i) ss[i] = 0.0f;
+    for (int i = 0; i < PP; ++i) ss[i] = 0.0f;
     for (int pass = 0; pass < npass; ++pass) {
       const bool count_src = pass == 0;
 #pragma unroll
       for (int i = PA; i < PP; ++i) {
         int c = min(pass * BN + rbase + 32 * (i - PA), k - 1);
         off[i] = (uint32_t)(kept[(int64_t)b * k + c] * rowb + piece * 16);
+        ss[i] = 0.0f;
       }
       uint4 st[3][PP];
       auto fetch = [&](uint4 (&dst)[PP], int s) {
@@ -140,7 +116,7 @@ __global__ __launch_bounds__(512) void k_sim(const T* __restrict__ xv, int64_t s
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
           *reinterpret_cast<uint4*>(dst + i * 32 * SIM_LDSROW) = src[i];
-          if (i < PA && count_src) ss[i] = sumsq16<T>(src[i], ss[i]);
+          if (i >= PA || count_src) ss[i] = sumsq16<T>(src[i], ss[i]);
         }
       };
       // step s with R = s % 3: the set of step s + 1 goes to LDS, set R is refilled for step s + 3
@@ -163,16 +139,19 @@ __global__ __launch_bounds__(512) void k_sim(const T* __restrict__ xv, int64_t s
         pstep(s, std::integral_constant<int, 2>{});
         ++s;
       }
-      if (count_src) {       // squared norms of the source rows: 8 consecutive lanes share a row
+      // squared norms of the rows this thread moved: 8 consecutive lanes share a row
 #pragma unroll
-        for (int i = 0; i < PA; ++i) {
-          float v = ss[i];
-          v += __shfl_xor(v, 1);
-          v += __shfl_xor(v, 2);
-          v += __shfl_xor(v, 4);
-          if (piece == 0) norm2[rbase + 32 * i] = v;
+      for (int i = 0; i < PP; ++i) {
+        float v = ss[i];
+        v += __shfl_xor(v, 1);
+        v += __shfl_xor(v, 2);
+        v += __shfl_xor(v, 4);
+        if (piece == 0) {
+          if (i >= PA) normk[rbase + 32 * (i - PA)] = v;
+          else if (count_src) norm2[rbase + 32 * i] = v;
         }
       }
+      __syncthreads();   // norms visible to the consumers' epilogue
       __syncthreads();
       __syncthreads();
     }
@@ -214,12 +193,14 @@ __global__ __launch_bounds__(512) void k_sim(const T* __restrict__ xv, int64_t s
         __syncthreads();
       }
       // row arg-max of dot / |x_i| over this pass's destinations (|x_j| > 0 does not move it)
+      __syncthreads();   // the producers' norms
       float invk[NT];
       int colv[NT];
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
-        colv[t] = n0 + wn * (BN / 2) + t * 32 + n;
-        invk[t] = colv[t] < k ? invk_g[(int64_t)b * k + colv[t]] : 0.0f;
+        const int cl = wn * (BN / 2) + t * 32 + n;
+        colv[t] = n0 + cl;
+        invk[t] = colv[t] < k ? 1.0f / fmaxf(sqrtf(normk[cl]), 1e-8f) : 0.0f;
       }
       // Each lane first takes the best of its NT columns per row; the 32 lanes that share a row then
       // exchange through LDS (the stage buffers are idle now): one lane per row scans the 32 partial
@@ -283,14 +264,14 @@ __global__ __launch_bounds__(512) void k_sim(const T* __restrict__ xv, int64_t s
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
-size_t sim_workspace_bytes(const asap_params& p) { return align256(sizeof(float) * (size_t)p.B * p.k); }
+size_t sim_workspace_bytes(const asap_params&) { return 0; }
 
 template <typename T, int NT>
 static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, int64_t sr, const int32_t* pruned,
-                                const int32_t* kept, const float* invk, int32_t* assign, float* best_sim,
+                                const int32_t* kept, int32_t* assign, float* best_sim,
                                 hipStream_t st, Timer* tm) {
   constexpr int BN = 64 * NT, ROWS = SIM_BM + BN;
-  const size_t lds = 2 * (size_t)ROWS * SIM_LDSROW + 5 * sizeof(float) * SIM_BM;
+  const size_t lds = 2 * (size_t)ROWS * SIM_LDSROW + sizeof(float) * (5 * SIM_BM + BN);
   auto kern = k_sim<T, NT>;
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -301,7 +282,7 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
   const int mtiles = (M + SIM_BM - 1) / SIM_BM;
   const int groups = (p.B + NUM_XCD - 1) / NUM_XCD;
   ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * mtiles), dim3(512), lds, st, xv, sb, sr, p.D, pruned,
-              kept, invk, p.B, M, p.k, mtiles, p.sim_threshold, assign, best_sim);
+              kept, p.B, M, p.k, mtiles, p.sim_threshold, assign, best_sim);
   return hipGetLastError();
 }
 
@@ -322,16 +303,13 @@ static hipError_t sim_typed(const asap_params& p, const void* hidden, int64_t hs
                             const int32_t* kept, const int32_t* pruned, int32_t* assign, float* best_sim,
                             char* ws, hipStream_t st, Timer* tm) {
   const T* xv = static_cast<const T*>(hidden) + (int64_t)p.P * hsr;
-  float* invk = reinterpret_cast<float*>(ws);
-  const int total = p.B * p.k;
-  ASAP_LAUNCH(tm, "k_knorm", k_knorm<T>, dim3((total + 3) / 4), dim3(256), 0, st, xv, hsb, hsr, p.D, kept, p.k,
-              total, invk);
+  (void)ws;
   switch (pick_nt(p.k)) {
-    case 1: return launch_sim_nt<T, 1>(p, xv, hsb, hsr, pruned, kept, invk, assign, best_sim, st, tm);
-    case 2: return launch_sim_nt<T, 2>(p, xv, hsb, hsr, pruned, kept, invk, assign, best_sim, st, tm);
-    case 3: return launch_sim_nt<T, 3>(p, xv, hsb, hsr, pruned, kept, invk, assign, best_sim, st, tm);
-    case 4: return launch_sim_nt<T, 4>(p, xv, hsb, hsr, pruned, kept, invk, assign, best_sim, st, tm);
-    default: return launch_sim_nt<T, 5>(p, xv, hsb, hsr, pruned, kept, invk, assign, best_sim, st, tm);
+    case 1: return launch_sim_nt<T, 1>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
+    case 2: return launch_sim_nt<T, 2>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
+    case 3: return launch_sim_nt<T, 3>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
+    case 4: return launch_sim_nt<T, 4>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
+    default: return launch_sim_nt<T, 5>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
   }
 }
 
