@@ -122,8 +122,13 @@ __global__ __launch_bounds__(512) void k_sim(const T* __restrict__ xv, int64_t s
       // step s with R = s % 3: the set of step s + 1 goes to LDS, set R is refilled for step s + 3
       auto pstep = [&](int s, auto r) {
         constexpr int R = decltype(r)::value;
-        if (s + 1 < steps) stash(st[(R + 1) % 3], (s + 1) & 1);
-        if (s + 3 < steps) fetch(st[R], s + 3);
+        if (wave & 1) {       // half of the producer waves load first, so LDS writes and global loads overlap
+          if (s + 3 < steps) fetch(st[R], s + 3);
+          if (s + 1 < steps) stash(st[(R + 1) % 3], (s + 1) & 1);
+        } else {
+          if (s + 1 < steps) stash(st[(R + 1) % 3], (s + 1) & 1);
+          if (s + 3 < steps) fetch(st[R], s + 3);
+        }
         __syncthreads();
       };
       fetch(st[0], 0);
