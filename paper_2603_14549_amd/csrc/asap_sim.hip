@@ -2,13 +2,20 @@
 // stage, (pruned rows) x (kept rows)^T over the hidden dimension, on the matrix cores, with the
 // row arg-max fused into the epilogue.
 //
-//   k_sim<T, NT>  workgroup tile BM = 128 source rows x BN = 64*NT destination rows.  The hidden
-//                 dimension is walked in steps of 128 bytes per row; a step's (BM + BN) x 128 B
-//                 panel is staged through LDS (rows padded to 144 B), double buffered, one barrier
-//                 per step.  512 threads: 4 consumer waves (2 x 2 over the tile, each 64 x 32*NT =
-//                 2 x NT MFMA tiles of 32 x 32) and 4 producer waves that move global -> LDS with
-//                 three steps in flight in registers and accumulate the squared norms of the
-//                 rows they move (sources once, kept rows every pass).
+//   k_sim<T, NT>  workgroup tile BM = 128 source rows x BN = 64*NT destination rows, 256 threads =
+//                 4 waves (2 x 2 over the tile, each 64 x 32*NT = 2 x NT MFMA tiles of 32 x 32), one
+//                 wave per SIMD so that a wave may use the whole 512-entry register file.  The
+//                 hidden dimension is walked in steps of 128 bytes per row, one barrier per step.
+//                 Operands reach LDS by direct global -> LDS loads (no registers in between) that
+//                 every wave issues between its MFMAs; the squared norms of the rows are added up
+//                 from the operands a wave holds, also in the shadow of the MFMAs.
+//                 The source rows are read once, from HBM, so their 128 x 128 B slices go through a
+//                 ring of 4 LDS slots and are asked for three steps ahead; the destination rows are
+//                 shared by all tiles of an image and come from L2, so two slots (one step ahead)
+//                 are enough for their BN x 128 B slices.
+//                 LDS rows are unpadded; the 16-byte piece p of row r is stored in slot
+//                 p ^ ((r >> 1) & 7): any 16 consecutive rows then cover all 64 banks once, for the
+//                 1 KiB-contiguous loads as well as for the strided 16-byte operand reads.
 //                 The grid is one-dimensional and XCD-aware: consecutive workgroup ids go to the 8
 //                 XCDs round-robin, so id % 8 picks the XCD and all tiles of one image are given
 //                 ids with the same id % 8 -- they then share that XCD's L2 for the kept panel.
@@ -18,50 +25,91 @@
 namespace asap {
 
 constexpr int SIM_BM = 128;
-constexpr int SIM_LDSROW = 144;
+constexpr int SIM_ROWB = 128;      // bytes of a row held in LDS per step
 constexpr int NUM_XCD = 8;
+constexpr int SIM_NA = 4;          // LDS ring slots for the source rows (power of two); destination rows have 2
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
-// sum of squares of the elements of a 16-byte chunk added to acc
-template <typename T> __device__ __forceinline__ float sumsq16(const uint4& c, float acc);
-template <> __device__ __forceinline__ float sumsq16<bf16_t>(const uint4& c, float acc) {
+// Sum of squares of the elements of a 16-byte chunk, kept in four independent partial sums so that
+// consecutive operations never wait for each other.
+struct SumSq4 {
+  float p[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  __device__ __forceinline__ float total() const { return (p[0] + p[1]) + (p[2] + p[3]); }
+};
+template <typename T> __device__ __forceinline__ void sumsq16(const uint4& c, SumSq4& acc);
+template <> __device__ __forceinline__ void sumsq16<bf16_t>(const uint4& c, SumSq4& acc) {
   bf16x2_t p;
-  __builtin_memcpy(&p, &c.x, 4); acc = __builtin_amdgcn_fdot2_f32_bf16(p, p, acc, false);
-  __builtin_memcpy(&p, &c.y, 4); acc = __builtin_amdgcn_fdot2_f32_bf16(p, p, acc, false);
-  __builtin_memcpy(&p, &c.z, 4); acc = __builtin_amdgcn_fdot2_f32_bf16(p, p, acc, false);
-  __builtin_memcpy(&p, &c.w, 4); acc = __builtin_amdgcn_fdot2_f32_bf16(p, p, acc, false);
-  return acc;
+  __builtin_memcpy(&p, &c.x, 4); acc.p[0] = __builtin_amdgcn_fdot2_f32_bf16(p, p, acc.p[0], false);
+  __builtin_memcpy(&p, &c.y, 4); acc.p[1] = __builtin_amdgcn_fdot2_f32_bf16(p, p, acc.p[1], false);
+  __builtin_memcpy(&p, &c.z, 4); acc.p[2] = __builtin_amdgcn_fdot2_f32_bf16(p, p, acc.p[2], false);
+  __builtin_memcpy(&p, &c.w, 4); acc.p[3] = __builtin_amdgcn_fdot2_f32_bf16(p, p, acc.p[3], false);
 }
-template <> __device__ __forceinline__ float sumsq16<float>(const uint4& c, float acc) {
+template <> __device__ __forceinline__ void sumsq16<float>(const uint4& c, SumSq4& acc) {
   float f[4];
   unpack16<float>(c, f);
-  acc = fmaf(f[0], f[0], acc); acc = fmaf(f[1], f[1], acc);
-  acc = fmaf(f[2], f[2], acc); acc = fmaf(f[3], f[3], acc);
-  return acc;
+  acc.p[0] = fmaf(f[0], f[0], acc.p[0]); acc.p[1] = fmaf(f[1], f[1], acc.p[1]);
+  acc.p[2] = fmaf(f[2], f[2], acc.p[2]); acc.p[3] = fmaf(f[3], f[3], acc.p[3]);
 }
 
-// k_sim: 512 threads = 4 consumer waves (MFMA, 2 x 2 over the tile) + 4 producer waves (global -> LDS).
-// A producer thread moves the 16-byte piece t % 8 of rows t / 8 + 32 i of every step's panel; it keeps
-// three steps in registers (issued at step s for step s + 3, written to LDS at step s + 2), so that
-// HBM latency is covered by two steps of MFMA work, and it accumulates the squared norms of its
-// source rows.  Consumers only read LDS and issue MFMAs.  Both roles meet at one barrier per step.
+// 16 bytes per lane from global memory straight into LDS: lane L's data, read from gbase + voff
+// (gbase wave-uniform), lands at LDS byte address lds_addr + 16 L (lds_addr wave-uniform, passed
+// in M0).  Completion is counted by vmcnt.  Written as assembly so that the compiler does not
+// order the workgroup's own LDS operand reads behind every outstanding load (it cannot tell the
+// ring slots apart); the waits below are placed by hand instead.
+__device__ __forceinline__ void load_to_lds16(const char* gbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(gbase), "s"(lds_addr) : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+__device__ __forceinline__ void wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// wait until at most N (< 16) of this wave's vector-memory loads are still outstanding
+template <int N> __device__ __forceinline__ void wait_vmem_but() {
+  static_assert(N >= 0 && N < 16, "vmcnt field");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// Workgroup barrier without the release fence of __syncthreads(): that fence would wait for every
+// outstanding load of the wave, also the ones that are meant to stay in flight across the barrier.
+__device__ __forceinline__ void barrier_keep_loads() { asm volatile("s_barrier" ::: "memory"); }
+
+// all-reduce over a row of 16 lanes by rotations inside the row (the caller joins the two rows of a
+// 32-lane half with one exchange)
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, 0xF, 0xF, false);
+}
+__device__ __forceinline__ float rowmax16(float x) {
+  x = fmaxf(x, __uint_as_float(dpp_u32<0x128>(__float_as_uint(x))));   // row_ror:8
+  x = fmaxf(x, __uint_as_float(dpp_u32<0x124>(__float_as_uint(x))));   // row_ror:4
+  x = fmaxf(x, __uint_as_float(dpp_u32<0x122>(__float_as_uint(x))));   // row_ror:2
+  x = fmaxf(x, __uint_as_float(dpp_u32<0x121>(__float_as_uint(x))));   // row_ror:1
+  return x;
+}
+__device__ __forceinline__ int rowmin16(int x) {
+  x = min(x, (int)dpp_u32<0x128>((uint32_t)x));
+  x = min(x, (int)dpp_u32<0x124>((uint32_t)x));
+  x = min(x, (int)dpp_u32<0x122>((uint32_t)x));
+  x = min(x, (int)dpp_u32<0x121>((uint32_t)x));
+  return x;
+}
+
 template <typename T, int NT>
-__global__ __launch_bounds__(512) void k_sim(const T* __restrict__ xv, int64_t sb, int64_t sr, int D,
+__global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t sb, int64_t sr, int D,
                                               const int32_t* __restrict__ pruned, const int32_t* __restrict__ kept,
-                                              int B, int M, int k, int mtiles,
-                                              float threshold, int32_t* __restrict__ assign,
-                                              float* __restrict__ best_sim) {
+                                              int B, int M, int k, int mtiles, float threshold,
+                                              int32_t* __restrict__ assign, float* __restrict__ best_sim) {
   constexpr int BN = 64 * NT;
-  constexpr int ROWS = SIM_BM + BN;
-  constexpr int PP = ROWS / 32;                  // 16-byte pieces a producer thread moves per step
-  constexpr int PA = SIM_BM / 32;                // of which source rows
-  constexpr int STAGE = ROWS * SIM_LDSROW;
+  constexpr int PA = SIM_BM / 32;                // source-row loads a thread issues per step
+  constexpr int PB = BN / 32;                    // destination-row loads
+  constexpr int ASTAGE = SIM_BM * SIM_ROWB, BSTAGE = BN * SIM_ROWB;
+  static_assert(PA + PB <= 8 * NT, "one load per MFMA slot");
   extern __shared__ __align__(16) char lds[];
-  float* norm2 = reinterpret_cast<float*>(lds + 2 * STAGE);   // [BM]
-  float* part_v = norm2 + SIM_BM;                             // [2][BM]
-  int* part_c = reinterpret_cast<int*>(part_v + 2 * SIM_BM);  // [2][BM]
-  float* normk = reinterpret_cast<float*>(part_c + 2 * SIM_BM);  // [BN] squared norms of this pass's kept rows
+  char* ldsB = lds + SIM_NA * ASTAGE;
+  const uint32_t lds_addr = lds_address(lds), ldsB_addr = lds_addr + SIM_NA * ASTAGE;
+  float* norm2 = reinterpret_cast<float*>(ldsB + 2 * BSTAGE);    // [BM] squared norms of the source rows
+  float* normk = norm2 + SIM_BM;                                 // [BN] squared norms of this pass's kept rows
+  uint2* part = reinterpret_cast<uint2*>(normk + BN);            // [2][BM] (value, column) per column half
 
   // XCD-aware decode of the linear workgroup id
   const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
@@ -69,200 +117,218 @@ __global__ __launch_bounds__(512) void k_sim(const T* __restrict__ xv, int64_t s
   if (b >= B) return;
   const int m0 = (slot % mtiles) * SIM_BM;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const bool producer = wave >= 4;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, hf = lane >> 5;
-  const int wm = (wave >> 1) & 1, wn = wave & 1;
-  const int ltid = tid & 255, piece = ltid & 7, rbase = ltid >> 3;
+  const int wm = wave >> 1, wn = wave & 1;
   const char* xb = reinterpret_cast<const char*>(xv + b * sb);
   const int64_t rowb = sr * (int64_t)sizeof(T);
-  const int steps = (D * (int)sizeof(T)) / 128;
+  const int steps = (D * (int)sizeof(T)) / SIM_ROWB;
   const int npass = (k + BN - 1) / BN;
   // Every workgroup walks the hidden dimension from its own starting step: rows are a power-of-two
   // number of bytes apart, so workgroups in lockstep would all hit the same memory channel.
   const int rot = ((slot % mtiles) + 16 * (slot / mtiles)) % steps;
+  auto step_base = [&](int s) {
+    int sr_ = s + rot;
+    if (sr_ >= steps) sr_ -= steps;
+    return xb + (int64_t)sr_ * SIM_ROWB;
+  };
 
-  float run_v = -INFINITY;   // running best over destination passes (consumer threads < BM)
+  // Loads: thread (rr, q) fetches, for rows rr + 32 i, the piece that belongs in slot q of the row;
+  // one load instruction of wave w fills rows 8 w .. 8 w + 7 of a 32-row block, 1 KiB contiguous.
+  const int rr = tid >> 3, q = tid & 7;
+  const uint32_t piece_off = (uint32_t)((q ^ ((rr >> 1) & 7)) * 16);
+  uint32_t offa[PA], offb[PB];      // byte offsets from the image base (an image spans < 4 GiB)
+#pragma unroll
+  for (int i = 0; i < PA; ++i) {
+    int r = min(m0 + rr + 32 * i, M - 1);
+    offa[i] = (uint32_t)(pruned[(int64_t)b * M + r] * rowb) + piece_off;
+  }
+  // Operand reads: byte offset of this lane's chunk kk inside its row
+  int sw[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) sw[kk] = ((hf * 4 + kk) ^ ((n >> 1) & 7)) * 16;
+
+  float run_v = -INFINITY;   // running best over destination passes (threads < BM)
   int run_c = 0;
 
-  if (producer) {
-    // byte offsets of this thread's rows from the image base (an image spans < 4 GiB)
-    uint32_t off[PP];
+  for (int pass = 0; pass < npass; ++pass) {
+    const int n0 = pass * BN;
 #pragma unroll
-    for (int i = 0; i < PA; ++i) {
-      int r = min(m0 + rbase + 32 * i, M - 1);
-      off[i] = (uint32_t)(pruned[(int64_t)b * M + r] * rowb + piece * 16);
+    for (int j = 0; j < PB; ++j) {
+      int c = min(n0 + rr + 32 * j, k - 1);
+      offb[j] = (uint32_t)(kept[(int64_t)b * k + c] * rowb) + piece_off;
     }
-    float ss[PP];
+    f32x16_t acc[2][NT];
 #pragma unroll
-    for (int i = 0; i < PP; ++i) ss[i] = 0.0f;
-    for (int pass = 0; pass < npass; ++pass) {
-      const bool count_src = pass == 0;
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int i = PA; i < PP; ++i) {
-        int c = min(pass * BN + rbase + 32 * (i - PA), k - 1);
-        off[i] = (uint32_t)(kept[(int64_t)b * k + c] * rowb + piece * 16);
-        ss[i] = 0.0f;
-      }
-      uint4 st[3][PP];
-      auto fetch = [&](uint4 (&dst)[PP], int s) {
-        int sr_ = s + rot; if (sr_ >= steps) sr_ -= steps;   // rotated walk, see rot
-        const char* base = xb + (int64_t)sr_ * 128;
+      for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int i = 0; i < PP; ++i) dst[i] = ldg16(base + off[i]);
-      };
-      auto stash = [&](const uint4 (&src)[PP], int buf) {
-        char* dst = lds + buf * STAGE + rbase * SIM_LDSROW + piece * 16;
+        for (int v = 0; v < 16; ++v) acc[i][t][v] = 0.0f;
+    SumSq4 ss_a[2], ss_b[NT];
+
+    // fill: destination slice 0, source slices 0 .. SIM_NA-2
+    {
+      const char* g = step_base(0);
 #pragma unroll
-        for (int i = 0; i < PP; ++i) {
-          *reinterpret_cast<uint4*>(dst + i * 32 * SIM_LDSROW) = src[i];
-          if (i >= PA || count_src) ss[i] = sumsq16<T>(src[i], ss[i]);
-        }
-      };
-      // step s with R = s % 3: the set of step s + 1 goes to LDS, set R is refilled for step s + 3
-      auto pstep = [&](int s, auto r) {
-        constexpr int R = decltype(r)::value;
-        if (wave & 1) {       // half of the producer waves load first, so LDS writes and global loads overlap
-          if (s + 3 < steps) fetch(st[R], s + 3);
-          if (s + 1 < steps) stash(st[(R + 1) % 3], (s + 1) & 1);
-        } else {
-          if (s + 1 < steps) stash(st[(R + 1) % 3], (s + 1) & 1);
-          if (s + 3 < steps) fetch(st[R], s + 3);
-        }
-        __syncthreads();
-      };
-      fetch(st[0], 0);
-      if (steps > 1) fetch(st[1], 1);
-      if (steps > 2) fetch(st[2], 2);
-      stash(st[0], 0);
-      __syncthreads();
-      for (int s = 0; s < steps;) {
-        pstep(s, std::integral_constant<int, 0>{});
-        if (++s >= steps) break;
-        pstep(s, std::integral_constant<int, 1>{});
-        if (++s >= steps) break;
-        pstep(s, std::integral_constant<int, 2>{});
-        ++s;
-      }
-      // squared norms of the rows this thread moved: 8 consecutive lanes share a row
+      for (int j = 0; j < PB; ++j) load_to_lds16(g, offb[j], ldsB_addr + (8 * wave + 32 * j) * SIM_ROWB);
 #pragma unroll
-      for (int i = 0; i < PP; ++i) {
-        float v = ss[i];
-        v += __shfl_xor(v, 1);
-        v += __shfl_xor(v, 2);
-        v += __shfl_xor(v, 4);
-        if (piece == 0) {
-          if (i >= PA) normk[rbase + 32 * (i - PA)] = v;
-          else if (count_src) norm2[rbase + 32 * i] = v;
+      for (int a = 0; a < SIM_NA - 1; ++a) {
+        if (a < steps) {
+          const char* ga = step_base(a);
+#pragma unroll
+          for (int i = 0; i < PA; ++i)
+            load_to_lds16(ga, offa[i], lds_addr + a * ASTAGE + (8 * wave + 32 * i) * SIM_ROWB);
         }
       }
-      __syncthreads();   // norms visible to the consumers' epilogue
-      __syncthreads();
+      wait_all_vmem();
       __syncthreads();
     }
-  } else {
-    for (int pass = 0; pass < npass; ++pass) {
-      const int n0 = pass * BN;
-      f32x16_t acc[2][NT];
+
+    for (int s = 0; s < steps; ++s) {
+      // During step s the waves read source slot s % SIM_NA and destination slot s % 2.  Meanwhile
+      // the destination rows of step s+1 are asked for first, then the source rows of step
+      // s+SIM_NA-1; loads retire in order, so leaving only the latter PA loads outstanding at the
+      // end of the step means that everything step s+1 needs has landed.
+      const char* A = lds + (s & (SIM_NA - 1)) * ASTAGE + (wm * 64 + n) * SIM_ROWB;
+      const char* Bp = ldsB + (s & 1) * BSTAGE + (wn * (BN / 2) + n) * SIM_ROWB;
+      // Past the last step the loads repeat the current step into a slot nobody reads any more:
+      // cheaper than branches around every load, which would also split the schedule below.
+      const bool do_a = s + SIM_NA - 1 < steps;
+      const char* gb = step_base(s + 1 < steps ? s + 1 : s);
+      const char* ga = step_base(do_a ? s + SIM_NA - 1 : s);
+      const uint32_t db = ldsB_addr + ((s + 1) & 1) * BSTAGE + (8 * wave) * SIM_ROWB;
+      const uint32_t da = lds_addr + ((s + SIM_NA - 1) & (SIM_NA - 1)) * ASTAGE + (8 * wave) * SIM_ROWB;
+      auto load_unit = [&](int u) {      // the u-th load of this step, if there is one
+        if (u < PB) load_to_lds16(gb, offb[u < PB ? u : 0], db + u * 32 * SIM_ROWB);
+        else if (u < PB + PA) load_to_lds16(ga, offa[u < PB + PA ? u - PB : 0], da + (u - PB) * 32 * SIM_ROWB);
+      };
+      // LDS operand reads run one contraction slice ahead of the MFMAs that use them
+      uint4 a[2][2], bq[2][NT];
+      auto load_op = [&](int set, int kk, int u) {      // in the order the MFMAs need them
+        if (u == 0) a[set][0] = *reinterpret_cast<const uint4*>(A + sw[kk]);
+        else if (u == 2) a[set][1] = *reinterpret_cast<const uint4*>(A + 32 * SIM_ROWB + sw[kk]);
+        else {
+          const int t = u == 1 ? 0 : u - 2;
+          if (t < NT) bq[set][t] = *reinterpret_cast<const uint4*>(Bp + t * 32 * SIM_ROWB + sw[kk]);
+        }
+      };
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int u = 0; u < NT + 2; ++u) load_op(0, 0, u);
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+      for (int kk = 0; kk < 4; ++kk) {
+        // After each MFMA: one LDS read for the next contraction slice, one global -> LDS load and a
+        // few dot products for the norms, all in the MFMA's shadow.  Waves that hold the same rows
+        // repeat the sums; wave-dependent branches would cost more.
 #pragma unroll
-          for (int v = 0; v < 16; ++v) acc[i][t][v] = 0.0f;
-      __syncthreads();
-      for (int s = 0; s < steps; ++s) {
-        // LDS operand reads run one contraction slice ahead of the MFMAs that use them
-        const char* A = lds + (s & 1) * STAGE + (wm * 64 + n) * SIM_LDSROW + hf * 64;
-        const char* Bp = lds + (s & 1) * STAGE + (SIM_BM + wn * (BN / 2) + n) * SIM_LDSROW + hf * 64;
-        uint4 a[2][2], bq[2][NT];
-        auto load_ops = [&](int set, int kk) {
-          a[set][0] = *reinterpret_cast<const uint4*>(A + kk * 16);
-          a[set][1] = *reinterpret_cast<const uint4*>(A + 32 * SIM_LDSROW + kk * 16);
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-            bq[set][t] = *reinterpret_cast<const uint4*>(Bp + t * 32 * SIM_LDSROW + kk * 16);
-        };
-        load_ops(0, 0);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          if (kk < 3) load_ops((kk + 1) & 1, kk + 1);
-          __builtin_amdgcn_sched_barrier(0);     // keep the next slice's reads ahead of this slice's MFMAs
-#pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            mma32<T>(acc[0][t], a[kk & 1][0], bq[kk & 1][t]);
-            mma32<T>(acc[1][t], a[kk & 1][1], bq[kk & 1][t]);
-          }
+        for (int t = 0; t < NT; ++t) {
           __builtin_amdgcn_sched_barrier(0);
+          mma32<T>(acc[0][t], a[kk & 1][0], bq[kk & 1][t]);
+          if (kk < 3) load_op((kk + 1) & 1, kk + 1, 2 * t);
+          sumsq16<T>(bq[kk & 1][t], ss_b[t]);
+          load_unit(kk * 2 * NT + 2 * t);
+          __builtin_amdgcn_sched_barrier(0);
+          mma32<T>(acc[1][t], a[kk & 1][1], bq[kk & 1][t]);
+          if (kk < 3) load_op((kk + 1) & 1, kk + 1, 2 * t + 1);
+          if (t == 0) sumsq16<T>(a[kk & 1][0], ss_a[0]);
+          if (t == 1 || NT == 1) sumsq16<T>(a[kk & 1][1], ss_a[1]);
+          load_unit(kk * 2 * NT + 2 * t + 1);
         }
-        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk < 3) {
+#pragma unroll
+          for (int u = 2 * NT; u < NT + 2; ++u) load_op((kk + 1) & 1, kk + 1, u);     // NT == 1 only
+        }
       }
-      // row arg-max of dot / |x_i| over this pass's destinations (|x_j| > 0 does not move it)
-      __syncthreads();   // the producers' norms
-      float invk[NT];
-      int colv[NT];
+      wait_vmem_but<PA>();
+      barrier_keep_loads();
+    }
+
+    wait_all_vmem();   // the repeated loads of the last steps
+    // the two lane halves hold the two halves of every 128-byte slice
+    if (pass == 0 && wn == 0) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        float v = ss_a[i].total();
+        v += __shfl_xor(v, 32);
+        if (hf == 0) norm2[wm * 64 + i * 32 + n] = v;
+      }
+    }
+    if (wm == 0) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
-        const int cl = wn * (BN / 2) + t * 32 + n;
-        colv[t] = n0 + cl;
-        invk[t] = colv[t] < k ? 1.0f / fmaxf(sqrtf(normk[cl]), 1e-8f) : 0.0f;
+        float v = ss_b[t].total();
+        v += __shfl_xor(v, 32);
+        if (hf == 0) normk[wn * (BN / 2) + t * 32 + n] = v;
       }
-      // Each lane first takes the best of its NT columns per row; the 32 lanes that share a row then
-      // exchange through LDS (the stage buffers are idle now): one lane per row scans the 32 partial
-      // results.  Lanes of one wave only talk to each other here, and a wave's LDS operations are
-      // carried out in order, so no barrier is needed.
-      {
-        constexpr int PITCH = 32 * 8 + 8;
-        char* scr = lds + wave * (32 * PITCH);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            float bv = -INFINITY;
-            int bc = 0x7fffffff;
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-              float c = acc[i][t][v] * invk[t];
-              bool take = (colv[t] < k) & (c > bv);      // columns ascend with t: strict > keeps the smaller
-              bv = take ? c : bv;
-              bc = take ? colv[t] : bc;
-            }
-            *reinterpret_cast<uint2*>(scr + mma32_row(v, lane) * PITCH + n * 8) =
-                make_uint2(__float_as_uint(bv), (uint32_t)bc);
-          }
-          if (lane < 32) {
-            float bv = -INFINITY;
-            int bc = 0x7fffffff;
-#pragma unroll
-            for (int e = 0; e < 32; ++e) {
-              uint2 u = *reinterpret_cast<const uint2*>(scr + lane * PITCH + e * 8);
-              float ov = __uint_as_float(u.x);
-              int oc = (int)u.y;
-              bool take = (ov > bv) | ((ov == bv) & (oc < bc));
-              bv = take ? ov : bv;
-              bc = take ? oc : bc;
-            }
-            int row = wm * 64 + i * 32 + lane;
-            part_v[wn * SIM_BM + row] = bv;
-            part_c[wn * SIM_BM + row] = bc;
-          }
-        }
-      }
-      __syncthreads();
-      if (tid < SIM_BM) {
-        float v0 = part_v[tid], v1 = part_v[SIM_BM + tid];
-        int c0 = part_c[tid], c1 = part_c[SIM_BM + tid];
-        if (v1 > v0 || (v1 == v0 && c1 < c0)) { v0 = v1; c0 = c1; }
-        if (v0 > run_v) { run_v = v0; run_c = c0; }     // earlier passes hold smaller columns
-      }
-      __syncthreads();
     }
-    if (tid < SIM_BM && m0 + tid < M) {
-      float c = run_v / fmaxf(sqrtf(norm2[tid]), 1e-8f);
-      int64_t o = (int64_t)b * M + m0 + tid;
-      best_sim[o] = c;
-      assign[o] = (c > threshold) ? run_c : -1;
+    __syncthreads();   // norms visible
+
+    // Row arg-max of dot / |x_j| over this pass's destinations (|x_i| > 0 does not move it).
+    // A lane first takes the best of its NT columns of a row (columns past k get -inf), then the 32
+    // lanes that share the row agree on the maximum and on the smallest column that reaches it.
+    float invk[NT], bias[NT];
+    int colv[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int cl = wn * (BN / 2) + t * 32 + n;
+      colv[t] = n0 + cl;
+      const bool valid = colv[t] < k;
+      invk[t] = valid ? 1.0f / fmaxf(sqrtf(normk[cl]), 1e-8f) : 0.0f;
+      bias[t] = valid ? 0.0f : -INFINITY;
     }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      // stage by stage over the 16 rows a lane holds, so that the cross-lane exchanges of
+      // different rows overlap instead of waiting for one another
+      float bv[16], mv[16], ov[16];
+      int bc[16], mc[16], oc[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float c[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) c[t] = fmaf(acc[i][t][v], invk[t], bias[t]);
+        bv[v] = c[0];
+#pragma unroll
+        for (int t = 1; t < NT; ++t) bv[v] = fmaxf(bv[v], c[t]);
+        bc[v] = 0x7fffffff;
+#pragma unroll
+        for (int t = NT - 1; t >= 0; --t) bc[v] = (c[t] == bv[v]) ? colv[t] : bc[v];   // columns ascend with t
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mv[v] = rowmax16(bv[v]);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) ov[v] = __shfl_xor(mv[v], 16);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        mv[v] = fmaxf(mv[v], ov[v]);
+        mc[v] = rowmin16(bv[v] == mv[v] ? bc[v] : 0x7fffffff);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oc[v] = __shfl_xor(mc[v], 16);
+      if (n == 0) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          part[wn * SIM_BM + wm * 64 + i * 32 + mma32_row(v, lane)] =
+              make_uint2(__float_as_uint(mv[v]), (uint32_t)min(mc[v], oc[v]));
+      }
+    }
+    __syncthreads();
+    if (tid < SIM_BM) {
+      uint2 p0 = part[tid], p1 = part[SIM_BM + tid];
+      float v0 = __uint_as_float(p0.x), v1 = __uint_as_float(p1.x);
+      int c0 = (int)p0.y, c1 = (int)p1.y;
+      if (v1 > v0 || (v1 == v0 && c1 < c0)) { v0 = v1; c0 = c1; }
+      if (v0 > run_v) { run_v = v0; run_c = c0; }     // earlier passes hold smaller columns
+    }
+    __syncthreads();
+  }
+  if (tid < SIM_BM && m0 + tid < M) {
+    float c = run_v / fmaxf(sqrtf(norm2[tid]), 1e-8f);
+    int64_t o = (int64_t)b * M + m0 + tid;
+    best_sim[o] = c;
+    assign[o] = (c > threshold) ? run_c : -1;
   }
 }
 
@@ -273,10 +339,10 @@ size_t sim_workspace_bytes(const asap_params&) { return 0; }
 
 template <typename T, int NT>
 static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, int64_t sr, const int32_t* pruned,
-                                const int32_t* kept, int32_t* assign, float* best_sim,
-                                hipStream_t st, Timer* tm) {
-  constexpr int BN = 64 * NT, ROWS = SIM_BM + BN;
-  const size_t lds = 2 * (size_t)ROWS * SIM_LDSROW + sizeof(float) * (5 * SIM_BM + BN);
+                                const int32_t* kept, int32_t* assign, float* best_sim, hipStream_t st,
+                                Timer* tm) {
+  constexpr int BN = 64 * NT;
+  const size_t lds = (size_t)(SIM_NA * SIM_BM + 2 * BN) * SIM_ROWB + sizeof(float) * (5 * SIM_BM + BN);
   auto kern = k_sim<T, NT>;
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -286,7 +352,7 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
   const int M = p.V - p.k;
   const int mtiles = (M + SIM_BM - 1) / SIM_BM;
   const int groups = (p.B + NUM_XCD - 1) / NUM_XCD;
-  ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * mtiles), dim3(512), lds, st, xv, sb, sr, p.D, pruned,
+  ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * mtiles), dim3(256), lds, st, xv, sb, sr, p.D, pruned,
               kept, p.B, M, p.k, mtiles, p.sim_threshold, assign, best_sim);
   return hipGetLastError();
 }
@@ -306,9 +372,8 @@ static int pick_nt(int k) {
 template <typename T>
 static hipError_t sim_typed(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
                             const int32_t* kept, const int32_t* pruned, int32_t* assign, float* best_sim,
-                            char* ws, hipStream_t st, Timer* tm) {
+                            hipStream_t st, Timer* tm) {
   const T* xv = static_cast<const T*>(hidden) + (int64_t)p.P * hsr;
-  (void)ws;
   switch (pick_nt(p.k)) {
     case 1: return launch_sim_nt<T, 1>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
     case 2: return launch_sim_nt<T, 2>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
@@ -321,9 +386,10 @@ static hipError_t sim_typed(const asap_params& p, const void* hidden, int64_t hs
 hipError_t launch_similarity(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
                              const int32_t* kept, const int32_t* pruned, int32_t* assign, float* best_sim,
                              char* ws, hipStream_t st, Timer* tm) {
+  (void)ws;
   if (p.h_dtype == ASAP_BF16)
-    return sim_typed<bf16_t>(p, hidden, hsb, hsr, kept, pruned, assign, best_sim, ws, st, tm);
-  return sim_typed<float>(p, hidden, hsb, hsr, kept, pruned, assign, best_sim, ws, st, tm);
+    return sim_typed<bf16_t>(p, hidden, hsb, hsr, kept, pruned, assign, best_sim, st, tm);
+  return sim_typed<float>(p, hidden, hsb, hsr, kept, pruned, assign, best_sim, st, tm);
 }
 
 }  // namespace asap
