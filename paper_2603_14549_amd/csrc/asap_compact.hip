@@ -31,12 +31,12 @@ __global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t*
 #pragma unroll
   for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
     int nrow = base + i * rpi;
-    if (nrow < nl) v[i] = ldg16(src + (int64_t)pos[nrow] * row_bytes);
+    if (nrow < nl) v[i] = ldg16_stream(src + (int64_t)pos[nrow] * row_bytes);
   }
 #pragma unroll
   for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
     int nrow = base + i * rpi;
-    if (nrow < nl) *reinterpret_cast<uint4*>(dst + (int64_t)nrow * row_bytes) = v[i];
+    if (nrow < nl) stg16_stream(dst + (int64_t)nrow * row_bytes, v[i]);
   }
 }
 

@@ -79,4 +79,19 @@ __device__ __forceinline__ double shfl_xor_f64(double x, int mask) {
 
 __device__ __forceinline__ uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 
+// 16-byte load of data that is read exactly once: marked non-temporal so that it does not push
+// out of the caches what later kernels come back to.
+typedef uint32_t u32x4_nt __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ldg16_stream(const void* p) {
+  u32x4_nt x = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(p));
+  return make_uint4(x.x, x.y, x.z, x.w);
+}
+
+// 16-byte store of data this stage does not read again (outputs): marked non-temporal so that the
+// lines do not linger dirty in the caches and get written back under a later kernel's reads.
+__device__ __forceinline__ void stg16_stream(void* p, const uint4& v) {
+  u32x4_nt x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, reinterpret_cast<u32x4_nt*>(p));
+}
+
 }  // namespace asap

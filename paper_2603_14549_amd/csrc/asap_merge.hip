@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void k_merge(const T* __restrict__ hidden, int
     if (tid == 0) pos_out[(int64_t)b * Nout + nrow] = src;
     if (src < 0) return;
     const char* s = hb + (int64_t)src * rowb;
-    for (int c = tid; c < nchunks; c += 256) *reinterpret_cast<uint4*>(orow + c * 16) = ldg16(s + c * 16);
+    for (int c = tid; c < nchunks; c += 256) stg16_stream(orow + c * 16, ldg16_stream(s + c * 16));
     return;
   }
 
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void k_merge(const T* __restrict__ hidden, int
     int c = tid + q * 256;
     if (c < nchunks) {
       float f[E];
-      unpack16<T>(ldg16(xrow + c * 16), f);
+      unpack16<T>(ldg16_stream(xrow + c * 16), f);
 #pragma unroll
       for (int e = 0; e < E; ++e) acc[q][e] = w_i * f[e];
     }
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256) void k_merge(const T* __restrict__ hidden, int
 #pragma unroll
         for (int q = 0; q < CPT; ++q) {
           int c = tid + q * 256;
-          if (c < nchunks) ch[u][q] = ldg16(srow + c * 16);
+          if (c < nchunks) ch[u][q] = ldg16_stream(srow + c * 16);
         }
       }
 #pragma unroll
@@ -146,11 +146,11 @@ __global__ __launch_bounds__(256) void k_merge(const T* __restrict__ hidden, int
         float f[E];
 #pragma unroll
         for (int e = 0; e < E; ++e) f[e] = acc[q][e] * inv;
-        *reinterpret_cast<uint4*>(orow + c * 16) = pack16<T>(f);
+        stg16_stream(orow + c * 16, pack16<T>(f));
       }
     }
   } else {                                               // nothing absorbed: Eq. 6 is the identity
-    for (int c = tid; c < nchunks; c += 256) *reinterpret_cast<uint4*>(orow + c * 16) = ldg16(xrow + c * 16);
+    for (int c = tid; c < nchunks; c += 256) stg16_stream(orow + c * 16, ldg16_stream(xrow + c * 16));
   }
 }
 

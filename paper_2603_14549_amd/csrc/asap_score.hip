@@ -72,7 +72,7 @@ __global__ __launch_bounds__(1024) void k_qsum(const T* __restrict__ q, Strides3
   for (; row + 7 * RPI < hi; row += 8 * RPI) {       // eight rows in flight, summed in fp32
     uint4 ch[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) ch[u] = ldg16(base + (int64_t)(row + u * RPI) * rowb);
+    for (int u = 0; u < 8; ++u) ch[u] = ldg16_stream(base + (int64_t)(row + u * RPI) * rowb);
     float f[E], g[E];
     unpack16<T>(ch[0], f);
 #pragma unroll
