@@ -2,7 +2,9 @@
 """Benchmark of the pruning stage on one MI355X.
 
 A step = one pass of the whole hot path (asap_score, asap_select, asap_merge, asap_compact_kv)
-over one batch of synthetic input already resident in HBM.  Default workload: C6, the
+over one batch of synthetic input already resident in HBM.  The K/V compaction runs on a second
+stream next to the similarity and merge kernels (its positions come from asap_positions right
+after the selection); the step ends when both streams are done.  Default workload: C6, the
 2304-visual-token, batch-16, bf16 configuration (LLaVA-NeXT-7B shaped) the metric is quoted on.
 
 Prints ONE JSON line: whole-job images/s, ms per step, the roofline of the dominant kernel
@@ -58,6 +60,7 @@ def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
         "k_attn_colsum": k_vis + q_txt + 4 * B * H * V,
         "k_score": 4 * B * H * V + 16 * B * V,
         "k_select": 12 * B * V,
+        "k_positions": 4 * B * k + 4 * B * (P + k + cfg.Tmax),
         "k_sim": vis_h + 8 * B * (V - k),
         "k_merge": vis_h + B * (P + T) * D * eh + out_rows * D * eh,
         "k_compact": 2 * 2 * n_layers * Hkv * out_rows * d * ek,
@@ -136,7 +139,7 @@ def main():
     images_per_s = cfg.B * args.steps / elapsed
 
     # second pass of the same K steps with the library's per-kernel HIP events on
-    launches_per_step = 16
+    launches_per_step = 18
     ctx.asap_timing_enable(min(8192, launches_per_step * args.steps))
     for _ in range(args.steps):
         stage.run_async()
@@ -161,7 +164,10 @@ def main():
                          "alg_MB": round(per_launch_bytes / 1e6, 2),
                          "GBps": round(per_launch_bytes / (avg_us * 1e-6) / 1e9, 1)}
     step_kernel_us = sum(1e3 * ms / args.steps for ms, _ in timing.values())
-    dominant = max(timing, key=lambda k: timing[k][0])
+    # The dominant kernel is looked for on the main stream: k_compact runs beside k_sim and k_merge on
+    # the second stream, so its elapsed time is the time it shares the memory system, not a cost of its own.
+    on_main = {k: v for k, v in timing.items() if not (stage.side_stream is not None and k == "k_compact")}
+    dominant = max(on_main, key=lambda k: on_main[k][0])
     d_ms, d_n = timing[dominant]
     d_avg_s = 1e-3 * d_ms / d_n
     traffic = MEASURED_TRAFFIC.get(cfg.name, {}).get(dominant)

@@ -149,13 +149,27 @@ asap_status asap_merge(asap_ctx* ctx, const asap_params* p,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * asap_positions -- pos_out and new_len of the output sequence, from the kept set alone.
+ * The stage keeps the survivors in their original order between the preserved prefix and text
+ * (Fig. 3, Sec. 4.2), and with ASAP_ROUTE_ABSORB every kept token survives, so
+ *   pos_out[b,n] = n (n < P);  P + kept_idx[b,n-P] (n < P+k);  P + V + (n-P-k) (n < new_len[b]);  -1 beyond,
+ *   new_len[b]   = P + k + text_len[b]
+ * are known as soon as asap_select has run.  A caller may therefore start asap_compact_kv (on
+ * another stream) before or while asap_merge runs; asap_merge writes the same values into its own
+ * pos_out / new_len.  kept_idx [B,k], text_len [B], pos_out [B,P+k+Tmax], new_len [B], int32, device.
+ * ASAP_EUNSUPPORTED for any other route.
+ */
+asap_status asap_positions(asap_ctx* ctx, const asap_params* p, const int32_t* kept_idx,
+                           const int32_t* text_len, int32_t* pos_out, int32_t* new_len, void* stream);
+
+/*
  * asap_compact_kv -- drops the pruned tokens from the K/V caches of the n_layers layers in
  * front of the pruning layer: for every layer, K and V, image b and kv head g,
  *   dst[b,g,n,:] = src[b,g,pos_out[b,n],:]   for n < new_len[b]      (bit-exact copy)
  * Rows of kept tokens are copied unchanged (only the hidden state is merged).
  * k_src, v_src, k_dst, v_dst: [host] arrays of n_layers DEVICE pointers; src [B,Hkv,N,d],
  * dst [B,Hkv,P+k+Tmax,d], kv_dtype, contiguous, 16-byte aligned; dst must not overlap src.
- * pos_out [B,P+k+Tmax], new_len [B] from asap_merge.  1 <= n_layers <= 64.
+ * pos_out [B,P+k+Tmax], new_len [B] from asap_merge or asap_positions.  1 <= n_layers <= 64.
  */
 asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layers,
                             const void* const* k_src, const void* const* v_src,

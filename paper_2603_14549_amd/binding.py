@@ -21,7 +21,7 @@ ASAP_MASK_OFF, ASAP_MASK_KEYBIAS = 0, 1
 ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
 
 EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
-           "asap_score", "asap_select", "asap_merge", "asap_compact_kv", "asap_timing_enable",
+           "asap_score", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv", "asap_timing_enable",
            "asap_timing_collect"]
 
 _DTYPE_CODE = {"f32": ASAP_F32, "bf16": ASAP_BF16, torch.float32: ASAP_F32, torch.bfloat16: ASAP_BF16}
@@ -81,6 +81,8 @@ def load() -> ctypes.CDLL:
     lib.asap_merge.argtypes = [vp, pp, vp, i64p, f32p, i32p, i32p, i32p, vp, i32p, i32p, i32p, f32p, f32p, i32p,
                                vp, ctypes.c_size_t, vp]
     lib.asap_merge.restype = ctypes.c_int
+    lib.asap_positions.argtypes = [vp, pp, i32p, i32p, i32p, i32p, vp]
+    lib.asap_positions.restype = ctypes.c_int
     lib.asap_compact_kv.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                     ctypes.POINTER(vp), ctypes.POINTER(vp), i32p, i32p, vp]
     lib.asap_compact_kv.restype = ctypes.c_int
@@ -194,6 +196,11 @@ class Context:
             _ptr(best_sim), _ptr(wsum), _ptr(final_idx), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream(stream)))
 
+    def asap_positions(self, p, kept_idx, text_len, pos_out, new_len, stream=None):
+        self._check(self._lib.asap_positions(
+            self._h, ctypes.byref(p), _ptr(kept_idx), _ptr(text_len), _ptr(pos_out), _ptr(new_len),
+            _stream(stream)))
+
     def asap_compact_kv(self, p, k_src: Sequence[torch.Tensor], v_src, k_dst, v_dst, pos_out, new_len,
                         stream=None):
         n = len(k_src)
@@ -219,6 +226,10 @@ class StageBuffers:
         self.out_hidden = torch.zeros(B, Nout, D, dtype=_TORCH_DTYPE[p.h_dtype], device=dev)
         self.pos_out = torch.empty(B, Nout, dtype=i32, device=dev)
         self.new_len = torch.empty(B, dtype=i32, device=dev)
+        # the same two, written by asap_positions right after the selection (read by the K/V
+        # compaction while the merge still runs)
+        self.pos_early = torch.empty(B, Nout, dtype=i32, device=dev)
+        self.new_len_early = torch.empty(B, dtype=i32, device=dev)
         self.assign = torch.empty(B, max(V - k, 1), dtype=i32, device=dev)
         self.best_sim = torch.empty(B, max(V - k, 1), dtype=f32, device=dev)
         self.wsum = torch.empty(B, k, dtype=f32, device=dev)
@@ -231,18 +242,34 @@ class StageBuffers:
 
 def run_stage(ctx: Context, p: asap_params, q: torch.Tensor, k: torch.Tensor, hidden: torch.Tensor,
               text_len: torch.Tensor, k_cache: List[torch.Tensor], v_cache: List[torch.Tensor],
-              buf: StageBuffers, lse_extra: Optional[torch.Tensor] = None, stream=None) -> StageBuffers:
-    """The four calls of one stage, back to back on one stream.  q [B,H,N,d], k [B,Hkv,N,d],
-    hidden [B,N,D]; the visual / text blocks are passed to the library as strided views."""
+              buf: StageBuffers, lse_extra: Optional[torch.Tensor] = None, stream=None,
+              side_stream=None) -> StageBuffers:
+    """The calls of one stage.  q [B,H,N,d], k [B,Hkv,N,d], hidden [B,N,D]; the visual / text blocks
+    are passed to the library as strided views.  With a side stream the K/V compaction, which only
+    needs the positions that follow from the kept set (asap_positions), runs there next to the
+    similarity and merge kernels of the main stream; the main stream waits for it at the end."""
     P, V = p.P, p.V
     q_vis, q_txt, k_vis = q[:, :, P:P + V], q[:, :, P + V:], k[:, :, P:P + V]
+    main = torch.cuda.current_stream() if stream is None else stream
     ctx.asap_score(p, q_vis, q_txt, k_vis, text_len, lse_extra, buf.s_raw, buf.s_hat, buf.score,
-                   buf.workspace, stream)
-    ctx.asap_select(p, buf.score, buf.kept_idx, buf.pruned_idx, buf.workspace, stream)
+                   buf.workspace, main)
+    ctx.asap_select(p, buf.score, buf.kept_idx, buf.pruned_idx, buf.workspace, main)
+    overlap = bool(k_cache) and side_stream is not None
+    if overlap:
+        ctx.asap_positions(p, buf.kept_idx, text_len, buf.pos_early, buf.new_len_early, main)
+        fork = torch.cuda.Event()
+        fork.record(main)
+        side_stream.wait_event(fork)
+        ctx.asap_compact_kv(p, k_cache, v_cache, buf.k_dst, buf.v_dst, buf.pos_early, buf.new_len_early,
+                            side_stream)
     ctx.asap_merge(p, hidden, buf.s_hat, text_len, buf.kept_idx, buf.pruned_idx, buf.out_hidden, buf.pos_out,
-                   buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace, stream)
-    if k_cache:
-        ctx.asap_compact_kv(p, k_cache, v_cache, buf.k_dst, buf.v_dst, buf.pos_out, buf.new_len, stream)
+                   buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace, main)
+    if overlap:
+        join = torch.cuda.Event()
+        join.record(side_stream)
+        main.wait_event(join)
+    elif k_cache:
+        ctx.asap_compact_kv(p, k_cache, v_cache, buf.k_dst, buf.v_dst, buf.pos_out, buf.new_len, main)
     return buf
 
 
@@ -256,9 +283,10 @@ def to_device(arr, dtype: str, device="cuda:0") -> torch.Tensor:
 
 class DeviceStage:
     """One batch from synth.make_inputs uploaded to the GPU, with output buffers; run() makes the
-    four library calls."""
+    library calls of one stage (overlap=True: K/V compaction on a second stream, see run_stage)."""
 
-    def __init__(self, inp: dict, ctx: Optional[Context] = None, lse_extra=None, **param_overrides):
+    def __init__(self, inp: dict, ctx: Optional[Context] = None, lse_extra=None, overlap: bool = True,
+                 **param_overrides):
         import numpy as np
         cfg = inp["cfg"]
         self.cfg = cfg
@@ -272,10 +300,12 @@ class DeviceStage:
         self.v_cache = [to_device(a, cfg.kv_dtype) for a in inp.get("v_cache", [])]
         self.lse_extra = None if lse_extra is None else torch.from_numpy(lse_extra.astype(np.float32)).cuda()
         self.buf = StageBuffers(self.p, len(self.k_cache))
+        # default-priority second stream for the K/V compaction (None = everything on one stream)
+        self.side_stream = torch.cuda.Stream() if (overlap and self.k_cache) else None
 
     def run_async(self) -> StageBuffers:
         return run_stage(self.ctx, self.p, self.q, self.k, self.hidden, self.text_len, self.k_cache,
-                         self.v_cache, self.buf, self.lse_extra)
+                         self.v_cache, self.buf, self.lse_extra, side_stream=self.side_stream)
 
     def run(self) -> StageBuffers:
         self.run_async()

@@ -277,6 +277,19 @@ asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, 
                     "asap_merge launch");
 }
 
+asap_status asap_positions(asap_ctx* ctx, const asap_params* p, const int32_t* kept_idx, const int32_t* text_len,
+                           int32_t* pos_out, int32_t* new_len, void* stream) {
+  asap_status st = common_checks(ctx, p);
+  if (st != ASAP_OK) return st;
+  if (p->route != ASAP_ROUTE_ABSORB)
+    return fail(ctx, ASAP_EUNSUPPORTED, "asap_positions: the positions follow from the kept set only with ASAP_ROUTE_ABSORB");
+  if (!kept_idx || !text_len || !pos_out || !new_len)
+    return fail(ctx, ASAP_EINVAL, "asap_positions: a required pointer is NULL");
+  return hip_result(ctx, launch_positions(*p, kept_idx, text_len, pos_out, new_len, static_cast<hipStream_t>(stream),
+                                          ctx->timer),
+                    "asap_positions launch");
+}
+
 asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layers, const void* const* k_src,
                             const void* const* v_src, void* const* k_dst, void* const* v_dst,
                             const int32_t* pos_out, const int32_t* new_len, void* stream) {

@@ -1,6 +1,7 @@
 // asap_compact_kv: gathers the K/V rows of the surviving positions of every cached layer
 // (KV-cache compatibility of the pruning stage).  Pure data movement, bit-exact.
 //
+// k_positions: grid (ceil(Nout / 256), B): the positions the compaction gathers, from the kept set alone.
 // k_compact: grid (ceil(Nout / ROWS_PER_BLOCK), B * Hkv, 2 * layers_in_launch), 256 threads.
 // A row is d elements = LPR 16-byte pieces; LPR consecutive lanes move one row.
 #include "asap_device.hpp"
@@ -38,6 +39,29 @@ __global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t*
     int nrow = base + i * rpi;
     if (nrow < nl) stg16_stream(dst + (int64_t)nrow * row_bytes, v[i]);
   }
+}
+
+// Output order of the stage (Fig. 3, Sec. 4.2): prefix | kept tokens in original order | valid text.
+__global__ __launch_bounds__(256) void k_positions(const int32_t* __restrict__ kept, const int32_t* __restrict__ text_len,
+                                                    int P, int V, int k, int Nout, int32_t* __restrict__ pos_out,
+                                                    int32_t* __restrict__ new_len) {
+  const int b = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;
+  const int len = text_len[b];
+  if (n == 0) new_len[b] = P + k + len;
+  if (n >= Nout) return;
+  int pos;
+  if (n < P) pos = n;
+  else if (n < P + k) pos = P + kept[(int64_t)b * k + (n - P)];
+  else pos = (n - P - k < len) ? P + V + (n - P - k) : -1;
+  pos_out[(int64_t)b * Nout + n] = pos;
+}
+
+hipError_t launch_positions(const asap_params& p, const int32_t* kept, const int32_t* text_len, int32_t* pos_out,
+                            int32_t* new_len, hipStream_t st, Timer* tm) {
+  const int Nout = p.P + p.k + p.Tmax;
+  ASAP_LAUNCH(tm, "k_positions", k_positions, dim3((Nout + 255) / 256, p.B), dim3(256), 0, st, kept, text_len, p.P,
+              p.V, p.k, Nout, pos_out, new_len);
+  return hipGetLastError();
 }
 
 hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* const* k_src,

@@ -76,6 +76,9 @@ hipError_t launch_similarity(const asap_params& p, const void* hidden, int64_t h
                              const int32_t* kept, const int32_t* pruned, int32_t* assign, float* best_sim,
                              char* ws, hipStream_t st, Timer* tm);
 
+hipError_t launch_positions(const asap_params& p, const int32_t* kept, const int32_t* text_len, int32_t* pos_out,
+                            int32_t* new_len, hipStream_t st, Timer* tm);
+
 hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* const* k_src,
                              const void* const* v_src, void* const* k_dst, void* const* v_dst,
                              const int32_t* pos_out, const int32_t* new_len, hipStream_t st, Timer* tm);

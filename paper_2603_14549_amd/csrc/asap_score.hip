@@ -226,8 +226,10 @@ __global__ __launch_bounds__(256) void k_mass(const T* __restrict__ kv, Strides3
 template <int CH>
 __device__ __forceinline__ void load_key_tile(uint4 (&kb)[CH], const char* krow) {
 #pragma unroll
-  for (int c = 0; c < CH; ++c) kb[c] = ldg16(krow + c * 16);
+  for (int c = 0; c < CH; ++c) kb[c] = ldg16(krow + c * 32);
 }
+
+constexpr int MASS_TILES_PER_WG = 1;   // key tiles a workgroup takes one after the other
 
 template <int CH>
 __global__ __launch_bounds__(256) void k_mass_mfma(const bf16_t* __restrict__ kv, Strides3 sk,
@@ -239,51 +241,57 @@ __global__ __launch_bounds__(256) void k_mass_mfma(const bf16_t* __restrict__ kv
   __shared__ unsigned long long blk_mm[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hf = lane >> 5;
-  const int b = blockIdx.y, j = blockIdx.x * 32 + n;
+  const int b = blockIdx.y;
   if (tid == 0) { blk_mm[0] = ~0ull; blk_mm[1] = 0ull; }
-  const char* kbase = reinterpret_cast<const char*>(kv + b * sk.b) + (int64_t)min(j, V - 1) * sk.r * 2 + hf * (CH * 16);
   const int64_t headb = sk.h * 2;
   // lane (m, hf) with m < 4 supplies piece m of qbar_g, half hf of the components
-  const char* qbase = reinterpret_cast<const char*>(qsplit + ((int64_t)b * Hkv * 4 + (n & 3)) * D) + hf * (CH * 16);
+  const char* qbase = reinterpret_cast<const char*>(qsplit + ((int64_t)b * Hkv * 4 + (n & 3)) * D) + hf * 16;
   const int64_t qheadb = (int64_t)4 * D * 2;
   const bool has_q = n < 4;
-  uint4 qa[CH], qn[CH], kb[CH], kn[CH];
-#pragma unroll
-  for (int c = 0; c < CH; ++c) qa[c] = qn[c] = make_uint4(0, 0, 0, 0);
-  int g = wave;
-  if (g < Hkv) {
-    load_key_tile<CH>(kb, kbase + g * headb);
-    if (has_q) load_key_tile<CH>(qa, qbase + g * qheadb);
-  }
-  double sum = 0.0;
-  for (; g < Hkv; g += 4) {
-    const int gn = g + 4;
-    if (gn < Hkv) {
-      load_key_tile<CH>(kn, kbase + gn * headb);
-      if (has_q) load_key_tile<CH>(qn, qbase + gn * qheadb);
-    }
-    f32x16_t acc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) mma32<bf16_t>(acc, qa[c], kb[c]);
-    sum += ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);   // rows 0..3 (lanes < 32)
-    if (gn < Hkv) {
-#pragma unroll
-      for (int c = 0; c < CH; ++c) { kb[c] = kn[c]; qa[c] = qn[c]; }
-    }
-  }
-  if (hf == 0) part[wave][n] = sum;
-  __syncthreads();
   unsigned long long kmin = ~0ull, kmax = 0ull;
-  const bool writer = tid < 32 && j < V;
-  if (writer) {
-    double s = (((part[0][n] + part[1][n]) + part[2][n]) + part[3][n]) * scale;
-    s64[(int64_t)b * V + j] = s;
-    s_raw[(int64_t)b * V + j] = (float)s;
-    kmin = kmax = f64_key(s);
+  for (int tt = 0; tt < MASS_TILES_PER_WG; ++tt) {
+    const int tile = blockIdx.x * MASS_TILES_PER_WG + tt;
+    if (tile * 32 >= V) break;
+    const int j = tile * 32 + n;
+    const char* kbase =
+        reinterpret_cast<const char*>(kv + b * sk.b) + (int64_t)min(j, V - 1) * sk.r * 2 + hf * 16;
+    uint4 qa[CH], kb[CH], kn[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) qa[c] = make_uint4(0, 0, 0, 0);
+    int g = wave;
+    if (g < Hkv) {
+      load_key_tile<CH>(kb, kbase + g * headb);
+      if (has_q) load_key_tile<CH>(qa, qbase + g * qheadb);
+    }
+    double sum = 0.0;
+    for (; g < Hkv; g += 4) {
+      const int gn = g + 4;
+      if (gn < Hkv) load_key_tile<CH>(kn, kbase + gn * headb);
+      f32x16_t acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) mma32<bf16_t>(acc, qa[c], kb[c]);
+      sum += ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);   // rows 0..3 (lanes < 32)
+      if (gn < Hkv) {
+        if (has_q) load_key_tile<CH>(qa, qbase + gn * qheadb);      // small, cached: not worth registers of its own
+#pragma unroll
+        for (int c = 0; c < CH; ++c) kb[c] = kn[c];
+      }
+    }
+    if (tt) __syncthreads();            // the previous tile's sums have been read
+    if (hf == 0) part[wave][n] = sum;
+    __syncthreads();
+    if (tid < 32 && j < V) {
+      double s = (((part[0][n] + part[1][n]) + part[2][n]) + part[3][n]) * scale;
+      s64[(int64_t)b * V + j] = s;
+      s_raw[(int64_t)b * V + j] = (float)s;
+      const unsigned long long key = f64_key(s);
+      kmin = key < kmin ? key : kmin;
+      kmax = key > kmax ? key : kmax;
+    }
   }
-  publish_minmax(kmin, kmax, writer, blk_mm, mmkey, b);
+  publish_minmax(kmin, kmax, tid < 32, blk_mm, mmkey, b);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -291,8 +299,9 @@ __global__ __launch_bounds__(256) void k_mass_mfma(const bf16_t* __restrict__ kv
 //   RB = 32-row blocks of text queries (Tmax <= 32*RB); CH = 16-byte chunks of a row per lane half
 //   (row bytes = 32*CH); QREG: the queries stay in registers as MFMA operands (else in LDS).
 // Every wave streams its own 32-key tiles of the split's key range straight from global memory:
-// lane (n, hf) of a tile reads the half row [hf*16*CH, +16*CH) bytes of key n, the query side holds
-// the same half of its row, so a chunk pair covers the same contraction slice.
+// lane (n, hf) of a tile reads the 16-byte pieces 2c + hf (c < CH) of key n -- the two lanes of a key
+// take 32 contiguous bytes per load, which halves the cache lines a load instruction touches -- and
+// the query side holds the same pieces of its row, so a chunk pair covers the same contraction slice.
 // ------------------------------------------------------------------------------------------
 struct AttnArgs {
   const void* qt; Strides3 sq;          // [B,H,Tmax,d]
@@ -316,13 +325,13 @@ template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, true> {
   __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char*) {
     const int m = lane & 31, hf = lane >> 5;
     const char* qbase = reinterpret_cast<const char*>(static_cast<const T*>(a.qt) + b * a.sq.b + h * a.sq.h) +
-                        hf * (CH * 16);
+                        hf * 16;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       const int row = rb * 32 + m;
 #pragma unroll
       for (int c = 0; c < CH; ++c)
-        qa[rb][c] = row < a.Tmax ? ldg16(qbase + (int64_t)row * a.sq.r * sizeof(T) + c * 16) : make_uint4(0, 0, 0, 0);
+        qa[rb][c] = row < a.Tmax ? ldg16(qbase + (int64_t)row * a.sq.r * sizeof(T) + c * 32) : make_uint4(0, 0, 0, 0);
     }
   }
   __device__ __forceinline__ uint4 get(int rb, int c) const { return qa[rb][c]; }
@@ -341,10 +350,10 @@ template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, false> {
       *reinterpret_cast<uint4*>(lds + row * LDSROW + pc * 16) = v;
     }
     __syncthreads();
-    qa = lds + (lane & 31) * LDSROW + (lane >> 5) * (CH * 16);
+    qa = lds + (lane & 31) * LDSROW + (lane >> 5) * 16;
   }
   __device__ __forceinline__ uint4 get(int rb, int c) const {
-    return *reinterpret_cast<const uint4*>(qa + rb * 32 * LDSROW + c * 16);
+    return *reinterpret_cast<const uint4*>(qa + rb * 32 * LDSROW + c * 32);
   }
   static constexpr size_t lds_bytes() { return (size_t)RB * 32 * LDSROW; }
 };
@@ -381,7 +390,7 @@ __global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_st
   const double mlo = f64_unkey(a.mmkey[2 * b]), mhi = f64_unkey(a.mmkey[2 * b + 1]);
   const double minv = 1.0 / (mhi - mlo + a.eps);
   const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.kv) + b * a.sk.b + g * a.sk.h) +
-                      hf * (CH * 16);
+                      hf * 16;
   const int64_t krow_bytes = a.sk.r * (int64_t)sizeof(T);
   const int ntiles = (a.V + 31) >> 5;
   const int t_end = min(ntiles, (sp + 1) * a.tiles_per_split);
@@ -501,7 +510,7 @@ __global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_co
       inv[rb][v] = fin_i[row];
     }
   const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.kv) + b * a.sk.b + g * a.sk.h) +
-                      hf * (CH * 16);
+                      hf * 16;
   const int64_t krow_bytes = a.sk.r * (int64_t)sizeof(T);
   const int ntiles = (a.V + 31) >> 5;
   const int t_end = min(ntiles, (sp + 1) * a.tiles_per_split);
@@ -670,10 +679,10 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   if constexpr (E == 8) {
     const bf16_t* kp = static_cast<const bf16_t*>(k_vis);
     if (ch == 8)
-      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<8>, dim3(ktiles, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
+      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<8>, dim3((ktiles + MASS_TILES_PER_WG - 1) / MASS_TILES_PER_WG, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
                   s64, s_raw, mmkey);
     else
-      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<4>, dim3(ktiles, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
+      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<4>, dim3((ktiles + MASS_TILES_PER_WG - 1) / MASS_TILES_PER_WG, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
                   s64, s_raw, mmkey);
   } else {
     ASAP_LAUNCH(tm, "k_mass", k_mass<T>, dim3(ktiles, p.B), dim3(256), sizeof(double) * p.Hkv * p.d, st,

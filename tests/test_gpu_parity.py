@@ -111,6 +111,31 @@ def test_determinism(ctx):
                                t.view(torch.uint8) if t.is_floating_point() else t), n
 
 
+def test_positions_and_two_stream_stage(ctx):
+    """asap_positions writes what asap_merge writes, and the stage with the K/V compaction on a
+    second stream gives bit-identical results to the stage on one stream."""
+    cfg = synth.CONFIGS["S3"]
+    inp = synth.make_inputs(cfg)
+    serial = U.GpuStage(inp, ctx=ctx, overlap=False)
+    bs = serial.run()
+    both = U.GpuStage(inp, ctx=ctx, overlap=True)
+    assert both.side_stream is not None
+    for _ in range(3):
+        bo = both.run()
+        assert torch.equal(bo.pos_early, bs.pos_out) and torch.equal(bo.new_len_early, bs.new_len)
+        assert torch.equal(bo.pos_out, bs.pos_out) and torch.equal(bo.new_len, bs.new_len)
+        for l in range(len(bs.k_dst)):
+            for b in range(cfg.B):
+                nl = int(bs.new_len[b])
+                assert torch.equal(bo.k_dst[l][b, :, :nl].view(torch.uint8), bs.k_dst[l][b, :, :nl].view(torch.uint8))
+                assert torch.equal(bo.v_dst[l][b, :, :nl].view(torch.uint8), bs.v_dst[l][b, :, :nl].view(torch.uint8))
+        assert torch.equal(bo.out_hidden.view(torch.uint8), bs.out_hidden.view(torch.uint8))
+    p = binding.params_from_config(cfg, route=binding.ASAP_ROUTE_PAPER)
+    with pytest.raises(binding.AsapError) as e:       # positions need the merge result with that route
+        ctx.asap_positions(p, bs.kept_idx, serial.text_len, bs.pos_early, bs.new_len_early)
+    assert e.value.status == binding.ASAP_EUNSUPPORTED
+
+
 def test_strided_views_and_errors(ctx):
     cfg = synth.CONFIGS["S0"]
     inp = synth.make_inputs(cfg)
