@@ -70,7 +70,7 @@ def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
     return {"per_kernel": per_kernel, "stage": stage, "sim_flops": 2.0 * B * (V - k) * k * D}
 
 
-def cpu_baseline(inp, cfg, budget_s: float = 12.0) -> dict:
+def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb") -> dict:
     """The oracle as it stands, timed on the host on the first few images of the batch."""
     from oracle import asap_oracle as O          # only this leg touches the oracle
     from paper_2603_14549_amd import synth
@@ -85,7 +85,7 @@ def cpu_baseline(inp, cfg, budget_s: float = 12.0) -> dict:
         b = done % cfg.B
         ref = O.stage(synth.to_f64(inp["q"][b], cfg.qk_dtype), synth.to_f64(inp["k"][b], cfg.qk_dtype),
                       synth.to_f64(inp["hidden"][b], cfg.h_dtype), int(inp["text_len"][b]), cfg.P, cfg.V,
-                      cfg.Tmax, cfg.k, linear_mass=True)
+                      cfg.Tmax, cfg.k, linear_mass=True, route=route)
         for l in range(cfg.L_kv):
             for cache in (inp["k_cache"][l], inp["v_cache"][l]):
                 O.gather_kv(cache[b], ref["pos_out"], ref["new_len"])
@@ -103,6 +103,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C6")
+    ap.add_argument("--route", choices=["absorb", "paper"], default="absorb",
+                    help="absorb (default, the headline workload): pruned -> kept routing; paper: Sec. 4.2 as "
+                         "written, routing inside the kept set + refill (threshold 0.8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (reference for HBM counters)")
@@ -124,7 +127,9 @@ def main():
     inp = synth.make_inputs(cfg)
     gen_s = time.perf_counter() - t0
     ctx = binding.Context(0)
-    stage = binding.DeviceStage(inp, ctx=ctx)
+    paper = args.route == "paper"
+    overrides = dict(route=binding.ASAP_ROUTE_PAPER, sim_threshold=0.8) if paper else {}
+    stage = binding.DeviceStage(inp, ctx=ctx, **overrides)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -156,6 +161,18 @@ def main():
 
     mean_text = float(np.mean(inp["text_len"]))
     alg = algorithmic_bytes(cfg, mean_text, cfg.L_kv)
+    if paper:
+        # kept x kept search; the merge reads the k final rows and the rows they absorb (counted from the run)
+        eh = esize(cfg.h_dtype)
+        n_src = int((stage.buf.assign.flatten()[:cfg.B * cfg.k] >= 0).sum())
+        kept_rows = cfg.B * cfg.k * cfg.D * eh
+        old_sim, old_merge = alg["per_kernel"]["k_sim"], alg["per_kernel"]["k_merge"]
+        alg["per_kernel"]["k_sim"] = kept_rows + 8 * cfg.B * cfg.k
+        alg["per_kernel"]["k_merge"] = old_merge - cfg.B * cfg.V * cfg.D * eh + kept_rows + n_src * cfg.D * eh
+        alg["per_kernel"]["k_paper_plan"] = 12 * cfg.B * cfg.k + 4 * cfg.B * cfg.V
+        alg["stage"] += (alg["per_kernel"]["k_sim"] - old_sim) + (alg["per_kernel"]["k_merge"] - old_merge) \
+            + alg["per_kernel"]["k_paper_plan"]
+        alg["sim_flops"] = 2.0 * cfg.B * cfg.k * cfg.k * cfg.D
     kernels = {}
     for name, (ms, n) in timing.items():
         avg_us = 1e3 * ms / n
@@ -170,7 +187,7 @@ def main():
     dominant = max(on_main, key=lambda k: on_main[k][0])
     d_ms, d_n = timing[dominant]
     d_avg_s = 1e-3 * d_ms / d_n
-    traffic = MEASURED_TRAFFIC.get(cfg.name, {}).get(dominant)
+    traffic = None if paper else MEASURED_TRAFFIC.get(cfg.name, {}).get(dominant)   # measured for the default route
     if dominant == "k_sim" and cfg.V > cfg.k:
         flops = alg["sim_flops"] * args.steps / d_n
         peak = MFMA_PEAK[cfg.h_dtype]
@@ -201,7 +218,8 @@ def main():
         "config": {"workload": f"{cfg.name}: B={cfg.B}, {cfg.P} prefix + {cfg.V} visual + {cfg.Tmax} text tokens, "
                                f"hidden {cfg.D}, {cfg.H}/{cfg.Hkv} heads x {cfg.d}, keep {cfg.k}, "
                                f"qk/hidden/kv dtypes {cfg.qk_dtype}/{cfg.h_dtype}/{cfg.kv_dtype}, "
-                               f"{cfg.L_kv} K/V layers, mask=keybias, route=absorb, mu=1",
+                               f"{cfg.L_kv} K/V layers, mask=keybias, route={args.route}"
+                               f"{' (t=0.8)' if paper else ''}, mu=1",
                    "input_generation_s": round(gen_s, 1)},
         "roofline": roofline,
         "stage_roofline": stage_roofline,
@@ -209,7 +227,7 @@ def main():
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(inp, cfg)
+        out["cpu_baseline"] = cpu_baseline(inp, cfg, route=args.route)
     print(json.dumps(out))
 
 

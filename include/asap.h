@@ -51,7 +51,10 @@ typedef enum { ASAP_F32 = 0, ASAP_BF16 = 1 } asap_dtype;
 typedef enum { ASAP_MASK_OFF = 0, ASAP_MASK_KEYBIAS = 1 } asap_mask_mode;
 
 /* ABSORB: every pruned token is routed to its most similar kept token.
- * PAPER:  Sec. 4.2 routing inside the kept set + budget reallocation (not built: EUNSUPPORTED). */
+ * PAPER: the consolidation of Sec. 4.2 as written -- redundancy is removed inside the kept set
+ * (a kept token merges into a more salient, sufficiently similar kept token) and the vacated
+ * slots are refilled with the pruned tokens of largest raw mass; see asap_merge.
+ * PAPER needs k <= V / 2. */
 typedef enum { ASAP_ROUTE_ABSORB = 0, ASAP_ROUTE_PAPER = 1 } asap_route;
 
 typedef struct {
@@ -125,7 +128,7 @@ asap_status asap_select(asap_ctx* ctx, const asap_params* p, const float* score,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * asap_merge -- Sec. 4.2 with ABSORB routing, Eq. 6, and the output sequence.
+ * asap_merge -- Sec. 4.2 routing, Eq. 6, and the output sequence.  With ASAP_ROUTE_ABSORB:
  *   c(j,i)    = x_j . x_i / (max(|x_j|,1e-8) max(|x_i|,1e-8))   for pruned j, kept i (hidden states)
  *   assign[j] = slot (0..k-1, position in kept_idx) of the kept token with the largest c(j,.),
  *               ties to the smaller slot; -1 if that c <= sim_threshold.  best_sim[j] = that c.
@@ -139,10 +142,24 @@ asap_status asap_select(asap_ctx* ctx, const asap_params* p, const float* score,
  * Dot products run on the matrix cores in the input precision (bf16 x bf16 or f32 x f32) with fp32
  * accumulation; Eq. 6 accumulates in fp32 and rounds once (nearest-even) to h_dtype.
  * assign [B,V-k] int32, best_sim [B,V-k] f32, wsum [B,k] f32, final_idx [B,k] int32 (= kept_idx here).
+ * s_raw [B,V] f32 from asap_score is read only with ASAP_ROUTE_PAPER (NULL allowed otherwise).
+ *
+ * With ASAP_ROUTE_PAPER (Sec. 4.2 as written), for kept tokens i, j with cosine c(j,i) as above:
+ *   j is a source iff some kept i has c(j,i) > sim_threshold and is stronger than j
+ *     (s_hat_i > s_hat_j, ties to the smaller index); it goes to the most similar such i (ties to
+ *     the smaller index) and chains are followed to their root, so each tree merges into one token
+ *     that is not itself a source;
+ *   the a vacated slots are refilled with the a pruned tokens of largest s_raw (ties to the
+ *     smaller index), which stay unmerged;
+ *   final_idx [B,k] = roots and refills, ascending; Eq. 6 over each root's tree; output sequence,
+ *     pos_out, new_len as above with final_idx in the place of kept_idx.
+ *   assign and best_sim then describe the kept tokens, laid out [B,k] at the start of the buffers:
+ *     assign[b,a] = slot in final_idx of the root that absorbs kept_idx[b,a], -1 if it survives;
+ *     best_sim[b,a] = cosine to its immediate destination (the best stronger token), -inf if none.
  */
 asap_status asap_merge(asap_ctx* ctx, const asap_params* p,
                        const void* hidden, const int64_t hidden_stride[2],
-                       const float* s_hat, const int32_t* text_len,
+                       const float* s_raw, const float* s_hat, const int32_t* text_len,
                        const int32_t* kept_idx, const int32_t* pruned_idx,
                        void* out_hidden, int32_t* pos_out, int32_t* new_len,
                        int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx,

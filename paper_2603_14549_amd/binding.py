@@ -78,7 +78,7 @@ def load() -> ctypes.CDLL:
     lib.asap_score.restype = ctypes.c_int
     lib.asap_select.argtypes = [vp, pp, f32p, i32p, i32p, vp, ctypes.c_size_t, vp]
     lib.asap_select.restype = ctypes.c_int
-    lib.asap_merge.argtypes = [vp, pp, vp, i64p, f32p, i32p, i32p, i32p, vp, i32p, i32p, i32p, f32p, f32p, i32p,
+    lib.asap_merge.argtypes = [vp, pp, vp, i64p, f32p, f32p, i32p, i32p, i32p, vp, i32p, i32p, i32p, f32p, f32p, i32p,
                                vp, ctypes.c_size_t, vp]
     lib.asap_merge.restype = ctypes.c_int
     lib.asap_positions.argtypes = [vp, pp, i32p, i32p, i32p, i32p, vp]
@@ -188,10 +188,10 @@ class Context:
             self._h, ctypes.byref(p), _ptr(score), _ptr(kept_idx), _ptr(pruned_idx), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream(stream)))
 
-    def asap_merge(self, p, hidden, s_hat, text_len, kept_idx, pruned_idx, out_hidden, pos_out, new_len,
+    def asap_merge(self, p, hidden, s_raw, s_hat, text_len, kept_idx, pruned_idx, out_hidden, pos_out, new_len,
                    assign, best_sim, wsum, final_idx, workspace, stream=None):
         self._check(self._lib.asap_merge(
-            self._h, ctypes.byref(p), _ptr(hidden), _strides(hidden, 2), _ptr(s_hat), _ptr(text_len),
+            self._h, ctypes.byref(p), _ptr(hidden), _strides(hidden, 2), _ptr(s_raw), _ptr(s_hat), _ptr(text_len),
             _ptr(kept_idx), _ptr(pruned_idx), _ptr(out_hidden), _ptr(pos_out), _ptr(new_len), _ptr(assign),
             _ptr(best_sim), _ptr(wsum), _ptr(final_idx), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream(stream)))
@@ -230,7 +230,7 @@ class StageBuffers:
         # compaction while the merge still runs)
         self.pos_early = torch.empty(B, Nout, dtype=i32, device=dev)
         self.new_len_early = torch.empty(B, dtype=i32, device=dev)
-        self.assign = torch.empty(B, max(V - k, 1), dtype=i32, device=dev)
+        self.assign = torch.empty(B, max(V - k, 1), dtype=i32, device=dev)      # paper route: [B,k] at the start
         self.best_sim = torch.empty(B, max(V - k, 1), dtype=f32, device=dev)
         self.wsum = torch.empty(B, k, dtype=f32, device=dev)
         self.final_idx = torch.empty(B, k, dtype=i32, device=dev)
@@ -254,7 +254,7 @@ def run_stage(ctx: Context, p: asap_params, q: torch.Tensor, k: torch.Tensor, hi
     ctx.asap_score(p, q_vis, q_txt, k_vis, text_len, lse_extra, buf.s_raw, buf.s_hat, buf.score,
                    buf.workspace, main)
     ctx.asap_select(p, buf.score, buf.kept_idx, buf.pruned_idx, buf.workspace, main)
-    overlap = bool(k_cache) and side_stream is not None
+    overlap = bool(k_cache) and side_stream is not None and p.route == ASAP_ROUTE_ABSORB
     if overlap:
         ctx.asap_positions(p, buf.kept_idx, text_len, buf.pos_early, buf.new_len_early, main)
         fork = torch.cuda.Event()
@@ -262,7 +262,7 @@ def run_stage(ctx: Context, p: asap_params, q: torch.Tensor, k: torch.Tensor, hi
         side_stream.wait_event(fork)
         ctx.asap_compact_kv(p, k_cache, v_cache, buf.k_dst, buf.v_dst, buf.pos_early, buf.new_len_early,
                             side_stream)
-    ctx.asap_merge(p, hidden, buf.s_hat, text_len, buf.kept_idx, buf.pruned_idx, buf.out_hidden, buf.pos_out,
+    ctx.asap_merge(p, hidden, buf.s_raw, buf.s_hat, text_len, buf.kept_idx, buf.pruned_idx, buf.out_hidden, buf.pos_out,
                    buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace, main)
     if overlap:
         join = torch.cuda.Event()

@@ -52,6 +52,7 @@ asap_status check_params(const asap_params* p, char* msg, size_t n) {
   BAD(!(p->merge_weight >= 0.0f) || !isfinite(p->merge_weight), "merge_weight must be finite and >= 0");
   BAD(p->mask_mode != ASAP_MASK_OFF && p->mask_mode != ASAP_MASK_KEYBIAS, "unknown mask_mode");
   BAD(p->route != ASAP_ROUTE_ABSORB && p->route != ASAP_ROUTE_PAPER, "unknown route");
+  BAD(p->route == ASAP_ROUTE_PAPER && 2 * (int64_t)p->k > p->V, "ASAP_ROUTE_PAPER needs k <= V / 2 (the vacated slots are refilled from the pruned tokens)");
   BAD((int64_t)p->B * p->Hkv > 65535 || (int64_t)p->B * p->H > 65535, "B * heads must be <= 65535");
 #undef BAD
   if (msg && n) msg[0] = 0;
@@ -201,7 +202,7 @@ asap_status asap_check_params(const asap_params* p, char* msg, size_t msg_len) {
 
 size_t asap_workspace_bytes(const asap_params* p) {
   if (check_params(p, nullptr, 0) != ASAP_OK) return 0;
-  size_t a = score_workspace(*p).total, b = sim_workspace_bytes(*p);
+  size_t a = score_workspace(*p).total, b = paper_workspace_bytes(*p);
   return a > b ? a : b;
 }
 
@@ -244,14 +245,15 @@ asap_status asap_select(asap_ctx* ctx, const asap_params* p, const float* score,
 }
 
 asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, const int64_t hidden_stride[2],
-                       const float* s_hat, const int32_t* text_len, const int32_t* kept_idx,
+                       const float* s_raw, const float* s_hat, const int32_t* text_len, const int32_t* kept_idx,
                        const int32_t* pruned_idx, void* out_hidden, int32_t* pos_out, int32_t* new_len,
                        int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx, void* workspace,
                        size_t workspace_bytes, void* stream) {
   asap_status st = common_checks(ctx, p);
   if (st != ASAP_OK) return st;
-  if (p->route != ASAP_ROUTE_ABSORB)
-    return fail(ctx, ASAP_EUNSUPPORTED, "asap_merge: only ASAP_ROUTE_ABSORB is built");
+  const bool paper = p->route == ASAP_ROUTE_PAPER;
+  if (paper && (!s_raw || !assign || !best_sim))
+    return fail(ctx, ASAP_EINVAL, "asap_merge: ASAP_ROUTE_PAPER needs s_raw, assign and best_sim");
   const bool has_pruned = p->k < p->V;
   if (!hidden || !s_hat || !text_len || !kept_idx || !out_hidden || !pos_out || !new_len || !wsum ||
       !final_idx || (has_pruned && (!pruned_idx || !assign || !best_sim)))
@@ -271,7 +273,7 @@ asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, 
   }
   if ((st = check_workspace(ctx, p, workspace, workspace_bytes)) != ASAP_OK) return st;
   return hip_result(ctx,
-                    launch_merge(*p, hidden, hidden_stride[0], hidden_stride[1], s_hat, text_len, kept_idx,
+                    launch_merge(*p, hidden, hidden_stride[0], hidden_stride[1], s_raw, s_hat, text_len, kept_idx,
                                  pruned_idx, out_hidden, pos_out, new_len, assign, best_sim, wsum, final_idx,
                                  static_cast<char*>(workspace), static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_merge launch");

@@ -64,17 +64,25 @@ hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, co
 hipError_t launch_select(const asap_params& p, const float* score, int32_t* kept, int32_t* pruned,
                          hipStream_t st, Timer* tm);
 
-hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
-                        const float* s_hat, const int32_t* text_len, const int32_t* kept,
-                        const int32_t* pruned, void* out_hidden, int32_t* pos_out, int32_t* new_len,
-                        int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx, char* ws,
-                        hipStream_t st, Timer* tm);
+hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr, const float* s_raw,
+                        const float* s_hat, const int32_t* text_len, const int32_t* kept, const int32_t* pruned,
+                        void* out_hidden, int32_t* pos_out, int32_t* new_len, int32_t* assign, float* best_sim,
+                        float* wsum, int32_t* final_idx, char* ws, hipStream_t st, Timer* tm);
 
-// cosine routing (asap_sim.hip); ws needs sim_workspace_bytes(p)
-size_t sim_workspace_bytes(const asap_params& p);
+// Cosine routing (asap_sim.hip): for each of the M source tokens srcs[b,:] the most similar kept
+// token (slot in kept, -1 if the similarity does not exceed the threshold) and that similarity.
+// anchored: the routing inside the kept set of Sec. 4.2 (srcs = kept, M = k): only destinations
+// stronger than the source count, by s_hat [B,V] and then by index.
 hipError_t launch_similarity(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
-                             const int32_t* kept, const int32_t* pruned, int32_t* assign, float* best_sim,
-                             char* ws, hipStream_t st, Timer* tm);
+                             const int32_t* kept, const int32_t* srcs, int M, bool anchored, const float* s_hat,
+                             int32_t* assign, float* best_sim, hipStream_t st, Timer* tm);
+
+// Second half of the paper's routing (asap_paper.hip): chains of destinations followed to their
+// roots, the vacated slots refilled with the pruned tokens of largest raw mass, the final kept list
+// and, per kept slot, the slot of the final token that absorbs it (-1: it survives).
+size_t paper_workspace_bytes(const asap_params& p);
+hipError_t launch_paper_plan(const asap_params& p, const int32_t* dest, const int32_t* kept, const float* s_raw,
+                             int32_t* final_idx, int32_t* assign, hipStream_t st, Timer* tm);
 
 hipError_t launch_positions(const asap_params& p, const int32_t* kept, const int32_t* text_len, int32_t* pos_out,
                             int32_t* new_len, hipStream_t st, Timer* tm);

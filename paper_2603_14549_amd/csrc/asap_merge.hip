@@ -1,8 +1,11 @@
 // asap_merge: the salience-weighted convex merge of Eq. 6 and the output sequence
-// [prefix | merged kept | text], after the cosine routing of asap_sim.hip.
+// [prefix | merged kept | text], after the cosine routing of asap_sim.hip (and, for the paper's
+// routing inside the kept set, the plan of asap_paper.hip).
 //
-//   k_merge<T>    one workgroup per output row: copies prefix / text rows, and for a kept
-//                 slot gathers its sources in ascending order and applies Eq. 6.
+//   k_merge<T>    one workgroup per output row: copies prefix / text rows, and for a final
+//                 slot gathers its sources in ascending order and applies Eq. 6.  The sources are
+//                 M candidate tokens with assign[] = the slot that absorbs each (or -1): the
+//                 pruned tokens with ABSORB routing, the kept tokens with the paper's.
 #include "asap_device.hpp"
 #include "asap_launch.hpp"
 
@@ -15,7 +18,7 @@ constexpr int MERGE_SEG = 2048;   // entries of assign[] scanned per round
 
 template <typename T, int CPT>    // CPT = 16-byte chunks of a row per thread (row = D elements)
 __global__ __launch_bounds__(256) void k_merge(const T* __restrict__ hidden, int64_t sb, int64_t sr, int D,
-                                                int P, int V, int k, int Tmax, float mu,
+                                                int P, int V, int k, int M, int Tmax, float mu,
                                                 const float* __restrict__ s_hat, const int32_t* __restrict__ text_len,
                                                 const int32_t* __restrict__ kept, const int32_t* __restrict__ pruned,
                                                 const int32_t* __restrict__ assign, T* __restrict__ out,
@@ -49,7 +52,6 @@ __global__ __launch_bounds__(256) void k_merge(const T* __restrict__ hidden, int
   }
 
   const int slot = nrow - P;
-  const int M = V - k;
   const int i_tok = kept[(int64_t)b * k + slot];
   const float* sh = s_hat + (int64_t)b * V;
   const float w_i = sh[i_tok];
@@ -160,9 +162,8 @@ __global__ __launch_bounds__(256) void k_merge(const T* __restrict__ hidden, int
 template <typename T>
 static hipError_t merge_typed(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
                               const float* s_hat, const int32_t* text_len, const int32_t* kept,
-                              const int32_t* pruned, void* out_hidden, int32_t* pos_out, int32_t* new_len,
-                              int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx,
-                              hipStream_t st, Timer* tm) {
+                              const int32_t* cand, int M, void* out_hidden, int32_t* pos_out, int32_t* new_len,
+                              int32_t* assign, float* wsum, int32_t* final_idx, hipStream_t st, Timer* tm) {
   const T* h = static_cast<const T*>(hidden);
   constexpr int E = elem<T>::per16;
   const int nchunks = p.D / E;
@@ -170,7 +171,7 @@ static hipError_t merge_typed(const asap_params& p, const void* hidden, int64_t 
   dim3 grid(p.P + p.k + p.Tmax, p.B);
 #define ASAP_MERGE(CPT)                                                                                    \
   ASAP_LAUNCH(tm, "k_merge", (k_merge<T, CPT>), grid, dim3(256), 0, st, h, hsb, hsr, p.D, p.P, p.V, p.k,   \
-              p.Tmax, p.merge_weight, s_hat, text_len, kept, pruned, assign, static_cast<T*>(out_hidden),  \
+              M, p.Tmax, p.merge_weight, s_hat, text_len, kept, cand, assign, static_cast<T*>(out_hidden), \
               pos_out, new_len, wsum, final_idx)
   if (cpt <= 1) ASAP_MERGE(1);
   else if (cpt <= 2) ASAP_MERGE(2);
@@ -181,20 +182,33 @@ static hipError_t merge_typed(const asap_params& p, const void* hidden, int64_t 
   return hipGetLastError();
 }
 
-hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
-                        const float* s_hat, const int32_t* text_len, const int32_t* kept,
-                        const int32_t* pruned, void* out_hidden, int32_t* pos_out, int32_t* new_len,
-                        int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx, char* ws,
-                        hipStream_t st, Timer* tm) {
-  if (p.V > p.k) {
-    hipError_t e = launch_similarity(p, hidden, hsb, hsr, kept, pruned, assign, best_sim, ws, st, tm);
+hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr, const float* s_raw,
+                        const float* s_hat, const int32_t* text_len, const int32_t* kept, const int32_t* pruned,
+                        void* out_hidden, int32_t* pos_out, int32_t* new_len, int32_t* assign, float* best_sim,
+                        float* wsum, int32_t* final_idx, char* ws, hipStream_t st, Timer* tm) {
+  const bool bf = p.h_dtype == ASAP_BF16;
+  if (p.route == ASAP_ROUTE_PAPER) {
+    // kept x kept search (destinations into the workspace) -> roots, refills, final list -> merge
+    // with the kept tokens as candidates and the final list in the place of the kept list
+    int32_t* dest = reinterpret_cast<int32_t*>(ws);
+    hipError_t e = launch_similarity(p, hidden, hsb, hsr, kept, kept, p.k, true, s_hat, dest, best_sim, st, tm);
+    if (e != hipSuccess) return e;
+    e = launch_paper_plan(p, dest, kept, s_raw, final_idx, assign, st, tm);
+    if (e != hipSuccess) return e;
+    return bf ? merge_typed<bf16_t>(p, hidden, hsb, hsr, s_hat, text_len, final_idx, kept, p.k, out_hidden, pos_out,
+                                    new_len, assign, wsum, final_idx, st, tm)
+              : merge_typed<float>(p, hidden, hsb, hsr, s_hat, text_len, final_idx, kept, p.k, out_hidden, pos_out,
+                                   new_len, assign, wsum, final_idx, st, tm);
+  }
+  const int M = p.V - p.k;
+  if (M > 0) {
+    hipError_t e = launch_similarity(p, hidden, hsb, hsr, kept, pruned, M, false, s_hat, assign, best_sim, st, tm);
     if (e != hipSuccess) return e;
   }
-  if (p.h_dtype == ASAP_BF16)
-    return merge_typed<bf16_t>(p, hidden, hsb, hsr, s_hat, text_len, kept, pruned, out_hidden, pos_out,
-                               new_len, assign, best_sim, wsum, final_idx, st, tm);
-  return merge_typed<float>(p, hidden, hsb, hsr, s_hat, text_len, kept, pruned, out_hidden, pos_out, new_len,
-                            assign, best_sim, wsum, final_idx, st, tm);
+  return bf ? merge_typed<bf16_t>(p, hidden, hsb, hsr, s_hat, text_len, kept, pruned, M, out_hidden, pos_out, new_len,
+                                  assign, wsum, final_idx, st, tm)
+            : merge_typed<float>(p, hidden, hsb, hsr, s_hat, text_len, kept, pruned, M, out_hidden, pos_out, new_len,
+                                 assign, wsum, final_idx, st, tm);
 }
 
 }  // namespace asap

@@ -94,11 +94,16 @@ __device__ __forceinline__ int rowmin16(int x) {
   return x;
 }
 
-template <typename T, int NT>
+// ANCHORED (the routing inside the kept set, Sec. 4.2): the source rows are the kept tokens too
+// (pruned == kept, M == k), and a destination counts for a source only if it is the stronger of the
+// two: larger salience s_hat, ties to the smaller index -- which is the smaller slot, both lists
+// being ascending.  A token is never its own destination.
+template <typename T, int NT, bool ANCHORED>
 __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t sb, int64_t sr, int D,
                                               const int32_t* __restrict__ pruned, const int32_t* __restrict__ kept,
-                                              int B, int M, int k, int mtiles, float threshold,
-                                              int32_t* __restrict__ assign, float* __restrict__ best_sim) {
+                                              const float* __restrict__ s_hat, int V, int B, int M, int k,
+                                              int mtiles, float threshold, int32_t* __restrict__ assign,
+                                              float* __restrict__ best_sim) {
   constexpr int BN = 64 * NT;
   constexpr int PA = SIM_BM / 32;                // source-row loads a thread issues per step
   constexpr int PB = BN / 32;                    // destination-row loads
@@ -110,6 +115,7 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
   float* norm2 = reinterpret_cast<float*>(ldsB + 2 * BSTAGE);    // [BM] squared norms of the source rows
   float* normk = norm2 + SIM_BM;                                 // [BN] squared norms of this pass's kept rows
   uint2* part = reinterpret_cast<uint2*>(normk + BN);            // [2][BM] (value, column) per column half
+  float* srow = reinterpret_cast<float*>(part + 2 * SIM_BM);     // [BM] salience of the source rows (ANCHORED)
 
   // XCD-aware decode of the linear workgroup id
   const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
@@ -149,6 +155,9 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) sw[kk] = ((hf * 4 + kk) ^ ((n >> 1) & 7)) * 16;
 
+  if (ANCHORED) {            // the barriers of the fill below make these visible
+    if (tid < SIM_BM) srow[tid] = s_hat[(int64_t)b * V + pruned[(int64_t)b * M + min(m0 + tid, M - 1)]];
+  }
   float run_v = -INFINITY;   // running best over destination passes (threads < BM)
   int run_c = 0;
 
@@ -278,6 +287,10 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
       invk[t] = valid ? 1.0f / fmaxf(sqrtf(normk[cl]), 1e-8f) : 0.0f;
       bias[t] = valid ? 0.0f : -INFINITY;
     }
+    float scol[NT];            // ANCHORED: salience of this lane's destination columns
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      scol[t] = (ANCHORED && colv[t] < k) ? s_hat[(int64_t)b * V + kept[(int64_t)b * k + colv[t]]] : 0.0f;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       // stage by stage over the 16 rows a lane holds, so that the cross-lane exchanges of
@@ -289,6 +302,16 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
         float c[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) c[t] = fmaf(acc[i][t][v], invk[t], bias[t]);
+        if (ANCHORED) {
+          const int rloc = wm * 64 + i * 32 + mma32_row(v, lane);
+          const float sr_ = srow[rloc];
+          const int rslot = m0 + rloc;
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            const bool stronger = (scol[t] > sr_) | ((scol[t] == sr_) & (colv[t] < rslot));
+            c[t] = stronger ? c[t] : -INFINITY;
+          }
+        }
         bv[v] = c[0];
 #pragma unroll
         for (int t = 1; t < NT; ++t) bv[v] = fmaxf(bv[v], c[t]);
@@ -335,25 +358,22 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
-size_t sim_workspace_bytes(const asap_params&) { return 0; }
-
-template <typename T, int NT>
-static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, int64_t sr, const int32_t* pruned,
-                                const int32_t* kept, int32_t* assign, float* best_sim, hipStream_t st,
-                                Timer* tm) {
+template <typename T, int NT, bool ANCHORED>
+static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, int64_t sr, const int32_t* srcs,
+                                int M, const int32_t* kept, const float* s_hat, int32_t* assign, float* best_sim,
+                                hipStream_t st, Timer* tm) {
   constexpr int BN = 64 * NT;
-  const size_t lds = (size_t)(SIM_NA * SIM_BM + 2 * BN) * SIM_ROWB + sizeof(float) * (5 * SIM_BM + BN);
-  auto kern = k_sim<T, NT>;
+  const size_t lds = (size_t)(SIM_NA * SIM_BM + 2 * BN) * SIM_ROWB + sizeof(float) * (6 * SIM_BM + BN);
+  auto kern = k_sim<T, NT, ANCHORED>;
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  const int M = p.V - p.k;
   const int mtiles = (M + SIM_BM - 1) / SIM_BM;
   const int groups = (p.B + NUM_XCD - 1) / NUM_XCD;
-  ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * mtiles), dim3(256), lds, st, xv, sb, sr, p.D, pruned,
-              kept, p.B, M, p.k, mtiles, p.sim_threshold, assign, best_sim);
+  ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * mtiles), dim3(256), lds, st, xv, sb, sr, p.D, srcs,
+              kept, s_hat, p.V, p.B, M, p.k, mtiles, p.sim_threshold, assign, best_sim);
   return hipGetLastError();
 }
 
@@ -369,27 +389,29 @@ static int pick_nt(int k) {
   return best_nt;
 }
 
-template <typename T>
+template <typename T, bool ANCHORED>
 static hipError_t sim_typed(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
-                            const int32_t* kept, const int32_t* pruned, int32_t* assign, float* best_sim,
-                            hipStream_t st, Timer* tm) {
+                            const int32_t* kept, const int32_t* srcs, int M, const float* s_hat, int32_t* assign,
+                            float* best_sim, hipStream_t st, Timer* tm) {
   const T* xv = static_cast<const T*>(hidden) + (int64_t)p.P * hsr;
   switch (pick_nt(p.k)) {
-    case 1: return launch_sim_nt<T, 1>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
-    case 2: return launch_sim_nt<T, 2>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
-    case 3: return launch_sim_nt<T, 3>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
-    case 4: return launch_sim_nt<T, 4>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
-    default: return launch_sim_nt<T, 5>(p, xv, hsb, hsr, pruned, kept, assign, best_sim, st, tm);
+    case 1: return launch_sim_nt<T, 1, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, st, tm);
+    case 2: return launch_sim_nt<T, 2, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, st, tm);
+    case 3: return launch_sim_nt<T, 3, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, st, tm);
+    case 4: return launch_sim_nt<T, 4, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, st, tm);
+    default: return launch_sim_nt<T, 5, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, st, tm);
   }
 }
 
 hipError_t launch_similarity(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
-                             const int32_t* kept, const int32_t* pruned, int32_t* assign, float* best_sim,
-                             char* ws, hipStream_t st, Timer* tm) {
-  (void)ws;
-  if (p.h_dtype == ASAP_BF16)
-    return sim_typed<bf16_t>(p, hidden, hsb, hsr, kept, pruned, assign, best_sim, st, tm);
-  return sim_typed<float>(p, hidden, hsb, hsr, kept, pruned, assign, best_sim, st, tm);
+                             const int32_t* kept, const int32_t* srcs, int M, bool anchored, const float* s_hat,
+                             int32_t* assign, float* best_sim, hipStream_t st, Timer* tm) {
+  const bool bf = p.h_dtype == ASAP_BF16;
+  if (anchored)
+    return bf ? sim_typed<bf16_t, true>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, st, tm)
+              : sim_typed<float, true>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, st, tm);
+  return bf ? sim_typed<bf16_t, false>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, st, tm)
+            : sim_typed<float, false>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, st, tm);
 }
 
 }  // namespace asap

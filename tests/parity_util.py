@@ -183,6 +183,78 @@ def compare_image(inp: dict, buf, b: int, ref: dict, mu=1.0, threshold=-math.inf
     return same_kept
 
 
+def compare_image_paper(inp: dict, buf, b: int, threshold: float, mu: float = 1.0) -> dict:
+    """Parity of image b with ASAP_ROUTE_PAPER.  The routing is judged stage-wise: the oracle's
+    route_paper runs on the GPU's own kept / pruned sets and on the GPU's f32 s_hat, s_raw (the
+    predicates s_hat_i > s_hat_j and the refill order are decisions taken in that precision); what
+    follows (Eq. 6, output sequence, K/V rows) is then compared as for the other route."""
+    cfg = inp["cfg"]
+    P, V, k, Tmax = cfg.P, cfg.V, cfg.k, cfg.Tmax
+    tl = int(inp["text_len"][b])
+    tol = TOL[cfg.h_dtype]
+    X = synth.to_f64(inp["hidden"][b], cfg.h_dtype)
+    Xv = X[P:P + V]
+    kept = buf.kept_idx[b].cpu().numpy().astype(np.int64)
+    pruned = buf.pruned_idx[b].cpu().numpy().astype(np.int64)[:V - k]
+    s_hat = from_device(buf.s_hat[b])
+    s_raw = from_device(buf.s_raw[b])
+    final_ref, sources_ref = O.route_paper(Xv, s_raw, s_hat, kept, pruned, threshold)
+    final = buf.final_idx[b].cpu().numpy().astype(np.int64)
+    assign = buf.assign.flatten()[b * k:(b + 1) * k].cpu().numpy().astype(np.int64)
+    best = from_device(buf.best_sim.flatten()[b * k:(b + 1) * k])
+
+    # immediate destinations: best stronger kept token above the threshold
+    C = O.cosine_matrix(Xv[kept], Xv[kept])
+    sh_k = s_hat[kept]
+    stronger = (sh_k[:, None] > sh_k[None, :]) | ((sh_k[:, None] == sh_k[None, :]) &
+                                                   (np.arange(k)[:, None] < np.arange(k)[None, :]))   # [dest, src]
+    Cm = np.where(stronger, C, -np.inf)
+    b_ref = Cm.max(axis=0)
+    has = np.isfinite(b_ref)
+    assert (np.isfinite(best) == has).all(), "which kept tokens have a stronger neighbour at all"
+    assert np.abs(best[has] - b_ref[has]).max(initial=0.0) <= 2e-5, "best_sim (paper route)"
+    near = has & (np.abs(b_ref - threshold) < ROUTE_GAP)        # decisions right at the threshold may flip
+    assert not near.any(), "test input has a similarity within 1e-5 of the threshold; pick another threshold"
+
+    assert final.shape == final_ref.shape and (final == final_ref).all(), "final_idx"
+    assert (np.diff(final) > 0).all()
+    sources = [kept[assign == c] for c in range(k)]
+    for c in range(k):
+        assert (sources[c] == sources_ref[c]).all(), f"sources of final slot {c}"
+    surv = assign < 0
+    assert set(kept[surv]).issubset(set(final.tolist())), "a surviving kept token is missing from final_idx"
+    n_sources = int((~surv).sum())
+    refill = np.setdiff1d(final, kept)
+    assert refill.size == n_sources, "one refill per vacated slot"
+
+    y_ref, w_ref = O.weighted_merge(Xv, s_hat, final, sources, mu)
+    Y_ref, pos_ref, nl_ref = O.assemble_sequence(X, y_ref, final, P, V, Tmax, tl)
+    Y = from_device(buf.out_hidden[b])
+    pos = buf.pos_out[b].cpu().numpy().astype(np.int64)
+    assert int(buf.new_len[b]) == nl_ref
+    assert (pos == pos_ref).all(), "pos_out"
+    wsum = from_device(buf.wsum[b])
+    assert np.abs(wsum - w_ref).max() <= 1e-5 * max(1.0, np.abs(w_ref).max()), "wsum"
+    check_rows(Y[P:P + k], Y_ref[P:P + k], tol, "merged rows (paper route)")
+    got_bits = raw_bits(buf.out_hidden[b])
+    src_bits = inp["hidden"][b]
+    if src_bits.dtype == np.float32:
+        src_bits = src_bits.view(np.uint32)
+    assert (got_bits[:P] == src_bits[:P]).all(), "prefix rows"
+    assert (got_bits[P + k:nl_ref] == src_bits[P + V:P + V + tl]).all(), "text rows"
+    absorbed = np.array([mu * s_hat[s].sum() if s.size else 0.0 for s in sources])
+    lone = np.nonzero(absorbed == 0.0)[0]
+    assert (got_bits[P + lone] == src_bits[P + final[lone]]).all(), "slots without sources"
+    for l in range(len(buf.k_dst)):
+        for dst, src in ((buf.k_dst[l], inp["k_cache"][l]), (buf.v_dst[l], inp["v_cache"][l])):
+            got = raw_bits(dst[b])
+            s = src[b]
+            if s.dtype == np.float32:
+                s = s.view(np.uint32)
+            assert (got[:, :nl_ref] == s[:, pos_ref[:nl_ref], :]).all(), f"K/V rows of layer {l}"
+    return {"n_sources": n_sources, "n_refill": int(refill.size)}
+
+
 def run_and_compare(cfg, images: Optional[Sequence[int]] = None, lse=False, ctx=None, report=None,
                     **param_overrides):
     """Generate, run on the GPU, compare the chosen images (all by default)."""

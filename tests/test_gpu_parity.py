@@ -114,7 +114,7 @@ def test_determinism(ctx):
 def test_positions_and_two_stream_stage(ctx):
     """asap_positions writes what asap_merge writes, and the stage with the K/V compaction on a
     second stream gives bit-identical results to the stage on one stream."""
-    cfg = synth.CONFIGS["S3"]
+    cfg = synth.CONFIGS["S1"]
     inp = synth.make_inputs(cfg)
     serial = U.GpuStage(inp, ctx=ctx, overlap=False)
     bs = serial.run()
@@ -147,14 +147,14 @@ def test_strided_views_and_errors(ctx):
                        st.text_len, None, buf.s_raw, buf.s_hat, buf.score, small)
     assert e.value.status == binding.ASAP_EWORKSPACE
     with pytest.raises(binding.AsapError) as e:       # out_hidden aliasing hidden
-        ctx.asap_merge(p, st.hidden, buf.s_hat, st.text_len, buf.kept_idx, buf.pruned_idx, st.hidden, buf.pos_out,
-                       buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace)
+        ctx.asap_merge(p, st.hidden, buf.s_raw, buf.s_hat, st.text_len, buf.kept_idx, buf.pruned_idx, st.hidden,
+                       buf.pos_out, buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace)
     assert e.value.status == binding.ASAP_EINVAL
     p2 = binding.params_from_config(cfg, route=binding.ASAP_ROUTE_PAPER)
-    with pytest.raises(binding.AsapError) as e:
-        ctx.asap_merge(p2, st.hidden, buf.s_hat, st.text_len, buf.kept_idx, buf.pruned_idx, buf.out_hidden,
+    with pytest.raises(binding.AsapError) as e:       # the paper's routing refills by raw mass: needs s_raw
+        ctx.asap_merge(p2, st.hidden, None, buf.s_hat, st.text_len, buf.kept_idx, buf.pruned_idx, buf.out_hidden,
                        buf.pos_out, buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace)
-    assert e.value.status == binding.ASAP_EUNSUPPORTED
+    assert e.value.status == binding.ASAP_EINVAL
     with pytest.raises(binding.AsapError) as e:       # K/V destination aliasing a source
         ctx.asap_compact_kv(p, st.k_cache, st.v_cache, st.k_cache, buf.v_dst, buf.pos_out, buf.new_len)
     assert e.value.status == binding.ASAP_EINVAL
@@ -162,6 +162,36 @@ def test_strided_views_and_errors(ctx):
 
 
 # ------------------------------------------------------------------ benchmark configurations, full size
+@pytest.mark.parametrize("name,threshold,mu", [("S0", 0.8, 1.0), ("S1", 0.8, 1.0), ("S2", 0.85, 1.0),
+                                               ("S4", 0.9, 0.5), ("S1", 2.0, 1.0), ("S2", -1.0, 1.0)])
+def test_paper_routing_small(ctx, name, threshold, mu):
+    """Sec. 4.2 as written: routing inside the kept set, roots, refill by raw mass, Eq. 6 over trees.
+    threshold 2.0: nothing merges (final = kept); -1.0: every kept token but the strongest is a source."""
+    cfg = synth.CONFIGS[name]
+    inp = synth.make_inputs(cfg)
+    st = U.GpuStage(inp, ctx=ctx, route=binding.ASAP_ROUTE_PAPER, sim_threshold=threshold, merge_weight=mu)
+    buf = st.run()
+    stats = [U.compare_image_paper(inp, buf, b, threshold, mu) for b in range(cfg.B)]
+    if threshold >= 2.0:
+        assert all(s["n_sources"] == 0 for s in stats)
+    elif threshold <= -1.0:
+        assert all(s["n_sources"] == cfg.k - 1 for s in stats)
+    elif name != "S0":
+        assert sum(s["n_sources"] for s in stats) > 0, "the case does not exercise any merge"
+
+
+def test_paper_routing_config2_and_config6_sample(ctx):
+    for name, images in (("C2", [0]), ("C6", [0, 9])):
+        cfg = synth.CONFIGS[name]
+        inp = synth.make_inputs(cfg)
+        st = U.GpuStage(inp, ctx=ctx, route=binding.ASAP_ROUTE_PAPER, sim_threshold=0.8)
+        buf = st.run()
+        tot = 0
+        for b in images:
+            tot += U.compare_image_paper(inp, buf, b, 0.8, 1.0)["n_sources"]
+        assert tot > 0
+
+
 def test_config1_llava15_single_image(ctx):
     U.run_and_compare(synth.CONFIGS["C1"], ctx=ctx)
 
