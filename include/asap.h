@@ -194,6 +194,19 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
                             const int32_t* pos_out, const int32_t* new_len, void* stream);
 
 /*
+ * Theoretical FLOPs of the image tokens (Sec. 5, Eq. 7) for a pruning schedule of n_stages
+ * stages, stage n running layers[n] decoder layers on tokens[n] image tokens, hidden size d and
+ * FFN intermediate size m:
+ *   flops = sum_n layers[n] * (4 v_n d^2 + 2 v_n^2 d + 3 v_n d m),   v_n = tokens[n]
+ * and their ratio (Eq. 8) to the cost of all the layers at v0 tokens.  Host-side arithmetic in
+ * double; layers, tokens [host], n_stages >= 1, every entry >= 0, d, m, v0 >= 1.
+ */
+asap_status asap_theoretical_flops(const int32_t* layers, const int32_t* tokens, int32_t n_stages,
+                                   int32_t d, int32_t m, double* flops);
+asap_status asap_flops_ratio(const int32_t* layers, const int32_t* tokens, int32_t n_stages,
+                             int32_t v0, int32_t d, int32_t m, double* ratio);
+
+/*
  * Kernel timing for benchmarks (not part of the method).  asap_timing_enable(ctx, n) with n > 0
  * creates a pool of n event pairs (n <= 8192); from then on each kernel the four calls launch
  * is bracketed by two HIP events recorded on the call's own stream, until the pool is used up

@@ -22,7 +22,7 @@ ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
 
 EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
            "asap_score", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv", "asap_timing_enable",
-           "asap_timing_collect"]
+           "asap_timing_collect", "asap_theoretical_flops", "asap_flops_ratio"]
 
 _DTYPE_CODE = {"f32": ASAP_F32, "bf16": ASAP_BF16, torch.float32: ASAP_F32, torch.bfloat16: ASAP_BF16}
 _TORCH_DTYPE = {ASAP_F32: torch.float32, ASAP_BF16: torch.bfloat16}
@@ -86,6 +86,12 @@ def load() -> ctypes.CDLL:
     lib.asap_compact_kv.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                     ctypes.POINTER(vp), ctypes.POINTER(vp), i32p, i32p, vp]
     lib.asap_compact_kv.restype = ctypes.c_int
+    lib.asap_theoretical_flops.argtypes = [i32p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.POINTER(ctypes.c_double)]
+    lib.asap_theoretical_flops.restype = ctypes.c_int
+    lib.asap_flops_ratio.argtypes = [i32p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                     ctypes.POINTER(ctypes.c_double)]
+    lib.asap_flops_ratio.restype = ctypes.c_int
     lib.asap_timing_enable.argtypes = [vp, ctypes.c_int32]
     lib.asap_timing_enable.restype = ctypes.c_int
     lib.asap_timing_collect.argtypes = [vp, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double),
@@ -116,6 +122,28 @@ def asap_check_params(p: asap_params):
 
 def asap_workspace_bytes(p: asap_params) -> int:
     return int(load().asap_workspace_bytes(ctypes.byref(p)))
+
+
+def _i32_array(values):
+    return (ctypes.c_int32 * len(values))(*[int(v) for v in values])
+
+
+def asap_theoretical_flops(layers, tokens, d: int, m: int) -> float:
+    """Eq. 7 through the library (host arithmetic)."""
+    out = ctypes.c_double()
+    st = load().asap_theoretical_flops(_i32_array(layers), _i32_array(tokens), len(layers), d, m, ctypes.byref(out))
+    if st != ASAP_OK:
+        raise AsapError(st, "asap_theoretical_flops: invalid arguments")
+    return out.value
+
+
+def asap_flops_ratio(layers, tokens, v0: int, d: int, m: int) -> float:
+    """Eq. 8 through the library (host arithmetic)."""
+    out = ctypes.c_double()
+    st = load().asap_flops_ratio(_i32_array(layers), _i32_array(tokens), len(layers), v0, d, m, ctypes.byref(out))
+    if st != ASAP_OK:
+        raise AsapError(st, "asap_flops_ratio: invalid arguments")
+    return out.value
 
 
 def _ptr(t: Optional[torch.Tensor]):

@@ -328,4 +328,32 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
                     "asap_compact_kv launch");
 }
 
+// Eq. 7 / Eq. 8: host-side arithmetic only
+static double layer_cost(double v, double d, double m) { return 4.0 * v * d * d + 2.0 * v * v * d + 3.0 * v * d * m; }
+
+asap_status asap_theoretical_flops(const int32_t* layers, const int32_t* tokens, int32_t n_stages, int32_t d,
+                                   int32_t m, double* flops) {
+  if (!layers || !tokens || !flops || n_stages < 1 || d < 1 || m < 1) return ASAP_EINVAL;
+  double total = 0.0;
+  for (int n = 0; n < n_stages; ++n) {
+    if (layers[n] < 0 || tokens[n] < 0) return ASAP_EINVAL;
+    total += (double)layers[n] * layer_cost(tokens[n], d, m);
+  }
+  *flops = total;
+  return ASAP_OK;
+}
+
+asap_status asap_flops_ratio(const int32_t* layers, const int32_t* tokens, int32_t n_stages, int32_t v0,
+                             int32_t d, int32_t m, double* ratio) {
+  if (!ratio || v0 < 1) return ASAP_EINVAL;
+  double pruned = 0.0;
+  asap_status st = asap_theoretical_flops(layers, tokens, n_stages, d, m, &pruned);
+  if (st != ASAP_OK) return st;
+  long total_layers = 0;
+  for (int n = 0; n < n_stages; ++n) total_layers += layers[n];
+  if (total_layers < 1) return ASAP_EINVAL;
+  *ratio = pruned / ((double)total_layers * layer_cost(v0, d, m));
+  return ASAP_OK;
+}
+
 }  // extern "C"

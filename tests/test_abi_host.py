@@ -85,3 +85,40 @@ def test_workspace_size_formula(lib):
 def test_struct_layout_matches_header(lib):
     # 9 int32 + 3 enums + 4 floats + 2 enums, all 4 bytes, no padding
     assert ctypes.sizeof(binding.asap_params) == 18 * 4
+
+
+def read_golden(name):
+    rows = []
+    for line in open(os.path.join(ROOT, "tests", "golden", name)):
+        line = line.split("#")[0].strip()
+        if line:
+            rows.append(line.split())
+    return rows
+
+
+def test_flops_utility_against_the_printed_tables_and_the_oracle(lib):
+    # Eq. 7 / Eq. 8 as the library computes them: the values the paper prints (Tables 1, 2, 5) ...
+    for row in read_golden("eq7_flops.txt"):
+        v, printed = int(row[0]), float(row[1])
+        assert abs(binding.asap_theoretical_flops([32], [v], 4096, 11008) / 1e12 - printed) <= 0.0006
+    for row in read_golden("eq8_ratio.txt"):
+        v, v0, pct = int(row[0]), int(row[1]), float(row[2])
+        assert abs(100.0 * binding.asap_flops_ratio([32], [v], v0, 4096, 11008) - pct) <= 0.006
+    # ... and a multi-stage schedule against the oracle's own formula
+    from oracle import asap_oracle as O
+    layers, tokens = [2, 14, 16], [2304, 576, 160]
+    assert binding.asap_theoretical_flops(layers, tokens, 5120, 13824) == O.theoretical_flops(layers, tokens, 5120, 13824)
+    assert abs(binding.asap_flops_ratio(layers, tokens, 2304, 5120, 13824) -
+               O.flops_ratio(layers, tokens, 2304, 5120, 13824)) <= 1e-15
+    with pytest.raises(binding.AsapError):
+        binding.asap_theoretical_flops([1], [-5], 64, 64)
+
+
+def test_paper_route_needs_room_to_refill(lib):
+    p = good()
+    p.route = binding.ASAP_ROUTE_PAPER
+    assert binding.asap_check_params(p)[0] == binding.ASAP_OK
+    assert binding.asap_workspace_bytes(p) >= 4 * p.B * p.k
+    p.k = p.V // 2 + 1
+    st, msg = binding.asap_check_params(p)
+    assert st == binding.ASAP_EINVAL and "V / 2" in msg
