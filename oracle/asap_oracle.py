@@ -16,6 +16,7 @@ order and notation, with no blocking, fusion or reordering:
   select_topk               top-k, ties to the smaller index
   route_absorb              cosine similarity (Sec. 4.2) of each pruned token to each kept token
   route_paper               Sec. 4.2 routing inside the kept set + budget reallocation
+  attention_forward         output of one attention layer under the Eq. 4-5 mask (whole sequence)
   weighted_merge            Eq. 6
   assemble_sequence         prefix | merged kept tokens | text           (Fig. 3 caption)
   gather_kv                 K/V rows of surviving positions
@@ -327,6 +328,20 @@ def full_bidirectional_attention(Q: np.ndarray, K: np.ndarray, P: int, V: int,
             e = np.exp(z - z.max())
             A[h, i] = e / e.sum()
     return A, s_hat
+
+
+def attention_forward(Q: np.ndarray, K: np.ndarray, Vval: np.ndarray, P: int, V: int,
+                      lambda_max: float = 1.0, eps: float = EPS_DEFAULT,
+                      mask: str = "bidir") -> Tuple[np.ndarray, np.ndarray]:
+    """Output of one attention layer under the mask of Eq. 4-5 (or Eq. 1 for mask="causal"):
+    out[h,i,:] = sum_j A[h,i,j] Vval[g(h),j,:] with A from full_bidirectional_attention.
+
+    Q [H,N,d], K, Vval [Hkv,N,d].  Returns (out [H,N,d], s_hat [V])."""
+    A, s_hat = full_bidirectional_attention(Q, K, P, V, lambda_max, eps, mask)
+    H = Q.shape[0]
+    Hkv = K.shape[0]
+    out = np.stack([A[h] @ Vval[kv_head(h, H, Hkv)] for h in range(H)])
+    return out, s_hat
 
 
 # ---------------------------------------------------------------- Eq. 7 / Eq. 8

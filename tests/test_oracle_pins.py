@@ -480,3 +480,49 @@ def test_flops_multi_stage_sum():
     want = 2 * O.layer_flops(100, d, m) + 3 * O.layer_flops(40, d, m) + 5 * O.layer_flops(10, d, m)
     assert O.theoretical_flops([2, 3, 5], [100, 40, 10], d, m) == want
     assert O.layer_flops(3, 5, 7) == 4 * 3 * 25 + 2 * 9 * 5 + 3 * 3 * 5 * 7
+
+
+# ---------------------------------------------------------------- attention forward under the Eq. 4-5 mask
+def _small_qkv(seed, H=2, Hkv=1, N=9, d=4):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((H, N, d)), rng.standard_normal((Hkv, N, d)), rng.standard_normal((Hkv, N, d)))
+
+
+def test_attention_forward_rows_are_convex_combinations():
+    # every row of A sums to one: constant values come out unchanged, whatever the mask
+    Q, K, Vv = _small_qkv(3)
+    Vc = np.broadcast_to(np.array([1.5, -2.0, 0.25, 7.0]), Vv.shape).copy()
+    for mask in ("bidir", "causal"):
+        out, _ = O.attention_forward(Q, K, Vc, 2, 5, lambda_max=0.8, mask=mask)
+        assert np.abs(out - Vc[0, 0]).max() < 1e-12
+
+
+def test_attention_forward_two_token_closed_form():
+    # N = 2, causal: row 0 sees key 0 only; row 1 is the two-term softmax written out
+    Q, K, Vv = _small_qkv(5, H=1, Hkv=1, N=2, d=3)
+    out, _ = O.attention_forward(Q, K, Vv, 0, 1, mask="causal")
+    assert np.allclose(out[0, 0], Vv[0, 0], rtol=0, atol=1e-15)
+    w0, w1 = Q[0, 1] @ K[0, 0] / math.sqrt(3), Q[0, 1] @ K[0, 1] / math.sqrt(3)
+    want = (math.exp(w0) * Vv[0, 0] + math.exp(w1) * Vv[0, 1]) / (math.exp(w0) + math.exp(w1))
+    assert np.allclose(out[0, 1], want, rtol=1e-13, atol=1e-15)
+
+
+def test_attention_forward_mask_touches_only_image_rows_and_adds_discounted_future_keys():
+    P, V = 2, 4
+    Q, K, Vv = _small_qkv(8, H=2, Hkv=2, N=9, d=4)
+    lam = 0.6
+    out_bi, s_hat = O.attention_forward(Q, K, Vv, P, V, lambda_max=lam, mask="bidir")
+    out_ca, _ = O.attention_forward(Q, K, Vv, P, V, mask="causal")
+    rows = np.arange(9)
+    outside = (rows < P) | (rows >= P + V - 1)        # the last image row has no future image key
+    assert np.array_equal(out_bi[:, outside], out_ca[:, outside])
+    assert np.abs(out_bi[:, P:P + V - 1] - out_ca[:, P:P + V - 1]).max() > 1e-6
+    # image row i written out: keys <= i with weight e^w, future image keys with weight lam' e^w
+    h, i = 1, P + 1
+    w = Q[h, i] @ K[h].T / 2.0
+    wt = np.zeros(9)
+    wt[:i + 1] = np.exp(w[:i + 1])
+    for j in range(i + 1, P + V):
+        wt[j] = max(lam * s_hat[j - P], 1e-6) * math.exp(w[j])
+    want = (wt[:, None] * Vv[h]).sum(0) / wt.sum()
+    assert np.allclose(out_bi[h, i], want, rtol=1e-12, atol=1e-14)
