@@ -97,6 +97,52 @@ def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb") -> dic
             "ms_per_image": 1e3 * t_total / done}
 
 
+def bench_attention(args, cfg):
+    """asap_attention on the workload's shapes: q, k from the generator, random values; one launch set
+    (bias, transpose, attention) per step.  Flops = 4 d per (query, key) pair the mask lets through."""
+    import numpy as np
+    import torch
+    from paper_2603_14549_amd import binding, synth
+    inp = synth.make_inputs(cfg, with_kv=False)
+    ctx = binding.Context(0)
+    stage = binding.DeviceStage(inp, ctx=ctx)
+    buf = stage.run()
+    vals = torch.randn(cfg.B, cfg.Hkv, cfg.N, cfg.d, device="cuda").to(stage.q.dtype)
+    out = torch.empty(cfg.B, cfg.H, cfg.N, cfg.d, dtype=stage.q.dtype, device="cuda")
+    ws = torch.empty(binding.asap_attention_workspace_bytes(stage.p), dtype=torch.uint8, device="cuda")
+    run = lambda: ctx.asap_attention(stage.p, stage.q, stage.k, vals, buf.s_hat, out, ws)
+    steps, warmup = min(args.steps, 10), min(args.warmup, 3)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ctx.asap_timing_enable(64)
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    timing = ctx.asap_timing_collect()
+    ctx.asap_timing_enable(0)
+    N, V = cfg.N, cfg.V
+    pairs = N * (N + 1) // 2 + V * (V - 1) // 2
+    flops = 4.0 * cfg.d * pairs * cfg.H * cfg.B
+    ms, n = timing["k_attention"]
+    k_s = 1e-3 * ms / n
+    peak = MFMA_PEAK[cfg.qk_dtype]
+    print(json.dumps({
+        "metric": "SG-BiMask attention forward, images/sec per layer", "value": cfg.B * steps / elapsed,
+        "unit": "images/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": 1e3 * elapsed / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.qk_dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B}, N={N} ({cfg.P}+{V}+{cfg.Tmax}), {cfg.H}/{cfg.Hkv} heads x {cfg.d}, "
+                               f"mask=keybias"},
+        "roofline": {"kernel": "k_attention", "bound": "mfma", "achieved": flops / k_s / 1e12, "peak": peak / 1e12,
+                     "unit": "TFLOP/s", "frac": flops / k_s / peak, "traffic": None},
+        "kernels": {k: {"avg_us": round(1e3 * v[0] / v[1], 1)} for k, v in timing.items()}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +152,9 @@ def main():
     ap.add_argument("--route", choices=["absorb", "paper"], default="absorb",
                     help="absorb (default, the headline workload): pruned -> kept routing; paper: Sec. 4.2 as "
                          "written, routing inside the kept set + refill (threshold 0.8)")
+    ap.add_argument("--attention", action="store_true",
+                    help="measure asap_attention (one layer's forward under the Eq. 4-5 mask) on the workload's "
+                         "shapes instead of the pruning stage; prints its own JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (reference for HBM counters)")
@@ -123,6 +172,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     binding.load()
     cfg = synth.CONFIGS[args.workload]
+    if args.attention:
+        return bench_attention(args, cfg)
     t0 = time.perf_counter()
     inp = synth.make_inputs(cfg)
     gen_s = time.perf_counter() - t0

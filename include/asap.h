@@ -194,6 +194,30 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
                             const int32_t* pos_out, const int32_t* new_len, void* stream);
 
 /*
+ * asap_attention -- the attention forward of one decoder layer in front of the pruning layer under
+ * the salience-guided bidirectional mask (Sec. 4.1, Eq. 4-5 applied to the whole sequence):
+ *   out[b,h,i,:] = sum_j A_ij v[b,g(h),j,:],   A_i. = softmax_j( q[b,h,i,:] . k[b,g(h),j,:] / sqrt(d) + M_ij ),
+ *   M_ij = 0                                         for j <= i                       (causal part, Eq. 1)
+ *        = ln( max(lambda_max * s_hat[b,j-P], eps) ) for j > i, P <= i, j < P + V     (image span, Eq. 4)
+ *        = -inf                                      otherwise;
+ * with ASAP_MASK_OFF the second case is -inf too (plain causal attention).  N = P + V + Tmax rows,
+ * all treated as valid.  q [B,H,N,d], k, v [B,Hkv,N,d] in qk_dtype with element strides of the
+ * three outer dims (last dim contiguous; q, k strides multiples of 8 elements), 16-byte aligned;
+ * s_hat [B,V] f32 = the salience asap_score returns for this layer's q, k (NULL allowed with
+ * ASAP_MASK_OFF); out [B,H,N,d] contiguous, qk_dtype.  Both contractions run on the matrix cores in
+ * the input precision with fp32 accumulation; the probabilities are rounded to the input precision
+ * before the second one.  The workspace (256-byte aligned) holds a transposed copy of v and the
+ * per-key log discounts: asap_attention_workspace_bytes(p) bytes.
+ */
+size_t      asap_attention_workspace_bytes(const asap_params* p);
+asap_status asap_attention(asap_ctx* ctx, const asap_params* p,
+                           const void* q, const int64_t q_stride[3],
+                           const void* k, const int64_t k_stride[3],
+                           const void* v, const int64_t v_stride[3],
+                           const float* s_hat, void* out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Theoretical FLOPs of the image tokens (Sec. 5, Eq. 7) for a pruning schedule of n_stages
  * stages, stage n running layers[n] decoder layers on tokens[n] image tokens, hidden size d and
  * FFN intermediate size m:

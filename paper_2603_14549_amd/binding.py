@@ -22,7 +22,8 @@ ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
 
 EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
            "asap_score", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv", "asap_timing_enable",
-           "asap_timing_collect", "asap_theoretical_flops", "asap_flops_ratio"]
+           "asap_timing_collect", "asap_theoretical_flops", "asap_flops_ratio", "asap_attention",
+           "asap_attention_workspace_bytes"]
 
 _DTYPE_CODE = {"f32": ASAP_F32, "bf16": ASAP_BF16, torch.float32: ASAP_F32, torch.bfloat16: ASAP_BF16}
 _TORCH_DTYPE = {ASAP_F32: torch.float32, ASAP_BF16: torch.bfloat16}
@@ -86,6 +87,10 @@ def load() -> ctypes.CDLL:
     lib.asap_compact_kv.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                     ctypes.POINTER(vp), ctypes.POINTER(vp), i32p, i32p, vp]
     lib.asap_compact_kv.restype = ctypes.c_int
+    lib.asap_attention_workspace_bytes.argtypes = [pp]
+    lib.asap_attention_workspace_bytes.restype = ctypes.c_size_t
+    lib.asap_attention.argtypes = [vp, pp, vp, i64p, vp, i64p, vp, i64p, f32p, vp, vp, ctypes.c_size_t, vp]
+    lib.asap_attention.restype = ctypes.c_int
     lib.asap_theoretical_flops.argtypes = [i32p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.POINTER(ctypes.c_double)]
     lib.asap_theoretical_flops.restype = ctypes.c_int
@@ -122,6 +127,10 @@ def asap_check_params(p: asap_params):
 
 def asap_workspace_bytes(p: asap_params) -> int:
     return int(load().asap_workspace_bytes(ctypes.byref(p)))
+
+
+def asap_attention_workspace_bytes(p: asap_params) -> int:
+    return int(load().asap_attention_workspace_bytes(ctypes.byref(p)))
 
 
 def _i32_array(values):
@@ -223,6 +232,12 @@ class Context:
             _ptr(kept_idx), _ptr(pruned_idx), _ptr(out_hidden), _ptr(pos_out), _ptr(new_len), _ptr(assign),
             _ptr(best_sim), _ptr(wsum), _ptr(final_idx), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream(stream)))
+
+    def asap_attention(self, p, q, k, v, s_hat, out, workspace, stream=None):
+        self._check(self._lib.asap_attention(
+            self._h, ctypes.byref(p), _ptr(q), _strides(q, 3), _ptr(k), _strides(k, 3), _ptr(v), _strides(v, 3),
+            _ptr(s_hat), _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+            _stream(stream)))
 
     def asap_positions(self, p, kept_idx, text_len, pos_out, new_len, stream=None):
         self._check(self._lib.asap_positions(

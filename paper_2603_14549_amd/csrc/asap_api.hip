@@ -328,6 +328,40 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
                     "asap_compact_kv launch");
 }
 
+size_t asap_attention_workspace_bytes(const asap_params* p) {
+  if (check_params(p, nullptr, 0) != ASAP_OK) return 0;
+  return attention_workspace_bytes(*p);
+}
+
+asap_status asap_attention(asap_ctx* ctx, const asap_params* p, const void* q, const int64_t q_stride[3],
+                           const void* k, const int64_t k_stride[3], const void* v, const int64_t v_stride[3],
+                           const float* s_hat, void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  asap_status st = common_checks(ctx, p);
+  if (st != ASAP_OK) return st;
+  if (!q || !k || !v || !out || (p->mask_mode == ASAP_MASK_KEYBIAS && !s_hat))
+    return fail(ctx, ASAP_EINVAL, "asap_attention: a required pointer is NULL");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+    return fail(ctx, ASAP_EINVAL, "asap_attention: q, k, v and out must be 16-byte aligned");
+  if ((st = check_strides(ctx, "q_stride", q_stride, 3, 8)) != ASAP_OK) return st;
+  if ((st = check_strides(ctx, "k_stride", k_stride, 3, 8)) != ASAP_OK) return st;
+  if ((st = check_strides(ctx, "v_stride", v_stride, 3, 1)) != ASAP_OK) return st;
+  if (q_stride[2] < p->d || k_stride[2] < p->d || v_stride[2] < p->d)
+    return fail(ctx, ASAP_EINVAL, "asap_attention: row strides must be >= d");
+  const size_t need = attention_workspace_bytes(*p);
+  if (!workspace) return fail(ctx, ASAP_EINVAL, "workspace is NULL");
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(ctx, ASAP_EINVAL, "workspace must be 256-byte aligned");
+  if (workspace_bytes < need)
+    return fail(ctx, ASAP_EWORKSPACE, "asap_attention: workspace of %zu bytes, %zu needed", workspace_bytes, need);
+  Strides3 sq{q_stride[0], q_stride[1], q_stride[2]};
+  Strides3 sk{k_stride[0], k_stride[1], k_stride[2]};
+  Strides3 sv{v_stride[0], v_stride[1], v_stride[2]};
+  return hip_result(ctx,
+                    launch_attention(*p, q, sq, k, sk, v, sv, s_hat, out, static_cast<char*>(workspace),
+                                     static_cast<hipStream_t>(stream), ctx->timer),
+                    "asap_attention launch");
+}
+
 // Eq. 7 / Eq. 8: host-side arithmetic only
 static double layer_cost(double v, double d, double m) { return 4.0 * v * d * d + 2.0 * v * v * d + 3.0 * v * d * m; }
 

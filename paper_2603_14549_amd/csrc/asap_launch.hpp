@@ -91,6 +91,12 @@ hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* con
                              const void* const* v_src, void* const* k_dst, void* const* v_dst,
                              const int32_t* pos_out, const int32_t* new_len, hipStream_t st, Timer* tm);
 
+// attention forward under the Eq. 4-5 mask (asap_attention.hip); ws needs attention_workspace_bytes(p)
+size_t attention_workspace_bytes(const asap_params& p);
+hipError_t launch_attention(const asap_params& p, const void* q, Strides3 sq, const void* k, Strides3 sk,
+                            const void* v, Strides3 sv, const float* s_hat, void* out, char* ws, hipStream_t st,
+                            Timer* tm);
+
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 }  // namespace asap

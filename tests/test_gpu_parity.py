@@ -10,6 +10,7 @@ import torch
 
 from paper_2603_14549_amd import binding, synth
 import parity_util as U
+from oracle import asap_oracle as O
 
 pytestmark = pytest.mark.gpu
 
@@ -190,6 +191,35 @@ def test_paper_routing_config2_and_config6_sample(ctx):
         for b in images:
             tot += U.compare_image_paper(inp, buf, b, 0.8, 1.0)["n_sources"]
         assert tot > 0
+
+
+@pytest.mark.parametrize("name,mask_mode,lam", [("S0", binding.ASAP_MASK_KEYBIAS, 1.0), ("S1", binding.ASAP_MASK_KEYBIAS, 0.7),
+                                                 ("S2", binding.ASAP_MASK_KEYBIAS, 1.0), ("S2", binding.ASAP_MASK_OFF, 1.0),
+                                                 ("S3", binding.ASAP_MASK_KEYBIAS, 1.0)])
+def test_attention_forward_under_the_bidirectional_mask(ctx, name, mask_mode, lam):
+    """asap_attention (flash-style, both contractions on MFMA) against the oracle's explicit N x N
+    softmax of Eq. 4-5, every image, every head, every row."""
+    cfg = synth.CONFIGS[name]
+    inp = synth.make_inputs(cfg, with_kv=False)
+    st = U.GpuStage(inp, ctx=ctx, mask_mode=mask_mode, lambda_max=lam)
+    buf = st.run()                                             # s_hat of this layer's q, k
+    rng = np.random.default_rng(cfg.seed + 4242)
+    vals = synth.quantise(rng.standard_normal((cfg.B, cfg.Hkv, cfg.N, cfg.d)).astype(np.float32), cfg.qk_dtype)
+    v_dev = binding.to_device(vals, cfg.qk_dtype)
+    out = torch.empty(cfg.B, cfg.H, cfg.N, cfg.d, dtype=st.q.dtype, device="cuda")
+    ws = torch.empty(binding.asap_attention_workspace_bytes(st.p), dtype=torch.uint8, device="cuda")
+    ctx.asap_attention(st.p, st.q, st.k, v_dev, buf.s_hat, out, ws)
+    torch.cuda.synchronize()
+    tol = U.TOL[cfg.qk_dtype]
+    for b in range(cfg.B):
+        Q = synth.to_f64(inp["q"][b], cfg.qk_dtype)
+        K = synth.to_f64(inp["k"][b], cfg.qk_dtype)
+        Vv = synth.to_f64(vals[b], cfg.qk_dtype)
+        ref, _ = O.attention_forward(Q, K, Vv, cfg.P, cfg.V, lambda_max=lam, eps=float(np.float32(1e-6)),
+                                     mask="bidir" if mask_mode == binding.ASAP_MASK_KEYBIAS else "causal")
+        got = U.from_device(out[b])
+        for h in range(cfg.H):
+            U.check_rows(got[h], ref[h], tol, f"attention output image {b} head {h}")
 
 
 def test_config1_llava15_single_image(ctx):
