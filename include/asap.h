@@ -202,7 +202,7 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
  *        = -inf                                      otherwise;
  * with ASAP_MASK_OFF the second case is -inf too (plain causal attention).  N = P + V + Tmax rows,
  * all treated as valid.  q [B,H,N,d], k, v [B,Hkv,N,d] in qk_dtype with element strides of the
- * three outer dims (last dim contiguous; q, k strides multiples of 8 elements), 16-byte aligned;
+ * three outer dims (last dim contiguous; strides multiples of 8 elements), 16-byte aligned;
  * s_hat [B,V] f32 = the salience asap_score returns for this layer's q, k (NULL allowed with
  * ASAP_MASK_OFF); out [B,H,N,d] contiguous, qk_dtype.  Both contractions run on the matrix cores in
  * the input precision with fp32 accumulation; the probabilities are rounded to the input precision

@@ -344,7 +344,7 @@ asap_status asap_attention(asap_ctx* ctx, const asap_params* p, const void* q, c
     return fail(ctx, ASAP_EINVAL, "asap_attention: q, k, v and out must be 16-byte aligned");
   if ((st = check_strides(ctx, "q_stride", q_stride, 3, 8)) != ASAP_OK) return st;
   if ((st = check_strides(ctx, "k_stride", k_stride, 3, 8)) != ASAP_OK) return st;
-  if ((st = check_strides(ctx, "v_stride", v_stride, 3, 1)) != ASAP_OK) return st;
+  if ((st = check_strides(ctx, "v_stride", v_stride, 3, 8)) != ASAP_OK) return st;
   if (q_stride[2] < p->d || k_stride[2] < p->d || v_stride[2] < p->d)
     return fail(ctx, ASAP_EINVAL, "asap_attention: row strides must be >= d");
   const size_t need = attention_workspace_bytes(*p);

@@ -52,28 +52,6 @@ template <> __device__ __forceinline__ void sumsq16<float>(const uint4& c, SumSq
   acc.p[2] = fmaf(f[2], f[2], acc.p[2]); acc.p[3] = fmaf(f[3], f[3], acc.p[3]);
 }
 
-// 16 bytes per lane from global memory straight into LDS: lane L's data, read from gbase + voff
-// (gbase wave-uniform), lands at LDS byte address lds_addr + 16 L (lds_addr wave-uniform, passed
-// in M0).  Completion is counted by vmcnt.  Written as assembly so that the compiler does not
-// order the workgroup's own LDS operand reads behind every outstanding load (it cannot tell the
-// ring slots apart); the waits below are placed by hand instead.
-__device__ __forceinline__ void load_to_lds16(const char* gbase, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(voff), "s"(gbase), "s"(lds_addr) : "memory", "m0");
-}
-__device__ __forceinline__ uint32_t lds_address(const void* p) {
-  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
-}
-__device__ __forceinline__ void wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-// wait until at most N (< 16) of this wave's vector-memory loads are still outstanding
-template <int N> __device__ __forceinline__ void wait_vmem_but() {
-  static_assert(N >= 0 && N < 16, "vmcnt field");
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-// Workgroup barrier without the release fence of __syncthreads(): that fence would wait for every
-// outstanding load of the wave, also the ones that are meant to stay in flight across the barrier.
-__device__ __forceinline__ void barrier_keep_loads() { asm volatile("s_barrier" ::: "memory"); }
-
 // all-reduce over a row of 16 lanes by rotations inside the row (the caller joins the two rows of a
 // 32-lane half with one exchange)
 template <int CTRL> __device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
