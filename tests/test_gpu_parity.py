@@ -181,6 +181,20 @@ def test_paper_routing_small(ctx, name, threshold, mu):
         assert sum(s["n_sources"] for s in stats) > 0, "the case does not exercise any merge"
 
 
+@pytest.mark.parametrize("V,k,clusters,threshold", [(2, 1, 1, 0.5), (5, 2, 1, 0.5), (64, 32, 2, 0.5), (257, 128, 3, 0.6),
+                                                    (1030, 515, 4, 0.7), (300, 129, 300, 0.8)])
+def test_paper_routing_shape_edges(ctx, V, k, clusters, threshold):
+    """Budgets at the k = V/2 limit, one kept token, few clusters (long chains, many refills) and as
+    many clusters as tokens (nothing merges)."""
+    cfg = dataclasses.replace(synth.CONFIGS["S2"], V=V, k=k, Tmax=9, B=2, n_clusters=clusters,
+                              name=f"paper{V}_{k}_{clusters}")
+    inp = synth.make_inputs(cfg)
+    st = U.GpuStage(inp, ctx=ctx, route=binding.ASAP_ROUTE_PAPER, sim_threshold=threshold)
+    buf = st.run()
+    for b in range(cfg.B):
+        U.compare_image_paper(inp, buf, b, threshold, 1.0)
+
+
 def test_paper_routing_config2_and_config6_sample(ctx):
     for name, images in (("C2", [0]), ("C6", [0, 9])):
         cfg = synth.CONFIGS[name]
