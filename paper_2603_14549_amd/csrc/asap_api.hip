@@ -202,7 +202,7 @@ asap_status asap_check_params(const asap_params* p, char* msg, size_t msg_len) {
 
 size_t asap_workspace_bytes(const asap_params* p) {
   if (check_params(p, nullptr, 0) != ASAP_OK) return 0;
-  size_t a = score_workspace(*p).total, b = paper_workspace_bytes(*p);
+  size_t a = score_workspace(*p).total, b = paper_workspace_bytes(*p) + sim_workspace_bytes(*p);
   return a > b ? a : b;
 }
 

@@ -72,10 +72,11 @@ hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, i
 // Cosine routing (asap_sim.hip): for each of the M source tokens srcs[b,:] the most similar kept
 // token (slot in kept, -1 if the similarity does not exceed the threshold) and that similarity.
 // anchored: the routing inside the kept set of Sec. 4.2 (srcs = kept, M = k): only destinations
-// stronger than the source count, by s_hat [B,V] and then by index.
+// stronger than the source count, by s_hat [B,V] and then by index.  ws: sim_workspace_bytes(p).
+size_t sim_workspace_bytes(const asap_params& p);
 hipError_t launch_similarity(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
                              const int32_t* kept, const int32_t* srcs, int M, bool anchored, const float* s_hat,
-                             int32_t* assign, float* best_sim, hipStream_t st, Timer* tm);
+                             int32_t* assign, float* best_sim, char* ws, hipStream_t st, Timer* tm);
 
 // Second half of the paper's routing (asap_paper.hip): chains of destinations followed to their
 // roots, the vacated slots refilled with the pruned tokens of largest raw mass, the final kept list

@@ -191,7 +191,8 @@ hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, i
     // kept x kept search (destinations into the workspace) -> roots, refills, final list -> merge
     // with the kept tokens as candidates and the final list in the place of the kept list
     int32_t* dest = reinterpret_cast<int32_t*>(ws);
-    hipError_t e = launch_similarity(p, hidden, hsb, hsr, kept, kept, p.k, true, s_hat, dest, best_sim, st, tm);
+    hipError_t e = launch_similarity(p, hidden, hsb, hsr, kept, kept, p.k, true, s_hat, dest, best_sim,
+                                     ws + paper_workspace_bytes(p), st, tm);
     if (e != hipSuccess) return e;
     e = launch_paper_plan(p, dest, kept, s_raw, final_idx, assign, st, tm);
     if (e != hipSuccess) return e;
@@ -202,7 +203,7 @@ hipError_t launch_merge(const asap_params& p, const void* hidden, int64_t hsb, i
   }
   const int M = p.V - p.k;
   if (M > 0) {
-    hipError_t e = launch_similarity(p, hidden, hsb, hsr, kept, pruned, M, false, s_hat, assign, best_sim, st, tm);
+    hipError_t e = launch_similarity(p, hidden, hsb, hsr, kept, pruned, M, false, s_hat, assign, best_sim, ws, st, tm);
     if (e != hipSuccess) return e;
   }
   return bf ? merge_typed<bf16_t>(p, hidden, hsb, hsr, s_hat, text_len, kept, pruned, M, out_hidden, pos_out, new_len,

@@ -16,6 +16,10 @@ __device__ __forceinline__ uint32_t float_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+__device__ __forceinline__ float float_unkey(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
 // exclusive block scan of one int per thread; returns the exclusive prefix, total via *total.
 __device__ __forceinline__ int block_scan_excl(int x, int* wave_sums /*[17]*/, int* total) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

@@ -21,6 +21,7 @@
 //                 ids with the same id % 8 -- they then share that XCD's L2 for the kept panel.
 #include "asap_device.hpp"
 #include "asap_launch.hpp"
+#include "asap_select.hpp"
 
 namespace asap {
 
@@ -80,8 +81,9 @@ template <typename T, int NT, bool ANCHORED>
 __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t sb, int64_t sr, int D,
                                               const int32_t* __restrict__ pruned, const int32_t* __restrict__ kept,
                                               const float* __restrict__ s_hat, int V, int B, int M, int k,
-                                              int mtiles, float threshold, int32_t* __restrict__ assign,
-                                              float* __restrict__ best_sim) {
+                                              int mtiles, int ptiles, float threshold, int32_t* __restrict__ assign,
+                                              float* __restrict__ best_sim, unsigned long long* __restrict__ best_key,
+                                              float* __restrict__ src_norm2) {
   constexpr int BN = 64 * NT;
   constexpr int PA = SIM_BM / 32;                // source-row loads a thread issues per step
   constexpr int PB = BN / 32;                    // destination-row loads
@@ -96,7 +98,10 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
   float* srow = reinterpret_cast<float*>(part + 2 * SIM_BM);     // [BM] salience of the source rows (ANCHORED)
 
   // XCD-aware decode of the linear workgroup id
-  const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
+  // (a workgroup = one source tile x one destination tile; the destination tiles of a source tile
+  // are neighbours in the id order)
+  const int xcd = blockIdx.x % NUM_XCD, slot_p = blockIdx.x / NUM_XCD;
+  const int pass = slot_p % ptiles, slot = slot_p / ptiles;
   const int b = (slot / mtiles) * NUM_XCD + xcd;
   if (b >= B) return;
   const int m0 = (slot % mtiles) * SIM_BM;
@@ -108,7 +113,6 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
   const char* xb = reinterpret_cast<const char*>(xv + b * sb);
   const int64_t rowb = sr * (int64_t)sizeof(T);
   const int steps = (D * (int)sizeof(T)) / SIM_ROWB;
-  const int npass = (k + BN - 1) / BN;
   // Every workgroup walks the hidden dimension from its own starting step: rows are a power-of-two
   // number of bytes apart, so workgroups in lockstep would all hit the same memory channel.
   const int rot = ((slot % mtiles) + 16 * (slot / mtiles)) % steps;
@@ -136,10 +140,10 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
   if (ANCHORED) {            // the barriers of the fill below make these visible
     if (tid < SIM_BM) srow[tid] = s_hat[(int64_t)b * V + pruned[(int64_t)b * M + min(m0 + tid, M - 1)]];
   }
-  float run_v = -INFINITY;   // running best over destination passes (threads < BM)
+  float run_v = -INFINITY;   // best of this workgroup's destination tile (threads < BM)
   int run_c = 0;
 
-  for (int pass = 0; pass < npass; ++pass) {
+  {
     const int n0 = pass * BN;
 #pragma unroll
     for (int j = 0; j < PB; ++j) {
@@ -234,7 +238,7 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
 
     wait_all_vmem();   // the repeated loads of the last steps
     // the two lane halves hold the two halves of every 128-byte slice
-    if (pass == 0 && wn == 0) {
+    if (wn == 0) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         float v = ss_a[i].total();
@@ -321,25 +325,60 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
       float v0 = __uint_as_float(p0.x), v1 = __uint_as_float(p1.x);
       int c0 = (int)p0.y, c1 = (int)p1.y;
       if (v1 > v0 || (v1 == v0 && c1 < c0)) { v0 = v1; c0 = c1; }
-      if (v0 > run_v) { run_v = v0; run_c = c0; }     // earlier passes hold smaller columns
+      run_v = v0;
+      run_c = c0;
     }
-    __syncthreads();
   }
   if (tid < SIM_BM && m0 + tid < M) {
-    float c = run_v / fmaxf(sqrtf(norm2[tid]), 1e-8f);
-    int64_t o = (int64_t)b * M + m0 + tid;
-    best_sim[o] = c;
-    assign[o] = (c > threshold) ? run_c : -1;
+    const int64_t o = (int64_t)b * M + m0 + tid;
+    if (ptiles == 1) {
+      float c = run_v / fmaxf(sqrtf(norm2[tid]), 1e-8f);
+      best_sim[o] = c;
+      assign[o] = (c > threshold) ? run_c : -1;
+    } else {
+      // several destination tiles per source row: the best (value, then smaller column) wins an
+      // integer max in global memory; k_sim_finish turns the winner into assign / best_sim
+      const unsigned long long key = ((unsigned long long)float_key(run_v) << 32) | (0xFFFFFFFFu - (uint32_t)run_c);
+      atomicMax(&best_key[o], key);
+      if (pass == 0) src_norm2[o] = norm2[tid];
+    }
   }
+}
+
+// grid (ceil(n / 256)): clears the arg-max keys (0 is below the key of every value, -inf included)
+__global__ __launch_bounds__(256) void k_sim_clear(unsigned long long* __restrict__ best_key, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) best_key[i] = 0ull;
+}
+
+// grid (ceil(n / 256)): winner of the destination tiles -> assign, best_sim
+__global__ __launch_bounds__(256) void k_sim_finish(const unsigned long long* __restrict__ best_key,
+                                                     const float* __restrict__ src_norm2, int n, float threshold,
+                                                     int32_t* __restrict__ assign, float* __restrict__ best_sim) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const unsigned long long key = best_key[i];
+  const float v = float_unkey((uint32_t)(key >> 32));
+  const int col = (int)(0xFFFFFFFFu - (uint32_t)key);
+  const float c = v / fmaxf(sqrtf(src_norm2[i]), 1e-8f);
+  best_sim[i] = c;
+  assign[i] = (c > threshold) ? col : -1;
 }
 
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+// arg-max keys and source norms for up to max(k, V-k) source rows per image (used when the
+// destination rows are split over several workgroups)
+size_t sim_workspace_bytes(const asap_params& p) {
+  const size_t m = (size_t)p.B * (p.V - p.k > p.k ? p.V - p.k : p.k);
+  return align256(sizeof(unsigned long long) * m) + align256(sizeof(float) * m);
+}
+
 template <typename T, int NT, bool ANCHORED>
 static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, int64_t sr, const int32_t* srcs,
                                 int M, const int32_t* kept, const float* s_hat, int32_t* assign, float* best_sim,
-                                hipStream_t st, Timer* tm) {
+                                char* ws, hipStream_t st, Timer* tm) {
   constexpr int BN = 64 * NT;
   const size_t lds = (size_t)(SIM_NA * SIM_BM + 2 * BN) * SIM_ROWB + sizeof(float) * (6 * SIM_BM + BN);
   auto kern = k_sim<T, NT, ANCHORED>;
@@ -349,19 +388,31 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
     if (e != hipSuccess) return e;
   }
   const int mtiles = (M + SIM_BM - 1) / SIM_BM;
+  const int ptiles = (p.k + BN - 1) / BN;
   const int groups = (p.B + NUM_XCD - 1) / NUM_XCD;
-  ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * mtiles), dim3(256), lds, st, xv, sb, sr, p.D, srcs,
-              kept, s_hat, p.V, p.B, M, p.k, mtiles, p.sim_threshold, assign, best_sim);
+  const int n = p.B * M;
+  unsigned long long* keys = reinterpret_cast<unsigned long long*>(ws);
+  float* norms = reinterpret_cast<float*>(ws + align256(sizeof(unsigned long long) * (size_t)p.B * (p.V - p.k > p.k ? p.V - p.k : p.k)));
+  if (ptiles > 1) ASAP_LAUNCH(tm, "k_sim_clear", k_sim_clear, dim3((n + 255) / 256), dim3(256), 0, st, keys, n);
+  ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * mtiles * ptiles), dim3(256), lds, st, xv, sb, sr, p.D, srcs,
+              kept, s_hat, p.V, p.B, M, p.k, mtiles, ptiles, p.sim_threshold, assign, best_sim, keys, norms);
+  if (ptiles > 1)
+    ASAP_LAUNCH(tm, "k_sim_finish", k_sim_finish, dim3((n + 255) / 256), dim3(256), 0, st, keys, norms, n,
+                p.sim_threshold, assign, best_sim);
   return hipGetLastError();
 }
 
-// destination tile width: fewest padded columns overall, then fewest passes
-static int pick_nt(int k) {
+// Destination tile width 64 * nt.  The kernel is bound by what it loads, (128 + 64 nt) rows per step
+// and workgroup, and the workgroups run in rounds of one per compute unit: fewest rounds x rows,
+// then the wider tile.
+static int pick_nt(const asap_params& p, int M) {
+  const long mt = (M + SIM_BM - 1) / SIM_BM;
   int best_nt = 5;
   long best_cost = -1;
-  for (int nt = 1; nt <= 5; ++nt) {
-    long bn = 64 * nt, passes = (k + bn - 1) / bn;
-    long cost = passes * bn * 8 + passes;     // padded MFMA columns dominate
+  for (int nt = 5; nt >= 1; --nt) {
+    const long bn = 64 * nt, passes = (p.k + bn - 1) / bn;
+    const long wgs = (long)p.B * mt * passes, rounds = (wgs + 255) / 256;
+    const long cost = rounds * (SIM_BM + bn);
     if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_nt = nt; }
   }
   return best_nt;
@@ -370,26 +421,26 @@ static int pick_nt(int k) {
 template <typename T, bool ANCHORED>
 static hipError_t sim_typed(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
                             const int32_t* kept, const int32_t* srcs, int M, const float* s_hat, int32_t* assign,
-                            float* best_sim, hipStream_t st, Timer* tm) {
+                            float* best_sim, char* ws, hipStream_t st, Timer* tm) {
   const T* xv = static_cast<const T*>(hidden) + (int64_t)p.P * hsr;
-  switch (pick_nt(p.k)) {
-    case 1: return launch_sim_nt<T, 1, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, st, tm);
-    case 2: return launch_sim_nt<T, 2, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, st, tm);
-    case 3: return launch_sim_nt<T, 3, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, st, tm);
-    case 4: return launch_sim_nt<T, 4, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, st, tm);
-    default: return launch_sim_nt<T, 5, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, st, tm);
+  switch (pick_nt(p, M)) {
+    case 1: return launch_sim_nt<T, 1, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, ws, st, tm);
+    case 2: return launch_sim_nt<T, 2, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, ws, st, tm);
+    case 3: return launch_sim_nt<T, 3, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, ws, st, tm);
+    case 4: return launch_sim_nt<T, 4, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, ws, st, tm);
+    default: return launch_sim_nt<T, 5, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, ws, st, tm);
   }
 }
 
 hipError_t launch_similarity(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr,
                              const int32_t* kept, const int32_t* srcs, int M, bool anchored, const float* s_hat,
-                             int32_t* assign, float* best_sim, hipStream_t st, Timer* tm) {
+                             int32_t* assign, float* best_sim, char* ws, hipStream_t st, Timer* tm) {
   const bool bf = p.h_dtype == ASAP_BF16;
   if (anchored)
-    return bf ? sim_typed<bf16_t, true>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, st, tm)
-              : sim_typed<float, true>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, st, tm);
-  return bf ? sim_typed<bf16_t, false>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, st, tm)
-            : sim_typed<float, false>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, st, tm);
+    return bf ? sim_typed<bf16_t, true>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, ws, st, tm)
+              : sim_typed<float, true>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, ws, st, tm);
+  return bf ? sim_typed<bf16_t, false>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, ws, st, tm)
+            : sim_typed<float, false>(p, hidden, hsb, hsr, kept, srcs, M, s_hat, assign, best_sim, ws, st, tm);
 }
 
 }  // namespace asap
