@@ -70,8 +70,9 @@ def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
     return {"per_kernel": per_kernel, "stage": stage, "sim_flops": 2.0 * B * (V - k) * k * D}
 
 
-def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb") -> dict:
+def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb", lse_extra=None) -> dict:
     """The oracle as it stands, timed on the host on the first few images of the batch."""
+    import numpy as np
     from oracle import asap_oracle as O          # only this leg touches the oracle
     from paper_2603_14549_amd import synth
     try:
@@ -85,7 +86,8 @@ def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb") -> dic
         b = done % cfg.B
         ref = O.stage(synth.to_f64(inp["q"][b], cfg.qk_dtype), synth.to_f64(inp["k"][b], cfg.qk_dtype),
                       synth.to_f64(inp["hidden"][b], cfg.h_dtype), int(inp["text_len"][b]), cfg.P, cfg.V,
-                      cfg.Tmax, cfg.k, linear_mass=True, route=route)
+                      cfg.Tmax, cfg.k, linear_mass=True, route=route,
+                      lse_extra=None if lse_extra is None else lse_extra[b].astype(np.float64))
         for l in range(cfg.L_kv):
             for cache in (inp["k_cache"][l], inp["v_cache"][l]):
                 O.gather_kv(cache[b], ref["pos_out"], ref["new_len"])
@@ -155,6 +157,9 @@ def main():
     ap.add_argument("--attention", action="store_true",
                     help="measure asap_attention (one layer's forward under the Eq. 4-5 mask) on the workload's "
                          "shapes instead of the pruning stage; prints its own JSON line")
+    ap.add_argument("--lse-extra", action="store_true",
+                    help="full-row softmax timing path (Eq. 5 over the whole row): pass a seeded log-sum-exp of "
+                         "every text row's non-visual logits, which the score kernels fold into the denominators")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (reference for HBM counters)")
@@ -180,7 +185,11 @@ def main():
     ctx = binding.Context(0)
     paper = args.route == "paper"
     overrides = dict(route=binding.ASAP_ROUTE_PAPER, sim_threshold=0.8) if paper else {}
-    stage = binding.DeviceStage(inp, ctx=ctx, **overrides)
+    lse_extra = None
+    if args.lse_extra:
+        lse_extra = np.random.default_rng(cfg.seed + 1000).normal(2.0, 2.0, size=(cfg.B, cfg.H, cfg.Tmax)) \
+            .astype(np.float32)
+    stage = binding.DeviceStage(inp, ctx=ctx, lse_extra=lse_extra, **overrides)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -270,7 +279,8 @@ def main():
                                f"hidden {cfg.D}, {cfg.H}/{cfg.Hkv} heads x {cfg.d}, keep {cfg.k}, "
                                f"qk/hidden/kv dtypes {cfg.qk_dtype}/{cfg.h_dtype}/{cfg.kv_dtype}, "
                                f"{cfg.L_kv} K/V layers, mask=keybias, route={args.route}"
-                               f"{' (t=0.8)' if paper else ''}, mu=1",
+                               f"{' (t=0.8)' if paper else ''}, mu=1"
+                               f"{', softmax over the full row (lse_extra)' if args.lse_extra else ''}",
                    "input_generation_s": round(gen_s, 1)},
         "roofline": roofline,
         "stage_roofline": stage_roofline,
@@ -278,7 +288,7 @@ def main():
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(inp, cfg, route=args.route)
+        out["cpu_baseline"] = cpu_baseline(inp, cfg, route=args.route, lse_extra=lse_extra)
     print(json.dumps(out))
 
 

@@ -267,6 +267,18 @@ def gather_kv(cache: np.ndarray, pos_out: np.ndarray, new_len: int) -> np.ndarra
     return cache[:, pos_out[:new_len], :]
 
 
+def gather_kv_paged(src_pool: np.ndarray, src_pages: np.ndarray, dst_pool: np.ndarray, dst_pages: np.ndarray,
+                    pos_out: np.ndarray, new_len: int) -> None:
+    """The same gather for one sequence of a paged cache (the block-table layout serving engines
+    use; "KV-cache compatibility" of the stage).  Pools are [n_pages, Hkv, page_size, d]; token n of
+    the sequence lives in page pages[n // page_size] at slot n % page_size.  Writes, in place,
+    dst token n = src token pos_out[n] for n < new_len; nothing else of dst_pool changes."""
+    ps = src_pool.shape[2]
+    for n in range(new_len):
+        m = int(pos_out[n])
+        dst_pool[dst_pages[n // ps], :, n % ps, :] = src_pool[src_pages[m // ps], :, m % ps, :]
+
+
 # ---------------------------------------------------------------- whole stage, one image
 def stage(Q: np.ndarray, K: np.ndarray, X: np.ndarray, text_len: int, P: int, V: int, Tmax: int,
           k: int, lambda_max: float = 1.0, eps: float = EPS_DEFAULT, mask_on: bool = True,

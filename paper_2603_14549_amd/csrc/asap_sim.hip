@@ -19,6 +19,13 @@
 //                 The grid is one-dimensional and XCD-aware: consecutive workgroup ids go to the 8
 //                 XCDs round-robin, so id % 8 picks the XCD and all tiles of one image are given
 //                 ids with the same id % 8 -- they then share that XCD's L2 for the kept panel.
+//                 A workgroup takes one destination tile.  When the destination rows need several
+//                 (k > 64*NT), the tiles of a source tile are workgroups of their own: each folds its
+//                 row winner into a 64-bit key (order-preserving value bits, then the inverted
+//                 column so that equal values keep the smaller column) with an integer atomic max
+//                 in global memory -- exact and order-independent.
+//   k_sim_clear   zeroes those keys (only launched when there are several destination tiles)
+//   k_sim_finish  winner key -> assign, best_sim (threshold and source norm applied here)
 #include "asap_device.hpp"
 #include "asap_launch.hpp"
 #include "asap_select.hpp"

@@ -398,6 +398,38 @@ def test_assemble_and_gather():
         assert (got[:, n] == cache[:, pos[n]]).all()
 
 
+def test_paged_gather_against_hand_placed_tokens():
+    """Paged K/V gather.  Token values encode (token, head) so every placement can be read off by
+    hand: a 7-token sequence scattered over pages 5, 0, 3 of a pool with 3 slots per page is
+    compacted to tokens 0, 2, 3, 6 in pages 4, 1.  Every other slot of the destination pool keeps
+    its sentinel, and with pages laid out in order the result is the contiguous gather."""
+    Hkv, d, ps = 2, 3, 3
+    src_pages, dst_pages = np.array([5, 0, 3]), np.array([4, 1])
+    src_pool = np.full((6, Hkv, ps, d), -7.0)
+    for n in range(7):
+        for g in range(Hkv):
+            src_pool[src_pages[n // ps], g, n % ps] = 100 * n + 10 * g + np.arange(d)
+    pos, new_len = np.array([0, 2, 3, 6, -1, -1]), 4
+    dst_pool = np.full((6, Hkv, ps, d), -1.0)
+    O.gather_kv_paged(src_pool, src_pages, dst_pool, dst_pages, pos, new_len)
+    expect = np.full((6, Hkv, ps, d), -1.0)
+    for g in range(Hkv):
+        expect[4, g, 0] = 0 + 10 * g + np.arange(d)       # token 0 -> page 4 slot 0
+        expect[4, g, 1] = 200 + 10 * g + np.arange(d)     # token 2 -> page 4 slot 1
+        expect[4, g, 2] = 300 + 10 * g + np.arange(d)     # token 3 -> page 4 slot 2
+        expect[1, g, 0] = 600 + 10 * g + np.arange(d)     # token 6 -> page 1 slot 0
+    assert (dst_pool == expect).all()
+    # identity tables: the pool is the contiguous cache cut into pages
+    N, ps2 = 12, 4
+    cache = rng(51).standard_normal((Hkv, N, d))
+    pool = cache.reshape(Hkv, N // ps2, ps2, d).transpose(1, 0, 2, 3).copy()
+    pos2, nl2 = np.array([1, 2, 5, 7, 8, 11, -1, -1]), 6
+    out_pool = np.zeros((2, Hkv, ps2, d))
+    O.gather_kv_paged(pool, np.arange(3), out_pool, np.arange(2), pos2, nl2)
+    flat = out_pool.transpose(1, 0, 2, 3).reshape(Hkv, 8, d)
+    assert (flat[:, :nl2] == cache[:, pos2[:nl2]]).all() and (flat[:, nl2:] == 0).all()
+
+
 # ------------------------------------------------------------------ whole stage: reduction invariant
 def test_stage_reduces_to_plain_topk_attention_pruning():
     """Mask off and merge weight 0 => the stage is the baseline the ablation starts from:
