@@ -194,6 +194,28 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
                             const int32_t* pos_out, const int32_t* new_len, void* stream);
 
 /*
+ * asap_compact_kv_paged -- asap_compact_kv for caches kept as pools of fixed-size pages with one
+ * block table per sequence (the layout of paged serving engines; the paper fixes no cache layout, its
+ * efficiency analysis only counts the K/V storage the pruned rows free).  A pool is
+ * [n_pages, Hkv, page_size, d] in kv_dtype, contiguous, 16-byte aligned; token n of image b lives in
+ * page table[b * table_stride + n / page_size] at slot n % page_size.  For every layer, K and V:
+ *   dst_pool[dst_table[b, n / page_size], g, n % page_size, :] =
+ *   src_pool[src_table[b, m / page_size], g, m % page_size, :],  m = pos_out[b,n],  n < new_len[b]
+ * (bit-exact copy); no other slot of a destination pool is written.  Out of place: a destination
+ * page must not be a source page of any sequence of the batch, but both tables may index one pool
+ * (k_dst_pool[l] == k_src_pool[l] is allowed).  Tables are int32 device arrays shared by all
+ * layers; src_table_stride >= ceil((P+V+Tmax) / page_size), dst_table_stride >=
+ * ceil((P+k+Tmax) / page_size); page numbers are not checked against the pool sizes, which the
+ * library does not know.  *_pool: [host] arrays of n_layers DEVICE pointers.  1 <= n_layers <= 64.
+ */
+asap_status asap_compact_kv_paged(asap_ctx* ctx, const asap_params* p, int32_t n_layers,
+                                  const void* const* k_src_pool, const void* const* v_src_pool,
+                                  void* const* k_dst_pool, void* const* v_dst_pool, int32_t page_size,
+                                  const int32_t* src_table, int32_t src_table_stride,
+                                  const int32_t* dst_table, int32_t dst_table_stride,
+                                  const int32_t* pos_out, const int32_t* new_len, void* stream);
+
+/*
  * asap_attention -- the attention forward of one decoder layer in front of the pruning layer under
  * the salience-guided bidirectional mask (Sec. 4.1, Eq. 4-5 applied to the whole sequence):
  *   out[b,h,i,:] = sum_j A_ij v[b,g(h),j,:],   A_i. = softmax_j( q[b,h,i,:] . k[b,g(h),j,:] / sqrt(d) + M_ij ),

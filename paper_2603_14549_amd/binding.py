@@ -21,7 +21,8 @@ ASAP_MASK_OFF, ASAP_MASK_KEYBIAS = 0, 1
 ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
 
 EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
-           "asap_score", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv", "asap_timing_enable",
+           "asap_score", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv", "asap_compact_kv_paged",
+           "asap_timing_enable",
            "asap_timing_collect", "asap_theoretical_flops", "asap_flops_ratio", "asap_attention",
            "asap_attention_workspace_bytes"]
 
@@ -87,6 +88,10 @@ def load() -> ctypes.CDLL:
     lib.asap_compact_kv.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                     ctypes.POINTER(vp), ctypes.POINTER(vp), i32p, i32p, vp]
     lib.asap_compact_kv.restype = ctypes.c_int
+    lib.asap_compact_kv_paged.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                          ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int32, i32p,
+                                          ctypes.c_int32, i32p, ctypes.c_int32, i32p, i32p, vp]
+    lib.asap_compact_kv_paged.restype = ctypes.c_int
     lib.asap_attention_workspace_bytes.argtypes = [pp]
     lib.asap_attention_workspace_bytes.restype = ctypes.c_size_t
     lib.asap_attention.argtypes = [vp, pp, vp, i64p, vp, i64p, vp, i64p, f32p, vp, vp, ctypes.c_size_t, vp]
@@ -252,6 +257,16 @@ class Context:
             self._h, ctypes.byref(p), n, arr(k_src), arr(v_src), arr(k_dst), arr(v_dst), _ptr(pos_out),
             _ptr(new_len), _stream(stream)))
 
+    def asap_compact_kv_paged(self, p, k_src_pool: Sequence[torch.Tensor], v_src_pool, k_dst_pool, v_dst_pool,
+                              page_size: int, src_table, dst_table, pos_out, new_len, stream=None):
+        """Pools [n_pages,Hkv,page_size,d] per layer; src_table / dst_table [B, pages per sequence] int32."""
+        n = len(k_src_pool)
+        arr = lambda ts: (ctypes.c_void_p * n)(*[t.data_ptr() for t in ts])
+        self._check(self._lib.asap_compact_kv_paged(
+            self._h, ctypes.byref(p), n, arr(k_src_pool), arr(v_src_pool), arr(k_dst_pool), arr(v_dst_pool),
+            int(page_size), _ptr(src_table), int(src_table.stride(0)), _ptr(dst_table), int(dst_table.stride(0)),
+            _ptr(pos_out), _ptr(new_len), _stream(stream)))
+
 
 class StageBuffers:
     """Device buffers of one pruning stage (outputs + workspace), allocated once with torch."""
@@ -283,36 +298,74 @@ class StageBuffers:
         self.workspace = torch.empty(max(asap_workspace_bytes(p), 256), dtype=torch.uint8, device=dev)
 
 
+class PagedKV:
+    """K/V caches of the layers in front of the pruning layer as pools of pages [n_pages,Hkv,page_size,d]
+    with block tables [B, pages per sequence]; built on the device from contiguous caches [B,Hkv,N,d]
+    with a seeded random placement of the pages.  Source and destination pages share one pool per
+    cache, as they would in a serving engine that frees the source pages afterwards."""
+
+    def __init__(self, p: asap_params, k_cache: List[torch.Tensor], v_cache: List[torch.Tensor], page_size: int,
+                 seed: int = 0):
+        N, Nout, ps = p.P + p.V + p.Tmax, p.P + p.k + p.Tmax, int(page_size)
+        sp, dp = -(-N // ps), -(-Nout // ps)
+        self.page_size, self.n_pages = ps, p.B * (sp + dp)
+        g = torch.Generator().manual_seed(seed)
+        perm = torch.randperm(self.n_pages, generator=g).to(torch.int32)
+        self.src_table = perm[:p.B * sp].reshape(p.B, sp).contiguous().cuda()
+        self.dst_table = perm[p.B * sp:].reshape(p.B, dp).contiguous().cuda()
+
+        def pool_of(cache):
+            padded = torch.zeros(p.B, p.Hkv, sp * ps, p.d, dtype=cache.dtype, device=cache.device)
+            padded[:, :, :N] = cache
+            pages = padded.view(p.B, p.Hkv, sp, ps, p.d).permute(0, 2, 1, 3, 4).reshape(p.B * sp, p.Hkv, ps, p.d)
+            pool = torch.zeros(self.n_pages, p.Hkv, ps, p.d, dtype=cache.dtype, device=cache.device)
+            pool[self.src_table.flatten().long()] = pages
+            return pool
+        self.k_pool = [pool_of(c) for c in k_cache]
+        self.v_pool = [pool_of(c) for c in v_cache]
+
+    def compact(self, ctx: "Context", p: asap_params, pos_out, new_len, stream=None):
+        ctx.asap_compact_kv_paged(p, self.k_pool, self.v_pool, self.k_pool, self.v_pool, self.page_size,
+                                  self.src_table, self.dst_table, pos_out, new_len, stream)
+
+
 def run_stage(ctx: Context, p: asap_params, q: torch.Tensor, k: torch.Tensor, hidden: torch.Tensor,
               text_len: torch.Tensor, k_cache: List[torch.Tensor], v_cache: List[torch.Tensor],
               buf: StageBuffers, lse_extra: Optional[torch.Tensor] = None, stream=None,
-              side_stream=None) -> StageBuffers:
+              side_stream=None, paged: Optional[PagedKV] = None) -> StageBuffers:
     """The calls of one stage.  q [B,H,N,d], k [B,Hkv,N,d], hidden [B,N,D]; the visual / text blocks
     are passed to the library as strided views.  With a side stream the K/V compaction, which only
     needs the positions that follow from the kept set (asap_positions), runs there next to the
-    similarity and merge kernels of the main stream; the main stream waits for it at the end."""
+    similarity and merge kernels of the main stream; the main stream waits for it at the end.
+    With `paged` the caches are its pools (k_cache / v_cache are ignored)."""
     P, V = p.P, p.V
     q_vis, q_txt, k_vis = q[:, :, P:P + V], q[:, :, P + V:], k[:, :, P:P + V]
     main = torch.cuda.current_stream() if stream is None else stream
     ctx.asap_score(p, q_vis, q_txt, k_vis, text_len, lse_extra, buf.s_raw, buf.s_hat, buf.score,
                    buf.workspace, main)
     ctx.asap_select(p, buf.score, buf.kept_idx, buf.pruned_idx, buf.workspace, main)
-    overlap = bool(k_cache) and side_stream is not None and p.route == ASAP_ROUTE_ABSORB
+    has_kv = bool(k_cache) or paged is not None
+
+    def compact(pos, nl, st):
+        if paged is not None:
+            paged.compact(ctx, p, pos, nl, st)
+        else:
+            ctx.asap_compact_kv(p, k_cache, v_cache, buf.k_dst, buf.v_dst, pos, nl, st)
+    overlap = has_kv and side_stream is not None and p.route == ASAP_ROUTE_ABSORB
     if overlap:
         ctx.asap_positions(p, buf.kept_idx, text_len, buf.pos_early, buf.new_len_early, main)
         fork = torch.cuda.Event()
         fork.record(main)
         side_stream.wait_event(fork)
-        ctx.asap_compact_kv(p, k_cache, v_cache, buf.k_dst, buf.v_dst, buf.pos_early, buf.new_len_early,
-                            side_stream)
+        compact(buf.pos_early, buf.new_len_early, side_stream)
     ctx.asap_merge(p, hidden, buf.s_raw, buf.s_hat, text_len, buf.kept_idx, buf.pruned_idx, buf.out_hidden, buf.pos_out,
                    buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace, main)
     if overlap:
         join = torch.cuda.Event()
         join.record(side_stream)
         main.wait_event(join)
-    elif k_cache:
-        ctx.asap_compact_kv(p, k_cache, v_cache, buf.k_dst, buf.v_dst, buf.pos_out, buf.new_len, main)
+    elif has_kv:
+        compact(buf.pos_out, buf.new_len, main)
     return buf
 
 
@@ -329,7 +382,7 @@ class DeviceStage:
     library calls of one stage (overlap=True: K/V compaction on a second stream, see run_stage)."""
 
     def __init__(self, inp: dict, ctx: Optional[Context] = None, lse_extra=None, overlap: bool = True,
-                 **param_overrides):
+                 page_size: Optional[int] = None, **param_overrides):
         import numpy as np
         cfg = inp["cfg"]
         self.cfg = cfg
@@ -342,13 +395,18 @@ class DeviceStage:
         self.k_cache = [to_device(a, cfg.kv_dtype) for a in inp.get("k_cache", [])]
         self.v_cache = [to_device(a, cfg.kv_dtype) for a in inp.get("v_cache", [])]
         self.lse_extra = None if lse_extra is None else torch.from_numpy(lse_extra.astype(np.float32)).cuda()
+        self.paged = None
+        if page_size and self.k_cache:
+            # the caches become pools of pages; the contiguous copies and destinations are not kept
+            self.paged = PagedKV(self.p, self.k_cache, self.v_cache, page_size, seed=cfg.seed)
+            self.k_cache, self.v_cache = [], []
         self.buf = StageBuffers(self.p, len(self.k_cache))
         # default-priority second stream for the K/V compaction (None = everything on one stream)
-        self.side_stream = torch.cuda.Stream() if (overlap and self.k_cache) else None
+        self.side_stream = torch.cuda.Stream() if (overlap and (self.k_cache or self.paged)) else None
 
     def run_async(self) -> StageBuffers:
         return run_stage(self.ctx, self.p, self.q, self.k, self.hidden, self.text_len, self.k_cache,
-                         self.v_cache, self.buf, self.lse_extra, side_stream=self.side_stream)
+                         self.v_cache, self.buf, self.lse_extra, side_stream=self.side_stream, paged=self.paged)
 
     def run(self) -> StageBuffers:
         self.run_async()

@@ -328,6 +328,41 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
                     "asap_compact_kv launch");
 }
 
+asap_status asap_compact_kv_paged(asap_ctx* ctx, const asap_params* p, int32_t n_layers,
+                                  const void* const* k_src_pool, const void* const* v_src_pool,
+                                  void* const* k_dst_pool, void* const* v_dst_pool, int32_t page_size,
+                                  const int32_t* src_table, int32_t src_table_stride, const int32_t* dst_table,
+                                  int32_t dst_table_stride, const int32_t* pos_out, const int32_t* new_len,
+                                  void* stream) {
+  asap_status st = common_checks(ctx, p);
+  if (st != ASAP_OK) return st;
+  if (n_layers < 1 || n_layers > 64)
+    return fail(ctx, ASAP_EINVAL, "asap_compact_kv_paged: n_layers must be in [1, 64]");
+  if (!k_src_pool || !v_src_pool || !k_dst_pool || !v_dst_pool || !src_table || !dst_table || !pos_out || !new_len)
+    return fail(ctx, ASAP_EINVAL, "asap_compact_kv_paged: a required pointer is NULL");
+  if (page_size < 1) return fail(ctx, ASAP_EINVAL, "asap_compact_kv_paged: page_size must be >= 1");
+  const int64_t n_in = (int64_t)p->P + p->V + p->Tmax, n_out = (int64_t)p->P + p->k + p->Tmax;
+  if (src_table_stride < (n_in + page_size - 1) / page_size)
+    return fail(ctx, ASAP_EINVAL, "asap_compact_kv_paged: src_table_stride %d below the %lld pages of a sequence",
+                src_table_stride, (long long)((n_in + page_size - 1) / page_size));
+  if (dst_table_stride < (n_out + page_size - 1) / page_size)
+    return fail(ctx, ASAP_EINVAL, "asap_compact_kv_paged: dst_table_stride %d below the %lld pages of a sequence",
+                dst_table_stride, (long long)((n_out + page_size - 1) / page_size));
+  for (int l = 0; l < n_layers; ++l) {
+    const void* ptrs[4] = {k_src_pool[l], v_src_pool[l], k_dst_pool[l], v_dst_pool[l]};
+    for (const void* q : ptrs) {
+      if (!q) return fail(ctx, ASAP_EINVAL, "asap_compact_kv_paged: layer %d has a NULL pointer", l);
+      if (!aligned16(q))
+        return fail(ctx, ASAP_EINVAL, "asap_compact_kv_paged: layer %d pointer not 16-byte aligned", l);
+    }
+  }
+  return hip_result(ctx,
+                    launch_compact_kv_paged(*p, n_layers, k_src_pool, v_src_pool, k_dst_pool, v_dst_pool, page_size,
+                                            src_table, src_table_stride, dst_table, dst_table_stride, pos_out,
+                                            new_len, static_cast<hipStream_t>(stream), ctx->timer),
+                    "asap_compact_kv_paged launch");
+}
+
 size_t asap_attention_workspace_bytes(const asap_params* p) {
   if (check_params(p, nullptr, 0) != ASAP_OK) return 0;
   return attention_workspace_bytes(*p);

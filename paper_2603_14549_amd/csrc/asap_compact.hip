@@ -3,6 +3,7 @@
 //
 // k_positions: grid (ceil(Nout / 256), B): the positions the compaction gathers, from the kept set alone.
 // k_compact: grid (ceil(Nout / ROWS_PER_BLOCK), B * Hkv, 2 * layers_in_launch), 256 threads.
+// k_compact_paged: the same grid for caches kept as pools of pages with one block table per sequence.
 // A row is d elements = LPR 16-byte pieces; LPR consecutive lanes move one row.
 #include "asap_device.hpp"
 #include "asap_launch.hpp"
@@ -38,6 +39,43 @@ __global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t*
   for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
     int nrow = base + i * rpi;
     if (nrow < nl) stg16_stream(dst + (int64_t)nrow * row_bytes, v[i]);
+  }
+}
+
+// Pools are [n_pages, Hkv, page_size, d]; token n of sequence b is in page table[b, n / page_size],
+// slot n % page_size.
+__global__ __launch_bounds__(256) void k_compact_paged(KvPointers ptrs, const int32_t* __restrict__ pos_out,
+                                                        const int32_t* __restrict__ new_len,
+                                                        const int32_t* __restrict__ src_table, int src_stride,
+                                                        const int32_t* __restrict__ dst_table, int dst_stride,
+                                                        int page_size, int Hkv, int Nout, int row_bytes) {
+  const int lpr = row_bytes >> 4, rpi = 256 / lpr;
+  const int tid = threadIdx.x, piece = tid % lpr, r0 = tid / lpr;
+  const int bg = blockIdx.y, b = bg / Hkv, g = bg % Hkv;
+  const int nl = new_len[b];
+  const char* src = ptrs.src[blockIdx.z] + piece * 16;
+  char* dst = ptrs.dst[blockIdx.z] + piece * 16;
+  const int32_t* pos = pos_out + (int64_t)b * Nout;
+  const int32_t* stab = src_table + (int64_t)b * src_stride;
+  const int32_t* dtab = dst_table + (int64_t)b * dst_stride;
+  const int base = blockIdx.x * rpi * KV_ROWS_PER_THREAD + r0;
+  uint4 v[KV_ROWS_PER_THREAD];
+#pragma unroll
+  for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
+    const int nrow = base + i * rpi;
+    if (nrow < nl) {
+      const int m = pos[nrow];
+      const int64_t row = ((int64_t)stab[m / page_size] * Hkv + g) * page_size + m % page_size;
+      v[i] = ldg16_stream(src + row * row_bytes);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
+    const int nrow = base + i * rpi;
+    if (nrow < nl) {
+      const int64_t row = ((int64_t)dtab[nrow / page_size] * Hkv + g) * page_size + nrow % page_size;
+      stg16_stream(dst + row * row_bytes, v[i]);
+    }
   }
 }
 
@@ -82,6 +120,33 @@ hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* con
     for (int l = 2 * nl; l < 2 * KV_LAYERS_PER_LAUNCH; ++l) { ptrs.src[l] = nullptr; ptrs.dst[l] = nullptr; }
     dim3 grid((Nout + rows_per_block - 1) / rows_per_block, p.B * p.Hkv, 2 * nl);
     ASAP_LAUNCH(tm, "k_compact", k_compact, grid, dim3(256), 0, st, ptrs, pos_out, new_len, p.Hkv, N, Nout, row_bytes);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_compact_kv_paged(const asap_params& p, int n_layers, const void* const* k_src,
+                                   const void* const* v_src, void* const* k_dst, void* const* v_dst, int page_size,
+                                   const int32_t* src_table, int src_stride, const int32_t* dst_table,
+                                   int dst_stride, const int32_t* pos_out, const int32_t* new_len, hipStream_t st,
+                                   Timer* tm) {
+  const int row_bytes = p.d * (p.kv_dtype == ASAP_BF16 ? 2 : 4);
+  const int Nout = p.P + p.k + p.Tmax;
+  const int rows_per_block = (256 / (row_bytes / 16)) * KV_ROWS_PER_THREAD;
+  for (int l0 = 0; l0 < n_layers; l0 += KV_LAYERS_PER_LAUNCH) {
+    const int nl = n_layers - l0 < KV_LAYERS_PER_LAUNCH ? n_layers - l0 : KV_LAYERS_PER_LAUNCH;
+    KvPointers ptrs;
+    for (int l = 0; l < nl; ++l) {
+      ptrs.src[2 * l] = static_cast<const char*>(k_src[l0 + l]);
+      ptrs.src[2 * l + 1] = static_cast<const char*>(v_src[l0 + l]);
+      ptrs.dst[2 * l] = static_cast<char*>(k_dst[l0 + l]);
+      ptrs.dst[2 * l + 1] = static_cast<char*>(v_dst[l0 + l]);
+    }
+    for (int l = 2 * nl; l < 2 * KV_LAYERS_PER_LAUNCH; ++l) { ptrs.src[l] = nullptr; ptrs.dst[l] = nullptr; }
+    dim3 grid((Nout + rows_per_block - 1) / rows_per_block, p.B * p.Hkv, 2 * nl);
+    ASAP_LAUNCH(tm, "k_compact_paged", k_compact_paged, grid, dim3(256), 0, st, ptrs, pos_out, new_len, src_table,
+                src_stride, dst_table, dst_stride, page_size, p.Hkv, Nout, row_bytes);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

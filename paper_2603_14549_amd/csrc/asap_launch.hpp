@@ -91,6 +91,11 @@ hipError_t launch_positions(const asap_params& p, const int32_t* kept, const int
 hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* const* k_src,
                              const void* const* v_src, void* const* k_dst, void* const* v_dst,
                              const int32_t* pos_out, const int32_t* new_len, hipStream_t st, Timer* tm);
+hipError_t launch_compact_kv_paged(const asap_params& p, int n_layers, const void* const* k_src,
+                                   const void* const* v_src, void* const* k_dst, void* const* v_dst, int page_size,
+                                   const int32_t* src_table, int src_stride, const int32_t* dst_table,
+                                   int dst_stride, const int32_t* pos_out, const int32_t* new_len, hipStream_t st,
+                                   Timer* tm);
 
 // attention forward under the Eq. 4-5 mask (asap_attention.hip); ws needs attention_workspace_bytes(p)
 size_t attention_workspace_bytes(const asap_params& p);

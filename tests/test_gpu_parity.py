@@ -137,6 +137,70 @@ def test_positions_and_two_stream_stage(ctx):
     assert e.value.status == binding.ASAP_EUNSUPPORTED
 
 
+@pytest.mark.parametrize("name,page_size", [("S1", 16), ("S1", 7), ("S3", 1), ("S3", 64), ("S0", 256)])
+def test_paged_kv_compaction(ctx, name, page_size):
+    """asap_compact_kv_paged against the oracle's paged gather, bit for bit over the WHOLE pool
+    (slots the gather must not touch keep their sentinel).  Source and destination pages are a
+    random permutation inside one pool, so the call also covers both tables indexing one buffer."""
+    cfg = synth.CONFIGS[name]
+    inp = synth.make_inputs(cfg)
+    st = U.GpuStage(inp, ctx=ctx)
+    buf = st.run()
+    pos_out, new_len = buf.pos_out.cpu().numpy(), buf.new_len.cpu().numpy()
+    N, Nout, ps = cfg.N, cfg.P + cfg.k + cfg.Tmax, page_size
+    sp, dp = -(-N // ps), -(-Nout // ps)
+    n_pages = cfg.B * (sp + dp) + 3
+    rng = np.random.default_rng(1234 + ps)
+    perm = rng.permutation(n_pages).astype(np.int32)
+    src_table = perm[:cfg.B * sp].reshape(cfg.B, sp)
+    dst_table = np.full((cfg.B, dp + 2), -1, np.int32)           # a wider table: the stride is an argument
+    dst_table[:, :dp] = perm[cfg.B * sp:cfg.B * (sp + dp)].reshape(cfg.B, dp)
+    pools_host, pools_dev = [], []
+    for l in range(cfg.L_kv):
+        for cache in (inp["k_cache"][l], inp["v_cache"][l]):
+            sentinel = 0x7FC1 if cache.dtype == np.uint16 else np.float32(-12345.5)
+            pool = np.full((n_pages, cfg.Hkv, ps, cfg.d), sentinel, cache.dtype)
+            for b in range(cfg.B):
+                for n in range(N):
+                    pool[src_table[b, n // ps], :, n % ps, :] = cache[b][:, n, :]
+            pools_host.append(pool)
+            pools_dev.append(binding.to_device(pool, cfg.kv_dtype))
+    kp, vp = pools_dev[0::2], pools_dev[1::2]
+    ctx.asap_compact_kv_paged(st.p, kp, vp, kp, vp, ps, torch.from_numpy(src_table).cuda(),
+                              torch.from_numpy(dst_table).cuda(), buf.pos_out, buf.new_len)
+    torch.cuda.synchronize()
+    for pool, dev in zip(pools_host, pools_dev):
+        want = pool.copy()
+        for b in range(cfg.B):
+            O.gather_kv_paged(pool, src_table[b], want, dst_table[b], pos_out[b], int(new_len[b]))
+        got = U.raw_bits(dev)
+        ref = want.view(np.uint32) if want.dtype == np.float32 else want
+        assert (got == ref).all()
+    with pytest.raises(binding.AsapError) as e:       # a table narrower than a sequence's pages
+        ctx.asap_compact_kv_paged(st.p, kp, vp, kp, vp, ps, torch.from_numpy(src_table[:, :sp - 1].copy()).cuda()
+                                  if sp > 1 else torch.zeros((cfg.B, 0), dtype=torch.int32, device="cuda"),
+                                  torch.from_numpy(dst_table).cuda(), buf.pos_out, buf.new_len)
+    assert e.value.status == binding.ASAP_EINVAL
+
+
+def test_paged_stage_matches_contiguous_stage(ctx):
+    """The stage with paged caches (compaction on the second stream) leaves, in its destination pages,
+    the rows the contiguous stage leaves in its destination buffers."""
+    cfg = synth.CONFIGS["S1"]
+    inp = synth.make_inputs(cfg)
+    flat = U.GpuStage(inp, ctx=ctx).run()
+    st = U.GpuStage(inp, ctx=ctx, page_size=16)
+    st.run()
+    pg, ps = st.paged, 16
+    for l in range(cfg.L_kv):
+        for pool, dst in ((pg.k_pool[l], flat.k_dst[l]), (pg.v_pool[l], flat.v_dst[l])):
+            for b in range(cfg.B):
+                nl = int(flat.new_len[b])
+                pages = pool[pg.dst_table[b].long()]                       # [dp,Hkv,ps,d]
+                rows = pages.permute(1, 0, 2, 3).reshape(cfg.Hkv, -1, cfg.d)[:, :nl]
+                assert torch.equal(rows.contiguous().view(torch.uint8), dst[b, :, :nl].contiguous().view(torch.uint8))
+
+
 def test_strided_views_and_errors(ctx):
     cfg = synth.CONFIGS["S0"]
     inp = synth.make_inputs(cfg)
