@@ -194,6 +194,23 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
                             const int32_t* pos_out, const int32_t* new_len, void* stream);
 
 /*
+ * asap_compact_kv_from_kept -- asap_compact_kv without pos_out: the source rows are taken from the
+ * list of surviving visual tokens and text_len, following the output order of the stage (Fig. 3:
+ * prefix and text preserved around the kept tokens in their original order):
+ *   dst[b,g,n,:]     = src[b,g,n,:]                      n < P
+ *   dst[b,g,P+a,:]   = src[b,g,P+final_idx[b,a],:]       a < k
+ *   dst[b,g,P+k+t,:] = src[b,g,P+V+t,:]                  t < text_len[b]
+ * final_idx [B,k] int32 ascending = kept_idx of asap_select with ASAP_ROUTE_ABSORB, so the call can
+ * be issued (on another stream) as soon as asap_select has run, without asap_positions in between;
+ * final_idx of asap_merge with ASAP_ROUTE_PAPER.  Writes exactly what asap_compact_kv writes.
+ * Buffers and limits as for asap_compact_kv.
+ */
+asap_status asap_compact_kv_from_kept(asap_ctx* ctx, const asap_params* p, int32_t n_layers,
+                                      const void* const* k_src, const void* const* v_src,
+                                      void* const* k_dst, void* const* v_dst,
+                                      const int32_t* final_idx, const int32_t* text_len, void* stream);
+
+/*
  * asap_compact_kv_paged -- asap_compact_kv for caches kept as pools of fixed-size pages with one
  * block table per sequence (the layout of paged serving engines; the paper fixes no cache layout, its
  * efficiency analysis only counts the K/V storage the pruned rows free).  A pool is

@@ -21,7 +21,8 @@ ASAP_MASK_OFF, ASAP_MASK_KEYBIAS = 0, 1
 ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
 
 EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
-           "asap_score", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv", "asap_compact_kv_paged",
+           "asap_score", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv",
+           "asap_compact_kv_from_kept", "asap_compact_kv_paged",
            "asap_timing_enable",
            "asap_timing_collect", "asap_theoretical_flops", "asap_flops_ratio", "asap_attention",
            "asap_attention_workspace_bytes"]
@@ -88,6 +89,9 @@ def load() -> ctypes.CDLL:
     lib.asap_compact_kv.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                     ctypes.POINTER(vp), ctypes.POINTER(vp), i32p, i32p, vp]
     lib.asap_compact_kv.restype = ctypes.c_int
+    lib.asap_compact_kv_from_kept.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                              ctypes.POINTER(vp), ctypes.POINTER(vp), i32p, i32p, vp]
+    lib.asap_compact_kv_from_kept.restype = ctypes.c_int
     lib.asap_compact_kv_paged.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                           ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int32, i32p,
                                           ctypes.c_int32, i32p, ctypes.c_int32, i32p, i32p, vp]
@@ -257,6 +261,13 @@ class Context:
             self._h, ctypes.byref(p), n, arr(k_src), arr(v_src), arr(k_dst), arr(v_dst), _ptr(pos_out),
             _ptr(new_len), _stream(stream)))
 
+    def asap_compact_kv_from_kept(self, p, k_src, v_src, k_dst, v_dst, final_idx, text_len, stream=None):
+        n = len(k_src)
+        arr = lambda ts: (ctypes.c_void_p * n)(*[t.data_ptr() for t in ts])
+        self._check(self._lib.asap_compact_kv_from_kept(
+            self._h, ctypes.byref(p), n, arr(k_src), arr(v_src), arr(k_dst), arr(v_dst), _ptr(final_idx),
+            _ptr(text_len), _stream(stream)))
+
     def asap_compact_kv_paged(self, p, k_src_pool: Sequence[torch.Tensor], v_src_pool, k_dst_pool, v_dst_pool,
                               page_size: int, src_table, dst_table, pos_out, new_len, stream=None):
         """Pools [n_pages,Hkv,page_size,d] per layer; src_table / dst_table [B, pages per sequence] int32."""
@@ -334,38 +345,45 @@ def run_stage(ctx: Context, p: asap_params, q: torch.Tensor, k: torch.Tensor, hi
               buf: StageBuffers, lse_extra: Optional[torch.Tensor] = None, stream=None,
               side_stream=None, paged: Optional[PagedKV] = None) -> StageBuffers:
     """The calls of one stage.  q [B,H,N,d], k [B,Hkv,N,d], hidden [B,N,D]; the visual / text blocks
-    are passed to the library as strided views.  With a side stream the K/V compaction, which only
-    needs the positions that follow from the kept set (asap_positions), runs there next to the
-    similarity and merge kernels of the main stream; the main stream waits for it at the end.
-    With `paged` the caches are its pools (k_cache / v_cache are ignored)."""
+    are passed to the library as strided views.  With a side stream the K/V compaction, which needs
+    only the kept set, runs there next to the similarity and merge kernels of the main stream (one
+    hand-over between the streams after the selection -- each costs the main stream about 6 us, so
+    the rows that depend on nothing are not started earlier on their own); the main stream waits for
+    the side stream at the end.  Contiguous caches are compacted by the call that takes the kept
+    list directly; paged caches (`paged`; k_cache / v_cache are then ignored) need asap_positions."""
     P, V = p.P, p.V
     q_vis, q_txt, k_vis = q[:, :, P:P + V], q[:, :, P + V:], k[:, :, P:P + V]
     main = torch.cuda.current_stream() if stream is None else stream
+    has_kv = bool(k_cache) or paged is not None
+    kv = (k_cache, v_cache, buf.k_dst, buf.v_dst)
+
+    def hand_over(src, dst):
+        ev = torch.cuda.Event()
+        ev.record(src)
+        dst.wait_event(ev)
+
     ctx.asap_score(p, q_vis, q_txt, k_vis, text_len, lse_extra, buf.s_raw, buf.s_hat, buf.score,
                    buf.workspace, main)
     ctx.asap_select(p, buf.score, buf.kept_idx, buf.pruned_idx, buf.workspace, main)
-    has_kv = bool(k_cache) or paged is not None
-
-    def compact(pos, nl, st):
+    # with ASAP_ROUTE_ABSORB the kept set is final before the merge
+    early = has_kv and side_stream is not None and p.route == ASAP_ROUTE_ABSORB
+    if early:
         if paged is not None:
-            paged.compact(ctx, p, pos, nl, st)
+            ctx.asap_positions(p, buf.kept_idx, text_len, buf.pos_early, buf.new_len_early, main)
+        hand_over(main, side_stream)
+        if paged is not None:
+            paged.compact(ctx, p, buf.pos_early, buf.new_len_early, side_stream)
         else:
-            ctx.asap_compact_kv(p, k_cache, v_cache, buf.k_dst, buf.v_dst, pos, nl, st)
-    overlap = has_kv and side_stream is not None and p.route == ASAP_ROUTE_ABSORB
-    if overlap:
-        ctx.asap_positions(p, buf.kept_idx, text_len, buf.pos_early, buf.new_len_early, main)
-        fork = torch.cuda.Event()
-        fork.record(main)
-        side_stream.wait_event(fork)
-        compact(buf.pos_early, buf.new_len_early, side_stream)
+            ctx.asap_compact_kv_from_kept(p, *kv, buf.kept_idx, text_len, side_stream)
     ctx.asap_merge(p, hidden, buf.s_raw, buf.s_hat, text_len, buf.kept_idx, buf.pruned_idx, buf.out_hidden, buf.pos_out,
                    buf.new_len, buf.assign, buf.best_sim, buf.wsum, buf.final_idx, buf.workspace, main)
-    if overlap:
-        join = torch.cuda.Event()
-        join.record(side_stream)
-        main.wait_event(join)
+    if early:
+        hand_over(side_stream, main)
     elif has_kv:
-        compact(buf.pos_out, buf.new_len, main)
+        if paged is not None:
+            paged.compact(ctx, p, buf.pos_out, buf.new_len, main)
+        else:
+            ctx.asap_compact_kv(p, *kv, buf.pos_out, buf.new_len, main)
     return buf
 
 

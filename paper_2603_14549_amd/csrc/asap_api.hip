@@ -292,22 +292,20 @@ asap_status asap_positions(asap_ctx* ctx, const asap_params* p, const int32_t* k
                     "asap_positions launch");
 }
 
-asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layers, const void* const* k_src,
-                            const void* const* v_src, void* const* k_dst, void* const* v_dst,
-                            const int32_t* pos_out, const int32_t* new_len, void* stream) {
-  asap_status st = common_checks(ctx, p);
-  if (st != ASAP_OK) return st;
-  if (n_layers < 1 || n_layers > 64) return fail(ctx, ASAP_EINVAL, "asap_compact_kv: n_layers must be in [1, 64]");
-  if (!k_src || !v_src || !k_dst || !v_dst || !pos_out || !new_len)
-    return fail(ctx, ASAP_EINVAL, "asap_compact_kv: a required pointer is NULL");
+// shared checks of the contiguous K/V compaction entry points
+static asap_status check_kv_buffers(asap_ctx* ctx, const asap_params* p, const char* fn, int32_t n_layers,
+                                    const void* const* k_src, const void* const* v_src, void* const* k_dst,
+                                    void* const* v_dst) {
+  if (n_layers < 1 || n_layers > 64) return fail(ctx, ASAP_EINVAL, "%s: n_layers must be in [1, 64]", fn);
+  if (!k_src || !v_src || !k_dst || !v_dst) return fail(ctx, ASAP_EINVAL, "%s: a required pointer is NULL", fn);
   const int64_t esz = dtype_size(p->kv_dtype);
   const int64_t src_bytes = (int64_t)p->B * p->Hkv * (p->P + p->V + p->Tmax) * p->d * esz;
   const int64_t dst_bytes = (int64_t)p->B * p->Hkv * (p->P + p->k + p->Tmax) * p->d * esz;
   for (int l = 0; l < n_layers; ++l) {
     const void* ptrs[4] = {k_src[l], v_src[l], k_dst[l], v_dst[l]};
     for (const void* q : ptrs) {
-      if (!q) return fail(ctx, ASAP_EINVAL, "asap_compact_kv: layer %d has a NULL pointer", l);
-      if (!aligned16(q)) return fail(ctx, ASAP_EINVAL, "asap_compact_kv: layer %d pointer not 16-byte aligned", l);
+      if (!q) return fail(ctx, ASAP_EINVAL, "%s: layer %d has a NULL pointer", fn, l);
+      if (!aligned16(q)) return fail(ctx, ASAP_EINVAL, "%s: layer %d pointer not 16-byte aligned", fn, l);
     }
   }
   // no destination may overlap any source (a kernel that reads and writes one buffer would race)
@@ -319,13 +317,38 @@ asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layer
         for (int w2 = 0; w2 < 2; ++w2) {
           const char* s0 = static_cast<const char*>(w2 ? v_src[m] : k_src[m]);
           if (d0 < s0 + src_bytes && s0 < d1)
-            return fail(ctx, ASAP_EINVAL, "asap_compact_kv: destination of layer %d overlaps a source", l);
+            return fail(ctx, ASAP_EINVAL, "%s: destination of layer %d overlaps a source", fn, l);
         }
     }
+  return ASAP_OK;
+}
+
+asap_status asap_compact_kv(asap_ctx* ctx, const asap_params* p, int32_t n_layers, const void* const* k_src,
+                            const void* const* v_src, void* const* k_dst, void* const* v_dst,
+                            const int32_t* pos_out, const int32_t* new_len, void* stream) {
+  asap_status st = common_checks(ctx, p);
+  if (st != ASAP_OK) return st;
+  if ((st = check_kv_buffers(ctx, p, "asap_compact_kv", n_layers, k_src, v_src, k_dst, v_dst)) != ASAP_OK) return st;
+  if (!pos_out || !new_len) return fail(ctx, ASAP_EINVAL, "asap_compact_kv: a required pointer is NULL");
   return hip_result(ctx,
-                    launch_compact_kv(*p, n_layers, k_src, v_src, k_dst, v_dst, pos_out, new_len,
+                    launch_compact_kv(*p, KV_BY_POS, n_layers, k_src, v_src, k_dst, v_dst, pos_out, new_len,
                                       static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_compact_kv launch");
+}
+
+asap_status asap_compact_kv_from_kept(asap_ctx* ctx, const asap_params* p, int32_t n_layers,
+                                      const void* const* k_src, const void* const* v_src, void* const* k_dst,
+                                      void* const* v_dst, const int32_t* final_idx, const int32_t* text_len,
+                                      void* stream) {
+  asap_status st = common_checks(ctx, p);
+  if (st != ASAP_OK) return st;
+  if ((st = check_kv_buffers(ctx, p, "asap_compact_kv_from_kept", n_layers, k_src, v_src, k_dst, v_dst)) != ASAP_OK)
+    return st;
+  if (!final_idx || !text_len) return fail(ctx, ASAP_EINVAL, "asap_compact_kv_from_kept: a required pointer is NULL");
+  return hip_result(ctx,
+                    launch_compact_kv(*p, KV_FROM_KEPT, n_layers, k_src, v_src, k_dst, v_dst, final_idx, text_len,
+                                      static_cast<hipStream_t>(stream), ctx->timer),
+                    "asap_compact_kv_from_kept launch");
 }
 
 asap_status asap_compact_kv_paged(asap_ctx* ctx, const asap_params* p, int32_t n_layers,

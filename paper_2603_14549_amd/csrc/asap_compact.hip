@@ -2,7 +2,8 @@
 // (KV-cache compatibility of the pruning stage).  Pure data movement, bit-exact.
 //
 // k_positions: grid (ceil(Nout / 256), B): the positions the compaction gathers, from the kept set alone.
-// k_compact: grid (ceil(Nout / ROWS_PER_BLOCK), B * Hkv, 2 * layers_in_launch), 256 threads.
+// k_compact<MODE>: grid (ceil(Nout / ROWS_PER_BLOCK), B * Hkv, 2 * layers_in_launch), 256 threads; the source
+// rows come from the position list or straight from the kept list (then nothing of asap_merge is needed).
 // k_compact_paged: the same grid for caches kept as pools of pages with one block table per sequence.
 // A row is d elements = LPR 16-byte pieces; LPR consecutive lanes move one row.
 #include "asap_device.hpp"
@@ -18,27 +19,34 @@ struct KvPointers {
   char* dst[2 * KV_LAYERS_PER_LAUNCH];
 };
 
-__global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t* __restrict__ pos_out,
-                                                  const int32_t* __restrict__ new_len, int Hkv, int N, int Nout,
-                                                  int row_bytes) {
+// Where the source rows come from: the position list of asap_merge / asap_positions, or the kept list
+// and text_len directly (the output order of Fig. 3 written out: prefix | kept | valid text).
+// idx = pos_out [B,Nout] and len = new_len (BY_POS); idx = kept list [B,k] and len = text_len (FROM_KEPT).
+template <int MODE>
+__global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t* __restrict__ idx,
+                                                  const int32_t* __restrict__ len, int Hkv, int N, int Nout,
+                                                  int row_bytes, int P, int V, int k) {
   const int lpr = row_bytes >> 4, rpi = 256 / lpr;
   const int tid = threadIdx.x, piece = tid % lpr, r0 = tid / lpr;
   const int bg = blockIdx.y, b = bg / Hkv;
-  const int nl = new_len[b];
+  const int n_rows = MODE == KV_BY_POS ? min(len[b], Nout) : P + k + min(len[b], Nout - P - k);
   const char* src = ptrs.src[blockIdx.z] + (int64_t)bg * N * row_bytes + piece * 16;
   char* dst = ptrs.dst[blockIdx.z] + (int64_t)bg * Nout * row_bytes + piece * 16;
-  const int32_t* pos = pos_out + (int64_t)b * Nout;
+  const int32_t* ix = idx + (int64_t)b * (MODE == KV_BY_POS ? Nout : k);
   const int base = blockIdx.x * rpi * KV_ROWS_PER_THREAD + r0;
   uint4 v[KV_ROWS_PER_THREAD];
 #pragma unroll
   for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
-    int nrow = base + i * rpi;
-    if (nrow < nl) v[i] = ldg16_stream(src + (int64_t)pos[nrow] * row_bytes);
+    const int r = base + i * rpi;
+    if (r < n_rows) {
+      const int srow = MODE == KV_BY_POS ? ix[r] : r < P ? r : r < P + k ? P + ix[r - P] : r - k + V;
+      v[i] = ldg16_stream(src + (int64_t)srow * row_bytes);
+    }
   }
 #pragma unroll
   for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
-    int nrow = base + i * rpi;
-    if (nrow < nl) stg16_stream(dst + (int64_t)nrow * row_bytes, v[i]);
+    const int r = base + i * rpi;
+    if (r < n_rows) stg16_stream(dst + (int64_t)r * row_bytes, v[i]);
   }
 }
 
@@ -102,9 +110,10 @@ hipError_t launch_positions(const asap_params& p, const int32_t* kept, const int
   return hipGetLastError();
 }
 
-hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* const* k_src,
+// mode: KV_BY_POS (idx = pos_out, len = new_len) or KV_FROM_KEPT (idx = kept list, len = text_len)
+hipError_t launch_compact_kv(const asap_params& p, int mode, int n_layers, const void* const* k_src,
                              const void* const* v_src, void* const* k_dst, void* const* v_dst,
-                             const int32_t* pos_out, const int32_t* new_len, hipStream_t st, Timer* tm) {
+                             const int32_t* idx, const int32_t* len, hipStream_t st, Timer* tm) {
   const int row_bytes = p.d * (p.kv_dtype == ASAP_BF16 ? 2 : 4);
   const int N = p.P + p.V + p.Tmax, Nout = p.P + p.k + p.Tmax;
   const int rows_per_block = (256 / (row_bytes / 16)) * KV_ROWS_PER_THREAD;
@@ -119,7 +128,12 @@ hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* con
     }
     for (int l = 2 * nl; l < 2 * KV_LAYERS_PER_LAUNCH; ++l) { ptrs.src[l] = nullptr; ptrs.dst[l] = nullptr; }
     dim3 grid((Nout + rows_per_block - 1) / rows_per_block, p.B * p.Hkv, 2 * nl);
-    ASAP_LAUNCH(tm, "k_compact", k_compact, grid, dim3(256), 0, st, ptrs, pos_out, new_len, p.Hkv, N, Nout, row_bytes);
+    if (mode == KV_BY_POS)
+      ASAP_LAUNCH(tm, "k_compact", k_compact<KV_BY_POS>, grid, dim3(256), 0, st, ptrs, idx, len, p.Hkv, N, Nout,
+                  row_bytes, p.P, p.V, p.k);
+    else
+      ASAP_LAUNCH(tm, "k_compact", k_compact<KV_FROM_KEPT>, grid, dim3(256), 0, st, ptrs, idx, len, p.Hkv, N, Nout,
+                  row_bytes, p.P, p.V, p.k);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

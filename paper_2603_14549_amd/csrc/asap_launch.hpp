@@ -88,9 +88,10 @@ hipError_t launch_paper_plan(const asap_params& p, const int32_t* dest, const in
 hipError_t launch_positions(const asap_params& p, const int32_t* kept, const int32_t* text_len, int32_t* pos_out,
                             int32_t* new_len, hipStream_t st, Timer* tm);
 
-hipError_t launch_compact_kv(const asap_params& p, int n_layers, const void* const* k_src,
+enum { KV_BY_POS = 0, KV_FROM_KEPT = 1 };
+hipError_t launch_compact_kv(const asap_params& p, int mode, int n_layers, const void* const* k_src,
                              const void* const* v_src, void* const* k_dst, void* const* v_dst,
-                             const int32_t* pos_out, const int32_t* new_len, hipStream_t st, Timer* tm);
+                             const int32_t* idx, const int32_t* len, hipStream_t st, Timer* tm);
 hipError_t launch_compact_kv_paged(const asap_params& p, int n_layers, const void* const* k_src,
                                    const void* const* v_src, void* const* k_dst, void* const* v_dst, int page_size,
                                    const int32_t* src_table, int src_stride, const int32_t* dst_table,

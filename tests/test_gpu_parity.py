@@ -113,8 +113,8 @@ def test_determinism(ctx):
 
 
 def test_positions_and_two_stream_stage(ctx):
-    """asap_positions writes what asap_merge writes, and the stage with the K/V compaction on a
-    second stream gives bit-identical results to the stage on one stream."""
+    """asap_positions writes what asap_merge writes, and the stage with the K/V compaction
+    on a second stream gives bit-identical results to the stage on one stream."""
     cfg = synth.CONFIGS["S1"]
     inp = synth.make_inputs(cfg)
     serial = U.GpuStage(inp, ctx=ctx, overlap=False)
@@ -123,6 +123,7 @@ def test_positions_and_two_stream_stage(ctx):
     assert both.side_stream is not None
     for _ in range(3):
         bo = both.run()
+        ctx.asap_positions(both.p, bo.kept_idx, both.text_len, bo.pos_early, bo.new_len_early)
         assert torch.equal(bo.pos_early, bs.pos_out) and torch.equal(bo.new_len_early, bs.new_len)
         assert torch.equal(bo.pos_out, bs.pos_out) and torch.equal(bo.new_len, bs.new_len)
         for l in range(len(bs.k_dst)):
@@ -181,6 +182,31 @@ def test_paged_kv_compaction(ctx, name, page_size):
                                   if sp > 1 else torch.zeros((cfg.B, 0), dtype=torch.int32, device="cuda"),
                                   torch.from_numpy(dst_table).cuda(), buf.pos_out, buf.new_len)
     assert e.value.status == binding.ASAP_EINVAL
+
+
+@pytest.mark.parametrize("name,route", [("S1", "absorb"), ("S3", "absorb"), ("S2", "paper")])
+def test_kv_compaction_from_the_kept_list(ctx, name, route):
+    """asap_compact_kv_from_kept (no pos_out) equals the oracle's gather at the stage's final
+    positions, bit for bit, and leaves the rows beyond new_len alone."""
+    cfg = synth.CONFIGS[name]
+    inp = synth.make_inputs(cfg)
+    over = dict(route=binding.ASAP_ROUTE_PAPER, sim_threshold=0.8) if route == "paper" else {}
+    st = U.GpuStage(inp, ctx=ctx, overlap=False, **over)
+    buf = st.run()
+    pos_out, new_len = buf.pos_out.cpu().numpy(), buf.new_len.cpu().numpy()
+    dk = [torch.full_like(t, 7.0) for t in buf.k_dst]
+    dv = [torch.full_like(t, 7.0) for t in buf.v_dst]
+    ctx.asap_compact_kv_from_kept(st.p, st.k_cache, st.v_cache, dk, dv, buf.final_idx, st.text_len)
+    torch.cuda.synchronize()
+    sentinel = U.raw_bits(torch.full((1,), 7.0, dtype=dk[0].dtype))[0]
+    for l in range(cfg.L_kv):
+        for dst, src in ((dk[l], inp["k_cache"][l]), (dv[l], inp["v_cache"][l])):
+            got = U.raw_bits(dst)
+            for b in range(cfg.B):
+                nl = int(new_len[b])
+                s = src[b].view(np.uint32) if src[b].dtype == np.float32 else src[b]
+                assert (got[b][:, :nl] == O.gather_kv(s, pos_out[b], nl)).all(), "gathered rows"
+                assert (got[b][:, nl:] == sentinel).all(), "rows beyond new_len"
 
 
 def test_paged_stage_matches_contiguous_stage(ctx):
