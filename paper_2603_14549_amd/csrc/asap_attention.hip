@@ -5,18 +5,26 @@
 // Flash-style: one pass over the keys with running row maxima and sums, both contractions on the
 // matrix cores, nothing of size N x N ever stored.
 //
-//   k_att_bias      log2 of the per-key discount by sequence position, [B,Npad] (-inf off the image span)
+//   k_att_bias      log2 of the per-key discount by sequence position, [B,Npad] (-inf off the image span,
+//                   and everywhere with the mask off)
 //   k_vtranspose    values transposed per (image, kv head) to [d, Npad]: the second contraction wants
-//                   its A operand (a row of values^T) contiguous along the keys
-//   k_attention     grid (ceil(N/256), H, B), 256 threads = 4 waves of 64 queries (two 32-query blocks,
-//                   so that every operand read from LDS feeds two MFMAs).  The 32-key tile of K and
-//                   of V^T goes to LDS by direct global -> LDS loads, double buffered, once for the
-//                   four waves.  Per tile a wave computes S^T = K_tile Q^T (keys are the tile rows, so
-//                   lane l owns query l % 32 and holds 16 of the tile's keys: the softmax bookkeeping
-//                   is per lane), then O^T += V^T_tile P^T, where the P^T operand is taken straight
-//                   from the accumulator registers: the contraction slice a lane half supplies is
-//                   defined as the keys that lane half already holds, and the V^T operand is read to
-//                   match.
+//                   its A operand (a row of values^T) contiguous along the keys, in the key order in
+//                   which the first contraction leaves P^T in the accumulators
+//   k_attention     grid (ceil(N/256), H, B), 512 threads = 8 waves (two per SIMD) of 32 queries.  Per
+//                   32-key tile a wave computes S^T = K_tile Q^T (keys are the tile rows, so lane l owns
+//                   query l % 32 and holds 16 of the tile's keys: the softmax bookkeeping is per lane),
+//                   then O^T += V^T_tile P^T, where the P^T operand is taken straight from the
+//                   accumulator registers: the contraction slice a lane half supplies is defined as
+//                   the keys that lane half already holds, and the V^T operand is stored to match.
+//                   A tile (keys, values^T, 32 discounts) goes to LDS by direct global -> LDS loads,
+//                   once for the eight waves, into a ring of PD + 2 slots, PD tiles ahead; the waits
+//                   for those loads are placed by hand and no other vector-memory instruction is left
+//                   in the loop, because any wait the compiler adds for one would drain the ring.
+//                   The raw scores of tile t + 1 are computed in the same basic block as the
+//                   exponentials of tile t.  Measured on this chip, plain VALU work overlaps with the
+//                   matrix pipe only up to about one VALU instruction per 8 MFMA cycles and SIMD, the
+//                   rest adds to the MFMA time: the ~115 VALU instructions of a tile against its 16
+//                   MFMAs are what bounds the kernel.
 #include "asap_device.hpp"
 #include "asap_launch.hpp"
 
@@ -29,12 +37,23 @@ __global__ __launch_bounds__(256) void k_att_bias(const float* __restrict__ s_ha
   const int j = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
   if (j >= Npad) return;
   float x = -INFINITY;
-  if (j >= P && j < P + V) x = log2f(fmaxf(lambda_max * s_hat[(int64_t)b * V + (j - P)], eps));
+  if (s_hat != nullptr && j >= P && j < P + V) x = log2f(fmaxf(lambda_max * s_hat[(int64_t)b * V + (j - P)], eps));
   bias2[(int64_t)b * Npad + j] = x;
 }
 
-// grid (ceil(Npad/32), Hkv, B), 256 threads; vt[b,g,c,n] = v[b,g,n,c] for n < N, 0 for N <= n < Npad.
+// grid (ceil(Npad/32), Hkv, B), 256 threads; vt[b,g,c,p] = v[b,g,att_vt_key(p),c] for keys < N, 0 for the
+// keys N .. Npad-1.
 // 16-byte loads along d into LDS, 16-byte stores along the keys out of it.
+// Key stored at position p of a values^T row.  The second product takes its P^T operand straight from
+// the accumulators of the first, where a lane half holds keys 4 hf .. 4 hf + 3 and 8 + 4 hf .. 8 + 4 hf + 3 of
+// every 16; with 2-byte elements (8 keys per 16-byte operand) the row is therefore stored in the order
+// 0-3, 8-11, 4-7, 12-15 within every 16 keys, so that a lane half's operand is one contiguous piece.
+__device__ __forceinline__ int att_vt_key(int p, int elems_per_16) {
+  if (elems_per_16 != 8) return p;
+  const int g = p & 15;
+  return (p & ~15) | (g & 3) | ((g & 4) << 1) | ((g & 8) >> 1);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_vtranspose(const T* __restrict__ v, Strides3 sv, int N, int Npad, int d,
                                                      T* __restrict__ vt) {
@@ -56,7 +75,7 @@ __global__ __launch_bounds__(256) void k_vtranspose(const T* __restrict__ v, Str
     const int c = idx / gpr, r0 = (idx - c * gpr) * E;
     T x[E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) x[e] = tile[r0 + e][c];
+    for (int e = 0; e < E; ++e) x[e] = tile[att_vt_key(r0 + e, E)][c];
     uint4 y;
     __builtin_memcpy(&y, x, 16);
     *reinterpret_cast<uint4*>(dst + (int64_t)c * Npad + n0 + r0) = y;
@@ -97,26 +116,57 @@ template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* dst, const fl
 __device__ __forceinline__ int att_key_of(int v, int hf) { return 8 * (v >> 2) + 4 * hf + (v & 3); }
 
 constexpr int ATT_QWG = 256;                   // queries per workgroup
+#ifndef ATT_PD
+#define ATT_PD 2                               /* key tiles requested ahead */
+#endif
+constexpr int ATT_NW = 8;                      // waves per workgroup (two per SIMD), 32 queries each
+constexpr float ATT_LAZY = 8.0f;               // growth of a row maximum (log2 units) that moves the baseline
+constexpr int ATT_BIASB = 128;                 // bytes of per-key log-discounts staged with a key tile
 
 // LDS swizzles: the 16-byte piece p of row r is stored in slot p ^ x(r), so that 16 consecutive rows
 // spread over all banks for the strided operand reads while the loads still write 1 KiB at a time
 __device__ __forceinline__ int att_kswz(int row, int row_bytes) { return row_bytes <= 128 ? (row >> 1) & 7 : row & 15; }
 __device__ __forceinline__ int att_vswz(int row, int row_bytes) { return row_bytes <= 64 ? (row >> 2) & 3 : (row >> 1) & 7; }
 
-// CH = 16-byte chunks of a row per lane half (row bytes = 32 * CH); NW waves of QB 32-query blocks each
-template <typename T, int CH, int NW, int QB>
-__global__ __launch_bounds__(64 * NW) void k_attention(const T* __restrict__ q, Strides3 sq, const T* __restrict__ k,
-                                                    Strides3 sk, const T* __restrict__ vt, int Npad,
-                                                    const float* __restrict__ bias2, T* __restrict__ out, int H,
-                                                    int Hkv, int N, int P, int V, float c2) {
+// how the mask acts on one (32 keys x 32 queries) tile
+enum { ATT_PLAIN = 0,     // every key precedes every query: no mask
+       ATT_AHEAD = 1,     // every key follows every query and all queries are image rows: the key's discount
+       ATT_GENERAL = 2 }; // anything else: decided per element
+
+// wait until only the loads of the newest `tiles_ahead` key tiles (cnt instructions each) are outstanding
+__device__ __forceinline__ void att_wait_tiles(int outstanding) {
+  switch (outstanding) {
+    case 0: wait_vmem_but<0>(); break;
+    case 1: wait_vmem_but<1>(); break;
+    case 2: wait_vmem_but<2>(); break;
+    case 3: wait_vmem_but<3>(); break;
+    case 4: wait_vmem_but<4>(); break;
+    case 5: wait_vmem_but<5>(); break;
+    case 6: wait_vmem_but<6>(); break;
+    default: wait_vmem_but<0>(); break;
+  }
+}
+
+// CH = 16-byte chunks of a row per lane half (row bytes = 32 * CH); PD = key tiles requested ahead
+template <typename T, int CH, int PD>
+__global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__ q, Strides3 sq,
+                                                            const T* __restrict__ k, Strides3 sk,
+                                                            const T* __restrict__ vt, int Npad,
+                                                            const float* __restrict__ bias2, int bidir,
+                                                            T* __restrict__ out, int H, int Hkv, int N, int P, int V,
+                                                            float c2) {
+  constexpr int NW = ATT_NW;
+  static_assert(NW * 32 == ATT_QWG, "workgroup shape");
   constexpr int E = elem<T>::per16;            // elements per 16-byte chunk
   constexpr int D = CH * 2 * E;                // head dimension
   constexpr int DT = D / 32;                   // 32-row tiles of O^T
   constexpr int NPS = 32 / (2 * E);            // contraction steps of the second product per key tile
   constexpr int RB = 32 * CH;                  // bytes of a key row
   constexpr int VB = 32 * (int)sizeof(T);      // bytes of a values^T row per key tile
-  constexpr int KTILE = 32 * RB, VTILE = D * VB, STAGE = KTILE + VTILE;
+  constexpr int KTILE = 32 * RB, VTILE = D * VB, STAGE = KTILE + VTILE + ATT_BIASB;
   constexpr int KLD = KTILE / 1024, VLD = VTILE / 1024;     // 1 KiB load instructions per tile
+  constexpr int TP = KLD + VLD + 1;            // load instructions per tile: keys, values^T, discounts
+  constexpr int NS = PD + 2;                   // ring slots: tile t (values, discounts), t+1 (keys), PD in flight
   extern __shared__ __align__(16) char lds[];
   const uint32_t lds_addr = lds_address(lds);
 
@@ -125,11 +175,9 @@ __global__ __launch_bounds__(64 * NW) void k_attention(const T* __restrict__ q, 
   const int n = lane & 31, hf = lane >> 5;
   const int b = blockIdx.z, h = blockIdx.y, g = (h * Hkv) / H;
   const int iw = blockIdx.x * ATT_QWG;          // first query of the workgroup
-  constexpr int ATT_QW = 32 * QB;               // queries per wave
-  static_assert(NW * ATT_QW == ATT_QWG, "workgroup shape");
-  const int i0 = iw + wave * ATT_QW;            // first query of the wave
-  const bool bidir = bias2 != nullptr;
+  const int i0 = iw + wave * 32;                // first query of the wave
   const float inv_c2 = 1.0f / c2;
+  const float lazy_raw = ATT_LAZY * inv_c2;     // ATT_LAZY log2 units, in units of the raw products
   const int img_lo = P, img_hi = P + V;         // image span [img_lo, img_hi)
 
   // keys to visit: up to the last query, or to the end of the image span if image rows are held
@@ -140,195 +188,199 @@ __global__ __launch_bounds__(64 * NW) void k_attention(const T* __restrict__ q, 
     if (bidir && hi >= img_lo && first < img_hi) jl = max(jl, img_hi - 1);
     return first < N ? jl : -1;
   };
-  const int jl_wg = last_key(iw, ATT_QWG), jl_w = last_key(i0, ATT_QW);
+  const int jl_wg = last_key(iw, ATT_QWG), jl_w = last_key(i0, 32);
   const int ntiles = jl_wg / 32 + 1;
+  const int my_tiles = jl_w / 32 + 1;           // this wave's tiles are 0 .. my_tiles-1 (none if its queries are past N)
 
   // queries: B operand of S^T, pieces 2c + hf of the row
-  uint4 qa[QB][CH];
-  int qi[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    qi[qb] = i0 + 32 * qb + n;
+  uint4 qa[CH];
+  const int qi = i0 + n;
+  {
     const char* qrow =
-        reinterpret_cast<const char*>(q + b * sq.b + h * sq.h + (int64_t)min(qi[qb], N - 1) * sq.r) + hf * 16;
+        reinterpret_cast<const char*>(q + b * sq.b + h * sq.h + (int64_t)min(qi, N - 1) * sq.r) + hf * 16;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) qa[qb][c] = ldg16(qrow + c * 32);
+    for (int c = 0; c < CH; ++c) qa[c] = ldg16(qrow + c * 32);
   }
 
-  // tile loads: wave w issues the 1 KiB pieces w, w + 4, ... of the key tile and of the values^T tile
+  // Tile loads: the 1 KiB pieces of a tile (keys, then values^T, then one piece with the 32 discounts)
+  // are dealt to the waves round-robin.  Tile numbers past the last one load the last tile again, so
+  // every iteration issues the same number of loads and one wait count serves the whole loop.
   const char* kg = reinterpret_cast<const char*>(k + b * sk.b + g * sk.h);
   const int64_t krow_bytes = sk.r * (int64_t)sizeof(T);
   const char* vg = reinterpret_cast<const char*>(vt + ((int64_t)b * Hkv + g) * D * Npad);
-  auto issue_tile = [&](int jt) {
-    const uint32_t st = lds_addr + (uint32_t)(jt & 1) * STAGE;
-    const int j0 = jt * 32;
+  const char* bg = reinterpret_cast<const char*>(bias2 + (int64_t)b * Npad);
+  auto issue_tile = [&](int t) {
+    const uint32_t st = lds_addr + (uint32_t)(t % NS) * STAGE;
+    const int j0 = min(t, ntiles - 1) * 32;
 #pragma unroll
-    for (int u = 0; u < (KLD + NW - 1) / NW; ++u) {
-      const int qn = wave + NW * u;
-      if (qn < KLD) {
-        const int off = qn * 1024 + 16 * lane, row = off / RB, slot = (off % RB) >> 4;
+    for (int u = 0; u < (TP + NW - 1) / NW; ++u) {
+      const int pc = wave + NW * u;
+      if (pc < KLD) {
+        const int off = pc * 1024 + 16 * lane, row = off / RB, slot = (off % RB) >> 4;
         const int piece = slot ^ att_kswz(row, RB);
         const uint32_t voff = (uint32_t)((int64_t)min(j0 + row, N - 1) * krow_bytes) + piece * 16;
-        load_to_lds16(kg, voff, st + qn * 1024);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < (VLD + NW - 1) / NW; ++u) {
-      const int qn = wave + NW * u;
-      if (qn < VLD) {
-        const int off = qn * 1024 + 16 * lane, row = off / VB, slot = (off % VB) >> 4;
+        load_to_lds16(kg, voff, st + pc * 1024);
+      } else if (pc < KLD + VLD) {
+        const int pv = pc - KLD;
+        const int off = pv * 1024 + 16 * lane, row = off / VB, slot = (off % VB) >> 4;
         const int piece = slot ^ att_vswz(row, VB);
         const uint32_t voff = (uint32_t)(((int64_t)row * Npad + j0) * sizeof(T)) + piece * 16;
-        load_to_lds16(vg, voff, st + KTILE + qn * 1024);
+        load_to_lds16(vg, voff, st + KTILE + pv * 1024);
+      } else if (pc < TP) {
+        if (lane < ATT_BIASB / 16) load_to_lds16(bg, (uint32_t)(j0 * 4 + 16 * lane), st + KTILE + VTILE);
       }
     }
   };
+  const int my_loads = TP / NW + (wave < TP % NW ? 1 : 0);     // load instructions of this wave per tile
 
-  f32x16_t o[QB][DT];
+  f32x16_t o[DT];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[t][v] = 0.0f;
+  float m_run = -INFINITY, l_run = 0.0f;
+
+  // operand read offsets inside a tile.  The values^T swizzle of row tt * 32 + n does not depend on tt
+  // (it looks at row bits below 5 only), so one offset per contraction step serves all DT row tiles.
+  const int k_off = n * RB, k_x = att_kswz(n, RB);
+  int v_off[NPS];
+#pragma unroll
+  for (int c = 0; c < NPS; ++c) v_off[c] = n * VB + (((2 * c + hf) ^ att_vswz(n, VB)) << 4);
+
+  // S^T of the wave's queries against key tile t, raw (unscaled) products
+  auto scores = [&](int t, f32x16_t& s) {
+    const char* Kt = lds + (t % NS) * STAGE;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const uint4 a = *reinterpret_cast<const uint4*>(Kt + k_off + (((2 * c + hf) ^ k_x) << 4));
+      mma32<T>(s, a, qa[c]);
+    }
+  };
+
+  // One key tile t, whose raw scores s arrive from the previous step: the mask, the softmax terms,
+  // the product with the values -- and the raw scores of tile t + 1, whose matrix instructions stand in
+  // the same basic block as the exponentials so that the two run side by side.
+  // The exponent's baseline m_run of a query follows the running maximum lazily: it moves only when the
+  // maximum has grown by more than ATT_LAZY (in log2 units), so that the accumulated columns are rescaled
+  // a few times per query instead of at most tiles; terms are then at most 2^ATT_LAZY, and the quotient
+  // O / l does not depend on the baseline.
+  auto step = [&](int t, f32x16_t& s, f32x16_t& s_next) {
+    const int j0 = t * 32;
+    // the mask, by the kind of tile (a wave-uniform choice; only the few lines that apply it differ)
+    const int mode = (j0 + 31 <= i0) ? ATT_PLAIN
+                     : (j0 > i0 + 31 && bidir && i0 >= img_lo && i0 + 31 < img_hi) ? ATT_AHEAD : ATT_GENERAL;
+    if (mode != ATT_PLAIN) {                   // ATT_PLAIN: raw, the scale goes into the exponent below
+      // discounts of this lane's 16 keys, staged with the tile
+      const char* Bt = lds + (t % NS) * STAGE + KTILE + VTILE;
+      float kbias[16];
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        const float4 x = *reinterpret_cast<const float4*>(Bt + (8 * gq + 4 * hf) * 4);
+        kbias[4 * gq] = x.x; kbias[4 * gq + 1] = x.y; kbias[4 * gq + 2] = x.z; kbias[4 * gq + 3] = x.w;
+      }
+      if (mode == ATT_AHEAD) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = fmaf(kbias[v], inv_c2, s[v]);
+      } else {
+        const bool q_img = bidir && qi >= img_lo && qi < img_hi;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int j = j0 + att_key_of(v, hf);
+          const float ahead = q_img ? kbias[v] : -INFINITY;      // a key after the query
+          s[v] += (j <= qi ? 0.0f : ahead) * inv_c2;
+        }
+      }
+    }
+    float mx = s[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));        // both lane halves of a query see the same maximum
+    // maxima are kept in units of the raw products (finite from the first tile on: key 0 precedes
+    // every query)
+    const bool moved = mx > m_run + lazy_raw;
+    if (__any(moved)) {
+      const float m_new = moved ? mx : m_run;
+      const float alpha = fast_exp2_att((m_run - m_new) * c2);
+      m_run = m_new;
+      l_run *= alpha;
+      // in place, as assembly: a plain product is hoisted above the branch and the untouched
+      // accumulators are then copied register by register on the path that skips it
+#pragma unroll
+      for (int tt = 0; tt < DT; ++tt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float x = o[tt][v];
+          asm volatile("v_mul_f32 %0, %0, %1" : "+v"(x) : "v"(alpha));
+          o[tt][v] = x;
+        }
+    }
+    const float m_c = m_run * c2;
+    scores(t + 1, s_next);
+    float p[16], psum = 0.0f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      p[v] = fast_exp2_att(fmaf(s[v], c2, -m_c));
+      psum += p[v];
+    }
+    l_run += psum;
+    uint4 pb[NPS];
+#pragma unroll
+    for (int c = 0; c < NPS; ++c) pb[c] = att_pack16<T>(&p[c * E]);
+    // O^T += V^T_tile P^T: piece 2c + hf of a values^T row holds the keys this lane half has in P^T
+    const char* Vt = lds + (t % NS) * STAGE + KTILE;
+#pragma unroll
+    for (int c = 0; c < NPS; ++c)
+#pragma unroll
+      for (int tt = 0; tt < DT; ++tt) {
+        const uint4 va = *reinterpret_cast<const uint4*>(Vt + v_off[c] + tt * 32 * VB);
+        mma32<T>(o[tt], va, pb[c]);
+      }
+  };
+
+  // Tiles 0 .. PD are requested up front; iteration t requests tile t + 1 + PD and, before its barrier,
+  // waits for everything but the newest PD - 1 tiles: tile t + 2 has then landed.  The queries are
+  // touched here so that the compiler's wait for their loads stands in front of the loop, not inside
+  // it, where it would also wait for the tile requests.
+#pragma unroll
+  for (int c = 0; c < CH; ++c) asm volatile("" ::"v"(qa[c].x), "v"(qa[c].y), "v"(qa[c].z), "v"(qa[c].w));
+#pragma unroll
+  for (int t = 0; t <= PD; ++t) issue_tile(t);
+  att_wait_tiles((PD - 1) * my_loads);
+  barrier_keep_loads();
+  f32x16_t s_cur, s_next;
+  if (my_tiles > 0) scores(0, s_cur);
+  for (int t = 0; t < ntiles; ++t) {
+    issue_tile(t + 1 + PD);
+    if (t < my_tiles) {
+      step(t, s_cur, s_next);
+      s_cur = s_next;
+    }
+    att_wait_tiles((PD - 1) * my_loads);
+    barrier_keep_loads();
+  }
+  wait_all_vmem();                             // the surplus requests of the last iterations
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float inv = 1.0f / l_tot;
+  if (qi < N) {
+    T* orow = out + (((int64_t)b * H + h) * N + qi) * D;
 #pragma unroll
     for (int t = 0; t < DT; ++t)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) o[qb][t][v] = 0.0f;
-  float m_run[QB], l_run[QB];
+      for (int gq = 0; gq < 4; ++gq) {
+        float f[4];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.0f; }
-
-  // operand read offsets inside a tile
-  const int k_off = n * RB, k_x = att_kswz(n, RB);
-  int v_off[DT], v_x[DT];
-#pragma unroll
-  for (int t = 0; t < DT; ++t) {
-    v_off[t] = (t * 32 + n) * VB;
-    v_x[t] = att_vswz(t * 32 + n, VB);
-  }
-
-  issue_tile(0);
-  wait_all_vmem();
-  __syncthreads();
-  for (int jt = 0; jt < ntiles; ++jt) {
-    if (jt + 1 < ntiles) issue_tile(jt + 1);
-    const int j0 = jt * 32;
-    if (j0 <= jl_w) {
-      const char* Kt = lds + (jt & 1) * STAGE;
-      const char* Vt = Kt + KTILE;
-      f32x16_t s[QB];
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[qb][v] = 0.0f;
-#pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        const uint4 a = *reinterpret_cast<const uint4*>(Kt + k_off + (((2 * c + hf) ^ k_x) << 4));
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) mma32<T>(s[qb], a, qa[qb][c]);
+        for (int e = 0; e < 4; ++e) f[e] = o[t][4 * gq + e] * inv;
+        store4<T>(orow + t * 32 + 8 * gq + 4 * hf, f);
       }
-      uint4 pb[QB][NPS];
-      // discounts of this lane's 16 keys (needed only where a key may follow a query)
-      float kbias[16];
-      const bool masked_tile = j0 + 31 > i0;
-      if (masked_tile) {
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          float4 x = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-          if (bidir) x = *reinterpret_cast<const float4*>(bias2 + (int64_t)b * Npad + j0 + 8 * gq + 4 * hf);
-          kbias[4 * gq] = x.x; kbias[4 * gq + 1] = x.y; kbias[4 * gq + 2] = x.z; kbias[4 * gq + 3] = x.w;
-        }
-      }
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int i = qi[qb];
-        float z[16];
-        if (j0 + 31 <= i0 + 32 * qb) {           // every key of the tile precedes every query of the block
-#pragma unroll
-          for (int v = 0; v < 16; ++v) z[v] = s[qb][v];       // raw: the scale goes into the exponent below
-        } else if (j0 > i0 + 32 * qb + 31 && i0 + 32 * qb >= img_lo && i0 + 32 * qb + 31 < img_hi) {
-          // every key follows every query of the block and all its queries are image rows: the mask
-          // is the key's discount (-inf off the image span), whatever the query
-#pragma unroll
-          for (int v = 0; v < 16; ++v) z[v] = fmaf(kbias[v], inv_c2, s[qb][v]);
-        } else {
-          const bool q_img = i >= img_lo && i < img_hi;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int j = j0 + att_key_of(v, hf);
-            const float ahead = q_img ? kbias[v] : -INFINITY;      // a key after the query
-            z[v] = s[qb][v] + (j <= i ? 0.0f : ahead) * inv_c2;
-          }
-        }
-        float mx = z[0];
-#pragma unroll
-        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, z[v]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // maxima are kept in units of the raw products; m_c = c2 * m is what the exponent subtracts
-        const float m_new = fmaxf(m_run[qb], mx);   // finite from the first tile on: key 0 precedes every query
-        const float alpha = fast_exp2_att((m_run[qb] - m_new) * c2);
-        const float m_c = m_new * c2;
-        float p[16], psum = 0.0f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          p[v] = fast_exp2_att(fmaf(z[v], c2, -m_c));
-          psum += p[v];
-        }
-        l_run[qb] = l_run[qb] * alpha + psum;
-        m_run[qb] = m_new;
-        if (__any(alpha != 1.0f)) {              // the running maxima settle after the first tiles
-#pragma unroll
-          for (int t = 0; t < DT; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[qb][t][v] *= alpha;
-        }
-#pragma unroll
-        for (int c = 0; c < NPS; ++c) pb[qb][c] = att_pack16<T>(&p[c * E]);
-      }
-#pragma unroll
-      for (int c = 0; c < NPS; ++c)
-#pragma unroll
-        for (int t = 0; t < DT; ++t) {
-          uint4 va;
-          if (E == 4) {                          // 4 keys of 4 bytes: piece 2c + hf of the row
-            va = *reinterpret_cast<const uint4*>(Vt + v_off[t] + (((2 * c + hf) ^ v_x[t]) << 4));
-          } else {                               // keys 16c + 4hf + 0..3 and 16c + 8 + 4hf + 0..3: halves of two pieces
-            const uint2 lo = *reinterpret_cast<const uint2*>(Vt + v_off[t] + (((2 * c) ^ v_x[t]) << 4) + 8 * hf);
-            const uint2 hi = *reinterpret_cast<const uint2*>(Vt + v_off[t] + (((2 * c + 1) ^ v_x[t]) << 4) + 8 * hf);
-            va = make_uint4(lo.x, lo.y, hi.x, hi.y);
-          }
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) mma32<T>(o[qb][t], va, pb[qb][c]);
-        }
-    }
-    wait_all_vmem();
-    __syncthreads();
-  }
-
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
-    const float inv = 1.0f / l_tot;
-    const int i = qi[qb];
-    if (i < N) {
-      T* orow = out + (((int64_t)b * H + h) * N + i) * D;
-#pragma unroll
-      for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          float f[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) f[e] = o[qb][t][4 * gq + e] * inv;
-          store4<T>(orow + t * 32 + 8 * gq + 4 * hf, f);
-        }
-    }
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
-#ifndef ATT_NW
-#define ATT_NW 8       /* waves per workgroup: two per SIMD, so that one wave's softmax arithmetic */
-#define ATT_QB 1       /* overlaps the other's MFMAs; one 32-query block per wave */
-#endif
 static int att_npad(const asap_params& p) { return ((p.P + p.V + p.Tmax + 31) / 32) * 32 + 32; }
 
 size_t attention_workspace_bytes(const asap_params& p) {
@@ -345,25 +397,26 @@ static hipError_t attention_typed(const asap_params& p, const void* q, Strides3 
   T* vt = reinterpret_cast<T*>(ws);
   float* bias2 = reinterpret_cast<float*>(ws + align256(sizeof(T) * (size_t)p.B * p.Hkv * p.d * Npad));
   const bool bidir = p.mask_mode == ASAP_MASK_KEYBIAS;
-  if (bidir)
-    ASAP_LAUNCH(tm, "k_att_bias", k_att_bias, dim3((Npad + 255) / 256, p.B), dim3(256), 0, st, s_hat, p.P, p.V, Npad,
-                p.lambda_max, p.eps, bias2);
+  // (with the mask off the table is -inf everywhere and s_hat is not read)
+  ASAP_LAUNCH(tm, "k_att_bias", k_att_bias, dim3((Npad + 255) / 256, p.B), dim3(256), 0, st, bidir ? s_hat : nullptr,
+              p.P, p.V, Npad, p.lambda_max, p.eps, bias2);
   ASAP_LAUNCH(tm, "k_vtranspose", k_vtranspose<T>, dim3(Npad / 32, p.Hkv, p.B), dim3(256), 0, st,
               static_cast<const T*>(v), sv, N, Npad, p.d, vt);
   const float c2 = 1.4426950408889634f / sqrtf((float)p.d);
   const dim3 grid((N + ATT_QWG - 1) / ATT_QWG, p.H, p.B);
   const int ch = p.d / E / 2;
-  const size_t lds = 2 * (size_t)(32 * 32 * ch + p.d * 32 * sizeof(T));   // two stages of (K tile + V^T tile)
+  constexpr int PD = ATT_PD;                   // key tiles requested ahead
+  const size_t lds = (PD + 2) * ((size_t)(32 * 32 * ch + p.d * 32 * sizeof(T)) + ATT_BIASB);
 #define ASAP_ATT(CHV)                                                                                          \
   do {                                                                                                         \
-    auto kern = k_attention<T, CHV, ATT_NW, ATT_QB>;                                                                           \
+    auto kern = k_attention<T, CHV, PD>;                                                                                    \
     if (lds > 48 * 1024) {                                                                                     \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                \
       if (e != hipSuccess) return e;                                                                           \
     }                                                                                                          \
-    ASAP_LAUNCH(tm, "k_attention", kern, grid, dim3(64 * ATT_NW), lds, st, static_cast<const T*>(q), sq,               \
-                static_cast<const T*>(k), sk, vt, Npad, bidir ? bias2 : nullptr, static_cast<T*>(out), p.H,    \
+    ASAP_LAUNCH(tm, "k_attention", kern, grid, dim3(64 * ATT_NW), lds, st, static_cast<const T*>(q), sq,       \
+                static_cast<const T*>(k), sk, vt, Npad, bias2, bidir ? 1 : 0, static_cast<T*>(out), p.H,       \
                 p.Hkv, N, p.P, p.V, c2);                                                                       \
   } while (0)
   if (ch == 4) ASAP_ATT(4);
