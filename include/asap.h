@@ -16,7 +16,9 @@
  *
  * Ownership: the caller owns every buffer including the workspace; the library
  * allocates nothing on the device, never synchronises the stream and keeps no
- * state between calls except the last error text of a context.
+ * state between calls except the last error text of a context (and, once
+ * asap_stage has been asked for two streams, that context's second stream and
+ * two events, released by asap_destroy).
  * Errors: shapes, dtypes, pointers and workspace size are checked on the host
  * before anything is launched; a failed check launches nothing.  Contents of device
  * buffers (NaNs, text_len outside [1, Tmax]) are not checked.
@@ -209,6 +211,45 @@ asap_status asap_compact_kv_from_kept(asap_ctx* ctx, const asap_params* p, int32
                                       const void* const* k_src, const void* const* v_src,
                                       void* const* k_dst, void* const* v_dst,
                                       const int32_t* final_idx, const int32_t* text_len, void* stream);
+
+/*
+ * asap_stage -- the whole stage in one call: asap_score, asap_select, asap_merge and the K/V
+ * compaction (asap_compact_kv_from_kept), with the arguments of those calls gathered in one struct
+ * (same meaning, layout and checks; every check runs before the first launch).  n_layers = 0 skips
+ * the compaction (the four K/V arrays may then be NULL).
+ * two_streams != 0 and ASAP_ROUTE_ABSORB: the K/V rows depend on the kept set only, so after the
+ * selection the compaction is launched on a second stream of the context (default priority, made
+ * on first use) ordered after `stream` by an event, next to the similarity and merge kernels, and
+ * `stream` waits for it at the end: work enqueued on `stream` after the call sees all outputs.
+ * The similarity kernel is bound on chip and the compaction by HBM, which is why the two go well
+ * side by side.  Otherwise, and always with ASAP_ROUTE_PAPER (final_idx exists only after the
+ * merge), everything runs on `stream` in order.  One context must not run two stages at once.
+ * The calls are capturable into a HIP graph (kernels, event record / wait; no memset, no sync).
+ */
+typedef struct asap_stage_io {
+  /* asap_score */
+  const void* q_vis;  int64_t q_vis_stride[3];
+  const void* q_txt;  int64_t q_txt_stride[3];
+  const void* k_vis;  int64_t k_vis_stride[3];
+  const int32_t* text_len;
+  const float* lse_extra;                      /* may be NULL */
+  float* s_raw;  float* s_hat;  float* score;
+  /* asap_select */
+  int32_t* kept_idx;  int32_t* pruned_idx;
+  /* asap_merge */
+  const void* hidden;  int64_t hidden_stride[2];
+  void* out_hidden;  int32_t* pos_out;  int32_t* new_len;
+  int32_t* assign;  float* best_sim;  float* wsum;  int32_t* final_idx;
+  /* K/V compaction: [host] arrays of n_layers device pointers, as for asap_compact_kv */
+  int32_t n_layers;
+  const void* const* k_src;  const void* const* v_src;
+  void* const* k_dst;  void* const* v_dst;
+  /* asap_workspace_bytes(p) bytes, 256-byte aligned */
+  void* workspace;  size_t workspace_bytes;
+} asap_stage_io;
+
+asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io* io, int32_t two_streams,
+                       void* stream);
 
 /*
  * asap_compact_kv_paged -- asap_compact_kv for caches kept as pools of fixed-size pages with one

@@ -22,7 +22,7 @@ ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
 
 EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
            "asap_score", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv",
-           "asap_compact_kv_from_kept", "asap_compact_kv_paged",
+           "asap_compact_kv_from_kept", "asap_compact_kv_paged", "asap_stage",
            "asap_timing_enable",
            "asap_timing_collect", "asap_theoretical_flops", "asap_flops_ratio", "asap_attention",
            "asap_attention_workspace_bytes"]
@@ -39,6 +39,22 @@ class asap_params(ctypes.Structure):
                 ("lambda_max", ctypes.c_float), ("eps", ctypes.c_float), ("sim_threshold", ctypes.c_float),
                 ("merge_weight", ctypes.c_float),
                 ("mask_mode", ctypes.c_int), ("route", ctypes.c_int)]
+
+
+class asap_stage_io(ctypes.Structure):
+    """Arguments of asap_stage (field for field the struct of include/asap.h)."""
+    _vp, _i64x3 = ctypes.c_void_p, ctypes.c_int64 * 3
+    _fields_ = [("q_vis", _vp), ("q_vis_stride", _i64x3), ("q_txt", _vp), ("q_txt_stride", _i64x3),
+                ("k_vis", _vp), ("k_vis_stride", _i64x3), ("text_len", _vp), ("lse_extra", _vp),
+                ("s_raw", _vp), ("s_hat", _vp), ("score", _vp),
+                ("kept_idx", _vp), ("pruned_idx", _vp),
+                ("hidden", _vp), ("hidden_stride", ctypes.c_int64 * 2),
+                ("out_hidden", _vp), ("pos_out", _vp), ("new_len", _vp),
+                ("assign", _vp), ("best_sim", _vp), ("wsum", _vp), ("final_idx", _vp),
+                ("n_layers", ctypes.c_int32),
+                ("k_src", ctypes.POINTER(_vp)), ("v_src", ctypes.POINTER(_vp)),
+                ("k_dst", ctypes.POINTER(_vp)), ("v_dst", ctypes.POINTER(_vp)),
+                ("workspace", _vp), ("workspace_bytes", ctypes.c_size_t)]
 
 
 class AsapError(RuntimeError):
@@ -92,6 +108,8 @@ def load() -> ctypes.CDLL:
     lib.asap_compact_kv_from_kept.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                               ctypes.POINTER(vp), ctypes.POINTER(vp), i32p, i32p, vp]
     lib.asap_compact_kv_from_kept.restype = ctypes.c_int
+    lib.asap_stage.argtypes = [vp, pp, ctypes.POINTER(asap_stage_io), ctypes.c_int32, vp]
+    lib.asap_stage.restype = ctypes.c_int
     lib.asap_compact_kv_paged.argtypes = [vp, pp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                           ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int32, i32p,
                                           ctypes.c_int32, i32p, ctypes.c_int32, i32p, i32p, vp]
@@ -268,6 +286,10 @@ class Context:
             self._h, ctypes.byref(p), n, arr(k_src), arr(v_src), arr(k_dst), arr(v_dst), _ptr(final_idx),
             _ptr(text_len), _stream(stream)))
 
+    def asap_stage(self, p, io: asap_stage_io, two_streams: bool = True, stream=None):
+        self._check(self._lib.asap_stage(self._h, ctypes.byref(p), ctypes.byref(io), 1 if two_streams else 0,
+                                         _stream(stream)))
+
     def asap_compact_kv_paged(self, p, k_src_pool: Sequence[torch.Tensor], v_src_pool, k_dst_pool, v_dst_pool,
                               page_size: int, src_table, dst_table, pos_out, new_len, stream=None):
         """Pools [n_pages,Hkv,page_size,d] per layer; src_table / dst_table [B, pages per sequence] int32."""
@@ -307,6 +329,36 @@ class StageBuffers:
         self.k_dst = [torch.zeros(B, p.Hkv, Nout, p.d, dtype=kvd, device=dev) for _ in range(n_layers)]
         self.v_dst = [torch.zeros(B, p.Hkv, Nout, p.d, dtype=kvd, device=dev) for _ in range(n_layers)]
         self.workspace = torch.empty(max(asap_workspace_bytes(p), 256), dtype=torch.uint8, device=dev)
+
+
+def stage_io(p: asap_params, q: torch.Tensor, k: torch.Tensor, hidden: torch.Tensor, text_len: torch.Tensor,
+             k_cache: List[torch.Tensor], v_cache: List[torch.Tensor], buf: "StageBuffers",
+             lse_extra: Optional[torch.Tensor] = None) -> asap_stage_io:
+    """asap_stage_io for one batch: pointers and strides only.  The returned struct refers to the
+    tensors' memory (and owns the four arrays of K/V layer pointers): keep the tensors alive."""
+    P, V = p.P, p.V
+    q_vis, q_txt, k_vis = q[:, :, P:P + V], q[:, :, P + V:], k[:, :, P:P + V]
+    io = asap_stage_io()
+    addr = lambda t: None if t is None else t.data_ptr()
+    io.q_vis, io.q_vis_stride = addr(q_vis), _strides(q_vis, 3)
+    io.q_txt, io.q_txt_stride = addr(q_txt), _strides(q_txt, 3)
+    io.k_vis, io.k_vis_stride = addr(k_vis), _strides(k_vis, 3)
+    io.text_len, io.lse_extra = addr(text_len), addr(lse_extra)
+    io.s_raw, io.s_hat, io.score = addr(buf.s_raw), addr(buf.s_hat), addr(buf.score)
+    io.kept_idx, io.pruned_idx = addr(buf.kept_idx), addr(buf.pruned_idx)
+    io.hidden, io.hidden_stride = addr(hidden), _strides(hidden, 2)
+    io.out_hidden, io.pos_out, io.new_len = addr(buf.out_hidden), addr(buf.pos_out), addr(buf.new_len)
+    io.assign, io.best_sim, io.wsum, io.final_idx = addr(buf.assign), addr(buf.best_sim), addr(buf.wsum), \
+        addr(buf.final_idx)
+    n = len(k_cache)
+    io.n_layers = n
+    if n:
+        arr = lambda ts: (ctypes.c_void_p * n)(*[t.data_ptr() for t in ts])
+        io._keep = [arr(k_cache), arr(v_cache), arr(buf.k_dst), arr(buf.v_dst)]
+        cast = lambda a: ctypes.cast(a, ctypes.POINTER(ctypes.c_void_p))
+        io.k_src, io.v_src, io.k_dst, io.v_dst = (cast(a) for a in io._keep)
+    io.workspace, io.workspace_bytes = addr(buf.workspace), buf.workspace.numel()
+    return io
 
 
 class PagedKV:
@@ -396,11 +448,12 @@ def to_device(arr, dtype: str, device="cuda:0") -> torch.Tensor:
 
 
 class DeviceStage:
-    """One batch from synth.make_inputs uploaded to the GPU, with output buffers; run() makes the
-    library calls of one stage (overlap=True: K/V compaction on a second stream, see run_stage)."""
+    """One batch from synth.make_inputs uploaded to the GPU, with output buffers.  run() is one
+    asap_stage call (overlap=True: two streams inside the library); with call_by_call=True, or with
+    paged caches, it is the sequence of single calls of run_stage, where the second stream is torch's."""
 
     def __init__(self, inp: dict, ctx: Optional[Context] = None, lse_extra=None, overlap: bool = True,
-                 page_size: Optional[int] = None, **param_overrides):
+                 page_size: Optional[int] = None, call_by_call: bool = False, **param_overrides):
         import numpy as np
         cfg = inp["cfg"]
         self.cfg = cfg
@@ -419,12 +472,21 @@ class DeviceStage:
             self.paged = PagedKV(self.p, self.k_cache, self.v_cache, page_size, seed=cfg.seed)
             self.k_cache, self.v_cache = [], []
         self.buf = StageBuffers(self.p, len(self.k_cache))
-        # default-priority second stream for the K/V compaction (None = everything on one stream)
-        self.side_stream = torch.cuda.Stream() if (overlap and (self.k_cache or self.paged)) else None
+        has_kv = bool(self.k_cache) or self.paged is not None
+        self.call_by_call = call_by_call or self.paged is not None
+        # whether the K/V compaction runs beside the similarity and merge kernels
+        self.two_streams = overlap and has_kv and self.p.route == ASAP_ROUTE_ABSORB
+        # torch's default-priority second stream, for the call-by-call path only
+        self.side_stream = torch.cuda.Stream() if (self.call_by_call and overlap and has_kv) else None
+        self.io = None if self.call_by_call else stage_io(self.p, self.q, self.k, self.hidden, self.text_len,
+                                                          self.k_cache, self.v_cache, self.buf, self.lse_extra)
 
     def run_async(self) -> StageBuffers:
-        return run_stage(self.ctx, self.p, self.q, self.k, self.hidden, self.text_len, self.k_cache,
-                         self.v_cache, self.buf, self.lse_extra, side_stream=self.side_stream, paged=self.paged)
+        if self.call_by_call:
+            return run_stage(self.ctx, self.p, self.q, self.k, self.hidden, self.text_len, self.k_cache,
+                             self.v_cache, self.buf, self.lse_extra, side_stream=self.side_stream, paged=self.paged)
+        self.ctx.asap_stage(self.p, self.io, self.two_streams)
+        return self.buf
 
     def run(self) -> StageBuffers:
         self.run_async()

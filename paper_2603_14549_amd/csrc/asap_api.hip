@@ -10,6 +10,8 @@ struct asap_ctx {
   int device;
   char err[512];
   asap::Timer* timer;   // non-null while kernel timing is on
+  hipStream_t side;     // second stream of asap_stage and its fork / join events; made on first use
+  hipEvent_t ev_fork, ev_join;
 };
 
 namespace {
@@ -116,6 +118,8 @@ asap_status asap_create(asap_ctx** out_ctx, int device) {
   c->device = device;
   c->err[0] = 0;
   c->timer = nullptr;
+  c->side = nullptr;
+  c->ev_fork = c->ev_join = nullptr;
   *out_ctx = c;
   return ASAP_OK;
 }
@@ -130,9 +134,18 @@ static void drop_timer(asap_ctx* ctx) {
   ctx->timer = nullptr;
 }
 
+static void drop_stage_resources(asap_ctx* ctx) {
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+  if (ctx->side) (void)hipStreamDestroy(ctx->side);
+  ctx->side = nullptr;
+  ctx->ev_fork = ctx->ev_join = nullptr;
+}
+
 void asap_destroy(asap_ctx* ctx) {
   if (!ctx) return;
   drop_timer(ctx);
+  drop_stage_resources(ctx);
   delete ctx;
 }
 
@@ -206,11 +219,10 @@ size_t asap_workspace_bytes(const asap_params* p) {
   return a > b ? a : b;
 }
 
-asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, const int64_t q_vis_stride[3],
-                       const void* q_txt, const int64_t q_txt_stride[3], const void* k_vis,
-                       const int64_t k_vis_stride[3], const int32_t* text_len, const float* lse_extra,
-                       float* s_raw, float* s_hat, float* score, void* workspace, size_t workspace_bytes,
-                       void* stream) {
+static asap_status score_checks(asap_ctx* ctx, const asap_params* p, const void* q_vis,
+                                const int64_t q_vis_stride[3], const void* q_txt, const int64_t q_txt_stride[3],
+                                const void* k_vis, const int64_t k_vis_stride[3], const int32_t* text_len,
+                                float* s_raw, float* s_hat, float* score, void* workspace, size_t workspace_bytes) {
   asap_status st = common_checks(ctx, p);
   if (st != ASAP_OK) return st;
   if (!q_vis || !q_txt || !k_vis || !text_len || !s_raw || !s_hat || !score)
@@ -222,7 +234,17 @@ asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, c
   if ((st = check_strides(ctx, "k_vis_stride", k_vis_stride, 3, 8)) != ASAP_OK) return st;
   if (q_vis_stride[2] < p->d || q_txt_stride[2] < p->d || k_vis_stride[2] < p->d)
     return fail(ctx, ASAP_EINVAL, "asap_score: row strides must be >= d");
-  if ((st = check_workspace(ctx, p, workspace, workspace_bytes)) != ASAP_OK) return st;
+  return check_workspace(ctx, p, workspace, workspace_bytes);
+}
+
+asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, const int64_t q_vis_stride[3],
+                       const void* q_txt, const int64_t q_txt_stride[3], const void* k_vis,
+                       const int64_t k_vis_stride[3], const int32_t* text_len, const float* lse_extra,
+                       float* s_raw, float* s_hat, float* score, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  asap_status st = score_checks(ctx, p, q_vis, q_vis_stride, q_txt, q_txt_stride, k_vis, k_vis_stride, text_len,
+                                s_raw, s_hat, score, workspace, workspace_bytes);
+  if (st != ASAP_OK) return st;
   Strides3 qv{q_vis_stride[0], q_vis_stride[1], q_vis_stride[2]};
   Strides3 qt{q_txt_stride[0], q_txt_stride[1], q_txt_stride[2]};
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
@@ -232,23 +254,31 @@ asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, c
                     "asap_score launch");
 }
 
-asap_status asap_select(asap_ctx* ctx, const asap_params* p, const float* score, int32_t* kept_idx,
-                        int32_t* pruned_idx, void* workspace, size_t workspace_bytes, void* stream) {
-  (void)workspace;
-  (void)workspace_bytes;
+static asap_status select_checks(asap_ctx* ctx, const asap_params* p, const float* score, int32_t* kept_idx,
+                                 int32_t* pruned_idx) {
   asap_status st = common_checks(ctx, p);
   if (st != ASAP_OK) return st;
   if (!score || !kept_idx || (!pruned_idx && p->k < p->V))
     return fail(ctx, ASAP_EINVAL, "asap_select: a required pointer is NULL");
+  return ASAP_OK;
+}
+
+asap_status asap_select(asap_ctx* ctx, const asap_params* p, const float* score, int32_t* kept_idx,
+                        int32_t* pruned_idx, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  asap_status st = select_checks(ctx, p, score, kept_idx, pruned_idx);
+  if (st != ASAP_OK) return st;
   return hip_result(ctx, launch_select(*p, score, kept_idx, pruned_idx, static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_select launch");
 }
 
-asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, const int64_t hidden_stride[2],
-                       const float* s_raw, const float* s_hat, const int32_t* text_len, const int32_t* kept_idx,
-                       const int32_t* pruned_idx, void* out_hidden, int32_t* pos_out, int32_t* new_len,
-                       int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx, void* workspace,
-                       size_t workspace_bytes, void* stream) {
+static asap_status merge_checks(asap_ctx* ctx, const asap_params* p, const void* hidden,
+                                const int64_t hidden_stride[2], const float* s_raw, const float* s_hat,
+                                const int32_t* text_len, const int32_t* kept_idx, const int32_t* pruned_idx,
+                                void* out_hidden, int32_t* pos_out, int32_t* new_len, int32_t* assign,
+                                float* best_sim, float* wsum, int32_t* final_idx, void* workspace,
+                                size_t workspace_bytes) {
   asap_status st = common_checks(ctx, p);
   if (st != ASAP_OK) return st;
   const bool paper = p->route == ASAP_ROUTE_PAPER;
@@ -271,7 +301,18 @@ asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, 
     const char* b1 = b0 + (int64_t)p->B * (p->P + p->k + p->Tmax) * p->D * esz;
     if (a0 < b1 && b0 < a1) return fail(ctx, ASAP_EINVAL, "asap_merge: out_hidden overlaps hidden");
   }
-  if ((st = check_workspace(ctx, p, workspace, workspace_bytes)) != ASAP_OK) return st;
+  return check_workspace(ctx, p, workspace, workspace_bytes);
+}
+
+asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, const int64_t hidden_stride[2],
+                       const float* s_raw, const float* s_hat, const int32_t* text_len, const int32_t* kept_idx,
+                       const int32_t* pruned_idx, void* out_hidden, int32_t* pos_out, int32_t* new_len,
+                       int32_t* assign, float* best_sim, float* wsum, int32_t* final_idx, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  asap_status st = merge_checks(ctx, p, hidden, hidden_stride, s_raw, s_hat, text_len, kept_idx, pruned_idx,
+                                out_hidden, pos_out, new_len, assign, best_sim, wsum, final_idx, workspace,
+                                workspace_bytes);
+  if (st != ASAP_OK) return st;
   return hip_result(ctx,
                     launch_merge(*p, hidden, hidden_stride[0], hidden_stride[1], s_raw, s_hat, text_len, kept_idx,
                                  pruned_idx, out_hidden, pos_out, new_len, assign, best_sim, wsum, final_idx,
@@ -349,6 +390,73 @@ asap_status asap_compact_kv_from_kept(asap_ctx* ctx, const asap_params* p, int32
                     launch_compact_kv(*p, KV_FROM_KEPT, n_layers, k_src, v_src, k_dst, v_dst, final_idx, text_len,
                                       static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_compact_kv_from_kept launch");
+}
+
+// The second stream and the two events of asap_stage, made on first use.
+static asap_status stage_resources(asap_ctx* ctx) {
+  if (ctx->side) return ASAP_OK;
+  hipError_t e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);     // default priority
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    drop_stage_resources(ctx);
+    return fail(ctx, ASAP_EHIP, "asap_stage: stream / event creation: %s", hipGetErrorString(e));
+  }
+  return ASAP_OK;
+}
+
+asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io* io, int32_t two_streams,
+                       void* stream) {
+  if (!ctx) return ASAP_EINVAL;
+  if (!io) return fail(ctx, ASAP_EINVAL, "asap_stage: io is NULL");
+  // every check of the single calls first: a failed check launches nothing
+  asap_status st = score_checks(ctx, p, io->q_vis, io->q_vis_stride, io->q_txt, io->q_txt_stride, io->k_vis,
+                                io->k_vis_stride, io->text_len, io->s_raw, io->s_hat, io->score, io->workspace,
+                                io->workspace_bytes);
+  if (st == ASAP_OK) st = select_checks(ctx, p, io->score, io->kept_idx, io->pruned_idx);
+  if (st == ASAP_OK)
+    st = merge_checks(ctx, p, io->hidden, io->hidden_stride, io->s_raw, io->s_hat, io->text_len, io->kept_idx,
+                      io->pruned_idx, io->out_hidden, io->pos_out, io->new_len, io->assign, io->best_sim, io->wsum,
+                      io->final_idx, io->workspace, io->workspace_bytes);
+  const bool has_kv = io->n_layers != 0;
+  if (st == ASAP_OK && has_kv)
+    st = check_kv_buffers(ctx, p, "asap_stage", io->n_layers, io->k_src, io->v_src, io->k_dst, io->v_dst);
+  if (st != ASAP_OK) return st;
+  // with ASAP_ROUTE_ABSORB the kept set is final after the selection: the K/V rows can move while the merge runs
+  const bool early = has_kv && two_streams && p->route == ASAP_ROUTE_ABSORB;
+  if (early && (st = stage_resources(ctx)) != ASAP_OK) return st;
+
+  hipStream_t main = static_cast<hipStream_t>(stream);
+  Strides3 qv{io->q_vis_stride[0], io->q_vis_stride[1], io->q_vis_stride[2]};
+  Strides3 qt{io->q_txt_stride[0], io->q_txt_stride[1], io->q_txt_stride[2]};
+  Strides3 kv{io->k_vis_stride[0], io->k_vis_stride[1], io->k_vis_stride[2]};
+  char* ws = static_cast<char*>(io->workspace);
+  hipError_t e = launch_score(*p, io->q_vis, qv, io->q_txt, qt, io->k_vis, kv, io->text_len, io->lse_extra, io->s_raw,
+                              io->s_hat, io->score, ws, main, ctx->timer);
+  if (e == hipSuccess) e = launch_select(*p, io->score, io->kept_idx, io->pruned_idx, main, ctx->timer);
+  bool forked = false;
+  if (e == hipSuccess && early) {
+    e = hipEventRecord(ctx->ev_fork, main);
+    if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
+    if (e == hipSuccess) {
+      forked = true;
+      e = launch_compact_kv(*p, KV_FROM_KEPT, io->n_layers, io->k_src, io->v_src, io->k_dst, io->v_dst, io->kept_idx,
+                            io->text_len, ctx->side, ctx->timer);
+    }
+  }
+  if (e == hipSuccess)
+    e = launch_merge(*p, io->hidden, io->hidden_stride[0], io->hidden_stride[1], io->s_raw, io->s_hat, io->text_len,
+                     io->kept_idx, io->pruned_idx, io->out_hidden, io->pos_out, io->new_len, io->assign, io->best_sim,
+                     io->wsum, io->final_idx, ws, main, ctx->timer);
+  if (forked) {      // also after an error: the caller's stream must not run ahead of the second one
+    hipError_t e2 = hipEventRecord(ctx->ev_join, ctx->side);
+    if (e2 == hipSuccess) e2 = hipStreamWaitEvent(main, ctx->ev_join, 0);
+    if (e == hipSuccess) e = e2;
+  } else if (e == hipSuccess && has_kv) {
+    e = launch_compact_kv(*p, KV_FROM_KEPT, io->n_layers, io->k_src, io->v_src, io->k_dst, io->v_dst, io->final_idx,
+                          io->text_len, main, ctx->timer);
+  }
+  return hip_result(ctx, e, "asap_stage launch");
 }
 
 asap_status asap_compact_kv_paged(asap_ctx* ctx, const asap_params* p, int32_t n_layers,

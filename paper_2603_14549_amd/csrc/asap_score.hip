@@ -217,8 +217,8 @@ __global__ __launch_bounds__(256) void k_mass(const T* __restrict__ kv, Strides3
 }
 
 // ------------------------------------------------------------------------------------------
-// k_mass_mfma (bf16 keys): grid (ceil(V/32), B), 256 threads = 4 waves.  A workgroup owns one
-// 32-key tile; wave w walks the kv heads g = w, w + 4, ...  The four bf16 pieces of qbar_g are rows
+// k_mass_mfma (bf16 keys): grid (ceil(V/32), B), MASS_NW waves.  A workgroup owns one
+// 32-key tile; wave w walks the kv heads g = w, w + MASS_NW, ...  The four bf16 pieces of qbar_g are rows
 // 0..3 of the MFMA A tile (rows 4..31 are zero), the keys are the B tile, so lane n (< 32) finds
 // the four partial dot products of key n in its first four accumulator registers.
 // CH = 16-byte chunks of a row per lane half (d = 16*CH).
@@ -230,14 +230,21 @@ __device__ __forceinline__ void load_key_tile(uint4 (&kb)[CH], const char* krow)
 }
 
 constexpr int MASS_TILES_PER_WG = 1;   // key tiles a workgroup takes one after the other
+#ifndef MASS_WAVES
+#define MASS_WAVES 4
+#endif
+// Waves per workgroup, which share the kv heads of the tile.  Measured at 2304 keys x 16 images x 32 heads:
+// 66.6 / 66.2 / 63.8 us with 4 / 2 / 1 waves, so the launch is not short of residency; four keep the
+// chain of dependent loads per wave short when a batch has few tiles.
+constexpr int MASS_NW = MASS_WAVES;
 
 template <int CH>
-__global__ __launch_bounds__(256) void k_mass_mfma(const bf16_t* __restrict__ kv, Strides3 sk,
+__global__ __launch_bounds__(64 * MASS_NW) void k_mass_mfma(const bf16_t* __restrict__ kv, Strides3 sk,
                                                     const uint16_t* __restrict__ qsplit, int Hkv, int V,
                                                     double scale, double* __restrict__ s64, float* __restrict__ s_raw,
                                                     unsigned long long* __restrict__ mmkey) {
   constexpr int D = CH * 16;
-  __shared__ double part[4][32];
+  __shared__ double part[MASS_NW][32];
   __shared__ unsigned long long blk_mm[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hf = lane >> 5;
@@ -264,8 +271,8 @@ __global__ __launch_bounds__(256) void k_mass_mfma(const bf16_t* __restrict__ kv
       if (has_q) load_key_tile<CH>(qa, qbase + g * qheadb);
     }
     double sum = 0.0;
-    for (; g < Hkv; g += 4) {
-      const int gn = g + 4;
+    for (; g < Hkv; g += MASS_NW) {
+      const int gn = g + MASS_NW;
       if (gn < Hkv) load_key_tile<CH>(kn, kbase + gn * headb);
       f32x16_t acc;
 #pragma unroll
@@ -283,7 +290,10 @@ __global__ __launch_bounds__(256) void k_mass_mfma(const bf16_t* __restrict__ kv
     if (hf == 0) part[wave][n] = sum;
     __syncthreads();
     if (tid < 32 && j < V) {
-      double s = (((part[0][n] + part[1][n]) + part[2][n]) + part[3][n]) * scale;
+      double s = part[0][n];
+#pragma unroll
+      for (int w = 1; w < MASS_NW; ++w) s += part[w][n];      // fixed order
+      s *= scale;
       s64[(int64_t)b * V + j] = s;
       s_raw[(int64_t)b * V + j] = (float)s;
       const unsigned long long key = f64_key(s);
@@ -679,10 +689,10 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   if constexpr (E == 8) {
     const bf16_t* kp = static_cast<const bf16_t*>(k_vis);
     if (ch == 8)
-      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<8>, dim3((ktiles + MASS_TILES_PER_WG - 1) / MASS_TILES_PER_WG, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
+      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<8>, dim3((ktiles + MASS_TILES_PER_WG - 1) / MASS_TILES_PER_WG, p.B), dim3(64 * MASS_NW), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
                   s64, s_raw, mmkey);
     else
-      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<4>, dim3((ktiles + MASS_TILES_PER_WG - 1) / MASS_TILES_PER_WG, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
+      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<4>, dim3((ktiles + MASS_TILES_PER_WG - 1) / MASS_TILES_PER_WG, p.B), dim3(64 * MASS_NW), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
                   s64, s_raw, mmkey);
   } else {
     ASAP_LAUNCH(tm, "k_mass", k_mass<T>, dim3(ktiles, p.B), dim3(256), sizeof(double) * p.Hkv * p.d, st,

@@ -113,29 +113,46 @@ def test_determinism(ctx):
 
 
 def test_positions_and_two_stream_stage(ctx):
-    """asap_positions writes what asap_merge writes, and the stage with the K/V compaction
-    on a second stream gives bit-identical results to the stage on one stream."""
+    """asap_positions writes what asap_merge writes, and the stage gives bit-identical results on one
+    stream and on two, as one asap_stage call and as the sequence of single calls."""
     cfg = synth.CONFIGS["S1"]
     inp = synth.make_inputs(cfg)
-    serial = U.GpuStage(inp, ctx=ctx, overlap=False)
+    serial = U.GpuStage(inp, ctx=ctx, overlap=False, call_by_call=True)
+    assert serial.side_stream is None
     bs = serial.run()
-    both = U.GpuStage(inp, ctx=ctx, overlap=True)
-    assert both.side_stream is not None
-    for _ in range(3):
-        bo = both.run()
-        ctx.asap_positions(both.p, bo.kept_idx, both.text_len, bo.pos_early, bo.new_len_early)
-        assert torch.equal(bo.pos_early, bs.pos_out) and torch.equal(bo.new_len_early, bs.new_len)
-        assert torch.equal(bo.pos_out, bs.pos_out) and torch.equal(bo.new_len, bs.new_len)
-        for l in range(len(bs.k_dst)):
-            for b in range(cfg.B):
-                nl = int(bs.new_len[b])
-                assert torch.equal(bo.k_dst[l][b, :, :nl].view(torch.uint8), bs.k_dst[l][b, :, :nl].view(torch.uint8))
-                assert torch.equal(bo.v_dst[l][b, :, :nl].view(torch.uint8), bs.v_dst[l][b, :, :nl].view(torch.uint8))
-        assert torch.equal(bo.out_hidden.view(torch.uint8), bs.out_hidden.view(torch.uint8))
+    variants = [U.GpuStage(inp, ctx=ctx, overlap=True, call_by_call=True), U.GpuStage(inp, ctx=ctx, overlap=True),
+                U.GpuStage(inp, ctx=ctx, overlap=False)]
+    assert variants[0].side_stream is not None and variants[1].two_streams and not variants[2].two_streams
+    for both in variants:
+        for _ in range(3):
+            bo = both.run()
+            ctx.asap_positions(both.p, bo.kept_idx, both.text_len, bo.pos_early, bo.new_len_early)
+            torch.cuda.synchronize()
+            assert torch.equal(bo.pos_early, bs.pos_out) and torch.equal(bo.new_len_early, bs.new_len)
+            assert torch.equal(bo.pos_out, bs.pos_out) and torch.equal(bo.new_len, bs.new_len)
+            for l in range(len(bs.k_dst)):
+                for b in range(cfg.B):
+                    nl = int(bs.new_len[b])
+                    assert torch.equal(bo.k_dst[l][b, :, :nl].view(torch.uint8), bs.k_dst[l][b, :, :nl].view(torch.uint8))
+                    assert torch.equal(bo.v_dst[l][b, :, :nl].view(torch.uint8), bs.v_dst[l][b, :, :nl].view(torch.uint8))
+            assert torch.equal(bo.out_hidden.view(torch.uint8), bs.out_hidden.view(torch.uint8))
+            for name in ("s_raw", "s_hat", "score", "kept_idx", "assign", "best_sim", "wsum", "final_idx"):
+                assert torch.equal(getattr(bo, name), getattr(bs, name)), name
     p = binding.params_from_config(cfg, route=binding.ASAP_ROUTE_PAPER)
     with pytest.raises(binding.AsapError) as e:       # positions need the merge result with that route
         ctx.asap_positions(p, bs.kept_idx, serial.text_len, bs.pos_early, bs.new_len_early)
     assert e.value.status == binding.ASAP_EUNSUPPORTED
+    # asap_stage checks everything before it launches anything
+    st = variants[1]
+    bad = binding.stage_io(st.p, st.q, st.k, st.hidden, st.text_len, st.k_cache, st.v_cache, st.buf)
+    bad.out_hidden = bad.hidden                        # the merge's output aliasing its input
+    st.buf.score.fill_(-7.0)
+    torch.cuda.synchronize()
+    with pytest.raises(binding.AsapError) as e:
+        ctx.asap_stage(st.p, bad, True)
+    assert e.value.status == binding.ASAP_EINVAL
+    torch.cuda.synchronize()
+    assert bool((st.buf.score == -7.0).all()), "a failed check must launch nothing"
 
 
 @pytest.mark.parametrize("name,page_size", [("S1", 16), ("S1", 7), ("S3", 1), ("S3", 64), ("S0", 256)])
