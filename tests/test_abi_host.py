@@ -87,6 +87,32 @@ def test_struct_layout_matches_header(lib):
     assert ctypes.sizeof(binding.asap_params) == 18 * 4
 
 
+def test_header_is_plain_c_and_the_binding_mirrors_its_structs(tmp_path):
+    """include/asap.h compiles as C11 on its own, and the ctypes mirrors of its two structs have the
+    size and the field offsets the C compiler gives them."""
+    import subprocess
+    fields = {"asap_params": [f[0] for f in binding.asap_params._fields_],
+              "asap_stage_io": [f[0] for f in binding.asap_stage_io._fields_]}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "asap.h"', 'int main(void) {']
+    for st, names in fields.items():
+        lines.append(f'  printf("{st} %zu\\n", sizeof({st}));')
+        for n in names:
+            lines.append(f'  printf("{st}.{n} %zu\\n", offsetof({st}, {n}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines) + "\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                       text=True).stdout.splitlines())
+    for st, names in fields.items():
+        cls = getattr(binding, st)
+        assert int(out[st]) == ctypes.sizeof(cls), st
+        for n in names:
+            assert int(out[f"{st}.{n}"]) == getattr(cls, n).offset, f"{st}.{n}"
+
+
 def read_golden(name):
     rows = []
     for line in open(os.path.join(ROOT, "tests", "golden", name)):
