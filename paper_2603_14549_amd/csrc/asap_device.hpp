@@ -113,9 +113,9 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
 }
 __device__ __forceinline__ void wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-// wait until at most N (< 16) of this wave's vector-memory loads are still outstanding
+// wait until at most N (< 64) of this wave's vector-memory loads are still outstanding
 template <int N> __device__ __forceinline__ void wait_vmem_but() {
-  static_assert(N >= 0 && N < 16, "vmcnt field");
+  static_assert(N >= 0 && N < 64, "vmcnt field");
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 // Workgroup barrier without the release fence of __syncthreads(): that fence would wait for every

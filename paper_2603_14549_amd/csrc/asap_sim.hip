@@ -12,13 +12,15 @@
 //                 The source rows are read once, from HBM, so their 128 x 128 B slices go through a
 //                 ring of 4 LDS slots and are asked for three steps ahead; the destination rows are
 //                 shared by all tiles of an image and come from L2, so two slots (one step ahead)
-//                 are enough for their BN x 128 B slices.
+//                 are enough for their BN x 128 B slices at the widest tile; narrower tiles leave
+//                 room for deeper rings (sim_na, sim_nb).
 //                 LDS rows are unpadded; the 16-byte piece p of row r is stored in slot
 //                 p ^ ((r >> 1) & 7): any 16 consecutive rows then cover all 64 banks once, for the
 //                 1 KiB-contiguous loads as well as for the strided 16-byte operand reads.
 //                 The grid is one-dimensional and XCD-aware: consecutive workgroup ids go to the 8
 //                 XCDs round-robin, so id % 8 picks the XCD and all tiles of one image are given
-//                 ids with the same id % 8 -- they then share that XCD's L2 for the kept panel.
+//                 ids with the same id % 8 -- they then share that XCD's L2 for the kept panel
+//                 (batches of fewer than 8 images spread an image over several XCDs instead).
 //                 A workgroup takes one destination tile.  When the destination rows need several
 //                 (k > 64*NT), the tiles of a source tile are workgroups of their own: each folds its
 //                 row winner into a 64-bit key (order-preserving value bits, then the inverted
@@ -35,7 +37,12 @@ namespace asap {
 constexpr int SIM_BM = 128;
 constexpr int SIM_ROWB = 128;      // bytes of a row held in LDS per step
 constexpr int NUM_XCD = 8;
-constexpr int SIM_NA = 4;          // LDS ring slots for the source rows (power of two); destination rows have 2
+// LDS ring slots for the source rows (NA) and the destination rows (NB) by tile width: as deep as
+// 160 KiB allow, NA > NB >= 2.  Narrow tiles belong to launches with few workgroups (small batches, the
+// search inside the kept set), whose steps last as long as a load takes to arrive divided by how many
+// steps ahead it was asked for.
+constexpr int sim_na(int nt) { return nt == 1 ? 6 : nt == 2 ? 5 : 4; }
+constexpr int sim_nb(int nt) { return nt == 1 ? 4 : nt <= 3 ? 3 : 2; }
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
@@ -88,18 +95,21 @@ template <typename T, int NT, bool ANCHORED>
 __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t sb, int64_t sr, int D,
                                               const int32_t* __restrict__ pruned, const int32_t* __restrict__ kept,
                                               const float* __restrict__ s_hat, int V, int B, int M, int k,
-                                              int mtiles, int ptiles, float threshold, int32_t* __restrict__ assign,
+                                              int mtiles, int ptiles, int spread, int vmt, float threshold,
+                                              int32_t* __restrict__ assign,
                                               float* __restrict__ best_sim, unsigned long long* __restrict__ best_key,
                                               float* __restrict__ src_norm2) {
   constexpr int BN = 64 * NT;
   constexpr int PA = SIM_BM / 32;                // source-row loads a thread issues per step
   constexpr int PB = BN / 32;                    // destination-row loads
   constexpr int ASTAGE = SIM_BM * SIM_ROWB, BSTAGE = BN * SIM_ROWB;
+  constexpr int NA = sim_na(NT), NB = sim_nb(NT);
+  static_assert(NA > NB && NB >= 2, "ring depths");
   static_assert(PA + PB <= 8 * NT, "one load per MFMA slot");
   extern __shared__ __align__(16) char lds[];
-  char* ldsB = lds + SIM_NA * ASTAGE;
-  const uint32_t lds_addr = lds_address(lds), ldsB_addr = lds_addr + SIM_NA * ASTAGE;
-  float* norm2 = reinterpret_cast<float*>(ldsB + 2 * BSTAGE);    // [BM] squared norms of the source rows
+  char* ldsB = lds + NA * ASTAGE;
+  const uint32_t lds_addr = lds_address(lds), ldsB_addr = lds_addr + NA * ASTAGE;
+  float* norm2 = reinterpret_cast<float*>(ldsB + NB * BSTAGE);   // [BM] squared norms of the source rows
   float* normk = norm2 + SIM_BM;                                 // [BN] squared norms of this pass's kept rows
   uint2* part = reinterpret_cast<uint2*>(normk + BN);            // [2][BM] (value, column) per column half
   float* srow = reinterpret_cast<float*>(part + 2 * SIM_BM);     // [BM] salience of the source rows (ANCHORED)
@@ -107,11 +117,16 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
   // XCD-aware decode of the linear workgroup id
   // (a workgroup = one source tile x one destination tile; the destination tiles of a source tile
   // are neighbours in the id order)
+  // With fewer than 8 images one image per XCD would leave XCDs idle: an image's source tiles are then
+  // dealt to `spread` XCDs (tile mt to the XCD of "virtual image" b * spread + mt % spread), each of
+  // which keeps its own copy of the image's destination panel in L2.
   const int xcd = blockIdx.x % NUM_XCD, slot_p = blockIdx.x / NUM_XCD;
   const int pass = slot_p % ptiles, slot = slot_p / ptiles;
-  const int b = (slot / mtiles) * NUM_XCD + xcd;
-  if (b >= B) return;
-  const int m0 = (slot % mtiles) * SIM_BM;
+  const int vb = (slot / vmt) * NUM_XCD + xcd;
+  const int b = vb / spread;
+  const int mt = vb % spread + spread * (slot % vmt);
+  if (b >= B || mt >= mtiles) return;
+  const int m0 = mt * SIM_BM;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -122,7 +137,7 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
   const int steps = (D * (int)sizeof(T)) / SIM_ROWB;
   // Every workgroup walks the hidden dimension from its own starting step: rows are a power-of-two
   // number of bytes apart, so workgroups in lockstep would all hit the same memory channel.
-  const int rot = ((slot % mtiles) + 16 * (slot / mtiles)) % steps;
+  const int rot = (mt + 16 * (slot / vmt)) % steps;
   auto step_base = [&](int s) {
     int sr_ = s + rot;
     if (sr_ >= steps) sr_ -= steps;
@@ -166,13 +181,19 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
         for (int v = 0; v < 16; ++v) acc[i][t][v] = 0.0f;
     SumSq4 ss_a[2], ss_b[NT];
 
-    // fill: destination slice 0, source slices 0 .. SIM_NA-2
+    // fill: destination slices 0 .. NB-2, source slices 0 .. NA-2
     {
-      const char* g = step_base(0);
 #pragma unroll
-      for (int j = 0; j < PB; ++j) load_to_lds16(g, offb[j], ldsB_addr + (8 * wave + 32 * j) * SIM_ROWB);
+      for (int a = 0; a < NB - 1; ++a) {
+        if (a < steps) {
+          const char* g = step_base(a);
 #pragma unroll
-      for (int a = 0; a < SIM_NA - 1; ++a) {
+          for (int j = 0; j < PB; ++j)
+            load_to_lds16(g, offb[j], ldsB_addr + a * BSTAGE + (8 * wave + 32 * j) * SIM_ROWB);
+        }
+      }
+#pragma unroll
+      for (int a = 0; a < NA - 1; ++a) {
         if (a < steps) {
           const char* ga = step_base(a);
 #pragma unroll
@@ -184,20 +205,23 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
       __syncthreads();
     }
 
+    int sa = 0, sb_ = 0;       // ring slots of the current step: s % NA, s % NB
     for (int s = 0; s < steps; ++s) {
-      // During step s the waves read source slot s % SIM_NA and destination slot s % 2.  Meanwhile
-      // the destination rows of step s+1 are asked for first, then the source rows of step
-      // s+SIM_NA-1; loads retire in order, so leaving only the latter PA loads outstanding at the
-      // end of the step means that everything step s+1 needs has landed.
-      const char* A = lds + (s & (SIM_NA - 1)) * ASTAGE + (wm * 64 + n) * SIM_ROWB;
-      const char* Bp = ldsB + (s & 1) * BSTAGE + (wn * (BN / 2) + n) * SIM_ROWB;
+      // During step s the waves read source slot s % NA and destination slot s % NB.  Meanwhile the
+      // destination rows of step s+NB-1 are asked for first, then the source rows of step s+NA-1, each
+      // into the slot the previous step has just left.  Loads retire in order, so what step s+1 needs
+      // has landed once nothing older than the source loads of step s-NB+2 is outstanding: those PA
+      // loads and the PA+PB loads of each of the NB-2 steps since.
+      const char* A = lds + sa * ASTAGE + (wm * 64 + n) * SIM_ROWB;
+      const char* Bp = ldsB + sb_ * BSTAGE + (wn * (BN / 2) + n) * SIM_ROWB;
       // Past the last step the loads repeat the current step into a slot nobody reads any more:
       // cheaper than branches around every load, which would also split the schedule below.
-      const bool do_a = s + SIM_NA - 1 < steps;
-      const char* gb = step_base(s + 1 < steps ? s + 1 : s);
-      const char* ga = step_base(do_a ? s + SIM_NA - 1 : s);
-      const uint32_t db = ldsB_addr + ((s + 1) & 1) * BSTAGE + (8 * wave) * SIM_ROWB;
-      const uint32_t da = lds_addr + ((s + SIM_NA - 1) & (SIM_NA - 1)) * ASTAGE + (8 * wave) * SIM_ROWB;
+      const char* gb = step_base(s + NB - 1 < steps ? s + NB - 1 : s);
+      const char* ga = step_base(s + NA - 1 < steps ? s + NA - 1 : s);
+      const uint32_t db = ldsB_addr + (sb_ == 0 ? NB - 1 : sb_ - 1) * BSTAGE + (8 * wave) * SIM_ROWB;
+      const uint32_t da = lds_addr + (sa == 0 ? NA - 1 : sa - 1) * ASTAGE + (8 * wave) * SIM_ROWB;
+      sa = sa + 1 == NA ? 0 : sa + 1;
+      sb_ = sb_ + 1 == NB ? 0 : sb_ + 1;
       auto load_unit = [&](int u) {      // the u-th load of this step, if there is one
         if (u < PB) load_to_lds16(gb, offb[u < PB ? u : 0], db + u * 32 * SIM_ROWB);
         else if (u < PB + PA) load_to_lds16(ga, offa[u < PB + PA ? u - PB : 0], da + (u - PB) * 32 * SIM_ROWB);
@@ -239,7 +263,7 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
           for (int u = 2 * NT; u < NT + 2; ++u) load_op((kk + 1) & 1, kk + 1, u);     // NT == 1 only
         }
       }
-      wait_vmem_but<PA>();
+      wait_vmem_but<PA + (NB - 2) * (PA + PB)>();
       barrier_keep_loads();
     }
 
@@ -387,7 +411,7 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
                                 int M, const int32_t* kept, const float* s_hat, int32_t* assign, float* best_sim,
                                 char* ws, hipStream_t st, Timer* tm) {
   constexpr int BN = 64 * NT;
-  const size_t lds = (size_t)(SIM_NA * SIM_BM + 2 * BN) * SIM_ROWB + sizeof(float) * (6 * SIM_BM + BN);
+  const size_t lds = (size_t)(sim_na(NT) * SIM_BM + sim_nb(NT) * BN) * SIM_ROWB + sizeof(float) * (6 * SIM_BM + BN);
   auto kern = k_sim<T, NT, ANCHORED>;
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -396,13 +420,16 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
   }
   const int mtiles = (M + SIM_BM - 1) / SIM_BM;
   const int ptiles = (p.k + BN - 1) / BN;
-  const int groups = (p.B + NUM_XCD - 1) / NUM_XCD;
+  const int spread = p.B >= NUM_XCD ? 1 : NUM_XCD / p.B;      // XCDs that share one image's source tiles
+  const int vmt = (mtiles + spread - 1) / spread;
+  const int groups = (p.B * spread + NUM_XCD - 1) / NUM_XCD;
   const int n = p.B * M;
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(ws);
   float* norms = reinterpret_cast<float*>(ws + align256(sizeof(unsigned long long) * (size_t)p.B * (p.V - p.k > p.k ? p.V - p.k : p.k)));
   if (ptiles > 1) ASAP_LAUNCH(tm, "k_sim_clear", k_sim_clear, dim3((n + 255) / 256), dim3(256), 0, st, keys, n);
-  ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * mtiles * ptiles), dim3(256), lds, st, xv, sb, sr, p.D, srcs,
-              kept, s_hat, p.V, p.B, M, p.k, mtiles, ptiles, p.sim_threshold, assign, best_sim, keys, norms);
+  ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * vmt * ptiles), dim3(256), lds, st, xv, sb, sr, p.D, srcs,
+              kept, s_hat, p.V, p.B, M, p.k, mtiles, ptiles, spread, vmt, p.sim_threshold, assign, best_sim, keys,
+              norms);
   if (ptiles > 1)
     ASAP_LAUNCH(tm, "k_sim_finish", k_sim_finish, dim3((n + 255) / 256), dim3(256), 0, st, keys, norms, n,
                 p.sim_threshold, assign, best_sim);
