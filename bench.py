@@ -105,10 +105,10 @@ def bench_attention(args, cfg):
     (bias, transpose, attention) per step.  Flops = 4 d per (query, key) pair the mask lets through."""
     import numpy as np
     import torch
-    from paper_2603_14549_amd import binding, synth
+    from paper_2603_14549_amd import binding, harness, synth
     inp = synth.make_inputs(cfg, with_kv=False)
     ctx = binding.Context(0)
-    stage = binding.DeviceStage(inp, ctx=ctx)
+    stage = harness.DeviceStage(inp, ctx=ctx)
     buf = stage.run()
     vals = torch.randn(cfg.B, cfg.Hkv, cfg.N, cfg.d, device="cuda").to(stage.q.dtype)
     out = torch.empty(cfg.B, cfg.H, cfg.N, cfg.d, dtype=stage.q.dtype, device="cuda")
@@ -176,7 +176,7 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2603_14549_amd import binding, synth
+    from paper_2603_14549_amd import binding, harness, synth
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     binding.load()
@@ -193,7 +193,7 @@ def main():
     if args.lse_extra:
         lse_extra = np.random.default_rng(cfg.seed + 1000).normal(2.0, 2.0, size=(cfg.B, cfg.H, cfg.Tmax)) \
             .astype(np.float32)
-    stage = binding.DeviceStage(inp, ctx=ctx, lse_extra=lse_extra, page_size=args.paged_kv or None, **overrides)
+    stage = harness.DeviceStage(inp, ctx=ctx, lse_extra=lse_extra, page_size=args.paged_kv or None, **overrides)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):

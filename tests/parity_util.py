@@ -21,14 +21,14 @@ import numpy as np
 import torch
 
 from oracle import asap_oracle as O
-from paper_2603_14549_amd import binding, synth
+from paper_2603_14549_amd import binding, harness, synth
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 TIE_REL = 1e-6
 ROUTE_GAP = 1e-5
 
 
-to_device = binding.to_device
+to_device = harness.to_device
 
 
 def from_device(t: torch.Tensor) -> np.ndarray:
@@ -50,7 +50,7 @@ def raw_bits(t: torch.Tensor) -> np.ndarray:
     return t.numpy()
 
 
-GpuStage = binding.DeviceStage
+GpuStage = harness.DeviceStage
 
 
 def oracle_image(inp: dict, b: int, lambda_max=1.0, eps=1e-6, mask_on=True, mu=1.0, threshold=None,

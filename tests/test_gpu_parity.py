@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2603_14549_amd import binding, synth
+from paper_2603_14549_amd import binding, harness, synth
 import parity_util as U
 from oracle import asap_oracle as O
 
@@ -144,7 +144,7 @@ def test_positions_and_two_stream_stage(ctx):
     assert e.value.status == binding.ASAP_EUNSUPPORTED
     # asap_stage checks everything before it launches anything
     st = variants[1]
-    bad = binding.stage_io(st.p, st.q, st.k, st.hidden, st.text_len, st.k_cache, st.v_cache, st.buf)
+    bad = harness.stage_io(st.p, st.q, st.k, st.hidden, st.text_len, st.k_cache, st.v_cache, st.buf)
     bad.out_hidden = bad.hidden                        # the merge's output aliasing its input
     st.buf.score.fill_(-7.0)
     torch.cuda.synchronize()
@@ -182,7 +182,7 @@ def test_paged_kv_compaction(ctx, name, page_size):
                 for n in range(N):
                     pool[src_table[b, n // ps], :, n % ps, :] = cache[b][:, n, :]
             pools_host.append(pool)
-            pools_dev.append(binding.to_device(pool, cfg.kv_dtype))
+            pools_dev.append(harness.to_device(pool, cfg.kv_dtype))
     kp, vp = pools_dev[0::2], pools_dev[1::2]
     ctx.asap_compact_kv_paged(st.p, kp, vp, kp, vp, ps, torch.from_numpy(src_table).cuda(),
                               torch.from_numpy(dst_table).cuda(), buf.pos_out, buf.new_len)
@@ -326,7 +326,7 @@ def test_attention_forward_under_the_bidirectional_mask(ctx, name, mask_mode, la
     buf = st.run()                                             # s_hat of this layer's q, k
     rng = np.random.default_rng(cfg.seed + 4242)
     vals = synth.quantise(rng.standard_normal((cfg.B, cfg.Hkv, cfg.N, cfg.d)).astype(np.float32), cfg.qk_dtype)
-    v_dev = binding.to_device(vals, cfg.qk_dtype)
+    v_dev = harness.to_device(vals, cfg.qk_dtype)
     out = torch.empty(cfg.B, cfg.H, cfg.N, cfg.d, dtype=st.q.dtype, device="cuda")
     ws = torch.empty(binding.asap_attention_workspace_bytes(st.p), dtype=torch.uint8, device="cuda")
     ctx.asap_attention(st.p, st.q, st.k, v_dev, buf.s_hat, out, ws)
@@ -353,7 +353,7 @@ def test_attention_forward_full_size_sampled_rows(ctx):
     buf = st.run()
     rng = np.random.default_rng(99)
     vals = synth.quantise(rng.standard_normal((cfg.B, cfg.Hkv, cfg.N, cfg.d)).astype(np.float32), cfg.qk_dtype)
-    v_dev = binding.to_device(vals, cfg.qk_dtype)
+    v_dev = harness.to_device(vals, cfg.qk_dtype)
     out = torch.empty(cfg.B, cfg.H, cfg.N, cfg.d, dtype=st.q.dtype, device="cuda")
     ws = torch.empty(binding.asap_attention_workspace_bytes(st.p), dtype=torch.uint8, device="cuda")
     ctx.asap_attention(st.p, st.q, st.k, v_dev, buf.s_hat, out, ws)
