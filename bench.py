@@ -274,6 +274,13 @@ def main():
                       "achieved": alg["stage"] / (ms_per_step * 1e-3) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                       "frac": alg["stage"] / (ms_per_step * 1e-3) / HBM_PEAK,
                       "sum_kernel_us": round(step_kernel_us, 1)}
+    # what the memory system really moved per step (counter runs of the default route): the keys are swept
+    # three times where the algorithmic figure counts them once
+    measured = MEASURED_TRAFFIC.get(cfg.name)
+    if measured and not paper and not args.paged_kv:
+        moved = sum(measured.get(name, 0.0) * n / args.steps for name, (_, n) in timing.items())
+        stage_roofline["traffic_MB"] = round(moved / 1e6, 1)
+        stage_roofline["traffic_frac"] = moved / (ms_per_step * 1e-3) / HBM_PEAK
 
     out = {
         "metric": "pruning-stage images/sec at %d visual tokens" % cfg.V,
