@@ -155,6 +155,41 @@ def test_positions_and_two_stream_stage(ctx):
     assert bool((st.buf.score == -7.0).all()), "a failed check must launch nothing"
 
 
+def test_stage_replayed_from_a_captured_graph(ctx):
+    """asap_stage records only kernels and event record / wait pairs, so it can be captured: every
+    replay, with eager stages and synchronisations in between, gives the eager stage's bits."""
+    cfg = synth.CONFIGS["S2"]
+    inp = synth.make_inputs(cfg)
+    st = U.GpuStage(inp, ctx=ctx)
+    assert st.two_streams
+    names = ("s_raw", "score", "kept_idx", "assign", "best_sim", "out_hidden", "pos_out", "new_len")
+    st.run()
+    ref = {n: getattr(st.buf, n).clone() for n in names}
+    ref_kv = [t.clone() for t in st.buf.k_dst + st.buf.v_dst]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        st.run_async()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            st.run_async()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for n in names:
+            getattr(st.buf, n).zero_()
+        for t in st.buf.k_dst + st.buf.v_dst:
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in names:
+            assert torch.equal(getattr(st.buf, n), ref[n]), f"replay {rep}: {n}"
+        for a, b in zip(st.buf.k_dst + st.buf.v_dst, ref_kv):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"replay {rep}: K/V rows"
+        st.run()                                   # eager work between the replays
+        assert torch.equal(st.buf.out_hidden.view(torch.uint8), ref["out_hidden"].view(torch.uint8))
+
+
 @pytest.mark.parametrize("name,page_size", [("S1", 16), ("S1", 7), ("S3", 1), ("S3", 64), ("S0", 256)])
 def test_paged_kv_compaction(ctx, name, page_size):
     """asap_compact_kv_paged against the oracle's paged gather, bit for bit over the WHOLE pool
