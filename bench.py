@@ -100,6 +100,42 @@ def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb", lse_ex
             "ms_per_image": 1e3 * t_total / done}
 
 
+def bench_library_gemm(args, cfg):
+    """Reference point, not part of the product: the vendor GEMM library (through torch.bmm) on the
+    similarity product's shape with dense, already gathered operands -- no row gather, no norms, no
+    arg-max -- and with torch's row arg-max added.  Says what fraction of the MFMA peak a plain GEMM of
+    this shape reaches on the same GPU."""
+    import torch
+    dt = torch.bfloat16 if cfg.h_dtype == "bf16" else torch.float32
+    M, K, N = cfg.V - cfg.k, cfg.D, cfg.k
+    a = torch.randn(cfg.B, M, K, device="cuda").to(dt)
+    b = torch.randn(cfg.B, N, K, device="cuda").to(dt)
+    big = torch.randn(8192, 8192, device="cuda").to(dt)
+
+    def timed(f):
+        for _ in range(args.warmup):
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps
+
+    flops = 2.0 * cfg.B * M * K * N
+    t_gemm = timed(lambda: torch.bmm(a, b.transpose(1, 2)))
+    t_argmax = timed(lambda: torch.bmm(a, b.transpose(1, 2)).max(dim=2))
+    t_big = timed(lambda: big @ big)
+    peak = MFMA_PEAK[cfg.h_dtype]
+    print(json.dumps({
+        "metric": "vendor-library GEMM on the similarity shape (reference)", "unit": "us", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "dtype": cfg.h_dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.B} x [{M} x {K}] x [{K} x {N}]"},
+        "bmm_us": 1e6 * t_gemm, "bmm_frac_of_mfma_peak": flops / t_gemm / peak,
+        "bmm_plus_row_argmax_us": 1e6 * t_argmax,
+        "gemm_8192_cubed_us": 1e6 * t_big, "gemm_8192_cubed_frac_of_mfma_peak": 2.0 * 8192 ** 3 / t_big / peak}))
+
+
 def bench_attention(args, cfg):
     """asap_attention on the workload's shapes: q, k from the generator, random values; one launch set
     (bias, transpose, attention) per step.  Flops = 4 d per (query, key) pair the mask lets through."""
@@ -158,6 +194,9 @@ def main():
     ap.add_argument("--attention", action="store_true",
                     help="measure asap_attention (one layer's forward under the Eq. 4-5 mask) on the workload's "
                          "shapes instead of the pruning stage; prints its own JSON line")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="reference point only: time the vendor GEMM library (torch.bmm) on the similarity "
+                         "product's shape with dense operands, and an 8192^3 GEMM; prints its own JSON line")
     ap.add_argument("--lse-extra", action="store_true",
                     help="full-row softmax timing path (Eq. 5 over the whole row): pass a seeded log-sum-exp of "
                          "every text row's non-visual logits, which the score kernels fold into the denominators")
@@ -183,6 +222,8 @@ def main():
     cfg = synth.CONFIGS[args.workload]
     if args.attention:
         return bench_attention(args, cfg)
+    if args.library_gemm:
+        return bench_library_gemm(args, cfg)
     t0 = time.perf_counter()
     inp = synth.make_inputs(cfg)
     gen_s = time.perf_counter() - t0
