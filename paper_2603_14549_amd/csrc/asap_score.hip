@@ -216,90 +216,99 @@ __global__ __launch_bounds__(256) void k_mass(const T* __restrict__ kv, Strides3
   publish_minmax(kmin, kmax, piece == 0, blk_mm, mmkey, b);
 }
 
-// ------------------------------------------------------------------------------------------
-// k_mass_mfma (bf16 keys): grid (ceil(V/32), B), MASS_NW waves.  A workgroup owns one
-// 32-key tile; wave w walks the kv heads g = w, w + MASS_NW, ...  The four bf16 pieces of qbar_g are rows
-// 0..3 of the MFMA A tile (rows 4..31 are zero), the keys are the B tile, so lane n (< 32) finds
-// the four partial dot products of key n in its first four accumulator registers.
-// CH = 16-byte chunks of a row per lane half (d = 16*CH).
-// ------------------------------------------------------------------------------------------
+// One key of a 32-key tile per lane pair in the matrix-core operand layout: lane (n, hf) takes the
+// 16-byte pieces 2c + hf (c < CH) of key n.  CH = 16-byte chunks of a row per lane half (d = 16*CH).
 template <int CH>
 __device__ __forceinline__ void load_key_tile(uint4 (&kb)[CH], const char* krow) {
 #pragma unroll
   for (int c = 0; c < CH; ++c) kb[c] = ldg16(krow + c * 32);
 }
 
-constexpr int MASS_TILES_PER_WG = 1;   // key tiles a workgroup takes one after the other
-#ifndef MASS_WAVES
-#define MASS_WAVES 4
-#endif
-// Waves per workgroup, which share the kv heads of the tile.  Measured at 2304 keys x 16 images x 32 heads:
-// 66.6 / 66.2 / 63.8 us with 4 / 2 / 1 waves, so the launch is not short of residency; four keep the
-// chain of dependent loads per wave short when a batch has few tiles.
-constexpr int MASS_NW = MASS_WAVES;
-
+// ------------------------------------------------------------------------------------------
+// k_mass_mfma (bf16 keys): grid (ceil(V/32), B), 256 threads = 4 waves.  A workgroup owns one
+// 32-key tile; wave w walks the kv heads g = w, w + 4, ...  The four bf16 pieces of qbar_g are rows
+// 0..3 of the MFMA A tile (rows 4..31 are zero), the keys are the B tile, so lane n (< 32) finds
+// the four partial dot products of key n in its first four accumulator registers.
+// The tile of a head is an isolated 8 KiB piece of memory, and reading such pieces in the operand
+// pattern (32 rows x 32 bytes per instruction) was measured at 4.2 TB/s against 6.0 TB/s for whole
+// rows.  So a wave reads whole rows (2 CH consecutive lanes per row) and turns the tile into the
+// operand layout through an LDS buffer of its own -- written and read by the same wave, in order, so
+// no barrier is involved.  CH = 16-byte chunks of a row per lane half (d = 16 CH).
+// ------------------------------------------------------------------------------------------
 template <int CH>
-__global__ __launch_bounds__(64 * MASS_NW) void k_mass_mfma(const bf16_t* __restrict__ kv, Strides3 sk,
+__global__ __launch_bounds__(256) void k_mass_mfma(const bf16_t* __restrict__ kv, Strides3 sk,
                                                     const uint16_t* __restrict__ qsplit, int Hkv, int V,
                                                     double scale, double* __restrict__ s64, float* __restrict__ s_raw,
                                                     unsigned long long* __restrict__ mmkey) {
-  constexpr int D = CH * 16;
-  __shared__ double part[MASS_NW][32];
+  constexpr int D = CH * 16, RB = 32 * CH;          // row bytes
+  constexpr int LPR = 2 * CH, RPI = 64 / LPR;        // lanes per row, rows per load instruction
+  __shared__ __align__(16) char stage[4][32 * RB];
+  __shared__ double part[4][32];
   __shared__ unsigned long long blk_mm[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hf = lane >> 5;
-  const int b = blockIdx.y;
+  const int piece = lane % LPR, r0 = lane / LPR;
+  const int b = blockIdx.y, j0 = blockIdx.x * 32;
   if (tid == 0) { blk_mm[0] = ~0ull; blk_mm[1] = 0ull; }
   const int64_t headb = sk.h * 2;
+  // LDS: the 16-byte piece p of row r sits in slot p ^ x(r): whole-row writes and operand reads of 16
+  // consecutive rows both cover all banks
+  auto swz = [](int row) { return RB <= 128 ? (row >> 1) & 7 : row & 15; };
+  char* st = stage[wave];
+  uint32_t roff[CH];          // byte offsets inside one head of one image (< 4 GiB)
+  int wr[CH];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int row = r0 + RPI * i;
+    roff[i] = (uint32_t)(min(j0 + row, V - 1) * (int)sk.r * 2 + piece * 16);
+    wr[i] = row * RB + ((piece ^ swz(row)) << 4);
+  }
+  // operand read c: piece (2c + hf) ^ x(n) of row n = rd0 ^ 32 c (the row offset has no low bits set)
+  const int rd0 = n * RB + ((hf ^ swz(n)) << 4);
+  const char* kbase = reinterpret_cast<const char*>(kv + b * sk.b);
   // lane (m, hf) with m < 4 supplies piece m of qbar_g, half hf of the components
   const char* qbase = reinterpret_cast<const char*>(qsplit + ((int64_t)b * Hkv * 4 + (n & 3)) * D) + hf * 16;
   const int64_t qheadb = (int64_t)4 * D * 2;
   const bool has_q = n < 4;
+  uint4 qa[CH], kb[CH], kn[CH];
+#pragma unroll
+  for (int c = 0; c < CH; ++c) qa[c] = make_uint4(0, 0, 0, 0);
+  int g = wave;
+  if (g < Hkv) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) kb[i] = ldg16(kbase + g * headb + roff[i]);
+    if (has_q) load_key_tile<CH>(qa, qbase + g * qheadb);
+  }
+  double sum = 0.0;
+  for (; g < Hkv; g += 4) {
+    const int gn = g + 4;
+    if (gn < Hkv) {
+#pragma unroll
+      for (int i = 0; i < CH; ++i) kn[i] = ldg16(kbase + gn * headb + roff[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < CH; ++i) *reinterpret_cast<uint4*>(st + wr[i]) = kb[i];
+    f32x16_t acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) mma32<bf16_t>(acc, qa[c], *reinterpret_cast<const uint4*>(st + (rd0 ^ (32 * c))));
+    sum += ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);   // rows 0..3 (lanes < 32)
+    if (gn < Hkv) {
+      if (has_q) load_key_tile<CH>(qa, qbase + gn * qheadb);      // small, cached: not worth registers of its own
+#pragma unroll
+      for (int i = 0; i < CH; ++i) kb[i] = kn[i];
+    }
+  }
+  if (hf == 0) part[wave][n] = sum;
+  __syncthreads();
   unsigned long long kmin = ~0ull, kmax = 0ull;
-  for (int tt = 0; tt < MASS_TILES_PER_WG; ++tt) {
-    const int tile = blockIdx.x * MASS_TILES_PER_WG + tt;
-    if (tile * 32 >= V) break;
-    const int j = tile * 32 + n;
-    const char* kbase =
-        reinterpret_cast<const char*>(kv + b * sk.b) + (int64_t)min(j, V - 1) * sk.r * 2 + hf * 16;
-    uint4 qa[CH], kb[CH], kn[CH];
-#pragma unroll
-    for (int c = 0; c < CH; ++c) qa[c] = make_uint4(0, 0, 0, 0);
-    int g = wave;
-    if (g < Hkv) {
-      load_key_tile<CH>(kb, kbase + g * headb);
-      if (has_q) load_key_tile<CH>(qa, qbase + g * qheadb);
-    }
-    double sum = 0.0;
-    for (; g < Hkv; g += MASS_NW) {
-      const int gn = g + MASS_NW;
-      if (gn < Hkv) load_key_tile<CH>(kn, kbase + gn * headb);
-      f32x16_t acc;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-#pragma unroll
-      for (int c = 0; c < CH; ++c) mma32<bf16_t>(acc, qa[c], kb[c]);
-      sum += ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);   // rows 0..3 (lanes < 32)
-      if (gn < Hkv) {
-        if (has_q) load_key_tile<CH>(qa, qbase + gn * qheadb);      // small, cached: not worth registers of its own
-#pragma unroll
-        for (int c = 0; c < CH; ++c) kb[c] = kn[c];
-      }
-    }
-    if (tt) __syncthreads();            // the previous tile's sums have been read
-    if (hf == 0) part[wave][n] = sum;
-    __syncthreads();
-    if (tid < 32 && j < V) {
-      double s = part[0][n];
-#pragma unroll
-      for (int w = 1; w < MASS_NW; ++w) s += part[w][n];      // fixed order
-      s *= scale;
-      s64[(int64_t)b * V + j] = s;
-      s_raw[(int64_t)b * V + j] = (float)s;
-      const unsigned long long key = f64_key(s);
-      kmin = key < kmin ? key : kmin;
-      kmax = key > kmax ? key : kmax;
-    }
+  const int j = j0 + n;
+  if (tid < 32 && j < V) {
+    const double s = (((part[0][n] + part[1][n]) + part[2][n]) + part[3][n]) * scale;
+    s64[(int64_t)b * V + j] = s;
+    s_raw[(int64_t)b * V + j] = (float)s;
+    kmin = kmax = f64_key(s);
   }
   publish_minmax(kmin, kmax, tid < 32, blk_mm, mmkey, b);
 }
@@ -689,10 +698,10 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   if constexpr (E == 8) {
     const bf16_t* kp = static_cast<const bf16_t*>(k_vis);
     if (ch == 8)
-      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<8>, dim3((ktiles + MASS_TILES_PER_WG - 1) / MASS_TILES_PER_WG, p.B), dim3(64 * MASS_NW), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
+      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<8>, dim3(ktiles, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
                   s64, s_raw, mmkey);
     else
-      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<4>, dim3((ktiles + MASS_TILES_PER_WG - 1) / MASS_TILES_PER_WG, p.B), dim3(64 * MASS_NW), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
+      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<4>, dim3(ktiles, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
                   s64, s_raw, mmkey);
   } else {
     ASAP_LAUNCH(tm, "k_mass", k_mass<T>, dim3(ktiles, p.B), dim3(256), sizeof(double) * p.Hkv * p.d, st,
