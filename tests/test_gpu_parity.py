@@ -378,6 +378,34 @@ def test_attention_forward_under_the_bidirectional_mask(ctx, name, mask_mode, la
             U.check_rows(got[h], ref[h], tol, f"attention output image {b} head {h}")
 
 
+def test_attention_argument_checks_and_strided_inputs(ctx):
+    """asap_attention refuses a short workspace, a missing s_hat and an unaligned pointer before it
+    launches anything, and takes q / k / v as strided views (here: slices of wider buffers)."""
+    cfg = synth.CONFIGS["S2"]
+    inp = synth.make_inputs(cfg, with_kv=False)
+    st = U.GpuStage(inp, ctx=ctx)
+    buf = st.run()
+    v = torch.randn(cfg.B, cfg.Hkv, cfg.N, cfg.d, device="cuda").to(st.q.dtype)
+    out = torch.full((cfg.B, cfg.H, cfg.N, cfg.d), 3.0, dtype=st.q.dtype, device="cuda")
+    ws = torch.empty(binding.asap_attention_workspace_bytes(st.p), dtype=torch.uint8, device="cuda")
+    off_by_one = torch.empty(st.q.numel() + 8, dtype=st.q.dtype, device="cuda")[1:1 + st.q.numel()].view(st.q.shape)
+    for bad in (lambda: ctx.asap_attention(st.p, st.q, st.k, v, buf.s_hat, out, ws[:256]),
+                lambda: ctx.asap_attention(st.p, st.q, st.k, v, None, out, ws),
+                lambda: ctx.asap_attention(st.p, off_by_one, st.k, v, buf.s_hat, out, ws)):
+        with pytest.raises(binding.AsapError) as e:
+            bad()
+        assert e.value.status in (binding.ASAP_EINVAL, binding.ASAP_EWORKSPACE)
+    torch.cuda.synchronize()
+    assert bool((out == 3.0).all()), "a failed check must launch nothing"
+    ctx.asap_attention(st.p, st.q, st.k, v, buf.s_hat, out, ws)
+    # the same tensors as the leading d columns of buffers twice as wide
+    wide = lambda t: torch.cat([t, torch.full_like(t, 9.0)], dim=-1)[..., :cfg.d]
+    out2 = torch.empty_like(out)
+    ctx.asap_attention(st.p, wide(st.q), wide(st.k), wide(v), buf.s_hat, out2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.uint8), out2.view(torch.uint8))
+
+
 def test_attention_forward_full_size_sampled_rows(ctx):
     """asap_attention at the benchmark shape (config 2: N = 2403, 32 heads, bf16) in the launch
     configuration bench.py --attention times; sampled (head, row) outputs against the row's softmax
