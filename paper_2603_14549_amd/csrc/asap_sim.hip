@@ -22,12 +22,10 @@
 //                 ids with the same id % 8 -- they then share that XCD's L2 for the kept panel
 //                 (batches of fewer than 8 images spread an image over several XCDs instead).
 //                 A workgroup takes one destination tile.  When the destination rows need several
-//                 (k > 64*NT), the tiles of a source tile are workgroups of their own: each folds its
-//                 row winner into a 64-bit key (order-preserving value bits, then the inverted
-//                 column so that equal values keep the smaller column) with an integer atomic max
-//                 in global memory -- exact and order-independent.
-//   k_sim_clear   zeroes those keys (only launched when there are several destination tiles)
-//   k_sim_finish  winner key -> assign, best_sim (threshold and source norm applied here)
+//                 (k > 64*NT), the tiles of a source tile are workgroups of their own: each leaves
+//                 its row winner as a 64-bit key (order-preserving value bits, then the inverted
+//                 column so that equal values keep the smaller column) in a slot of its own.
+//   k_sim_finish  largest key of a row -> assign, best_sim (threshold and source norm applied here)
 #include "asap_device.hpp"
 #include "asap_launch.hpp"
 #include "asap_select.hpp"
@@ -367,28 +365,28 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
       best_sim[o] = c;
       assign[o] = (c > threshold) ? run_c : -1;
     } else {
-      // several destination tiles per source row: the best (value, then smaller column) wins an
-      // integer max in global memory; k_sim_finish turns the winner into assign / best_sim
+      // several destination tiles per source row: every tile leaves its best as a 64-bit key (value,
+      // then the inverted column so that equal values keep the smaller column); k_sim_finish takes the
+      // largest key of a row and turns it into assign / best_sim
       const unsigned long long key = ((unsigned long long)float_key(run_v) << 32) | (0xFFFFFFFFu - (uint32_t)run_c);
-      atomicMax(&best_key[o], key);
+      best_key[(int64_t)pass * ((int64_t)B * M) + o] = key;
       if (pass == 0) src_norm2[o] = norm2[tid];
     }
   }
 }
 
-// grid (ceil(n / 256)): clears the arg-max keys (0 is below the key of every value, -inf included)
-__global__ __launch_bounds__(256) void k_sim_clear(unsigned long long* __restrict__ best_key, int n) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < n) best_key[i] = 0ull;
-}
-
-// grid (ceil(n / 256)): winner of the destination tiles -> assign, best_sim
+// grid (ceil(n / 256)): the largest key over the destination tiles of a row -> assign, best_sim
 __global__ __launch_bounds__(256) void k_sim_finish(const unsigned long long* __restrict__ best_key,
-                                                     const float* __restrict__ src_norm2, int n, float threshold,
-                                                     int32_t* __restrict__ assign, float* __restrict__ best_sim) {
+                                                     const float* __restrict__ src_norm2, int n, int ptiles,
+                                                     float threshold, int32_t* __restrict__ assign,
+                                                     float* __restrict__ best_sim) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
-  const unsigned long long key = best_key[i];
+  unsigned long long key = best_key[i];
+  for (int t = 1; t < ptiles; ++t) {
+    const unsigned long long other = best_key[(int64_t)t * n + i];
+    key = other > key ? other : key;
+  }
   const float v = float_unkey((uint32_t)(key >> 32));
   const int col = (int)(0xFFFFFFFFu - (uint32_t)key);
   const float c = v / fmaxf(sqrtf(src_norm2[i]), 1e-8f);
@@ -399,11 +397,20 @@ __global__ __launch_bounds__(256) void k_sim_finish(const unsigned long long* __
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
-// arg-max keys and source norms for up to max(k, V-k) source rows per image (used when the
-// destination rows are split over several workgroups)
+static int pick_nt(const asap_params& p, int M);
+
+// One key per destination tile and source row, and the source norms, for either kind of search
+// (pruned -> kept: V-k source rows; inside the kept set: k), when the destination rows are split
+// over several workgroups.
+static size_t sim_workspace_for(const asap_params& p, int M) {
+  if (M <= 0) return 0;
+  const int bn = 64 * pick_nt(p, M), ptiles = (p.k + bn - 1) / bn;
+  const size_t rows = (size_t)p.B * M;
+  return align256(sizeof(unsigned long long) * rows * ptiles) + align256(sizeof(float) * rows);
+}
 size_t sim_workspace_bytes(const asap_params& p) {
-  const size_t m = (size_t)p.B * (p.V - p.k > p.k ? p.V - p.k : p.k);
-  return align256(sizeof(unsigned long long) * m) + align256(sizeof(float) * m);
+  const size_t a = sim_workspace_for(p, p.V - p.k), b = sim_workspace_for(p, p.k);
+  return a > b ? a : b;
 }
 
 template <typename T, int NT, bool ANCHORED>
@@ -424,14 +431,13 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
   const int vmt = (mtiles + spread - 1) / spread;
   const int groups = (p.B * spread + NUM_XCD - 1) / NUM_XCD;
   const int n = p.B * M;
-  unsigned long long* keys = reinterpret_cast<unsigned long long*>(ws);
-  float* norms = reinterpret_cast<float*>(ws + align256(sizeof(unsigned long long) * (size_t)p.B * (p.V - p.k > p.k ? p.V - p.k : p.k)));
-  if (ptiles > 1) ASAP_LAUNCH(tm, "k_sim_clear", k_sim_clear, dim3((n + 255) / 256), dim3(256), 0, st, keys, n);
+  unsigned long long* keys = reinterpret_cast<unsigned long long*>(ws);               // [ptiles][B*M]
+  float* norms = reinterpret_cast<float*>(ws + align256(sizeof(unsigned long long) * (size_t)n * ptiles));
   ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * vmt * ptiles), dim3(256), lds, st, xv, sb, sr, p.D, srcs,
               kept, s_hat, p.V, p.B, M, p.k, mtiles, ptiles, spread, vmt, p.sim_threshold, assign, best_sim, keys,
               norms);
   if (ptiles > 1)
-    ASAP_LAUNCH(tm, "k_sim_finish", k_sim_finish, dim3((n + 255) / 256), dim3(256), 0, st, keys, norms, n,
+    ASAP_LAUNCH(tm, "k_sim_finish", k_sim_finish, dim3((n + 255) / 256), dim3(256), 0, st, keys, norms, n, ptiles,
                 p.sim_threshold, assign, best_sim);
   return hipGetLastError();
 }
