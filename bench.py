@@ -34,8 +34,8 @@ MFMA_PEAK = {"bf16": 2.5e15, "f32": 157.3e12}
 # (see profiles/); keyed by workload then kernel.  None = not measured for that workload.
 MEASURED_TRAFFIC = {
     # profiles/bench_C6_hbm_traffic.txt (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0, from the 1 GiB copy)
-    "C6": {"k_qsum": 303.6e6, "k_mass": 307.2e6, "k_attn_stats": 320.5e6, "k_attn_colsum": 325.3e6,
-           "k_score": 5.4e6, "k_select": 0.5e6, "k_sim": 312.9e6, "k_merge": 386.9e6, "k_compact": 439.6e6},
+    "C6": {"k_qsum": 303.6e6, "k_mass": 307.2e6, "k_attn_stats": 313.1e6, "k_attn_colsum": 315.4e6,
+           "k_score": 5.4e6, "k_select": 0.5e6, "k_sim": 312.9e6, "k_merge": 387.1e6, "k_compact": 439.6e6},
 }
 
 

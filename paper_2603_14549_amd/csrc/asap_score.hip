@@ -605,14 +605,31 @@ __global__ __launch_bounds__(256) void k_score(const float* __restrict__ upart, 
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+// Key-range splits of the two text-row sweeps.  Their workgroups run in rounds of as many as fit
+// on the chip at once (1 to 4 per compute unit, by the registers of the instantiation); a round
+// costs the tiles of one split plus a fixed part (start-up, the text queries, the last tiles' tail:
+// about 8 tile times, fitted to measurements), and more than one workgroup per compute unit at a
+// time slows each of them (about 1.4x).  The count with the least modelled time wins, fewer splits
+// on ties; a split has at least 4 tiles (one per wave).
 static int attn_splits(const asap_params& p) {
   const int ntiles = (p.V + 31) / 32;
-  int s = (1024 + p.H * p.B - 1) / (p.H * p.B);
-  int smax = ntiles / 8;
-  if (s > smax) s = smax;
-  if (s > 16) s = 16;
-  if (s < 1) s = 1;
-  return s;
+  const int rb = (p.Tmax + 31) / 32, ch = p.d / (p.qk_dtype == ASAP_BF16 ? 16 : 8);
+  const int per_cu = rb * ch <= 4 ? 4 : (rb * ch <= 8 && ch == 8) ? 3 : (rb * ch <= 16 && ch <= 8) ? 2 : 1;
+  const long slots = 256L * per_cu, groups = (long)p.H * p.B;
+  int smax = ntiles / 4;
+  if (smax > 16) smax = 16;
+  if (smax < 1) smax = 1;
+  int best = 1;
+  double best_cost = -1.0;
+  for (int s = 1; s <= smax; ++s) {
+    const int tps = (ntiles + s - 1) / s;
+    if ((ntiles + tps - 1) / tps != s) continue;           // the same split length with fewer splits exists
+    const long wgs = groups * s, rounds = (wgs + slots - 1) / slots;
+    const double crowd = (wgs < slots ? wgs : slots) <= 256 ? 1.0 : 1.4;
+    const double cost = (double)rounds * (tps + 8) * crowd;
+    if (best_cost < 0.0 || cost < best_cost) { best_cost = cost; best = s; }
+  }
+  return best;
 }
 
 ScoreWorkspace score_workspace(const asap_params& p) {

@@ -72,12 +72,12 @@ def test_k_equal_v_and_infinite_threshold_are_legal(lib):
 
 def test_workspace_size_formula(lib):
     # query sums + per-kv-head sums + fp64 mass + min/max keys + per-split row statistics
-    # + per-head column sums (C6: one query chunk, two key splits, 64 text rows)
+    # + per-head column sums (C6: one query chunk, one key split, 64 text rows)
     p = good()
     B, H, Hkv, d, V = p.B, p.H, p.Hkv, p.d, p.V
     al = lambda x: (x + 255) // 256 * 256
     want = (al(8 * B * H * 1 * d) + al(8 * B * Hkv * d) + al(2 * B * Hkv * 4 * d) + al(8 * B * V) + al(16 * B)
-            + al(4 * B * H * 2 * 2 * 64) + al(4 * B * H * V))
+            + al(4 * B * H * 1 * 2 * 64) + al(4 * B * H * V))
     assert binding.asap_workspace_bytes(p) == want
     assert want >= al(4 * B * p.k)          # also covers the kept-row norms of asap_merge
 
