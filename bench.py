@@ -185,8 +185,8 @@ def bench_attention(args, cfg):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C6")
     ap.add_argument("--route", choices=["absorb", "paper"], default="absorb",
                     help="absorb (default, the headline workload): pruned -> kept routing; paper: Sec. 4.2 as "
