@@ -283,13 +283,22 @@ def gather_kv_paged(src_pool: np.ndarray, src_pages: np.ndarray, dst_pool: np.nd
 def stage(Q: np.ndarray, K: np.ndarray, X: np.ndarray, text_len: int, P: int, V: int, Tmax: int,
           k: int, lambda_max: float = 1.0, eps: float = EPS_DEFAULT, mask_on: bool = True,
           mu: float = 1.0, threshold: Optional[float] = None, route: str = "absorb",
-          lse_extra: Optional[np.ndarray] = None, linear_mass: bool = False) -> dict:
-    """All steps for one image.  Q [H,N,d], K [Hkv,N,d], X [N,D], N = P+V+Tmax."""
+          lse_extra: Optional[np.ndarray] = None, linear_mass: bool = False,
+          score_rows: str = "all") -> dict:
+    """All steps for one image.  Q [H,N,d], K [Hkv,N,d], X [N,D], N = P+V+Tmax.
+
+    score_rows: which text rows rank the visual tokens (Sec. 4.1 does not say): "all" = the mean
+    over every valid text row; "last" = the last valid text token's row alone, the criterion of the
+    attention-score pruning the paper's ablation starts from (Sec. 5.3)."""
     Qv, Kv, Qt = Q[:, P:P + V], K[:, P:P + V], Q[:, P + V:]
     s = attention_mass_linear(Qv, Kv) if linear_mass else attention_mass(Qv, Kv)
     s_hat = salience(s, eps)
     bias = mask_log_discount(s_hat, lambda_max, eps, mask_on)
-    A = text_visual_attention(Qt, Kv, bias, text_len, lse_extra)
+    if score_rows == "last":
+        last = slice(text_len - 1, text_len)
+        A = text_visual_attention(Qt[:, last], Kv, bias, 1, None if lse_extra is None else lse_extra[:, last])
+    else:
+        A = text_visual_attention(Qt, Kv, bias, text_len, lse_extra)
     r = selection_score(A)
     kept, pruned = select_topk(r, k)
     Xv = X[P:P + V]

@@ -205,6 +205,25 @@ def test_text_rows_against_full_nxn_attention(P, V, T):
     np.testing.assert_allclose(A_r, ref / ref.sum(axis=2, keepdims=True), rtol=1e-11)
 
 
+def test_last_token_score_is_the_last_text_row_of_the_full_attention():
+    """score_rows="last": the ranking is the last valid text row of the full N x N attention
+    (brute force), renormalised over the image span and averaged over heads -- not the mean over
+    all text rows, and not a padded row."""
+    H, Hkv, d, P, V, T, text_len, D = 4, 2, 8, 2, 9, 4, 3, 6
+    N = P + V + T
+    Q, K = tiny_qk(31, H, Hkv, N, d)
+    X = np.random.default_rng(5).normal(size=(N, D))
+    out = O.stage(Q, K, X, text_len, P, V, T, k=4, mask_on=False, mu=0.0, score_rows="last")
+    A, _ = O.full_bidirectional_attention(Q, K, P, V, mask="causal")
+    row = A[:, P + V + text_len - 1, P:P + V]
+    r = (row / row.sum(axis=1, keepdims=True)).mean(axis=0)
+    np.testing.assert_allclose(out["score"], r, rtol=1e-11)
+    assert out["score"].sum() == pytest.approx(1.0, rel=1e-12)
+    every = O.stage(Q, K, X, text_len, P, V, T, k=4, mask_on=False, mu=0.0)
+    assert np.abs(every["score"] - out["score"]).max() > 1e-3
+    assert set(out["kept"]) == set(np.argsort(-r, kind="stable")[:4])
+
+
 def test_causal_reference_is_causal():
     Q, K = tiny_qk(20, 2, 2, 9, 4)
     A, _ = O.full_bidirectional_attention(Q, K, 2, 4, mask="causal")
