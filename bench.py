@@ -71,7 +71,8 @@ def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
     return {"per_kernel": per_kernel, "stage": stage, "sim_flops": 2.0 * B * (V - k) * k * D}
 
 
-def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb", lse_extra=None) -> dict:
+def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb", lse_extra=None,
+                 score_rows: str = "all") -> dict:
     """The oracle as it stands, timed on the host on the first few images of the batch."""
     import numpy as np
     from oracle import asap_oracle as O          # only this leg touches the oracle
@@ -88,7 +89,8 @@ def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb", lse_ex
         ref = O.stage(synth.to_f64(inp["q"][b], cfg.qk_dtype), synth.to_f64(inp["k"][b], cfg.qk_dtype),
                       synth.to_f64(inp["hidden"][b], cfg.h_dtype), int(inp["text_len"][b]), cfg.P, cfg.V,
                       cfg.Tmax, cfg.k, linear_mass=True, route=route,
-                      lse_extra=None if lse_extra is None else lse_extra[b].astype(np.float64))
+                      lse_extra=None if lse_extra is None else lse_extra[b].astype(np.float64),
+                      score_rows=score_rows)
         for l in range(cfg.L_kv):
             for cache in (inp["k_cache"][l], inp["v_cache"][l]):
                 O.gather_kv(cache[b], ref["pos_out"], ref["new_len"])
@@ -203,6 +205,8 @@ def main():
     ap.add_argument("--paged-kv", type=int, default=0, metavar="PAGE_SIZE",
                     help="keep the K/V caches as pools of PAGE_SIZE-token pages with block tables and compact them "
                          "with asap_compact_kv_paged (0 = contiguous caches, the headline workload)")
+    ap.add_argument("--last-token", action="store_true",
+                    help="rank the visual tokens by the last text token's row alone (scoring call with Tmax = 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (reference for HBM counters)")
@@ -234,7 +238,8 @@ def main():
     if args.lse_extra:
         lse_extra = np.random.default_rng(cfg.seed + 1000).normal(2.0, 2.0, size=(cfg.B, cfg.H, cfg.Tmax)) \
             .astype(np.float32)
-    stage = harness.DeviceStage(inp, ctx=ctx, lse_extra=lse_extra, page_size=args.paged_kv or None, **overrides)
+    stage = harness.DeviceStage(inp, ctx=ctx, lse_extra=lse_extra, page_size=args.paged_kv or None,
+                                last_token=args.last_token, **overrides)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -335,6 +340,7 @@ def main():
                                f"{cfg.L_kv} K/V layers, mask=keybias, route={args.route}"
                                f"{' (t=0.8)' if paper else ''}, mu=1"
                                f"{', softmax over the full row (lse_extra)' if args.lse_extra else ''}"
+                               f"{', ranked by the last text token' if args.last_token else ''}"
                                f"{f', K/V in pages of {args.paged_kv} tokens' if args.paged_kv else ''}",
                    "input_generation_s": round(gen_s, 1)},
         "roofline": roofline,
@@ -343,7 +349,8 @@ def main():
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(inp, cfg, route=args.route, lse_extra=lse_extra)
+        out["cpu_baseline"] = cpu_baseline(inp, cfg, route=args.route, lse_extra=lse_extra,
+                                           score_rows="last" if args.last_token else "all")
     print(json.dumps(out))
 
 

@@ -54,7 +54,8 @@ GpuStage = harness.DeviceStage
 
 
 def oracle_image(inp: dict, b: int, lambda_max=1.0, eps=1e-6, mask_on=True, mu=1.0, threshold=None,
-                 lse_extra: Optional[np.ndarray] = None, linear_mass: Optional[bool] = None) -> dict:
+                 lse_extra: Optional[np.ndarray] = None, linear_mass: Optional[bool] = None,
+                 score_rows: str = "all") -> dict:
     cfg = inp["cfg"]
     Q = synth.to_f64(inp["q"][b], cfg.qk_dtype)
     K = synth.to_f64(inp["k"][b], cfg.qk_dtype)
@@ -64,7 +65,7 @@ def oracle_image(inp: dict, b: int, lambda_max=1.0, eps=1e-6, mask_on=True, mu=1
     return O.stage(Q, K, X, int(inp["text_len"][b]), cfg.P, cfg.V, cfg.Tmax, cfg.k, lambda_max=lambda_max,
                    eps=eps, mask_on=mask_on, mu=mu, threshold=threshold,
                    lse_extra=None if lse_extra is None else lse_extra[b].astype(np.float64),
-                   linear_mass=linear_mass)
+                   linear_mass=linear_mass, score_rows=score_rows)
 
 
 def check_rows(got: np.ndarray, ref: np.ndarray, tol: float, what: str):
@@ -256,14 +257,14 @@ def compare_image_paper(inp: dict, buf, b: int, threshold: float, mu: float = 1.
 
 
 def run_and_compare(cfg, images: Optional[Sequence[int]] = None, lse=False, ctx=None, report=None,
-                    **param_overrides):
+                    last_token=False, **param_overrides):
     """Generate, run on the GPU, compare the chosen images (all by default)."""
     inp = synth.make_inputs(cfg)
     lse_extra = None
     if lse:
         rng = np.random.default_rng(cfg.seed + 77)
         lse_extra = rng.normal(2.0, 2.0, size=(cfg.B, cfg.H, cfg.Tmax)).astype(np.float32)
-    stage = GpuStage(inp, ctx=ctx, lse_extra=lse_extra, **param_overrides)
+    stage = GpuStage(inp, ctx=ctx, lse_extra=lse_extra, last_token=last_token, **param_overrides)
     buf = stage.run()
     mask_on = param_overrides.get("mask_mode", binding.ASAP_MASK_KEYBIAS) == binding.ASAP_MASK_KEYBIAS
     mu = param_overrides.get("merge_weight", 1.0)
@@ -272,6 +273,6 @@ def run_and_compare(cfg, images: Optional[Sequence[int]] = None, lse=False, ctx=
     eps = param_overrides.get("eps", 1e-6)
     for b in (range(cfg.B) if images is None else images):
         ref = oracle_image(inp, b, lambda_max=lam, eps=float(np.float32(eps)), mask_on=mask_on, mu=mu,
-                           threshold=thr, lse_extra=lse_extra)
+                           threshold=thr, lse_extra=lse_extra, score_rows="last" if last_token else "all")
         compare_image(inp, buf, b, ref, mu=mu, threshold=thr, report=report)
     return inp, stage

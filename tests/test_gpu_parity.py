@@ -45,6 +45,13 @@ def test_full_row_softmax_with_lse_extra(ctx):
     U.run_and_compare(synth.CONFIGS["S2"], ctx=ctx, lse=True)
 
 
+@pytest.mark.parametrize("name", ["S1", "S2", "S4"])
+def test_ranking_by_the_last_text_token(ctx, name):
+    """The scoring call with its own params (Tmax = 1), the gathered last valid query row per image
+    and a text length of one; selection, merge and compaction with the stage's params."""
+    U.run_and_compare(synth.CONFIGS[name], ctx=ctx, last_token=True)
+
+
 def test_reduction_to_plain_topk_pruning(ctx):
     """Mask off and merge weight 0: the output is a pure gather of the top-k rows."""
     cfg = synth.CONFIGS["S2"]
