@@ -77,6 +77,14 @@ def test_shape_edges(ctx, V, k, Tmax):
     U.run_and_compare(cfg, ctx=ctx)
 
 
+def test_maximum_visual_tokens(ctx):
+    """V = 16384, the largest image span the library takes: 512 key tiles in the sweeps, 16 items per
+    thread in the selection, 13 destination tiles per source row in the similarity search."""
+    cfg = dataclasses.replace(synth.CONFIGS["S2"], V=16384, k=4096, Tmax=64, B=1, D=256, H=4, Hkv=2, P=3,
+                              n_clusters=700, name="maxV")
+    U.run_and_compare(cfg, ctx=ctx)
+
+
 def test_f32_long_text_and_gqa_d64(ctx):
     cfg = dataclasses.replace(synth.CONFIGS["S0"], Tmax=128, V=150, k=40, H=8, Hkv=2, B=2, ragged_text=True,
                               text_lo=100, name="f32T128")
