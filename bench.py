@@ -262,6 +262,21 @@ def main():
     timing = ctx.asap_timing_collect()
     ctx.asap_timing_enable(0)
 
+    # third pass: every step bracketed by its own pair of events on the caller's stream (the stage ends
+    # with the second stream joined), for the spread; the pairs cost a few microseconds per step, which is
+    # why `value` comes from the unbracketed pass above
+    n_spread = min(args.steps, 200)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_spread + 1)]
+    marks[0].record()
+    for i in range(n_spread):
+        stage.run_async()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = np.sort(np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(n_spread)]))
+    step_spread = {"p10": float(per_step[int(0.1 * (n_spread - 1))]), "median": float(np.median(per_step)),
+                   "p90": float(per_step[int(0.9 * (n_spread - 1))]), "steps": n_spread,
+                   "note": "per-step event pairs on the caller's stream"}
+
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -344,6 +359,7 @@ def main():
                                f"{f', K/V in pages of {args.paged_kv} tokens' if args.paged_kv else ''}",
                    "input_generation_s": round(gen_s, 1)},
         "roofline": roofline,
+        "step_ms": step_spread,
         "stage_roofline": stage_roofline,
         "similarity_gemm": sim_roofline,
         "kernels": kernels,
