@@ -77,6 +77,14 @@ def test_shape_edges(ctx, V, k, Tmax):
     U.run_and_compare(cfg, ctx=ctx)
 
 
+@pytest.mark.parametrize("B", [3, 5, 7, 9, 17])
+def test_batch_sizes_that_do_not_divide_the_chip(ctx, B):
+    """The similarity search deals images (or parts of one image) to the eight XCDs; batch sizes that are
+    neither divisors nor multiples of eight leave ragged groups in that mapping."""
+    cfg = dataclasses.replace(synth.CONFIGS["S2"], B=B, V=300, k=70, name=f"batch{B}")
+    U.run_and_compare(cfg, ctx=ctx)
+
+
 def test_maximum_visual_tokens(ctx):
     """V = 16384, the largest image span the library takes: 512 key tiles in the sweeps, 16 items per
     thread in the selection, 13 destination tiles per source row in the similarity search."""
