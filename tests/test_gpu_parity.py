@@ -360,6 +360,15 @@ def test_paper_routing_shape_edges(ctx, V, k, clusters, threshold):
         U.compare_image_paper(inp, buf, b, threshold, 1.0)
 
 
+@pytest.mark.parametrize("B", [3, 11])
+def test_paper_routing_odd_batch_sizes(ctx, B):
+    cfg = dataclasses.replace(synth.CONFIGS["S2"], V=400, k=150, Tmax=9, B=B, n_clusters=12, name=f"paperB{B}")
+    inp = synth.make_inputs(cfg)
+    st = U.GpuStage(inp, ctx=ctx, route=binding.ASAP_ROUTE_PAPER, sim_threshold=0.8)
+    buf = st.run()
+    assert sum(U.compare_image_paper(inp, buf, b, 0.8, 1.0)["n_sources"] for b in range(cfg.B)) > 0
+
+
 def test_paper_routing_config2_and_config6_sample(ctx):
     for name, images in (("C2", [0]), ("C6", [0, 9])):
         cfg = synth.CONFIGS[name]
