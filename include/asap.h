@@ -111,6 +111,11 @@ size_t asap_workspace_bytes(const asap_params* p);
  * logits over its NON-visual keys (then A is the full-row softmax of Eq. 5); NULL drops that term.
  * Outputs s_raw, s_hat, score: [B,V] f32, contiguous.  Sums are carried in fp64 up to the
  * final rounding of s_raw / s_hat, and per-row softmax terms in fp32.
+ * Which text rows rank the visual tokens is the caller's choice of q_txt: Sec. 4.1 does not fix
+ * it and the mean over all valid rows is what the description above gives.  To rank by the
+ * last text token alone, pass that row of every image as a [B,H,1,d] q_txt, a text_len of
+ * ones, and a copy of the params with Tmax = 1 (this call only; the workspace must then
+ * satisfy asap_workspace_bytes() of both params).
  */
 asap_status asap_score(asap_ctx* ctx, const asap_params* p,
                        const void* q_vis, const int64_t q_vis_stride[3],
