@@ -277,6 +277,18 @@ def main():
                    "p90": float(per_step[int(0.9 * (n_spread - 1))]), "steps": n_spread,
                    "note": "per-step event pairs on the caller's stream"}
 
+    # fourth pass, only when the K/V compaction runs beside k_sim: a few steps on one stream with the
+    # per-kernel events on, for the duration of k_sim when nothing shares the memory system with it
+    sim_alone = None
+    if stage.two_streams and not stage.call_by_call:
+        n_alone = min(args.steps, 20)
+        ctx.asap_timing_enable(launches_per_step * n_alone)
+        for _ in range(n_alone):
+            ctx.asap_stage(stage.p, stage.io, False)
+        torch.cuda.synchronize()
+        sim_alone = ctx.asap_timing_collect().get("k_sim")
+        ctx.asap_timing_enable(0)
+
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -331,6 +343,11 @@ def main():
         sim_roofline = {"bound": "mfma", "achieved": alg["sim_flops"] / s_avg / 1e12,
                         "peak": MFMA_PEAK[cfg.h_dtype] / 1e12, "unit": "TFLOP/s",
                         "frac": alg["sim_flops"] / s_avg / MFMA_PEAK[cfg.h_dtype]}
+    if sim_roofline is not None and sim_alone:
+        a_avg = 1e-3 * sim_alone[0] / sim_alone[1]
+        sim_roofline["alone"] = {"avg_us": round(1e6 * a_avg, 2), "achieved": alg["sim_flops"] / a_avg / 1e12,
+                                 "frac": alg["sim_flops"] / a_avg / MFMA_PEAK[cfg.h_dtype],
+                                 "note": "same kernel in a single-stream run of the stage"}
     stage_roofline = {"bound": "hbm", "alg_MB": round(alg["stage"] / 1e6, 1),
                       "achieved": alg["stage"] / (ms_per_step * 1e-3) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                       "frac": alg["stage"] / (ms_per_step * 1e-3) / HBM_PEAK,
