@@ -291,8 +291,9 @@ asap_status asap_compact_kv_paged(asap_ctx* ctx, const asap_params* p, int32_t n
  * s_hat [B,V] f32 = the salience asap_score returns for this layer's q, k (NULL allowed with
  * ASAP_MASK_OFF); out [B,H,N,d] contiguous, qk_dtype.  Both contractions run on the matrix cores in
  * the input precision with fp32 accumulation; the probabilities are rounded to the input precision
- * before the second one.  The workspace (256-byte aligned) holds a transposed copy of v and the
- * per-key log discounts: asap_attention_workspace_bytes(p) bytes.
+ * before the second one.  The workspace (256-byte aligned) holds the per-key log discounts and,
+ * except for bf16 with d = 128 (whose values are read in place), a transposed copy of v:
+ * asap_attention_workspace_bytes(p) bytes.
  */
 size_t      asap_attention_workspace_bytes(const asap_params* p);
 asap_status asap_attention(asap_ctx* ctx, const asap_params* p,

@@ -9,7 +9,9 @@
 //                   and everywhere with the mask off)
 //   k_vtranspose    values transposed per (image, kv head) to [d, Npad]: the second contraction wants
 //                   its A operand (a row of values^T) contiguous along the keys, in the key order in
-//                   which the first contraction leaves P^T in the accumulators
+//                   which the first contraction leaves P^T in the accumulators.  Not needed for bf16
+//                   with d = 128: there the values go to LDS row-major and the operand is fetched
+//                   with the chip's transposing LDS read (ds_read_b64_tr_b16), two per operand.
 //   k_attention     grid (ceil(N/256), H, B), 512 threads = 8 waves (two per SIMD) of 32 queries.  Per
 //                   32-key tile a wave computes S^T = K_tile Q^T (keys are the tile rows, so lane l owns
 //                   query l % 32 and holds 16 of the tile's keys: the softmax bookkeeping is per lane),
@@ -112,6 +114,18 @@ template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* dst, const fl
       make_uint2(cvt_pk_bf16(f[0], f[1]), cvt_pk_bf16(f[2], f[3]));
 }
 
+// The transposing LDS read of gfx950 for 16-bit elements (ds_read_b64_tr_b16): every lane names 8
+// bytes; in each group of 16 lanes, lane 4 a + c receives the c-th 16-bit element of the pieces named
+// by lanes a, 4 + a, 8 + a and 12 + a, in that order.
+typedef short att_i16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint2 att_tr_read(const char* lds_ptr) {
+  const att_i16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) att_i16x4*)(uintptr_t)lds_address(lds_ptr));
+  uint2 u;
+  __builtin_memcpy(&u, &r, 8);
+  return u;
+}
+
 // key held in accumulator register v of a lane of half hf, relative to the tile
 __device__ __forceinline__ int att_key_of(int v, int hf) { return 8 * (v >> 2) + 4 * hf + (v & 3); }
 
@@ -152,6 +166,7 @@ template <typename T, int CH, int PD>
 __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__ q, Strides3 sq,
                                                             const T* __restrict__ k, Strides3 sk,
                                                             const T* __restrict__ vt, int Npad,
+                                                            const T* __restrict__ vrm, Strides3 sv,
                                                             const float* __restrict__ bias2, int bidir,
                                                             T* __restrict__ out, int H, int Hkv, int N, int P, int V,
                                                             float c2) {
@@ -167,6 +182,9 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
   constexpr int KLD = KTILE / 1024, VLD = VTILE / 1024;     // 1 KiB load instructions per tile
   constexpr int TP = KLD + VLD + 1;            // load instructions per tile: keys, values^T, discounts
   constexpr int NS = PD + 2;                   // ring slots: tile t (values, discounts), t+1 (keys), PD in flight
+  // 2-byte elements with d = 128: the values stay row-major, as the caller has them, and the second
+  // product's operand is fetched with the transposing LDS read of this chip (see att_tr_read)
+  constexpr bool TR = (E == 8 && CH == 8);
   extern __shared__ __align__(16) char lds[];
   const uint32_t lds_addr = lds_address(lds);
 
@@ -207,7 +225,9 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
   // every iteration issues the same number of loads and one wait count serves the whole loop.
   const char* kg = reinterpret_cast<const char*>(k + b * sk.b + g * sk.h);
   const int64_t krow_bytes = sk.r * (int64_t)sizeof(T);
-  const char* vg = reinterpret_cast<const char*>(vt + ((int64_t)b * Hkv + g) * D * Npad);
+  const char* vg = TR ? reinterpret_cast<const char*>(vrm + b * sv.b + g * sv.h)
+                      : reinterpret_cast<const char*>(vt + ((int64_t)b * Hkv + g) * D * Npad);
+  const int64_t vrow_bytes = sv.r * (int64_t)sizeof(T);
   const char* bg = reinterpret_cast<const char*>(bias2 + (int64_t)b * Npad);
   auto issue_tile = [&](int t) {
     const uint32_t st = lds_addr + (uint32_t)(t % NS) * STAGE;
@@ -222,10 +242,18 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
         load_to_lds16(kg, voff, st + pc * 1024);
       } else if (pc < KLD + VLD) {
         const int pv = pc - KLD;
-        const int off = pv * 1024 + 16 * lane, row = off / VB, slot = (off % VB) >> 4;
-        const int piece = slot ^ att_vswz(row, VB);
-        const uint32_t voff = (uint32_t)(((int64_t)row * Npad + j0) * sizeof(T)) + piece * 16;
-        load_to_lds16(vg, voff, st + KTILE + pv * 1024);
+        if constexpr (TR) {
+          // row-major values: 4 key rows of 256 bytes per instruction, piece p of row r in slot p ^ 4 (r & 3)
+          const int off = pv * 1024 + 16 * lane, row = off / RB, slot = (off % RB) >> 4;
+          const int piece = slot ^ ((row & 3) << 2);
+          const uint32_t voff = (uint32_t)((int64_t)min(j0 + row, N - 1) * vrow_bytes) + piece * 16;
+          load_to_lds16(vg, voff, st + KTILE + pv * 1024);
+        } else {
+          const int off = pv * 1024 + 16 * lane, row = off / VB, slot = (off % VB) >> 4;
+          const int piece = slot ^ att_vswz(row, VB);
+          const uint32_t voff = (uint32_t)(((int64_t)row * Npad + j0) * sizeof(T)) + piece * 16;
+          load_to_lds16(vg, voff, st + KTILE + pv * 1024);
+        }
       } else if (pc < TP) {
         if (lane < ATT_BIASB / 16) load_to_lds16(bg, (uint32_t)(j0 * 4 + 16 * lane), st + KTILE + VTILE);
       }
@@ -246,6 +274,15 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
   int v_off[NPS];
 #pragma unroll
   for (int c = 0; c < NPS; ++c) v_off[c] = n * VB + (((2 * c + hf) ^ att_vswz(n, VB)) << 4);
+
+  // Transposing read (TR): a lane is both a source -- it names 8 bytes, four consecutive columns of one key
+  // row -- and a receiver.  Inside a group of 16 lanes, source 4 i + a names key i of four consecutive
+  // keys and column block a, and lane 4 a + c receives column 4 a + c of those four keys: the 16 lanes
+  // cover 16 consecutive columns (rows of values^T) with four keys each, which is half of the
+  // operand.  The key of slot e of contraction step c for lane half hf is 16 c + 8 (e / 4) + 4 hf + e % 4,
+  // the order in which the first product leaves P^T in the accumulators.
+  const int src16 = lane & 15, src_key = src16 >> 2;
+  const int vtr_base = (4 * hf + src_key) * RB + ((2 * ((lane >> 4) & 1) + ((src16 & 3) >> 1)) << 4) + 8 * (src16 & 1);
 
   // S^T of the wave's queries against key tile t, raw (unscaled) products
   auto scores = [&](int t, f32x16_t& s) {
@@ -334,7 +371,16 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
     for (int c = 0; c < NPS; ++c)
 #pragma unroll
       for (int tt = 0; tt < DT; ++tt) {
-        const uint4 va = *reinterpret_cast<const uint4*>(Vt + v_off[c] + tt * 32 * VB);
+        uint4 va;
+        if constexpr (TR) {
+          // row tile tt of values^T = columns 32 tt .. 32 tt + 31 = 16-byte pieces 4 tt .. 4 tt + 3 of a key
+          // row, stored in slots (4 tt + x) ^ 4 (key & 3)
+          const char* src = Vt + vtr_base + 16 * c * RB + ((tt ^ src_key) << 6);
+          const uint2 lo = att_tr_read(src), hi = att_tr_read(src + 8 * RB);
+          va = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        } else {
+          va = *reinterpret_cast<const uint4*>(Vt + v_off[c] + tt * 32 * VB);
+        }
         mma32<T>(o[tt], va, pb[c]);
       }
   };
@@ -383,9 +429,13 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
 // ------------------------------------------------------------------------------------------
 static int att_npad(const asap_params& p) { return ((p.P + p.V + p.Tmax + 31) / 32) * 32 + 32; }
 
+// bf16 values with d = 128 are read as they are; every other case goes through a transposed copy
+static bool att_row_major_values(const asap_params& p) { return p.qk_dtype == ASAP_BF16 && p.d == 128; }
+
 size_t attention_workspace_bytes(const asap_params& p) {
   const size_t es = p.qk_dtype == ASAP_BF16 ? 2 : 4;
-  return align256(es * (size_t)p.B * p.Hkv * p.d * att_npad(p)) + align256(sizeof(float) * (size_t)p.B * att_npad(p));
+  const size_t vt = att_row_major_values(p) ? 0 : align256(es * (size_t)p.B * p.Hkv * p.d * att_npad(p));
+  return vt + align256(sizeof(float) * (size_t)p.B * att_npad(p));
 }
 
 template <typename T>
@@ -394,14 +444,17 @@ static hipError_t attention_typed(const asap_params& p, const void* q, Strides3 
                                   hipStream_t st, Timer* tm) {
   constexpr int E = elem<T>::per16;
   const int N = p.P + p.V + p.Tmax, Npad = att_npad(p);
-  T* vt = reinterpret_cast<T*>(ws);
-  float* bias2 = reinterpret_cast<float*>(ws + align256(sizeof(T) * (size_t)p.B * p.Hkv * p.d * Npad));
+  const bool row_major_values = att_row_major_values(p);    // the kernel transposes while it reads LDS
+  T* vt = reinterpret_cast<T*>(ws);                         // (not used then)
+  float* bias2 = reinterpret_cast<float*>(
+      ws + (row_major_values ? 0 : align256(sizeof(T) * (size_t)p.B * p.Hkv * p.d * Npad)));
   const bool bidir = p.mask_mode == ASAP_MASK_KEYBIAS;
   // (with the mask off the table is -inf everywhere and s_hat is not read)
   ASAP_LAUNCH(tm, "k_att_bias", k_att_bias, dim3((Npad + 255) / 256, p.B), dim3(256), 0, st, bidir ? s_hat : nullptr,
               p.P, p.V, Npad, p.lambda_max, p.eps, bias2);
-  ASAP_LAUNCH(tm, "k_vtranspose", k_vtranspose<T>, dim3(Npad / 32, p.Hkv, p.B), dim3(256), 0, st,
-              static_cast<const T*>(v), sv, N, Npad, p.d, vt);
+  if (!row_major_values)
+    ASAP_LAUNCH(tm, "k_vtranspose", k_vtranspose<T>, dim3(Npad / 32, p.Hkv, p.B), dim3(256), 0, st,
+                static_cast<const T*>(v), sv, N, Npad, p.d, vt);
   const float c2 = 1.4426950408889634f / sqrtf((float)p.d);
   const dim3 grid((N + ATT_QWG - 1) / ATT_QWG, p.H, p.B);
   const int ch = p.d / E / 2;
@@ -416,7 +469,8 @@ static hipError_t attention_typed(const asap_params& p, const void* q, Strides3 
       if (e != hipSuccess) return e;                                                                           \
     }                                                                                                          \
     ASAP_LAUNCH(tm, "k_attention", kern, grid, dim3(64 * ATT_NW), lds, st, static_cast<const T*>(q), sq,       \
-                static_cast<const T*>(k), sk, vt, Npad, bias2, bidir ? 1 : 0, static_cast<T*>(out), p.H,       \
+                static_cast<const T*>(k), sk, vt, Npad, static_cast<const T*>(v), sv, bias2, bidir ? 1 : 0,    \
+                static_cast<T*>(out), p.H,                                                                      \
                 p.Hkv, N, p.P, p.V, c2);                                                                       \
   } while (0)
   if (ch == 4) ASAP_ATT(4);
