@@ -499,6 +499,51 @@ def test_config6_target_2304_tokens_batch16(ctx):
     print("C6", rep)
 
 
+def test_config6_invariants_on_every_image(ctx):
+    """What holds at any size, checked on all 16 images of the configuration bench.py times (the oracle
+    comparison above samples three of them): scores are a distribution, the kept set is the top-k of
+    the score, the two index lists partition the image, routing targets are kept slots, Eq. 6 conserves
+    the merge weight and the weighted sum, positions and lengths follow the kept list, prefix and text
+    rows and every K/V row are bit-exact copies."""
+    cfg = synth.CONFIGS["C6"]
+    inp = synth.make_inputs(cfg)
+    st = U.GpuStage(inp, ctx=ctx)
+    buf = st.run()
+    B, P, V, k, T = cfg.B, cfg.P, cfg.V, cfg.k, cfg.Tmax
+    dev = buf.score.device
+    score, s_hat = buf.score.double(), buf.s_hat.double()
+    assert torch.all(buf.score >= 0) and torch.allclose(score.sum(1), torch.ones(B, dtype=torch.float64, device=dev),
+                                                         atol=1e-5)
+    kept, pruned = buf.kept_idx.long(), buf.pruned_idx.long()
+    assert torch.all(kept[:, 1:] > kept[:, :-1]) and torch.all(pruned[:, 1:] > pruned[:, :-1])
+    both = torch.sort(torch.cat([kept, pruned], 1), 1).values
+    assert torch.equal(both, torch.arange(V, device=dev).expand(B, V))
+    assert torch.all(score.gather(1, kept).min(1).values >= score.gather(1, pruned).max(1).values)
+    assign = buf.assign.long()
+    assert torch.all((assign >= 0) & (assign < k)) and torch.all(buf.best_sim.abs() <= 1.0 + 2e-5)
+    # Eq. 6: weight and weighted-sum conservation over the members of every slot
+    w_kept, w_pruned = s_hat.gather(1, kept), s_hat.gather(1, pruned)
+    wsum_ref = w_kept.clone().scatter_add_(1, assign, w_pruned)
+    assert torch.allclose(buf.wsum.double(), wsum_ref, rtol=1e-5, atol=1e-7)
+    tl = st.text_len.long()
+    for b in range(B):
+        xv = st.hidden[b, P:P + V].double()
+        num = w_kept[b, :, None] * xv[kept[b]]
+        num.index_add_(0, assign[b], w_pruned[b, :, None] * xv[pruned[b]])
+        y = buf.out_hidden[b, P:P + k].double() * buf.wsum[b].double()[:, None]
+        err = (y - num).norm() / num.norm()
+        assert err < 5e-3, f"image {b}: weighted sum off by {err:.3g}"      # one bf16 rounding per element
+        n_new = int(buf.new_len[b])
+        assert n_new == P + k + int(tl[b])
+        pos = buf.pos_out[b, :n_new].long()
+        want = torch.cat([torch.arange(P, device=dev), P + kept[b], P + V + torch.arange(int(tl[b]), device=dev)])
+        assert torch.equal(pos, want)
+        assert torch.equal(buf.out_hidden[b, :P], st.hidden[b, :P])
+        assert torch.equal(buf.out_hidden[b, P + k:n_new], st.hidden[b, P + V:P + V + int(tl[b])])
+        for src, dst in zip(st.k_cache + st.v_cache, buf.k_dst + buf.v_dst):
+            assert torch.equal(dst[b, :, :n_new], src[b][:, pos])
+
+
 def test_config5_two_stage(ctx):
     """Stage 1 (2304 -> 576) then stage 2 (576 -> 160) on the GPU's stage-1 output, with Q/K of the
     survivors rotated at their original position ids; stage 2 is judged stage-wise."""
