@@ -96,7 +96,8 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
                                               int mtiles, int ptiles, int spread, int vmt, float threshold,
                                               int32_t* __restrict__ assign,
                                               float* __restrict__ best_sim, unsigned long long* __restrict__ best_key,
-                                              float* __restrict__ src_norm2) {
+                                              float* __restrict__ src_norm2, int ksplit, float* __restrict__ dots,
+                                              float* __restrict__ kept_norm2) {
   constexpr int BN = 64 * NT;
   constexpr int PA = SIM_BM / 32;                // source-row loads a thread issues per step
   constexpr int PB = BN / 32;                    // destination-row loads
@@ -118,8 +119,11 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
   // With fewer than 8 images one image per XCD would leave XCDs idle: an image's source tiles are then
   // dealt to `spread` XCDs (tile mt to the XCD of "virtual image" b * spread + mt % spread), each of
   // which keeps its own copy of the image's destination panel in L2.
+  // With ksplit > 1 (launches that would leave most of the chip idle) the hidden dimension is cut into
+  // ksplit slices, each with workgroups of its own, which leave raw partial products and partial
+  // squared norms for k_sim_reduce instead of taking the arg-max themselves.
   const int xcd = blockIdx.x % NUM_XCD, slot_p = blockIdx.x / NUM_XCD;
-  const int pass = slot_p % ptiles, slot = slot_p / ptiles;
+  const int pass = slot_p % ptiles, ks = (slot_p / ptiles) % ksplit, slot = slot_p / (ptiles * ksplit);
   const int vb = (slot / vmt) * NUM_XCD + xcd;
   const int b = vb / spread;
   const int mt = vb % spread + spread * (slot % vmt);
@@ -132,14 +136,15 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
   const int wm = wave >> 1, wn = wave & 1;
   const char* xb = reinterpret_cast<const char*>(xv + b * sb);
   const int64_t rowb = sr * (int64_t)sizeof(T);
-  const int steps = (D * (int)sizeof(T)) / SIM_ROWB;
-  // Every workgroup walks the hidden dimension from its own starting step: rows are a power-of-two
-  // number of bytes apart, so workgroups in lockstep would all hit the same memory channel.
+  const int steps = (D * (int)sizeof(T)) / SIM_ROWB / ksplit;     // ksplit divides the step count
+  const int step_lo = ks * steps;
+  // Every workgroup walks its part of the hidden dimension from its own starting step: rows are a
+  // power-of-two number of bytes apart, so workgroups in lockstep would all hit the same memory channel.
   const int rot = (mt + 16 * (slot / vmt)) % steps;
   auto step_base = [&](int s) {
     int sr_ = s + rot;
     if (sr_ >= steps) sr_ -= steps;
-    return xb + (int64_t)sr_ * SIM_ROWB;
+    return xb + (int64_t)(step_lo + sr_) * SIM_ROWB;
   };
 
   // Loads: thread (rr, q) fetches, for rows rr + 32 i, the piece that belongs in slot q of the row;
@@ -285,6 +290,25 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
     }
     __syncthreads();   // norms visible
 
+    if (ksplit > 1) {
+      // this slice's share of the products and of the squared norms; k_sim_reduce adds the slices up
+      const int64_t img = (int64_t)ks * B + b;
+      if (pass == 0 && tid < SIM_BM && m0 + tid < M) src_norm2[img * M + m0 + tid] = norm2[tid];
+      if (mt == 0 && tid < BN && n0 + tid < k) kept_norm2[img * k + n0 + tid] = normk[tid];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * 64 + i * 32 + mma32_row(v, lane);
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            const int col = n0 + wn * (BN / 2) + t * 32 + n;
+            if (row < M && col < k) dots[(img * M + row) * k + col] = acc[i][t][v];
+          }
+        }
+      return;
+    }
+
     // Row arg-max of dot / |x_j| over this pass's destinations (|x_i| > 0 does not move it).
     // A lane first takes the best of its NT columns of a row (columns past k get -inf), then the 32
     // lanes that share the row agree on the maximum and on the smallest column that reaches it.
@@ -394,18 +418,94 @@ __global__ __launch_bounds__(256) void k_sim_finish(const unsigned long long* __
   assign[i] = (c > threshold) ? col : -1;
 }
 
+// grid (ceil(M / 4), B), 256 threads: one wave per source row.  Adds the ksplit partial products of
+// every destination column in slice order, scales by the destination's norm, applies the predicate
+// of the anchored search, takes the row's arg-max (ties to the smaller column) and divides by the
+// source norm -- the arithmetic of k_sim's own epilogue.
+template <bool ANCHORED>
+__global__ __launch_bounds__(256) void k_sim_reduce(const float* __restrict__ dots, const float* __restrict__ src_norm2,
+                                                     const float* __restrict__ kept_norm2, int B, int M, int k,
+                                                     int ksplit, const int32_t* __restrict__ srcs,
+                                                     const int32_t* __restrict__ kept, const float* __restrict__ s_hat,
+                                                     int V, float threshold, int32_t* __restrict__ assign,
+                                                     float* __restrict__ best_sim) {
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y;
+  if (row >= M) return;
+  const float sr_ = ANCHORED ? s_hat[(int64_t)b * V + srcs[(int64_t)b * M + row]] : 0.0f;
+  float bv = -INFINITY;
+  int bc = 0x7fffffff;
+  for (int col = lane; col < k; col += 64) {
+    // four running sums (slices q, q+1, q+2, q+3 of every four), so that the loads do not wait for
+    // one another; the order of the additions is fixed all the same
+    float d4[4] = {0.0f, 0.0f, 0.0f, 0.0f}, n4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const int64_t dstride = (int64_t)B * M * k, nstride = (int64_t)B * k;
+    const float* dp = dots + ((int64_t)b * M + row) * k + col;
+    const float* np = kept_norm2 + (int64_t)b * k + col;
+    int q = 0;
+    for (; q + 3 < ksplit; q += 4) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        d4[u] += dp[(q + u) * dstride];
+        n4[u] += np[(q + u) * nstride];
+      }
+    }
+    for (; q < ksplit; ++q) {
+      d4[0] += dp[q * dstride];
+      n4[0] += np[q * nstride];
+    }
+    const float dot = (d4[0] + d4[1]) + (d4[2] + d4[3]), kn = (n4[0] + n4[1]) + (n4[2] + n4[3]);
+    float c = dot * (1.0f / fmaxf(sqrtf(kn), 1e-8f));
+    if (ANCHORED) {
+      const float sc = s_hat[(int64_t)b * V + kept[(int64_t)b * k + col]];
+      const bool stronger = (sc > sr_) | ((sc == sr_) & (col < row));
+      c = stronger ? c : -INFINITY;
+    }
+    if (c > bv) { bv = c; bc = col; }             // a lane's columns ascend: the first maximum stays
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float ov = __shfl_xor(bv, off);
+    const int oc = __shfl_xor(bc, off);
+    if (ov > bv || (ov == bv && oc < bc)) { bv = ov; bc = oc; }
+  }
+  if (lane == 0) {
+    float sn = 0.0f;
+    for (int q = 0; q < ksplit; ++q) sn += src_norm2[((int64_t)q * B + b) * M + row];
+    const float c = bv / fmaxf(sqrtf(sn), 1e-8f);
+    best_sim[(int64_t)b * M + row] = c;
+    assign[(int64_t)b * M + row] = (c > threshold) ? bc : -1;
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
 static int pick_nt(const asap_params& p, int M);
+
+// Slices of the hidden dimension: 1 unless the launch has at most 128 workgroups; then as many as
+// bring it to about one workgroup per compute unit, with at least 8 steps per slice and a count that
+// divides the steps, while the partial products stay under 64 MB.
+static int pick_ksplit(const asap_params& p, int M, int nt) {
+  const int bn = 64 * nt, ptiles = (p.k + bn - 1) / bn, mtiles = (M + SIM_BM - 1) / SIM_BM;
+  const long wgs = (long)p.B * mtiles * ptiles;
+  const int steps = p.D * (p.h_dtype == ASAP_BF16 ? 2 : 4) / SIM_ROWB;
+  if (wgs > 128 || steps < 16) return 1;
+  int ks = (int)(256 / wgs);
+  if (ks > steps / 8) ks = steps / 8;
+  while (ks > 1 && (steps % ks != 0 || (size_t)ks * p.B * M * p.k * sizeof(float) > ((size_t)64 << 20))) --ks;
+  return ks < 1 ? 1 : ks;
+}
 
 // One key per destination tile and source row, and the source norms, for either kind of search
 // (pruned -> kept: V-k source rows; inside the kept set: k), when the destination rows are split
 // over several workgroups.
 static size_t sim_workspace_for(const asap_params& p, int M) {
   if (M <= 0) return 0;
-  const int bn = 64 * pick_nt(p, M), ptiles = (p.k + bn - 1) / bn;
+  const int nt = pick_nt(p, M), bn = 64 * nt, ptiles = (p.k + bn - 1) / bn, ks = pick_ksplit(p, M, nt);
   const size_t rows = (size_t)p.B * M;
+  if (ks > 1)      // partial products, source norms, destination norms per slice
+    return align256(sizeof(float) * ks * rows * p.k) + align256(sizeof(float) * ks * rows) +
+           align256(sizeof(float) * ks * (size_t)p.B * p.k);
   return align256(sizeof(unsigned long long) * rows * ptiles) + align256(sizeof(float) * rows);
 }
 size_t sim_workspace_bytes(const asap_params& p) {
@@ -431,11 +531,23 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
   const int vmt = (mtiles + spread - 1) / spread;
   const int groups = (p.B * spread + NUM_XCD - 1) / NUM_XCD;
   const int n = p.B * M;
+  const int ksplit = pick_ksplit(p, M, NT);
+  if (ksplit > 1) {
+    float* dots = reinterpret_cast<float*>(ws);                                       // [ksplit][B][M][k]
+    float* nsrc = reinterpret_cast<float*>(ws + align256(sizeof(float) * ksplit * (size_t)n * p.k));
+    float* nkept = reinterpret_cast<float*>(reinterpret_cast<char*>(nsrc) + align256(sizeof(float) * ksplit * (size_t)n));
+    ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * vmt * ptiles * ksplit), dim3(256), lds, st, xv, sb, sr, p.D,
+                srcs, kept, s_hat, p.V, p.B, M, p.k, mtiles, ptiles, spread, vmt, p.sim_threshold, assign, best_sim,
+                static_cast<unsigned long long*>(nullptr), nsrc, ksplit, dots, nkept);
+    ASAP_LAUNCH(tm, "k_sim_reduce", k_sim_reduce<ANCHORED>, dim3((M + 3) / 4, p.B), dim3(256), 0, st, dots, nsrc, nkept,
+                p.B, M, p.k, ksplit, srcs, kept, s_hat, p.V, p.sim_threshold, assign, best_sim);
+    return hipGetLastError();
+  }
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(ws);               // [ptiles][B*M]
   float* norms = reinterpret_cast<float*>(ws + align256(sizeof(unsigned long long) * (size_t)n * ptiles));
   ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * vmt * ptiles), dim3(256), lds, st, xv, sb, sr, p.D, srcs,
               kept, s_hat, p.V, p.B, M, p.k, mtiles, ptiles, spread, vmt, p.sim_threshold, assign, best_sim, keys,
-              norms);
+              norms, 1, static_cast<float*>(nullptr), static_cast<float*>(nullptr));
   if (ptiles > 1)
     ASAP_LAUNCH(tm, "k_sim_finish", k_sim_finish, dim3((n + 255) / 256), dim3(256), 0, st, keys, norms, n, ptiles,
                 p.sim_threshold, assign, best_sim);
