@@ -25,7 +25,11 @@
 //                 (k > 64*NT), the tiles of a source tile are workgroups of their own: each leaves
 //                 its row winner as a 64-bit key (order-preserving value bits, then the inverted
 //                 column so that equal values keep the smaller column) in a slot of its own.
+//                 Launches of at most 128 workgroups also cut the hidden dimension into slices
+//                 with workgroups of their own, which leave raw partial products and partial
+//                 squared norms instead of a row winner.
 //   k_sim_finish  largest key of a row -> assign, best_sim (threshold and source norm applied here)
+//   k_sim_reduce  sums the slices of a split launch, then the same scaling, predicate and arg-max
 #include "asap_device.hpp"
 #include "asap_launch.hpp"
 #include "asap_select.hpp"
