@@ -85,6 +85,14 @@ def test_batch_sizes_that_do_not_divide_the_chip(ctx, B):
     U.run_and_compare(cfg, ctx=ctx)
 
 
+@pytest.mark.parametrize("base,D", [("S2", 8192), ("S0", 8192), ("S2", 64), ("S0", 64)])
+def test_hidden_size_limits(ctx, base, D):
+    """The widest and the narrowest hidden rows the library takes (bf16 and fp32): 16 KiB / 32 KiB rows in
+    the similarity search's ring and the merge, and rows shorter than one 128-byte step."""
+    cfg = dataclasses.replace(synth.CONFIGS[base], D=D, V=200, k=60, B=2, name=f"{base}D{D}")
+    U.run_and_compare(cfg, ctx=ctx)
+
+
 def test_maximum_visual_tokens(ctx):
     """V = 16384, the largest image span the library takes: 512 key tiles in the sweeps, 16 items per
     thread in the selection, 13 destination tiles per source row in the similarity search."""
