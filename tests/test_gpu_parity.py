@@ -93,6 +93,32 @@ def test_hidden_size_limits(ctx, base, D):
     U.run_and_compare(cfg, ctx=ctx)
 
 
+@pytest.mark.parametrize("layers,paged", [(17, False), (33, False), (19, True)])
+def test_more_cached_layers_than_one_launch_takes(ctx, layers, paged):
+    """The compaction kernels take the K and V pointers of 16 layers per launch; more layers mean several
+    launches (contiguous caches from the kept list on the second stream, and paged caches)."""
+    cfg = dataclasses.replace(synth.CONFIGS["S1"], L_kv=layers, name=f"layers{layers}")
+    inp = synth.make_inputs(cfg)
+    st = U.GpuStage(inp, ctx=ctx, page_size=8 if paged else None)
+    buf = st.run()
+    for b in range(cfg.B):
+        n_new = int(buf.new_len[b])
+        pos = buf.pos_out[b, :n_new].long()
+        if paged:
+            # token n of sequence b sits in page table[b, n / 8], slot n % 8; source pages stay as they were
+            ps, pg = 8, st.paged
+            new = torch.arange(n_new, device=pos.device)
+            for pool in pg.k_pool + pg.v_pool:
+                got = pool[pg.dst_table[b].long()[new // ps], :, new % ps]
+                want = pool[pg.src_table[b].long()[pos // ps], :, pos % ps]
+                assert torch.equal(got, want)
+        else:
+            for src, dst in zip(st.k_cache + st.v_cache, buf.k_dst + buf.v_dst):
+                assert torch.equal(dst[b, :, :n_new], src[b][:, pos])
+    if not paged:
+        U.compare_image(inp, buf, 0, U.oracle_image(inp, 0))
+
+
 def test_maximum_visual_tokens(ctx):
     """V = 16384, the largest image span the library takes: 512 key tiles in the sweeps, 16 items per
     thread in the selection, 13 destination tiles per source row in the similarity search."""
