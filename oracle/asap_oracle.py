@@ -20,6 +20,8 @@ order and notation, with no blocking, fusion or reordering:
   weighted_merge            Eq. 6
   assemble_sequence         prefix | merged kept tokens | text           (Fig. 3 caption)
   gather_kv                 K/V rows of surviving positions
+  gather_kv_paged           the same for caches kept as pools of pages with block tables
+  stage                     all steps for one image (score_rows="last": ranking by the last text token)
   full_bidirectional_attention   literal N x N Eq. 4-5, brute force, for pins only
   theoretical_flops / flops_ratio   Eq. 7 / Eq. 8 (appendix)
 
