@@ -148,3 +148,20 @@ def test_paper_route_needs_room_to_refill(lib):
     p.k = p.V // 2 + 1
     st, msg = binding.asap_check_params(p)
     assert st == binding.ASAP_EINVAL and "V / 2" in msg
+
+
+def test_a_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    """The product path has one implementation: without the built library every entry fails at load
+    time, and nothing under paper_2603_14549_amd imports the oracle."""
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libasap.so"))
+    with pytest.raises(FileNotFoundError, match="no fallback"):
+        binding.load()
+    with pytest.raises(FileNotFoundError):
+        binding.asap_workspace_bytes(binding.params_from_config(synth.CONFIGS["S1"]))
+    pkg = os.path.dirname(os.path.abspath(binding.__file__))
+    for root, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(root, f), encoding="utf-8").read()
+                assert "import oracle" not in text and "from oracle" not in text and "asap_oracle" not in text, f
