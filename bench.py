@@ -209,7 +209,8 @@ def main():
                     help="rank the visual tokens by the last text token's row alone (scoring call with Tmax = 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 1 GiB device copy a few times (reference for HBM counters)")
+                    help="accepted for the counter runs documented in profiles/: the 1 GiB device copies that "
+                         "calibrate FETCH_SIZE / WRITE_SIZE are part of every run now")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU (the pruning stage of one GPU's share of the batch); "
@@ -289,12 +290,21 @@ def main():
         sim_alone = ctx.asap_timing_collect().get("k_sim")
         ctx.asap_timing_enable(0)
 
-    if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
+    # what a plain device-to-device copy of 1 GiB reaches on this machine (bytes read + bytes written per
+    # second), as a second yardstick beside the nominal peak; with --copy-calibration the copies also
+    # serve to scale the traffic counters of a rocprofv3 run
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_bw = 5 * 2.0 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3)
+    del src, dst
 
     mean_text = float(np.mean(inp["text_len"]))
     alg = algorithmic_bytes(cfg, mean_text, cfg.L_kv)
@@ -359,6 +369,8 @@ def main():
         moved = sum(measured.get(name, 0.0) * n / args.steps for name, (_, n) in timing.items())
         stage_roofline["traffic_MB"] = round(moved / 1e6, 1)
         stage_roofline["traffic_frac"] = moved / (ms_per_step * 1e-3) / HBM_PEAK
+        stage_roofline["traffic_vs_copy"] = moved / (ms_per_step * 1e-3) / copy_bw
+    stage_roofline["measured_copy_GBps"] = round(copy_bw / 1e9, 1)
 
     out = {
         "metric": "pruning-stage images/sec at %d visual tokens" % cfg.V,
