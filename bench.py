@@ -282,7 +282,7 @@ def main():
     # per-kernel events on, for the duration of k_sim when nothing shares the memory system with it
     sim_alone = None
     if stage.two_streams and not stage.call_by_call:
-        n_alone = min(args.steps, 20)
+        n_alone = min(args.steps, 5)
         ctx.asap_timing_enable(launches_per_step * n_alone)
         for _ in range(n_alone):
             ctx.asap_stage(stage.p, stage.io, False)
