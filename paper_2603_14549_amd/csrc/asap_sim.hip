@@ -298,7 +298,9 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
       // this slice's share of the products and of the squared norms; k_sim_reduce adds the slices up
       const int64_t img = (int64_t)ks * B + b;
       if (pass == 0 && tid < SIM_BM && m0 + tid < M) src_norm2[img * M + m0 + tid] = norm2[tid];
-      if (mt == 0 && tid < BN && n0 + tid < k) kept_norm2[img * k + n0 + tid] = normk[tid];
+      if (mt == 0)
+        for (int c = tid; c < BN; c += 256)        // BN may exceed the workgroup size
+          if (n0 + c < k) kept_norm2[img * k + n0 + c] = normk[c];
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -558,17 +560,22 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
   return hipGetLastError();
 }
 
-// Destination tile width 64 * nt.  The kernel is bound by what it loads, (128 + 64 nt) rows per step
-// and workgroup, and the workgroups run in rounds of one per compute unit: fewest rounds x rows,
-// then the wider tile.
+// Destination tile width 64 * nt.  The kernel is bound by what a workgroup loads (or, for fp32, by
+// what it multiplies): (128 + 64 nt) rows per step, over the steps of its slice of the hidden
+// dimension, and the workgroups run in rounds of one per compute unit: fewest rounds x steps x rows
+// (the slicing of pick_ksplit taken into account), then the wider tile.
 static int pick_nt(const asap_params& p, int M) {
   const long mt = (M + SIM_BM - 1) / SIM_BM;
+  const long steps = p.D * (p.h_dtype == ASAP_BF16 ? 2 : 4) / SIM_ROWB;
   int best_nt = 5;
   long best_cost = -1;
   for (int nt = 5; nt >= 1; --nt) {
     const long bn = 64 * nt, passes = (p.k + bn - 1) / bn;
-    const long wgs = (long)p.B * mt * passes, rounds = (wgs + 255) / 256;
-    const long cost = rounds * (SIM_BM + bn);
+    const long ks = pick_ksplit(p, M, nt);
+    const long wgs = (long)p.B * mt * passes * ks, rounds = (wgs + 255) / 256;
+    // a split launch also pays for the partial products' round trip and for k_sim_reduce: about as
+    // much as 6000 row-steps, from measurements on the small configurations
+    const long cost = rounds * (steps / ks) * (SIM_BM + bn) + (ks > 1 ? 6000 : 0);
     if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_nt = nt; }
   }
   return best_nt;

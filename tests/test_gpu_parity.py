@@ -119,6 +119,23 @@ def test_more_cached_layers_than_one_launch_takes(ctx, layers, paged):
         U.compare_image(inp, buf, 0, U.oracle_image(inp, 0))
 
 
+@pytest.mark.parametrize("route", ["absorb", "paper"])
+def test_wide_destination_tiles_with_a_split_hidden_dimension(ctx, route):
+    """Few source tiles and many kept tokens: the similarity search takes its widest destination tile
+    (320 columns, more than a workgroup has threads) and cuts the hidden dimension into slices."""
+    if route == "absorb":
+        cfg = dataclasses.replace(synth.CONFIGS["S2"], B=4, V=2560, k=640, D=1024, Tmax=16, n_clusters=200,
+                                  name="wide_split")
+        U.run_and_compare(cfg, images=[0, 3], ctx=ctx)
+    else:
+        cfg = dataclasses.replace(synth.CONFIGS["S2"], B=16, V=700, k=320, D=2048, Tmax=9, n_clusters=40,
+                                  name="wide_split_paper")
+        inp = synth.make_inputs(cfg)
+        st = U.GpuStage(inp, ctx=ctx, route=binding.ASAP_ROUTE_PAPER, sim_threshold=0.8)
+        buf = st.run()
+        assert sum(U.compare_image_paper(inp, buf, b, 0.8, 1.0)["n_sources"] for b in (0, 15)) > 0
+
+
 def test_maximum_visual_tokens(ctx):
     """V = 16384, the largest image span the library takes: 512 key tiles in the sweeps, 16 items per
     thread in the selection, 13 destination tiles per source row in the similarity search."""
