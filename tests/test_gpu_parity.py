@@ -136,6 +136,42 @@ def test_wide_destination_tiles_with_a_split_hidden_dimension(ctx, route):
         assert sum(U.compare_image_paper(inp, buf, b, 0.8, 1.0)["n_sources"] for b in (0, 15)) > 0
 
 
+def _random_config(seed: int):
+    """A legal shape drawn from the whole range the library takes (kept small enough for the oracle)."""
+    r = np.random.default_rng(1000 + seed)
+    d = int(r.choice([64, 128]))
+    Hkv = int(r.choice([1, 2, 3, 4, 8]))
+    H = Hkv * int(r.choice([1, 2, 4]))
+    V = int(r.choice([1, 2, 3, 17, 31, 32, 33, 63, 64, 65, 100, 129, 255, 256, 300, 511, 640, 700, 1100]))
+    paper = bool(r.integers(0, 3) == 0) and V >= 2
+    k = int(r.integers(1, (V // 2 if paper else V) + 1))
+    qk = str(r.choice(["bf16", "f32"]))
+    cfg = synth.StageConfig(
+        name=f"rand{seed}", B=int(r.choice([1, 2, 3, 5, 8, 13, 16, 24])), D=64 * int(r.integers(1, 41)), H=H, Hkv=Hkv,
+        d=d, P=int(r.choice([0, 1, 7, 35])), V=V, Tmax=int(r.choice([1, 2, 31, 32, 33, 64, 65, 100, 128])), k=k,
+        qk_dtype=qk, h_dtype=str(r.choice(["bf16", "f32"])), kv_dtype=str(r.choice(["bf16", "f32"])),
+        n_clusters=int(r.integers(1, 40)), outliers=bool(r.integers(0, 2)), L_kv=int(r.integers(0, 4)),
+        seed=5000 + seed, ragged_text=True, text_lo=1)
+    return cfg, paper
+
+
+@pytest.mark.parametrize("seed", list(range(32)))
+def test_random_shapes(ctx, seed):
+    """Seeded shapes over the whole legal range -- batch, heads and groups, head and hidden sizes, prefix,
+    image span, budget, text block, the three dtypes, layer count, both routings -- compared with the
+    oracle like the named configurations (two images each)."""
+    cfg, paper = _random_config(seed)
+    images = sorted({0, cfg.B - 1})
+    if paper:
+        inp = synth.make_inputs(cfg)
+        st = U.GpuStage(inp, ctx=ctx, route=binding.ASAP_ROUTE_PAPER, sim_threshold=0.8)
+        buf = st.run()
+        for b in images:
+            U.compare_image_paper(inp, buf, b, 0.8, 1.0)
+    else:
+        U.run_and_compare(cfg, images=images, ctx=ctx)
+
+
 def test_maximum_visual_tokens(ctx):
     """V = 16384, the largest image span the library takes: 512 key tiles in the sweeps, 16 items per
     thread in the selection, 13 destination tiles per source row in the similarity search."""
