@@ -474,7 +474,10 @@ def test_paper_routing_config2_and_config6_sample(ctx):
 def test_attention_forward_under_the_bidirectional_mask(ctx, name, mask_mode, lam):
     """asap_attention (flash-style, both contractions on MFMA) against the oracle's explicit N x N
     softmax of Eq. 4-5, every image, every head, every row."""
-    cfg = synth.CONFIGS[name]
+    _attention_case(ctx, synth.CONFIGS[name], mask_mode, lam)
+
+
+def _attention_case(ctx, cfg, mask_mode, lam):
     inp = synth.make_inputs(cfg, with_kv=False)
     st = U.GpuStage(inp, ctx=ctx, mask_mode=mask_mode, lambda_max=lam)
     buf = st.run()                                             # s_hat of this layer's q, k
@@ -495,6 +498,24 @@ def test_attention_forward_under_the_bidirectional_mask(ctx, name, mask_mode, la
         got = U.from_device(out[b])
         for h in range(cfg.H):
             U.check_rows(got[h], ref[h], tol, f"attention output image {b} head {h}")
+
+
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_attention_forward_random_shapes(ctx, seed):
+    """Seeded shapes for asap_attention: sequence lengths around the 32-key and 256-query tile edges,
+    both head sizes and dtypes (bf16 with d = 128 takes the transposing-read path, the others the
+    transposed copy), grouped heads, with and without prefix, mask on and off."""
+    r = np.random.default_rng(7000 + seed)
+    d = int(r.choice([64, 128]))
+    Hkv = int(r.choice([1, 2, 3]))
+    V = int(r.choice([1, 30, 33, 95, 200, 256, 257, 500]))
+    cfg = synth.StageConfig(
+        name=f"att{seed}", B=int(r.choice([1, 2, 3])), D=64 * int(r.integers(2, 9)), H=Hkv * int(r.choice([1, 2, 4])),
+        Hkv=Hkv, d=d, P=int(r.choice([0, 3, 35])), V=V, Tmax=int(r.choice([1, 17, 32, 64, 100])), k=max(1, V // 3),
+        qk_dtype=str(r.choice(["bf16", "bf16", "f32"])), h_dtype="bf16", kv_dtype="bf16", n_clusters=5,
+        outliers=bool(r.integers(0, 2)), L_kv=0, seed=7100 + seed)
+    mask = binding.ASAP_MASK_KEYBIAS if r.integers(0, 4) else binding.ASAP_MASK_OFF
+    _attention_case(ctx, cfg, mask, float(r.choice([1.0, 0.6])))
 
 
 def test_attention_argument_checks_and_strided_inputs(ctx):
