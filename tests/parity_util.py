@@ -93,7 +93,17 @@ def compare_image(inp: dict, buf, b: int, ref: dict, mu=1.0, threshold=-math.inf
     s_raw = from_device(buf.s_raw[b])
     s_hat = from_device(buf.s_hat[b])
     smax = np.abs(ref["s_raw"]).max()
-    assert np.abs(s_raw - ref["s_raw"]).max() <= 2e-7 * smax + 1e-30, "s_raw"
+    # one f32 rounding of s (6e-8 |s|) plus the fp32 sums of a head's products inside the matrix
+    # instruction: their error scales with the heads' partial sums, which cancel in s when heads
+    # disagree in sign (images with two or three visual tokens show it)
+    Qf = synth.to_f64(inp["q"][b], cfg.qk_dtype)[:, P:P + V]
+    Kf = synth.to_f64(inp["k"][b], cfg.qk_dtype)[:, P:P + V]
+    qbar = np.zeros((cfg.Hkv, cfg.d))
+    for h in range(cfg.H):
+        qbar[(h * cfg.Hkv) // cfg.H] += Qf[h].sum(axis=0)
+    head_scale = np.abs(np.einsum("gd,gjd->gj", qbar, Kf)).sum(axis=0).max() / (cfg.H * math.sqrt(cfg.d))
+    s_tol = 2e-7 * max(smax, 0.6 * head_scale) + 1e-30
+    assert np.abs(s_raw - ref["s_raw"]).max() <= s_tol, "s_raw"
     assert np.abs(s_hat - ref["s_hat"]).max() <= 2e-7, "s_hat"
 
     # ---- Eq. 5 -> selection score

@@ -172,6 +172,26 @@ def test_random_shapes(ctx, seed):
         U.run_and_compare(cfg, images=images, ctx=ctx)
 
 
+@pytest.mark.parametrize("seed", list(range(100, 116)))
+def test_random_shapes_with_parameter_variants(ctx, seed):
+    """The seeded shapes again (absorb routing) with drawn parameters: mask off, lambda_max, the merge
+    weight, a finite similarity threshold, the full-row softmax term, ranking by the last text token."""
+    cfg, _ = _random_config(seed)
+    r = np.random.default_rng(9000 + seed)
+    ov = {}
+    if r.integers(0, 3) == 0:
+        ov["mask_mode"] = binding.ASAP_MASK_OFF
+    if r.integers(0, 2):
+        ov["lambda_max"] = float(r.choice([0.3, 0.7, 1.0]))
+    if r.integers(0, 2):
+        ov["merge_weight"] = float(r.choice([0.0, 0.5, 2.0]))
+    if r.integers(0, 2):
+        ov["sim_threshold"] = float(r.choice([0.2, 0.6, 0.95]))
+    lse = bool(r.integers(0, 3) == 0)
+    last = (not lse) and bool(r.integers(0, 3) == 0)
+    U.run_and_compare(cfg, images=sorted({0, cfg.B - 1}), ctx=ctx, lse=lse, last_token=last, **ov)
+
+
 def test_maximum_visual_tokens(ctx):
     """V = 16384, the largest image span the library takes: 512 key tiles in the sweeps, 16 items per
     thread in the selection, 13 destination tiles per source row in the similarity search."""
