@@ -325,7 +325,18 @@ def test_paged_kv_compaction(ctx, name, page_size):
     """asap_compact_kv_paged against the oracle's paged gather, bit for bit over the WHOLE pool
     (slots the gather must not touch keep their sentinel).  Source and destination pages are a
     random permutation inside one pool, so the call also covers both tables indexing one buffer."""
-    cfg = synth.CONFIGS[name]
+    _paged_case(ctx, synth.CONFIGS[name], page_size)
+
+
+@pytest.mark.parametrize("seed", list(range(200, 208)))
+def test_paged_kv_compaction_random_shapes(ctx, seed):
+    cfg, _ = _random_config(seed)
+    if cfg.L_kv == 0:
+        cfg = dataclasses.replace(cfg, L_kv=1)
+    _paged_case(ctx, cfg, int(np.random.default_rng(seed).choice([1, 2, 3, 7, 16, 33, 128])))
+
+
+def _paged_case(ctx, cfg, page_size):
     inp = synth.make_inputs(cfg)
     st = U.GpuStage(inp, ctx=ctx)
     buf = st.run()
