@@ -399,6 +399,79 @@ def test_route_paper_chain_resolves_to_root():
     assert sources[0].tolist() == [0, 1] and sources[1].size == 0 and sources[2].size == 0
 
 
+def _unit(deg):
+    return [math.cos(math.radians(deg)), math.sin(math.radians(deg))]
+
+
+@pytest.mark.parametrize("order", ["far_first", "near_first"])
+def test_route_paper_takes_the_most_similar_of_two_eligible_roots(order):
+    """Sec. 4.2, several eligible destinations for one source.  Three kept tokens in the plane:
+    the source j at 0 degrees, one stronger token at +30 degrees (cosine 0.866 to j), another at
+    -20 degrees (cosine 0.940).  The two stronger tokens are 50 degrees apart (cosine 0.643 < t =
+    0.8), so neither merges into the other: they are roots of different trees and j has to choose.
+    The nearer one (-20 degrees) must absorb it, wherever it stands in the index order."""
+    far, near, src = _unit(30.0), _unit(-20.0), _unit(0.0)
+    filler = [[0.0, 0.0, 1.0], [0.0, 0.0, -1.0]]                 # pruned tokens, orthogonal to the plane
+    if order == "far_first":
+        X = np.array([far + [0.0], near + [0.0], src + [0.0]] + filler)
+        i_far, i_near, i_src = 0, 1, 2
+    else:
+        X = np.array([near + [0.0], far + [0.0], src + [0.0]] + filler)
+        i_near, i_far, i_src = 0, 1, 2
+    s_raw = np.zeros(5)
+    s_raw[i_far], s_raw[i_near], s_raw[i_src] = 5.0, 4.0, 1.0    # both stronger than the source
+    s_raw[3], s_raw[4] = 0.7, 0.2
+    s_hat = O.salience(s_raw)
+    kept, pruned = np.array([0, 1, 2]), np.array([3, 4])
+    final_idx, sources = O.route_paper(X, s_raw, s_hat, kept, pruned, threshold=0.8)
+    # one slot is vacated and refilled with the pruned token of larger raw mass (token 3)
+    assert final_idx.tolist() == [0, 1, 3]
+    got = {int(i): s.tolist() for i, s in zip(final_idx, sources)}
+    assert got[i_near] == [i_src] and got[i_far] == [] and got[3] == []
+
+
+def test_route_paper_equal_salience_goes_to_the_smaller_index():
+    """Sec. 4.2: ties in salience are broken by sequence index.  Tokens 1 and 2 are near-duplicates
+    (cosine 0.99995 > t) with bit-equal salience; the one that comes first in the sequence is the
+    anchor, so token 1 absorbs token 2 and not the other way round.  Token 0 is unrelated."""
+    X = np.array([[0.0, 1.0, 0.0], [1.0, 0.0, 0.0], [1.0, 0.01, 0.0], [0.0, 0.0, 1.0], [0.0, 0.0, -1.0]])
+    s_raw = np.array([3.0, 2.0, 2.0, 0.5, 1.5])
+    s_hat = O.salience(s_raw)
+    assert s_hat[1] == s_hat[2]
+    kept, pruned = np.array([0, 1, 2]), np.array([3, 4])
+    final_idx, sources = O.route_paper(X, s_raw, s_hat, kept, pruned, threshold=0.9)
+    assert final_idx.tolist() == [0, 1, 4]                       # token 2 left; refill = largest raw mass
+    assert [s.tolist() for s in sources] == [[], [2], []]
+
+
+def test_stage_merge_weights_are_the_saliences_not_the_raw_masses():
+    """Whole stage with mu = 1 on a case small enough to do by hand (Eq. 2, 3, 6).  One head of size
+    1, three visual tokens, one text token, budget 1.  Visual queries 0.5, 0.25, 0.25 sum to 1 and
+    the keys are 1, 3, 2, so Eq. 2 gives the raw masses s = (1, 3, 2) and Eq. 3 the saliences
+    s_hat = (0, 2, 1) / (2 + eps).  The text query 1 sees logits 1, 3, 2 plus the log-discounts, so
+    token 1 is kept and absorbs tokens 0 and 2 (no threshold).  Eq. 6 weighs with s_hat: hidden
+    states 10, 20, 40 give (2*20 + 1*40 + 0*10) / 3 = 80/3; weighing with the raw masses instead
+    would give (3*20 + 2*40 + 1*10) / 6 = 25."""
+    P, V, T, k = 0, 3, 1, 1
+    Q = np.array([[[0.5], [0.25], [0.25], [1.0]]])               # [H=1, N=4, d=1]
+    K = np.array([[[1.0], [3.0], [2.0], [0.0]]])
+    X = np.array([[10.0, -1.0], [20.0, 2.0], [40.0, 4.0], [7.0, 7.0]])
+    out = O.stage(Q, K, X, T, P, V, T, k, mu=1.0)
+    np.testing.assert_allclose(out["s_raw"], [1.0, 3.0, 2.0], rtol=1e-15)
+    np.testing.assert_allclose(out["s_hat"], np.array([0.0, 2.0, 1.0]) / (2.0 + 1e-6), rtol=1e-15)
+    assert out["kept"].tolist() == [1] and out["pruned"].tolist() == [0, 2]
+    assert out["assign"].tolist() == [0, 0]
+    np.testing.assert_allclose(out["y"][0], [80.0 / 3.0, (2 * 2.0 + 1 * 4.0) / 3.0], rtol=1e-14)
+    np.testing.assert_allclose(out["wsum"], [3.0 / (2.0 + 1e-6)], rtol=1e-15)
+    assert abs(out["y"][0, 0] - 25.0) > 1.0                      # not the raw-mass weighting
+    np.testing.assert_allclose(out["Y"][:out["new_len"]], [out["y"][0], X[3]], rtol=1e-14)
+    # the paper's routing uses the same Eq. 6 weights: kept = {1, 2} (cosine 1 > t), 2 -> 1, refill 0
+    X2 = np.array([[10.0, -1.0], [20.0, 2.0], [40.0, 4.0], [7.0, 7.0]])
+    out2 = O.stage(Q, K, X2, T, P, V, T, 2, mu=1.0, route="paper", threshold=0.99)
+    assert out2["kept"].tolist() == [1, 2] and out2["final_idx"].tolist() == [0, 1]
+    np.testing.assert_allclose(out2["y"], [X2[0], (2 * X2[1] + 1 * X2[2]) / 3.0], rtol=1e-14)
+
+
 # ------------------------------------------------------------------ sequence assembly, K/V
 def test_assemble_and_gather():
     P, V, Tmax, tl = 2, 6, 3, 2
