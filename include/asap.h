@@ -126,6 +126,28 @@ asap_status asap_score(asap_ctx* ctx, const asap_params* p,
                        void* workspace, size_t workspace_bytes, void* stream /* hipStream_t */);
 
 /*
+ * asap_score_static -- asap_score for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Arguments, results and checks are those of asap_score without the workspace; the
+ * scratch is an array of ASAP_STATIC_SCRATCH_BYTES bytes that is part of the library's code object
+ * (every GPU the library runs on holds its own copy until the process ends; asap_create looks up
+ * its address on the context's device).  The call allocates and frees nothing.
+ * ASAP_EWORKSPACE if the parameters need more scratch than the array holds (the message names both
+ * sizes; asap_score with a caller workspace then serves): the array covers every benchmark
+ * configuration, e.g. 16 images x 32 heads x 2304 visual tokens x 64 text rows takes 5.8 MB.
+ * All calls on one GPU share that GPU's array and nothing in it has to survive between calls, but two
+ * calls that overlap in time on one GPU (different streams, different contexts, different threads)
+ * race on it: keep them ordered.
+ */
+#define ASAP_STATIC_SCRATCH_BYTES (16u << 20)
+asap_status asap_score_static(asap_ctx* ctx, const asap_params* p,
+                              const void* q_vis, const int64_t q_vis_stride[3],
+                              const void* q_txt, const int64_t q_txt_stride[3],
+                              const void* k_vis, const int64_t k_vis_stride[3],
+                              const int32_t* text_len, const float* lse_extra,
+                              float* s_raw, float* s_hat, float* score, void* stream /* hipStream_t */);
+
+/*
  * asap_select -- the k largest score[b,:] per image, ties to the smaller index (Fig. 3:
  * "retains top-k salient visual tokens").  score [B,V] f32, finite and >= 0.
  * kept_idx [B,k] and pruned_idx [B,V-k]: visual-local indices, each ascending.

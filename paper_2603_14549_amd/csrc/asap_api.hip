@@ -4,10 +4,20 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "asap_launch.hpp"
+
+// Scratch of asap_score_static: one array per GPU, part of the library's code object, so that the
+// call needs no allocation and no workspace from the caller.  In host code the name stands for the
+// symbol only; the device address is asked for once per device (scratch_for_device) and that pointer
+// is what the launches get.
+static __device__ __align__(256) unsigned char scratch[ASAP_STATIC_SCRATCH_BYTES];
 
 struct asap_ctx {
   int device;
+  void* static_scratch;   // device address of `scratch` on this context's GPU; null if the query failed
+  hipError_t static_scratch_err;
   char err[512];
   asap::Timer* timer;   // non-null while kernel timing is on
   hipStream_t side;     // second stream of asap_stage and its fork / join events; made on first use
@@ -26,6 +36,38 @@ asap_status fail(asap_ctx* ctx, asap_status st, const char* fmt, ...) {
     va_end(ap);
   }
   return st;
+}
+
+// Address of `scratch` on `device`, asked for once per device with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];
+bool g_scratch_known[kMaxDevices];
+
+hipError_t scratch_for_device(int device, void** out) {
+  *out = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_known[device]) {
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+  }
+  int prev = -1;
+  hipError_t e = hipGetDevice(&prev);
+  if (e != hipSuccess) return e;
+  if (prev != device && (e = hipSetDevice(device)) != hipSuccess) return e;
+  void* ptr = nullptr;
+  e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (prev != device) {
+    hipError_t e2 = hipSetDevice(prev);
+    if (e == hipSuccess) e = e2;
+  }
+  if (e != hipSuccess) return e;
+  if (ptr == nullptr) return hipErrorInvalidSymbol;
+  g_scratch_ptr[device] = ptr;
+  g_scratch_known[device] = true;
+  *out = ptr;
+  return hipSuccess;
 }
 
 bool valid_dtype(asap_dtype t) { return t == ASAP_F32 || t == ASAP_BF16; }
@@ -116,6 +158,7 @@ asap_status asap_create(asap_ctx** out_ctx, int device) {
   asap_ctx* c = new (std::nothrow) asap_ctx;
   if (!c) return ASAP_EHIP;
   c->device = device;
+  c->static_scratch_err = scratch_for_device(device, &c->static_scratch);   // reported by asap_score_static
   c->err[0] = 0;
   c->timer = nullptr;
   c->side = nullptr;
@@ -252,6 +295,37 @@ asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, c
                     launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
                                  static_cast<char*>(workspace), static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_score launch");
+}
+
+asap_status asap_score_static(asap_ctx* ctx, const asap_params* p, const void* q_vis,
+                              const int64_t q_vis_stride[3], const void* q_txt, const int64_t q_txt_stride[3],
+                              const void* k_vis, const int64_t k_vis_stride[3], const int32_t* text_len,
+                              const float* lse_extra, float* s_raw, float* s_hat, float* score, void* stream) {
+  if (!ctx) return ASAP_EINVAL;
+  ctx->err[0] = 0;
+  char msg[128];
+  asap_status st = check_params(p, msg, sizeof(msg));
+  if (st != ASAP_OK) return fail(ctx, st, "invalid parameters: %s", msg);
+  const size_t need = score_workspace(*p).total;
+  if (need > (size_t)ASAP_STATIC_SCRATCH_BYTES)
+    return fail(ctx, ASAP_EWORKSPACE,
+                "asap_score_static: these parameters need %zu bytes of scratch, the built-in array holds %zu; "
+                "use asap_score with a workspace",
+                need, (size_t)ASAP_STATIC_SCRATCH_BYTES);
+  if (!ctx->static_scratch)
+    return fail(ctx, ASAP_EHIP, "asap_score_static: address of the built-in scratch array: %s",
+                hipGetErrorString(ctx->static_scratch_err));
+  st = score_checks(ctx, p, q_vis, q_vis_stride, q_txt, q_txt_stride, k_vis, k_vis_stride, text_len, s_raw, s_hat,
+                    score, ctx->static_scratch, ASAP_STATIC_SCRATCH_BYTES);
+  if (st != ASAP_OK) return st;
+  Strides3 qv{q_vis_stride[0], q_vis_stride[1], q_vis_stride[2]};
+  Strides3 qt{q_txt_stride[0], q_txt_stride[1], q_txt_stride[2]};
+  Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
+  return hip_result(ctx,
+                    launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
+                                 static_cast<char*>(ctx->static_scratch), static_cast<hipStream_t>(stream),
+                                 ctx->timer),
+                    "asap_score_static launch");
 }
 
 static asap_status select_checks(asap_ctx* ctx, const asap_params* p, const float* score, int32_t* kept_idx,
