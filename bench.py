@@ -60,6 +60,7 @@ def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
         "k_attn_colsum": k_vis + q_txt + 4 * B * H * V,
         "k_score": 4 * B * H * V + 16 * B * V,
         "k_select": 12 * B * V,
+        "k_score_select": 4 * B * H * V + 16 * B * V + 8 * B * V,
         "k_positions": 4 * B * k + 4 * B * (P + k + cfg.Tmax),
         "k_sim": vis_h + 8 * B * (V - k),
         "k_merge": vis_h + B * (P + T) * D * eh + out_rows * D * eh,

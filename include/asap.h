@@ -148,8 +148,8 @@ asap_status asap_score_static(asap_ctx* ctx, const asap_params* p,
                               float* s_raw, float* s_hat, float* score, void* stream /* hipStream_t */);
 
 /*
- * asap_select -- the k largest score[b,:] per image, ties to the smaller index (Fig. 3:
- * "retains top-k salient visual tokens").  score [B,V] f32, finite and >= 0.
+ * asap_select -- the k largest score[b,:] per image, ties to the smaller index (Fig. 3, first
+ * stage: only the k most salient visual tokens go on).  score [B,V] f32, finite and >= 0.
  * kept_idx [B,k] and pruned_idx [B,V-k]: visual-local indices, each ascending.
  */
 asap_status asap_select(asap_ctx* ctx, const asap_params* p, const float* score,

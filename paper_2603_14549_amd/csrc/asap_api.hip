@@ -128,6 +128,15 @@ asap_status check_strides(asap_ctx* ctx, const char* name, const int64_t* s, int
   return ASAP_OK;
 }
 
+// The kernels address the rows of one (image, head) block -- or of one image's hidden states --
+// with 32-bit byte offsets: the block, rows * stride elements of esz bytes, must stay below 2 GiB.
+asap_status check_span(asap_ctx* ctx, const char* name, int64_t rows, int64_t row_stride, int64_t esz) {
+  if (rows * row_stride * esz >= ((int64_t)1 << 31))
+    return fail(ctx, ASAP_EUNSUPPORTED, "%s: %lld rows at a stride of %lld elements span 2 GiB or more", name,
+                (long long)rows, (long long)row_stride);
+  return ASAP_OK;
+}
+
 asap_status check_workspace(asap_ctx* ctx, const asap_params* p, const void* ws, size_t bytes) {
   size_t need = asap_workspace_bytes(p);
   if (need == 0) return ASAP_OK;
@@ -277,6 +286,10 @@ static asap_status score_checks(asap_ctx* ctx, const asap_params* p, const void*
   if ((st = check_strides(ctx, "k_vis_stride", k_vis_stride, 3, 8)) != ASAP_OK) return st;
   if (q_vis_stride[2] < p->d || q_txt_stride[2] < p->d || k_vis_stride[2] < p->d)
     return fail(ctx, ASAP_EINVAL, "asap_score: row strides must be >= d");
+  const int64_t esz = dtype_size(p->qk_dtype);
+  if ((st = check_span(ctx, "q_vis", p->V, q_vis_stride[2], esz)) != ASAP_OK) return st;
+  if ((st = check_span(ctx, "q_txt", p->Tmax, q_txt_stride[2], esz)) != ASAP_OK) return st;
+  if ((st = check_span(ctx, "k_vis", p->V, k_vis_stride[2], esz)) != ASAP_OK) return st;
   return check_workspace(ctx, p, workspace, workspace_bytes);
 }
 
@@ -293,7 +306,7 @@ asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, c
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
   return hip_result(ctx,
                     launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                                 static_cast<char*>(workspace), static_cast<hipStream_t>(stream), ctx->timer),
+                                 nullptr, nullptr, static_cast<char*>(workspace), static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_score launch");
 }
 
@@ -323,7 +336,7 @@ asap_status asap_score_static(asap_ctx* ctx, const asap_params* p, const void* q
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
   return hip_result(ctx,
                     launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                                 static_cast<char*>(ctx->static_scratch), static_cast<hipStream_t>(stream),
+                                 nullptr, nullptr, static_cast<char*>(ctx->static_scratch), static_cast<hipStream_t>(stream),
                                  ctx->timer),
                     "asap_score_static launch");
 }
@@ -366,6 +379,9 @@ static asap_status merge_checks(asap_ctx* ctx, const asap_params* p, const void*
     return fail(ctx, ASAP_EINVAL, "asap_merge: hidden and out_hidden must be 16-byte aligned");
   if ((st = check_strides(ctx, "hidden_stride", hidden_stride, 2, 8)) != ASAP_OK) return st;
   if (hidden_stride[1] < p->D) return fail(ctx, ASAP_EINVAL, "asap_merge: hidden row stride must be >= D");
+  if ((st = check_span(ctx, "hidden", (int64_t)p->P + p->V + p->Tmax, hidden_stride[1], dtype_size(p->h_dtype))) !=
+      ASAP_OK)
+    return st;
   {
     const int64_t esz = dtype_size(p->h_dtype);
     const char* a0 = static_cast<const char*>(hidden);
@@ -505,9 +521,9 @@ asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io*
   Strides3 qt{io->q_txt_stride[0], io->q_txt_stride[1], io->q_txt_stride[2]};
   Strides3 kv{io->k_vis_stride[0], io->k_vis_stride[1], io->k_vis_stride[2]};
   char* ws = static_cast<char*>(io->workspace);
+  // the selection rides in the launch that finishes the score
   hipError_t e = launch_score(*p, io->q_vis, qv, io->q_txt, qt, io->k_vis, kv, io->text_len, io->lse_extra, io->s_raw,
-                              io->s_hat, io->score, ws, main, ctx->timer);
-  if (e == hipSuccess) e = launch_select(*p, io->score, io->kept_idx, io->pruned_idx, main, ctx->timer);
+                              io->s_hat, io->score, io->kept_idx, io->pruned_idx, ws, main, ctx->timer);
   bool forked = false;
   if (e == hipSuccess && early) {
     e = hipEventRecord(ctx->ev_fork, main);
@@ -587,6 +603,12 @@ asap_status asap_attention(asap_ctx* ctx, const asap_params* p, const void* q, c
   if ((st = check_strides(ctx, "v_stride", v_stride, 3, 8)) != ASAP_OK) return st;
   if (q_stride[2] < p->d || k_stride[2] < p->d || v_stride[2] < p->d)
     return fail(ctx, ASAP_EINVAL, "asap_attention: row strides must be >= d");
+  {
+    const int64_t n = (int64_t)p->P + p->V + p->Tmax, esz = dtype_size(p->qk_dtype);
+    if ((st = check_span(ctx, "q", n, q_stride[2], esz)) != ASAP_OK) return st;
+    if ((st = check_span(ctx, "k", n, k_stride[2], esz)) != ASAP_OK) return st;
+    if ((st = check_span(ctx, "v", n, v_stride[2], esz)) != ASAP_OK) return st;
+  }
   const size_t need = attention_workspace_bytes(*p);
   if (!workspace) return fail(ctx, ASAP_EINVAL, "workspace is NULL");
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)

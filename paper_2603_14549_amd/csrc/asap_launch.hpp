@@ -57,9 +57,12 @@ struct Timer {
     ::asap::Timer::end(asap_rec_, st);                                          \
   } while (0)
 
+// kept != nullptr: the top-k selection runs in the launch that finishes the score (the stage as one
+// call), writing kept [B,k] and pruned [B,V-k] exactly as launch_select would.
 hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
                         const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
-                        float* s_raw, float* s_hat, float* score, char* ws, hipStream_t st, Timer* tm);
+                        float* s_raw, float* s_hat, float* score, int32_t* kept, int32_t* pruned, char* ws,
+                        hipStream_t st, Timer* tm);
 
 hipError_t launch_select(const asap_params& p, const float* score, int32_t* kept, int32_t* pruned,
                          hipStream_t st, Timer* tm);

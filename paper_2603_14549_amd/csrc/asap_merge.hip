@@ -20,10 +20,11 @@ template <typename T, int CPT>    // CPT = 16-byte chunks of a row per thread (r
 __global__ __launch_bounds__(256) void k_merge(const T* __restrict__ hidden, int64_t sb, int64_t sr, int D,
                                                 int P, int V, int k, int M, int Tmax, float mu,
                                                 const float* __restrict__ s_hat, const int32_t* __restrict__ text_len,
-                                                const int32_t* __restrict__ kept, const int32_t* __restrict__ pruned,
+                                                const int32_t* kept /* may be final_idx */,
+                                                const int32_t* __restrict__ pruned,
                                                 const int32_t* __restrict__ assign, T* __restrict__ out,
                                                 int32_t* __restrict__ pos_out, int32_t* __restrict__ new_len,
-                                                float* __restrict__ wsum, int32_t* __restrict__ final_idx) {
+                                                float* __restrict__ wsum, int32_t* final_idx) {
   constexpr int E = elem<T>::per16;
   __shared__ int list[MERGE_SEG];
   __shared__ int wave_cnt[4];

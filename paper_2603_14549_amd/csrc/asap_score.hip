@@ -17,10 +17,13 @@
 //                 normalised column sums per key
 //   k_score       fixed-order head reduction, times lambda' (Eq. 4) in fp64, mean over heads and
 //                 text rows; also writes s_hat (Eq. 3)
+//   k_score_select  the same followed by the top-k selection of asap_select in one launch (one
+//                 workgroup per image), when the stage runs as one call
 // Logits stay in accumulator units; the factor log2(e)/sqrt(d) is applied to differences from the
 // row maximum only, so its rounding error scales with the distance from the maximum.
 #include "asap_device.hpp"
 #include "asap_launch.hpp"
+#include "asap_select.hpp"
 
 namespace asap {
 
@@ -341,7 +344,8 @@ struct AttnArgs {
 template <typename T, int RB, int CH, bool QREG> struct QueryOps;
 template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, true> {
   uint4 qa[RB][CH];
-  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char*) {
+  // rows at or past `len` (padding of a ragged batch, whatever it holds) become zero operands
+  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char*, int len) {
     const int m = lane & 31, hf = lane >> 5;
     const char* qbase = reinterpret_cast<const char*>(static_cast<const T*>(a.qt) + b * a.sq.b + h * a.sq.h) +
                         hf * 16;
@@ -350,7 +354,7 @@ template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, true> {
       const int row = rb * 32 + m;
 #pragma unroll
       for (int c = 0; c < CH; ++c)
-        qa[rb][c] = row < a.Tmax ? ldg16(qbase + (int64_t)row * a.sq.r * sizeof(T) + c * 32) : make_uint4(0, 0, 0, 0);
+        qa[rb][c] = row < len ? ldg16(qbase + (int64_t)row * a.sq.r * sizeof(T) + c * 32) : make_uint4(0, 0, 0, 0);
     }
   }
   __device__ __forceinline__ uint4 get(int rb, int c) const { return qa[rb][c]; }
@@ -359,13 +363,13 @@ template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, true> {
 template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, false> {
   static constexpr int ROWB = CH * 32, LDSROW = ROWB + 16;
   const char* qa;
-  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char* lds) {
+  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char* lds, int len) {
     const char* qbase = reinterpret_cast<const char*>(static_cast<const T*>(a.qt) + b * a.sq.b + h * a.sq.h);
     constexpr int PPR = ROWB / 16;
     for (int i = threadIdx.x; i < RB * 32 * PPR; i += 256) {
       int row = i / PPR, pc = i % PPR;
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (row < a.Tmax) v = ldg16(qbase + (int64_t)row * a.sq.r * sizeof(T) + pc * 16);
+      if (row < len) v = ldg16(qbase + (int64_t)row * a.sq.r * sizeof(T) + pc * 16);
       *reinterpret_cast<uint4*>(lds + row * LDSROW + pc * 16) = v;
     }
     __syncthreads();
@@ -404,8 +408,10 @@ __global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_st
   const int n = lane & 31, hf = lane >> 5;
   const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int g = (h * a.Hkv) / a.H;
+  const int len = min(max(a.text_len[b], 0), a.Tmax);
+  const int nrb = (len + 31) >> 5;          // row blocks that hold a valid text row of this image
   Q q;
-  q.init(a, b, h, lane, lds);
+  q.init(a, b, h, lane, lds, len);
   const double mlo = f64_unkey(a.mmkey[2 * b]), mhi = f64_unkey(a.mmkey[2 * b + 1]);
   const double minv = 1.0 / (mhi - mlo + a.eps);
   const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.kv) + b * a.sk.b + g * a.sk.h) +
@@ -434,6 +440,7 @@ __global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_st
     const bool ragged = tile * 32 + 32 > a.V;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
+      if (rb >= nrb) continue;               // wave-uniform: nothing but padding in this block
       f32x16_t acc;
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
@@ -498,7 +505,8 @@ __global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_co
   const int n = lane & 31, hf = lane >> 5;
   const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int g = (h * a.Hkv) / a.H;
-  const int len = a.text_len[b];
+  const int len = min(max(a.text_len[b], 0), a.Tmax);
+  const int nrb = (len + 31) >> 5;
   const float c2 = a.c2;
   // merged row statistics of this (image, head): fixed order over the splits
   if (tid < NR) {
@@ -517,7 +525,7 @@ __global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_co
     fin_i[tid] = row_ok ? 1.0f / s : 0.0f;
   }
   Q q;
-  q.init(a, b, h, lane, lds);
+  q.init(a, b, h, lane, lds, len);
   __syncthreads();
   float off[RB][16], inv[RB][16];
 #pragma unroll
@@ -544,6 +552,7 @@ __global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_co
     float u = 0.0f;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
+      if (rb >= nrb) continue;               // wave-uniform: padded rows add nothing
       f32x16_t acc;
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
@@ -599,6 +608,69 @@ __global__ __launch_bounds__(256) void k_score(const float* __restrict__ upart, 
     const double lam = mask_on ? fmax(lambda_max * sh, eps) : 1.0;
     s_hat[(int64_t)b * V + j] = (float)sh;
     score[(int64_t)b * V + j] = (float)(lam * u / ((double)H * (double)text_len[b]));
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// k_score_select: grid (B), 1024 threads.  Thread t owns the keys t*ipt .. t*ipt+ipt-1 of its image:
+// it reduces their per-head column sums in the order k_score uses (four interleaved head groups in
+// fp64, then ((0+1)+2)+3), so that score and s_hat come out bit-identical to k_score's, and the
+// workgroup then selects exactly as k_select does.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(SEL_THREADS) void k_score_select(const float* __restrict__ upart,
+                                                               const double* __restrict__ s64,
+                                                               const unsigned long long* __restrict__ mmkey,
+                                                               const int32_t* __restrict__ text_len, int H, int V,
+                                                               int k, double lambda_max, double eps, int mask_on,
+                                                               float* __restrict__ s_hat, float* __restrict__ score,
+                                                               int32_t* __restrict__ kept,
+                                                               int32_t* __restrict__ pruned) {
+  __shared__ SelectShared sh;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int ipt = (V + SEL_THREADS - 1) / SEL_THREADS;
+  const int i0 = tid * ipt;
+  const double lo = f64_unkey(mmkey[2 * b]), hi = f64_unkey(mmkey[2 * b + 1]);
+  const double inv = 1.0 / (hi - lo + eps);
+  const double norm = (double)H * (double)text_len[b];
+  const float* up = upart + (int64_t)b * H * V;
+  uint32_t key[SEL_IPT];
+#pragma unroll
+  for (int e = 0; e < SEL_IPT; ++e) {
+    const int j = i0 + e;
+    key[e] = 0u;
+    if (e < ipt && j < V) {
+      double part[4] = {0.0, 0.0, 0.0, 0.0};
+      int h = 0;
+      for (; h + 16 <= H; h += 16) {          // 16 loads in flight; head h adds to group h % 4, in order
+        float u[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) u[q] = up[(int64_t)(h + q) * V + j];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) part[q & 3] += (double)u[q];
+      }
+      for (; h < H; ++h) part[h & 3] += (double)up[(int64_t)h * V + j];
+      const double usum = ((part[0] + part[1]) + part[2]) + part[3];
+      const double shat = (s64[(int64_t)b * V + j] - lo) * inv;
+      const double lam = mask_on ? fmax(lambda_max * shat, eps) : 1.0;
+      const float sc = (float)(lam * usum / norm);
+      s_hat[(int64_t)b * V + j] = (float)shat;
+      score[(int64_t)b * V + j] = sc;
+      key[e] = float_key(sc);
+    }
+  }
+  int n_keep;
+  const uint32_t keep_bits = radix_topk(key, ipt, i0, V, k, sh, &n_keep);
+  int tot;
+  int kept_before = block_scan_excl(n_keep, sh.wave_sums, &tot);
+  int32_t* kout = kept + (int64_t)b * k;
+  int32_t* pout = pruned + (int64_t)b * (V - k);
+#pragma unroll
+  for (int e = 0; e < SEL_IPT; ++e) {
+    const int i = i0 + e;
+    if (e < ipt && i < V) {
+      if (keep_bits & (1u << e)) kout[kept_before++] = i;
+      else pout[i - kept_before] = i;
+    }
   }
 }
 
@@ -690,8 +762,8 @@ static hipError_t dispatch_rb(const asap_params& p, const AttnArgs& a, hipStream
 template <typename T>
 static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt,
                               Strides3 qt, const void* k_vis, Strides3 kv, const int32_t* text_len,
-                              const float* lse_extra, float* s_raw, float* s_hat, float* score, char* ws,
-                              hipStream_t st, Timer* tm) {
+                              const float* lse_extra, float* s_raw, float* s_hat, float* score, int32_t* kept,
+                              int32_t* pruned, char* ws, hipStream_t st, Timer* tm) {
   const ScoreWorkspace w = score_workspace(p);
   double* qpart = reinterpret_cast<double*>(ws + w.off_qpart);
   double* qbar = reinterpret_cast<double*>(ws + w.off_qbar);
@@ -746,19 +818,24 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
     e = hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;
-  ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
-              p.H, p.V, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
+  if (kept != nullptr)
+    ASAP_LAUNCH(tm, "k_score_select", k_score_select, dim3(p.B), dim3(SEL_THREADS), 0, st, upart, s64, mmkey,
+                text_len, p.H, p.V, p.k, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score, kept, pruned);
+  else
+    ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
+                p.H, p.V, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
   return hipGetLastError();
 }
 
 hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
                         const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
-                        float* s_raw, float* s_hat, float* score, char* ws, hipStream_t st, Timer* tm) {
+                        float* s_raw, float* s_hat, float* score, int32_t* kept, int32_t* pruned, char* ws,
+                        hipStream_t st, Timer* tm) {
   if (p.qk_dtype == ASAP_BF16)
     return score_typed<bf16_t>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                               ws, st, tm);
-  return score_typed<float>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score, ws,
-                            st, tm);
+                               kept, pruned, ws, st, tm);
+  return score_typed<float>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score, kept,
+                            pruned, ws, st, tm);
 }
 
 }  // namespace asap

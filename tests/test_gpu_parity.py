@@ -52,6 +52,37 @@ def test_ranking_by_the_last_text_token(ctx, name):
     U.run_and_compare(synth.CONFIGS[name], ctx=ctx, last_token=True)
 
 
+@pytest.mark.parametrize("base,Tmax,text_lo", [("S1", 24, 3), ("S2", 40, 5), ("S2", 100, 30), ("S0", 128, 20)])
+def test_padded_text_rows_may_hold_anything(ctx, base, Tmax, text_lo):
+    """Rows of a ragged text block at or past text_len[b] are padding: a two-stage pipeline leaves
+    them unwritten.  NaNs there (queries and hidden states) must change nothing, bit for bit."""
+    cfg = dataclasses.replace(synth.CONFIGS[base], Tmax=Tmax, ragged_text=True, text_lo=text_lo, B=3,
+                              name=f"{base}pad{Tmax}")
+    inp = synth.make_inputs(cfg)
+    assert int(inp["text_len"].min()) < Tmax
+    clean = U.GpuStage(inp, ctx=ctx).run()
+    names = ("s_raw", "s_hat", "score", "kept_idx", "pruned_idx", "assign", "best_sim", "wsum", "pos_out", "new_len")
+    ref = {n: getattr(clean, n).clone() for n in names}
+    ref_rows = clean.out_hidden.clone()
+    dirty = dict(inp)
+    dirty["q"], dirty["hidden"] = inp["q"].copy(), inp["hidden"].copy()
+    nan_q = np.uint16(0x7FC0) if cfg.qk_dtype == "bf16" else np.float32("nan")
+    nan_h = np.uint16(0x7FC0) if cfg.h_dtype == "bf16" else np.float32("nan")
+    for b in range(cfg.B):
+        first_pad = cfg.P + cfg.V + int(inp["text_len"][b])
+        dirty["q"][b, :, first_pad:] = nan_q
+        dirty["hidden"][b, first_pad:] = nan_h
+    st = U.GpuStage(dirty, ctx=ctx)
+    got = st.run()
+    for n in names:
+        a, r = getattr(got, n), ref[n]
+        assert torch.equal(a.view(torch.int32), r.view(torch.int32)), n
+    for b in range(cfg.B):
+        nl = int(got.new_len[b])
+        assert torch.equal(got.out_hidden[b, :nl].view(torch.uint8), ref_rows[b, :nl].view(torch.uint8))
+    U.compare_image(dirty, got, 0, U.oracle_image(dirty, 0))
+
+
 def test_reduction_to_plain_topk_pruning(ctx):
     """Mask off and merge weight 0: the output is a pure gather of the top-k rows."""
     cfg = synth.CONFIGS["S2"]
@@ -245,6 +276,17 @@ def test_determinism(ctx):
 def test_positions_and_two_stream_stage(ctx):
     """asap_positions writes what asap_merge writes, and the stage gives bit-identical results on one
     stream and on two, as one asap_stage call and as the sequence of single calls."""
+    # more than 1024 visual tokens: several keys per thread in the selection, which asap_stage runs in
+    # the launch that finishes the score and the single calls run on their own
+    big = dataclasses.replace(synth.CONFIGS["S2"], V=2500, k=300, B=2, H=4, Hkv=2, D=128, name="S2wide")
+    inp_big = synth.make_inputs(big)
+    one, calls = U.GpuStage(inp_big, ctx=ctx).run(), U.GpuStage(inp_big, ctx=ctx, call_by_call=True).run()
+    for name in ("s_raw", "s_hat", "score", "kept_idx", "pruned_idx", "assign", "best_sim", "wsum", "final_idx",
+                 "pos_out", "new_len"):
+        assert torch.equal(getattr(one, name), getattr(calls, name)), name
+    assert torch.equal(one.out_hidden.view(torch.uint8), calls.out_hidden.view(torch.uint8))
+    U.compare_image(inp_big, one, 1, U.oracle_image(inp_big, 1))
+
     cfg = synth.CONFIGS["S1"]
     inp = synth.make_inputs(cfg)
     serial = U.GpuStage(inp, ctx=ctx, overlap=False, call_by_call=True)
@@ -442,6 +484,22 @@ def test_strided_views_and_errors(ctx):
     with pytest.raises(binding.AsapError) as e:       # K/V destination aliasing a source
         ctx.asap_compact_kv(p, st.k_cache, st.v_cache, st.k_cache, buf.v_dst, buf.pos_out, buf.new_len)
     assert e.value.status == binding.ASAP_EINVAL
+    # rows of one (image, head) block are addressed with 32-bit byte offsets: a view whose rows span
+    # 2 GiB or more is refused (the strides are only looked at, the memory behind them never is)
+    class FarRows:
+        def __init__(self, t, row_stride):
+            self.t, self.row_stride = t, row_stride
+        def data_ptr(self): return self.t.data_ptr()
+        def stride(self, i): return self.row_stride if i in (2, -2) else self.t.stride(i)
+    buf.score.fill_(-3.0)
+    torch.cuda.synchronize()
+    q_vis, q_txt, k_vis = st.q[:, :, cfg.P:cfg.P + cfg.V], st.q[:, :, cfg.P + cfg.V:], st.k[:, :, cfg.P:cfg.P + cfg.V]
+    with pytest.raises(binding.AsapError) as e:
+        ctx.asap_score(p, q_vis, q_txt, FarRows(k_vis, 1 << 23), st.text_len, None, buf.s_raw, buf.s_hat, buf.score,
+                       buf.workspace)
+    assert e.value.status == binding.ASAP_EUNSUPPORTED and "k_vis" in str(e.value)
+    torch.cuda.synchronize()
+    assert bool((buf.score == -3.0).all())
     st.run()                                           # the context still works afterwards
 
 
