@@ -58,6 +58,9 @@ def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
         "k_mass": k_vis + 12 * B * V,
         "k_attn_stats": k_vis + q_txt + 8 * B * V,
         "k_attn_colsum": k_vis + q_txt + 4 * B * H * V,
+        "k_mass_finish": 20 * B * V,
+        "k_rowstats_logits": 4 * B * H * V + 8 * B * V,
+        "k_colsum_logits": 8 * B * H * V,
         "k_score": 4 * B * H * V + 16 * B * V,
         "k_select": 12 * B * V,
         "k_score_select": 4 * B * H * V + 16 * B * V + 8 * B * V,
@@ -207,7 +210,7 @@ def main():
                     help="keep the K/V caches as pools of PAGE_SIZE-token pages with block tables and compact them "
                          "with asap_compact_kv_paged (0 = contiguous caches, the headline workload)")
     ap.add_argument("--last-token", action="store_true",
-                    help="rank the visual tokens by the last text token's row alone (scoring call with Tmax = 1)")
+                    help="rank the visual tokens by the last text token's row alone (score_rows = ASAP_ROWS_LAST)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="accepted for the counter runs documented in profiles/: the 1 GiB device copies that "

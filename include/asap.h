@@ -59,6 +59,12 @@ typedef enum { ASAP_MASK_OFF = 0, ASAP_MASK_KEYBIAS = 1 } asap_mask_mode;
  * PAPER needs k <= V / 2. */
 typedef enum { ASAP_ROUTE_ABSORB = 0, ASAP_ROUTE_PAPER = 1 } asap_route;
 
+/* Which text rows rank the visual tokens (Sec. 4.1 leaves it open).
+ * ALL:  the mean over every valid text row (rows 0 .. text_len[b]-1 of q_txt).
+ * LAST: the last valid text token's row alone (row text_len[b]-1), the criterion of plain
+ *       attention-score pruning, the first rung of the ablation in Sec. 5.3. */
+typedef enum { ASAP_ROWS_ALL = 0, ASAP_ROWS_LAST = 1 } asap_score_rows;
+
 typedef struct {
   int32_t B;        /* images in the batch                                   >= 1 */
   int32_t H;        /* query heads                                                */
@@ -78,6 +84,7 @@ typedef struct {
   float merge_weight;    /* mu >= 0 on the source terms of Eq. 6; 1 = Eq. 6, 0 = no merging */
   asap_mask_mode mask_mode;
   asap_route route;
+  asap_score_rows score_rows;
 } asap_params;
 
 /* Context for one device.  [host] pointers.  asap_create checks that `device` exists and
@@ -104,6 +111,7 @@ size_t asap_workspace_bytes(const asap_params* p);
  *   A[b,h,t,j] = lam_j exp(z_tj) / (sum_j' lam_j' exp(z_tj') + exp(lse_extra[b,h,t])),
  *                z_tj = q_txt[b,h,t,:] . k_vis[b,g(h),j,:] / sqrt(d)                        (Eq. 5, text rows)
  *   score[b,j] = 1/(H text_len[b]) * sum_h sum_{t<text_len[b]} A[b,h,t,j]
+ *                (ASAP_ROWS_LAST: the one row t = text_len[b]-1, and 1/H in front)
  * q_vis [B,H,V,d], q_txt [B,H,Tmax,d], k_vis [B,Hkv,V,d] in qk_dtype; each *_stride[3] gives
  * the element strides of the three outer dims (last dim contiguous) so that the three may be
  * views into [B,heads,N,d] tensors.  Pointers 16-byte aligned, strides multiples of 8 elements.
@@ -111,11 +119,10 @@ size_t asap_workspace_bytes(const asap_params* p);
  * logits over its NON-visual keys (then A is the full-row softmax of Eq. 5); NULL drops that term.
  * Outputs s_raw, s_hat, score: [B,V] f32, contiguous.  Sums are carried in fp64 up to the
  * final rounding of s_raw / s_hat, and per-row softmax terms in fp32.
- * Which text rows rank the visual tokens is the caller's choice of q_txt: Sec. 4.1 does not fix
- * it and the mean over all valid rows is what the description above gives.  To rank by the
- * last text token alone, pass that row of every image as a [B,H,1,d] q_txt, a text_len of
- * ones, and a copy of the params with Tmax = 1 (this call only; the workspace must then
- * satisfy asap_workspace_bytes() of both params).
+ * Rows of q_txt at or past text_len[b] are padding: they are never used, whatever they hold.
+ * When the rows that rank are few (ASAP_ROWS_LAST, or (H / Hkv) * Tmax <= 28 with bf16 keys), their
+ * logits are taken in the sweep that computes s and kept in the workspace, and the keys are read
+ * twice instead of three times.
  */
 asap_status asap_score(asap_ctx* ctx, const asap_params* p,
                        const void* q_vis, const int64_t q_vis_stride[3],

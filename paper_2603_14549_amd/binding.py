@@ -19,6 +19,7 @@ ASAP_OK, ASAP_EINVAL, ASAP_EUNSUPPORTED, ASAP_EWORKSPACE, ASAP_EHIP = 0, 1, 2, 3
 ASAP_F32, ASAP_BF16 = 0, 1
 ASAP_MASK_OFF, ASAP_MASK_KEYBIAS = 0, 1
 ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
+ASAP_ROWS_ALL, ASAP_ROWS_LAST = 0, 1
 
 EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
            "asap_score", "asap_score_static", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv",
@@ -38,7 +39,7 @@ class asap_params(ctypes.Structure):
                 ("qk_dtype", ctypes.c_int), ("h_dtype", ctypes.c_int), ("kv_dtype", ctypes.c_int),
                 ("lambda_max", ctypes.c_float), ("eps", ctypes.c_float), ("sim_threshold", ctypes.c_float),
                 ("merge_weight", ctypes.c_float),
-                ("mask_mode", ctypes.c_int), ("route", ctypes.c_int)]
+                ("mask_mode", ctypes.c_int), ("route", ctypes.c_int), ("score_rows", ctypes.c_int)]
 
 
 class asap_stage_io(ctypes.Structure):
@@ -137,9 +138,10 @@ def load() -> ctypes.CDLL:
 
 def make_params(B, H, Hkv, d, D, P, V, Tmax, k, qk_dtype, h_dtype, kv_dtype, lambda_max=1.0, eps=1e-6,
                 sim_threshold=float("-inf"), merge_weight=1.0, mask_mode=ASAP_MASK_KEYBIAS,
-                route=ASAP_ROUTE_ABSORB) -> asap_params:
+                route=ASAP_ROUTE_ABSORB, score_rows=ASAP_ROWS_ALL) -> asap_params:
     return asap_params(B, H, Hkv, d, D, P, V, Tmax, k, _DTYPE_CODE[qk_dtype], _DTYPE_CODE[h_dtype],
-                       _DTYPE_CODE[kv_dtype], lambda_max, eps, sim_threshold, merge_weight, mask_mode, route)
+                       _DTYPE_CODE[kv_dtype], lambda_max, eps, sim_threshold, merge_weight, mask_mode, route,
+                       score_rows)
 
 
 def params_from_config(cfg, **overrides) -> asap_params:

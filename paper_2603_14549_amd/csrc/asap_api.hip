@@ -96,6 +96,7 @@ asap_status check_params(const asap_params* p, char* msg, size_t n) {
   BAD(!(p->merge_weight >= 0.0f) || !isfinite(p->merge_weight), "merge_weight must be finite and >= 0");
   BAD(p->mask_mode != ASAP_MASK_OFF && p->mask_mode != ASAP_MASK_KEYBIAS, "unknown mask_mode");
   BAD(p->route != ASAP_ROUTE_ABSORB && p->route != ASAP_ROUTE_PAPER, "unknown route");
+  BAD(p->score_rows != ASAP_ROWS_ALL && p->score_rows != ASAP_ROWS_LAST, "unknown score_rows");
   BAD(p->route == ASAP_ROUTE_PAPER && 2 * (int64_t)p->k > p->V, "ASAP_ROUTE_PAPER needs k <= V / 2 (the vacated slots are refilled from the pruned tokens)");
   BAD((int64_t)p->B * p->Hkv > 65535 || (int64_t)p->B * p->H > 65535, "B * heads must be <= 65535");
 #undef BAD

@@ -5,20 +5,32 @@
 //   k_qsum        column sums of the visual queries per (image, head[, row chunk]); rows are added
 //                 eight at a time in fp32, the eights in fp64
 //   k_qsplit      fixed-order sum of those partials per kv head (fp64), also split into four bf16
-//                 pieces per component (32 significant bits) for the matrix-core form of k_mass
-//   k_mass        s_j = sum_g qbar_g . k_{g,j} / (H sqrt d)  (Eq. 2 by linearity) and the per-image
-//                 min / max of s through order-preserving integer atomics.  bf16 keys: the four
-//                 pieces of qbar are four query rows of an MFMA tile, products are exact, one head's
-//                 128 products are added in fp32 and everything above that in fp64.  f32 keys: fp64
-//                 FMAs on the vector ALUs.
+//                 pieces per component (32 significant bits) for the matrix cores
+//   k_mass_mfma   s_j = sum_g qbar_g . k_{g,j} / (H sqrt d)  (Eq. 2 by linearity) and the per-image
+//                 min / max of s through order-preserving integer atomics.  The four pieces of
+//                 qbar are four query rows of an MFMA tile; bf16 keys enter as they are, f32 keys
+//                 as three bf16 pieces each (hi + mid + lo = the key to 2^-27), so every product is
+//                 exact; one head's 128 products per piece pair are added in fp32 by the matrix
+//                 instruction, everything above that in fp64.
+//                 When the text rows that rank the tokens are few (rows of a kv head's query heads
+//                 <= 28, bf16), they ride in the free rows of that tile: the sweep then also leaves
+//                 their raw logits in the workspace, and no further sweep over the keys is needed.
+//                 Small batches cut the kv heads into groups with workgroups of their own, which
+//                 leave partial masses; k_mass_finish adds them and takes min / max.
+//   either the two sweeps over the keys
 //   k_attn_stats  per (image, head, key split): key x text-query logits on the matrix cores (keys as
 //                 tile rows, so a lane owns one text row), online (max, sum) of lambda'_j 2^z per row
 //   k_attn_colsum the sweep again with queries as tile rows and the merged row statistics:
 //                 normalised column sums per key
+//   or, from stored logits,
+//   k_rowstats_logits / k_colsum_logits   the same two reductions over the [rows, V] logits
 //   k_score       fixed-order head reduction, times lambda' (Eq. 4) in fp64, mean over heads and
 //                 text rows; also writes s_hat (Eq. 3)
 //   k_score_select  the same followed by the top-k selection of asap_select in one launch (one
 //                 workgroup per image), when the stage runs as one call
+// f32 queries and keys reach the bf16 matrix instructions as three bf16 pieces each; a logit is the
+// sum of the six piece products that matter (hi.hi, hi.mid, mid.hi, mid.mid, hi.lo, lo.hi: what is
+// left out is below 2^-25 of sum |q_c k_c|, half a unit of the fp32 accumulation itself).
 // Logits stay in accumulator units; the factor log2(e)/sqrt(d) is applied to differences from the
 // row maximum only, so its rounding error scales with the distance from the maximum.
 #include "asap_device.hpp"
@@ -48,6 +60,44 @@ __device__ __forceinline__ void split_bf16x4(double x, uint16_t* out, int stride
     out[p * stride] = (uint16_t)bits;
     rest -= (double)bf16_bits_to_f32(bits);
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// Eight consecutive f32 values (two 16-byte chunks) as three bf16x8 operands: hi = rne(x),
+// mid = rne(x - hi), lo = rne(x - hi - mid); the differences are exact, |x - hi - mid - lo| <= 2^-27 |x|.
+// ------------------------------------------------------------------------------------------
+typedef __bf16 sc_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float sc_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_bf16(float a, float b) {
+  sc_f32x2 x = {a, b};
+  sc_bf16x2 y = __builtin_convertvector(x, sc_bf16x2);
+  uint32_t u;
+  __builtin_memcpy(&u, &y, 4);
+  return u;
+}
+struct Split3 { uint4 hi, mid, lo; };
+__device__ __forceinline__ void split_pair(float a, float b, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
+  hi = pk_bf16(a, b);
+  const float ra = a - __uint_as_float(hi << 16), rb = b - __uint_as_float(hi & 0xffff0000u);
+  mid = pk_bf16(ra, rb);
+  lo = pk_bf16(ra - __uint_as_float(mid << 16), rb - __uint_as_float(mid & 0xffff0000u));
+}
+__device__ __forceinline__ Split3 split_f32x8(const uint4& c0, const uint4& c1) {
+  Split3 s;
+  split_pair(__uint_as_float(c0.x), __uint_as_float(c0.y), s.hi.x, s.mid.x, s.lo.x);
+  split_pair(__uint_as_float(c0.z), __uint_as_float(c0.w), s.hi.y, s.mid.y, s.lo.y);
+  split_pair(__uint_as_float(c1.x), __uint_as_float(c1.y), s.hi.z, s.mid.z, s.lo.z);
+  split_pair(__uint_as_float(c1.z), __uint_as_float(c1.w), s.hi.w, s.mid.w, s.lo.w);
+  return s;
+}
+// the six piece products of one contraction group: the small ones into acc_l, smallest first
+__device__ __forceinline__ void mma_split(f32x16_t& acc_h, f32x16_t& acc_l, const Split3& a, const Split3& b) {
+  mma32<bf16_t>(acc_l, a.lo, b.hi);
+  mma32<bf16_t>(acc_l, a.hi, b.lo);
+  mma32<bf16_t>(acc_l, a.mid, b.mid);
+  mma32<bf16_t>(acc_l, a.mid, b.hi);
+  mma32<bf16_t>(acc_l, a.hi, b.mid);
+  mma32<bf16_t>(acc_h, a.hi, b.hi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -127,10 +177,6 @@ __global__ void k_qsplit(const double* __restrict__ qpart, double* __restrict__ 
   split_bf16x4(s, qsplit + ((int64_t)b * Hkv + g) * 4 * d + c, d);
 }
 
-// ------------------------------------------------------------------------------------------
-// k_mass (vector-ALU form, f32 keys): grid (ceil(V/32), B), 256 threads, dynamic LDS = Hkv*d doubles
-// (qbar of the image, stored so that lanes with consecutive pieces read consecutive 16 bytes).
-// ------------------------------------------------------------------------------------------
 __device__ __forceinline__ void publish_minmax(unsigned long long kmin, unsigned long long kmax, bool active,
                                                unsigned long long* blk_mm, unsigned long long* mmkey, int b) {
   if (active) {
@@ -144,163 +190,172 @@ __device__ __forceinline__ void publish_minmax(unsigned long long kmin, unsigned
   }
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void k_mass(const T* __restrict__ kv, Strides3 sk, const double* __restrict__ qbar,
-                                               int Hkv, int V, int d, double scale, double* __restrict__ s64,
-                                               float* __restrict__ s_raw, unsigned long long* __restrict__ mmkey) {
-  constexpr int E = elem<T>::per16;
-  constexpr int JT = 32;
-  extern __shared__ __align__(16) double qb_s[];
-  __shared__ unsigned long long blk_mm[2];
-  const int LPR = d / E, RPI = 256 / LPR, NP = JT / RPI;   // NP passes of RPI rows
-  const int tid = threadIdx.x, piece = tid % LPR, r0 = tid / LPR;
-  const int b = blockIdx.y, j0 = blockIdx.x * JT;
-  // qb_s[g][e / 2][piece][e % 2]: element e of piece `piece`
-  for (int i = tid; i < Hkv * d; i += 256) {
-    int g = i / d, col = i % d, pc = col / E, e = col % E;
-    qb_s[g * d + (e >> 1) * (LPR * 2) + pc * 2 + (e & 1)] = qbar[(int64_t)b * Hkv * d + i];
-  }
-  if (tid == 0) { blk_mm[0] = ~0ull; blk_mm[1] = 0ull; }
-  __syncthreads();
-  double acc[4] = {0.0, 0.0, 0.0, 0.0};
-  const char* base = reinterpret_cast<const char*>(kv + b * sk.b + piece * E);
-  const int64_t rowb = sk.r * (int64_t)sizeof(T), headb = sk.h * (int64_t)sizeof(T);
-  int rows[4];
-#pragma unroll
-  for (int p = 0; p < 4; ++p) rows[p] = min(j0 + p * RPI + r0, V - 1);
-  constexpr int GU = 4;                                // kv heads in flight
-  for (int g0 = 0; g0 < Hkv; g0 += GU) {
-    uint4 ch[GU][4];
-#pragma unroll
-    for (int u = 0; u < GU; ++u)
-#pragma unroll
-      for (int p = 0; p < 4; ++p)
-        if (p < NP && g0 + u < Hkv) ch[u][p] = ldg16(base + (g0 + u) * headb + rows[p] * rowb);
-#pragma unroll
-    for (int u = 0; u < GU; ++u) {
-      if (g0 + u < Hkv) {
-        double qb[E];
-        const double* qs = qb_s + (g0 + u) * d + piece * 2;
-#pragma unroll
-        for (int e = 0; e < E; e += 2) {
-          double2 t2 = *reinterpret_cast<const double2*>(qs + (e >> 1) * (LPR * 2));
-          qb[e] = t2.x;
-          qb[e + 1] = t2.y;
-        }
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          if (p < NP) {
-            float f[E];
-            unpack16<T>(ch[u][p], f);
-#pragma unroll
-            for (int e = 0; e < E; ++e) acc[p] = fma(qb[e], (double)f[e], acc[p]);
-          }
-        }
-      }
-    }
-  }
-  unsigned long long kmin = ~0ull, kmax = 0ull;
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    if (p < NP) {
-      double a = acc[p];
-      for (int off = LPR >> 1; off > 0; off >>= 1) a += shfl_xor_f64(a, off);
-      int row = j0 + p * RPI + r0;
-      if (piece == 0 && row < V) {
-        double s = a * scale;
-        s64[(int64_t)b * V + row] = s;
-        s_raw[(int64_t)b * V + row] = (float)s;
-        unsigned long long key = f64_key(s);
-        kmin = key < kmin ? key : kmin;
-        kmax = key > kmax ? key : kmax;
-      }
-    }
-  }
-  publish_minmax(kmin, kmax, piece == 0, blk_mm, mmkey, b);
-}
+// A lane's share of one contraction group (8 elements): one 16-byte chunk of bf16, two of f32.
+template <typename T> struct group_bytes;
+template <> struct group_bytes<bf16_t> { static constexpr int value = 16; };
+template <> struct group_bytes<float> { static constexpr int value = 32; };
 
-// One key of a 32-key tile per lane pair in the matrix-core operand layout: lane (n, hf) takes the
-// 16-byte pieces 2c + hf (c < CH) of key n.  CH = 16-byte chunks of a row per lane half (d = 16*CH).
-template <int CH>
-__device__ __forceinline__ void load_key_tile(uint4 (&kb)[CH], const char* krow) {
-#pragma unroll
-  for (int c = 0; c < CH; ++c) kb[c] = ldg16(krow + c * 32);
-}
+// Text rows that ride in the mass sweep (bf16 only).  Rows 4 .. 4 + R - 1 of the A tile of kv head g
+// hold text row t = r % T_eff of query head g G + r / T_eff; their logits against every key go to
+// zlog [B, H, T_eff, V].
+struct RideArgs {
+  const void* qt; Strides3 sq;      // [B,H,Tmax,d]
+  const int32_t* text_len;          // [B]
+  float* zlog;
+  int H, G, T_eff, Tmax, last_only;
+};
 
 // ------------------------------------------------------------------------------------------
-// k_mass_mfma (bf16 keys): grid (ceil(V/32), B), 256 threads = 4 waves.  A workgroup owns one
-// 32-key tile; wave w walks the kv heads g = w, w + 4, ...  The four bf16 pieces of qbar_g are rows
-// 0..3 of the MFMA A tile (rows 4..31 are zero), the keys are the B tile, so lane n (< 32) finds
-// the four partial dot products of key n in its first four accumulator registers.
-// The tile of a head is an isolated 8 KiB piece of memory, and reading such pieces in the operand
-// pattern (32 rows x 32 bytes per instruction) was measured at 4.2 TB/s against 6.0 TB/s for whole
-// rows.  So a wave reads whole rows (2 CH consecutive lanes per row) and turns the tile into the
-// operand layout through an LDS buffer of its own -- written and read by the same wave, in order, so
-// no barrier is involved.  CH = 16-byte chunks of a row per lane half (d = 16 CH).
+// k_mass_mfma: grid (ceil(V/32), B * HS), 256 threads = 4 waves.  A workgroup owns one 32-key tile
+// and the kv heads of group hs (Hkv / HS of them); wave w walks the heads g_lo + w, g_lo + w + 4, ...
+// The four bf16 pieces of qbar_g are rows 0..3 of the MFMA A tile (rows 4..31 are zero, or text
+// rows that ride along), the keys are the B tile, so lane n (< 32) finds the four partial dot
+// products of key n in its first four accumulator registers.
+// The tile of a head is an isolated piece of memory (8 KiB for bf16, d = 128), and reading such
+// pieces in the operand pattern (32 rows x 32 bytes per instruction) was measured at 4.2 TB/s against
+// 6.0 TB/s for whole rows.  So a wave reads whole rows (LPR consecutive lanes per row) and turns the
+// tile into the operand layout through an LDS buffer of its own -- written and read by the same
+// wave, in order, so no barrier is involved.  NG = contraction groups of 8 elements (d = 16 NG).
+// HS == 1: writes s64, s_raw and publishes min / max; HS > 1: writes the group's partial mass to
+// spart [HS, B, V] for k_mass_finish.
 // ------------------------------------------------------------------------------------------
-template <int CH>
-__global__ __launch_bounds__(256) void k_mass_mfma(const bf16_t* __restrict__ kv, Strides3 sk,
-                                                    const uint16_t* __restrict__ qsplit, int Hkv, int V,
+template <typename T, int NG, bool RIDE>
+__global__ __launch_bounds__(256) void k_mass_mfma(const T* __restrict__ kv, Strides3 sk,
+                                                    const uint16_t* __restrict__ qsplit, int Hkv, int V, int HS,
                                                     double scale, double* __restrict__ s64, float* __restrict__ s_raw,
-                                                    unsigned long long* __restrict__ mmkey) {
-  constexpr int D = CH * 16, RB = 32 * CH;          // row bytes
-  constexpr int LPR = 2 * CH, RPI = 64 / LPR;        // lanes per row, rows per load instruction
-  __shared__ __align__(16) char stage[4][32 * RB];
+                                                    unsigned long long* __restrict__ mmkey,
+                                                    double* __restrict__ spart, RideArgs ra) {
+  constexpr int GB = group_bytes<T>::value;
+  constexpr int RBY = NG * 2 * GB;                    // row bytes
+  constexpr int LPR = RBY / 16, RPI = 64 / LPR;       // lanes per row, rows per load instruction
+  constexpr int NL = 32 / RPI;                        // load instructions per tile
+  constexpr int NC = GB / 16;                         // 16-byte chunks per group and lane
+  constexpr bool F32 = GB == 32;
+  static_assert(!RIDE || !F32, "text rows ride with bf16 keys only");
+  __shared__ __align__(16) char stage[4][32 * RBY];
   __shared__ double part[4][32];
   __shared__ unsigned long long blk_mm[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hf = lane >> 5;
   const int piece = lane % LPR, r0 = lane / LPR;
-  const int b = blockIdx.y, j0 = blockIdx.x * 32;
+  const int b = blockIdx.y / HS, hs = blockIdx.y % HS, j0 = blockIdx.x * 32;
+  const int g_lo = hs * (Hkv / HS), g_hi = g_lo + Hkv / HS;
   if (tid == 0) { blk_mm[0] = ~0ull; blk_mm[1] = 0ull; }
-  const int64_t headb = sk.h * 2;
+  const int64_t headb = sk.h * (int64_t)sizeof(T);
   // LDS: the 16-byte piece p of row r sits in slot p ^ x(r): whole-row writes and operand reads of 16
   // consecutive rows both cover all banks
-  auto swz = [](int row) { return RB <= 128 ? (row >> 1) & 7 : row & 15; };
+  auto swz = [](int row) { return LPR == 8 ? (row >> 1) & 7 : row & (LPR - 1); };
   char* st = stage[wave];
-  uint32_t roff[CH];          // byte offsets inside one head of one image (< 4 GiB)
-  int wr[CH];
+  uint32_t roff[NL];          // byte offsets inside one head of one image (< 2 GiB, checked on the host)
+  int wr[NL];
 #pragma unroll
-  for (int i = 0; i < CH; ++i) {
+  for (int i = 0; i < NL; ++i) {
     const int row = r0 + RPI * i;
-    roff[i] = (uint32_t)(min(j0 + row, V - 1) * (int)sk.r * 2 + piece * 16);
-    wr[i] = row * RB + ((piece ^ swz(row)) << 4);
+    roff[i] = (uint32_t)(min(j0 + row, V - 1) * (int)sk.r * (int)sizeof(T) + piece * 16);
+    wr[i] = row * RBY + ((piece ^ swz(row)) << 4);
   }
-  // operand read c: piece (2c + hf) ^ x(n) of row n = rd0 ^ 32 c (the row offset has no low bits set)
-  const int rd0 = n * RB + ((hf ^ swz(n)) << 4);
+  // operand read (c, u): piece NC (2c + hf) + u of row n
+  int rd[NG][NC];
+#pragma unroll
+  for (int c = 0; c < NG; ++c)
+#pragma unroll
+    for (int u = 0; u < NC; ++u) rd[c][u] = n * RBY + (((NC * (2 * c + hf) + u) ^ swz(n)) << 4);
   const char* kbase = reinterpret_cast<const char*>(kv + b * sk.b);
-  // lane (m, hf) with m < 4 supplies piece m of qbar_g, half hf of the components
-  const char* qbase = reinterpret_cast<const char*>(qsplit + ((int64_t)b * Hkv * 4 + (n & 3)) * D) + hf * 16;
-  const int64_t qheadb = (int64_t)4 * D * 2;
+  // lane (m, hf) with m < 4 supplies piece m of qbar_g, half hf of each group's components
+  const char* qbase = reinterpret_cast<const char*>(qsplit + ((int64_t)b * Hkv * 4 + (n & 3)) * (NG * 16)) + hf * 16;
+  const int64_t qheadb = (int64_t)4 * NG * 16 * 2;
+  // text rows that ride: lane n in [4, 4 + R) supplies text row (n - 4) % T_eff of query head g G + (n - 4) / T_eff
+  int ride_rows = 0, ride_head = 0;
+  const char* tbase = nullptr;
+  bool ride_src = false;
+  if (RIDE) {
+    ride_rows = ra.G * ra.T_eff;
+    const int r = n - 4;
+    if (r >= 0 && r < ride_rows) {
+      const int len = min(max(ra.text_len[b], 0), ra.Tmax);
+      const int t = r % ra.T_eff;
+      ride_head = r / ra.T_eff;
+      const int src = ra.last_only ? len - 1 : t;
+      ride_src = ra.last_only ? len >= 1 : t < len;         // padding rows stay zero operands
+      tbase = reinterpret_cast<const char*>(static_cast<const bf16_t*>(ra.qt) + b * ra.sq.b +
+                                            (int64_t)max(src, 0) * ra.sq.r) + hf * 16;
+    }
+  }
+  const int64_t theadb = RIDE ? ra.sq.h * 2 : 0;
   const bool has_q = n < 4;
-  uint4 qa[CH], kb[CH], kn[CH];
+  auto load_a = [&](uint4 (&qa)[NG], int g) {
+    if (has_q) {
 #pragma unroll
-  for (int c = 0; c < CH; ++c) qa[c] = make_uint4(0, 0, 0, 0);
-  int g = wave;
-  if (g < Hkv) {
+      for (int c = 0; c < NG; ++c) qa[c] = ldg16(qbase + g * qheadb + c * 32);
+    } else if (RIDE && ride_src) {
+      const char* tp = tbase + (int64_t)(g * ra.G + ride_head) * theadb;
 #pragma unroll
-    for (int i = 0; i < CH; ++i) kb[i] = ldg16(kbase + g * headb + roff[i]);
-    if (has_q) load_key_tile<CH>(qa, qbase + g * qheadb);
+      for (int c = 0; c < NG; ++c) qa[c] = ldg16(tp + c * 32);
+    }
+  };
+  uint4 qa[NG], kb[NL], kn[NL];
+#pragma unroll
+  for (int c = 0; c < NG; ++c) qa[c] = make_uint4(0, 0, 0, 0);
+  int g = g_lo + wave;
+  if (g < g_hi) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i) kb[i] = ldg16(kbase + g * headb + roff[i]);
+    load_a(qa, g);
   }
   double sum = 0.0;
-  for (; g < Hkv; g += 4) {
+  for (; g < g_hi; g += 4) {
     const int gn = g + 4;
-    if (gn < Hkv) {
+    if (!F32 && gn < g_hi) {
 #pragma unroll
-      for (int i = 0; i < CH; ++i) kn[i] = ldg16(kbase + gn * headb + roff[i]);
+      for (int i = 0; i < NL; ++i) kn[i] = ldg16(kbase + gn * headb + roff[i]);
     }
 #pragma unroll
-    for (int i = 0; i < CH; ++i) *reinterpret_cast<uint4*>(st + wr[i]) = kb[i];
-    f32x16_t acc;
+    for (int i = 0; i < NL; ++i) *reinterpret_cast<uint4*>(st + wr[i]) = kb[i];
+    if (F32 && gn < g_hi) {      // 16 registers per row set: the next head's rows reuse this head's
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+      for (int i = 0; i < NL; ++i) kb[i] = ldg16(kbase + gn * headb + roff[i]);
+    }
+    if constexpr (!F32) {
+      f32x16_t acc;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) mma32<bf16_t>(acc, qa[c], *reinterpret_cast<const uint4*>(st + (rd0 ^ (32 * c))));
-    sum += ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);   // rows 0..3 (lanes < 32)
-    if (gn < Hkv) {
-      if (has_q) load_key_tile<CH>(qa, qbase + gn * qheadb);      // small, cached: not worth registers of its own
+      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
-      for (int i = 0; i < CH; ++i) kb[i] = kn[i];
+      for (int c = 0; c < NG; ++c) mma32<bf16_t>(acc, qa[c], *reinterpret_cast<const uint4*>(st + rd[c][0]));
+      sum += ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);   // rows 0..3 (lanes < 32)
+      if (RIDE) {
+        float* zl = ra.zlog + ((int64_t)(b * ra.H + g * ra.G) * ra.T_eff) * V + j0 + n;
+        if (j0 + n < V) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v >> 2) + 4 * hf + (v & 3) - 4;
+            if (r >= 0 && r < ride_rows) zl[(int64_t)r * V] = acc[v];
+          }
+        }
+      }
+    } else {
+      // key pieces as three B tiles; the accumulators of the three are added in fp64
+      f32x16_t ah, am, al;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { ah[v] = 0.0f; am[v] = 0.0f; al[v] = 0.0f; }
+#pragma unroll
+      for (int c = 0; c < NG; ++c) {
+        const Split3 k3 = split_f32x8(*reinterpret_cast<const uint4*>(st + rd[c][0]),
+                                      *reinterpret_cast<const uint4*>(st + rd[c][NC - 1]));
+        mma32<bf16_t>(al, qa[c], k3.lo);
+        mma32<bf16_t>(am, qa[c], k3.mid);
+        mma32<bf16_t>(ah, qa[c], k3.hi);
+      }
+      const double l = ((double)al[0] + (double)al[1]) + ((double)al[2] + (double)al[3]);
+      const double m = ((double)am[0] + (double)am[1]) + ((double)am[2] + (double)am[3]);
+      const double h = ((double)ah[0] + (double)ah[1]) + ((double)ah[2] + (double)ah[3]);
+      sum += (l + m) + h;
+    }
+    if (gn < g_hi) {
+      load_a(qa, gn);      // small, cached: not worth registers of its own
+      if (!F32) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) kb[i] = kn[i];
+      }
     }
   }
   if (hf == 0) part[wave][n] = sum;
@@ -308,22 +363,66 @@ __global__ __launch_bounds__(256) void k_mass_mfma(const bf16_t* __restrict__ kv
   unsigned long long kmin = ~0ull, kmax = 0ull;
   const int j = j0 + n;
   if (tid < 32 && j < V) {
-    const double s = (((part[0][n] + part[1][n]) + part[2][n]) + part[3][n]) * scale;
+    const double tot = ((part[0][n] + part[1][n]) + part[2][n]) + part[3][n];
+    if (HS == 1) {
+      const double s = tot * scale;
+      s64[(int64_t)b * V + j] = s;
+      s_raw[(int64_t)b * V + j] = (float)s;
+      kmin = kmax = f64_key(s);
+    } else {
+      spart[((int64_t)hs * gridDim.y / HS + b) * V + j] = tot;
+    }
+  }
+  if (HS == 1) publish_minmax(kmin, kmax, tid < 32, blk_mm, mmkey, b);
+}
+
+// k_mass_finish: grid (B), 1024 threads: adds the HS partial masses of every key in group order,
+// scales, writes s64 / s_raw and the image's min / max keys.
+__global__ __launch_bounds__(1024) void k_mass_finish(const double* __restrict__ spart, int HS, int B, int V,
+                                                       double scale, double* __restrict__ s64,
+                                                       float* __restrict__ s_raw,
+                                                       unsigned long long* __restrict__ mmkey) {
+  __shared__ unsigned long long blk_mm[2];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  if (tid == 0) { blk_mm[0] = ~0ull; blk_mm[1] = 0ull; }
+  __syncthreads();
+  unsigned long long kmin = ~0ull, kmax = 0ull;
+  for (int j = tid; j < V; j += 1024) {
+    double t = 0.0;
+    for (int q = 0; q < HS; ++q) t += spart[((int64_t)q * B + b) * V + j];
+    const double s = t * scale;
     s64[(int64_t)b * V + j] = s;
     s_raw[(int64_t)b * V + j] = (float)s;
-    kmin = kmax = f64_key(s);
+    const unsigned long long key = f64_key(s);
+    kmin = key < kmin ? key : kmin;
+    kmax = key > kmax ? key : kmax;
   }
-  publish_minmax(kmin, kmax, tid < 32, blk_mm, mmkey, b);
+  // wave first (1024 same-address LDS atomics would take longer than everything else here)
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const unsigned long long omin = __shfl_xor(kmin, off), omax = __shfl_xor(kmax, off);
+    kmin = omin < kmin ? omin : kmin;
+    kmax = omax > kmax ? omax : kmax;
+  }
+  if ((tid & 63) == 0) {
+    atomicMin(&blk_mm[0], kmin);
+    atomicMax(&blk_mm[1], kmax);
+  }
+  __syncthreads();
+  if (tid == 0) { mmkey[2 * b] = blk_mm[0]; mmkey[2 * b + 1] = blk_mm[1]; }
 }
 
 // ------------------------------------------------------------------------------------------
 // Text-row attention sweeps.  grid (S, H, B), 256 threads = 4 waves.
-//   RB = 32-row blocks of text queries (Tmax <= 32*RB); CH = 16-byte chunks of a row per lane half
-//   (row bytes = 32*CH); QREG: the queries stay in registers as MFMA operands (else in LDS).
+//   RB = 32-row blocks of text queries the launch provides for (Tmax <= 32 RB); the body is compiled
+//   for every block count NRB <= RB and picked by the image's own text length, so that an image
+//   with few text rows in a padded batch costs what its rows cost.
+//   NG = contraction groups of 8 elements (d = 16 NG); QREG: the queries stay in registers as MFMA
+//   operands (bf16 with at most two row blocks), else in LDS.
 // Every wave streams its own 32-key tiles of the split's key range straight from global memory:
-// lane (n, hf) of a tile reads the 16-byte pieces 2c + hf (c < CH) of key n -- the two lanes of a key
-// take 32 contiguous bytes per load, which halves the cache lines a load instruction touches -- and
-// the query side holds the same pieces of its row, so a chunk pair covers the same contraction slice.
+// lane (n, hf) of a tile reads, for group c, the bytes [GB (2c + hf), + GB) of key n (GB = 16 for
+// bf16, 32 for f32) -- the two lanes of a key take contiguous bytes, which halves the cache lines a
+// load instruction touches -- and the query side holds the same elements of its row.
 // ------------------------------------------------------------------------------------------
 struct AttnArgs {
   const void* qt; Strides3 sq;          // [B,H,Tmax,d]
@@ -334,42 +433,51 @@ struct AttnArgs {
   const float* lse_extra;               // [B,H,Tmax] or null
   float* pstat;                         // [B,H,S,2,NR]   partial (max, sum) per text row
   float* upart;                         // [B,H,V]
+  const float* zlog;                    // [B,H,T_eff,V]  stored logits (k_rowstats_logits / k_colsum_logits)
   int H, Hkv, V, Tmax, S, tiles_per_split;
+  int T_eff, last_only;                 // rows that rank: all valid text rows, or the last one alone
   float c2;                             // log2(e) / sqrt(d): accumulator units -> log2 units
   double lambda_max, eps;
   int mask_on;
 };
 
-// Query operands: registers or LDS.
-template <typename T, int RB, int CH, bool QREG> struct QueryOps;
-template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, true> {
-  uint4 qa[RB][CH];
-  // rows at or past `len` (padding of a ragged batch, whatever it holds) become zero operands
-  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char*, int len) {
+// first text row that ranks and how many do, for image b
+__device__ __forceinline__ void ranking_rows(const AttnArgs& a, int b, int& row0, int& nrows) {
+  const int len = min(max(a.text_len[b], 0), a.Tmax);
+  row0 = a.last_only ? max(len - 1, 0) : 0;
+  nrows = a.last_only ? min(len, 1) : len;
+}
+
+// Query operands: registers or LDS.  Operand row m is text row row0 + m; rows at or past nrows
+// (padding of a ragged batch, whatever it holds) are zero operands.
+template <typename T, int NRB, int NG, bool QREG> struct QueryOps;
+template <int NRB, int NG> struct QueryOps<bf16_t, NRB, NG, true> {
+  uint4 qa[NRB][NG];
+  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char*, int row0, int nrows) {
     const int m = lane & 31, hf = lane >> 5;
-    const char* qbase = reinterpret_cast<const char*>(static_cast<const T*>(a.qt) + b * a.sq.b + h * a.sq.h) +
-                        hf * 16;
+    const char* qbase = reinterpret_cast<const char*>(static_cast<const bf16_t*>(a.qt) + b * a.sq.b + h * a.sq.h +
+                                                      (int64_t)row0 * a.sq.r) + hf * 16;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
+    for (int rb = 0; rb < NRB; ++rb) {
       const int row = rb * 32 + m;
 #pragma unroll
-      for (int c = 0; c < CH; ++c)
-        qa[rb][c] = row < len ? ldg16(qbase + (int64_t)row * a.sq.r * sizeof(T) + c * 32) : make_uint4(0, 0, 0, 0);
+      for (int c = 0; c < NG; ++c)
+        qa[rb][c] = row < nrows ? ldg16(qbase + (int64_t)row * a.sq.r * 2 + c * 32) : make_uint4(0, 0, 0, 0);
     }
   }
   __device__ __forceinline__ uint4 get(int rb, int c) const { return qa[rb][c]; }
-  static constexpr size_t lds_bytes() { return 0; }
 };
-template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, false> {
-  static constexpr int ROWB = CH * 32, LDSROW = ROWB + 16;
+template <int NRB, int NG> struct QueryOps<bf16_t, NRB, NG, false> {
+  static constexpr int ROWB = NG * 32, LDSROW = ROWB + 16;
   const char* qa;
-  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char* lds, int len) {
-    const char* qbase = reinterpret_cast<const char*>(static_cast<const T*>(a.qt) + b * a.sq.b + h * a.sq.h);
+  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char* lds, int row0, int nrows) {
+    const char* qbase = reinterpret_cast<const char*>(static_cast<const bf16_t*>(a.qt) + b * a.sq.b + h * a.sq.h +
+                                                      (int64_t)row0 * a.sq.r);
     constexpr int PPR = ROWB / 16;
-    for (int i = threadIdx.x; i < RB * 32 * PPR; i += 256) {
+    for (int i = threadIdx.x; i < NRB * 32 * PPR; i += 256) {
       int row = i / PPR, pc = i % PPR;
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (row < len) v = ldg16(qbase + (int64_t)row * a.sq.r * sizeof(T) + pc * 16);
+      if (row < nrows) v = ldg16(qbase + (int64_t)row * a.sq.r * 2 + pc * 16);
       *reinterpret_cast<uint4*>(lds + row * LDSROW + pc * 16) = v;
     }
     __syncthreads();
@@ -378,7 +486,70 @@ template <typename T, int RB, int CH> struct QueryOps<T, RB, CH, false> {
   __device__ __forceinline__ uint4 get(int rb, int c) const {
     return *reinterpret_cast<const uint4*>(qa + rb * 32 * LDSROW + c * 32);
   }
-  static constexpr size_t lds_bytes() { return (size_t)RB * 32 * LDSROW; }
+};
+// f32 queries: three bf16 planes in LDS, split once per workgroup
+template <int NRB, int NG> struct QueryOps<float, NRB, NG, false> {
+  static constexpr int ROWB = NG * 32, LDSROW = ROWB + 16, PLANE = NRB * 32 * LDSROW;
+  const char* base;     // the workgroup's LDS
+  int qoff;             // this lane's operand row and half, as a byte offset
+  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char* lds, int row0, int nrows) {
+    const char* qbase = reinterpret_cast<const char*>(static_cast<const float*>(a.qt) + b * a.sq.b + h * a.sq.h +
+                                                      (int64_t)row0 * a.sq.r);
+    constexpr int PPR = ROWB / 16;         // groups of 8 elements per row
+    for (int i = threadIdx.x; i < NRB * 32 * PPR; i += 256) {
+      int row = i / PPR, pc = i % PPR;
+      Split3 s;
+      s.hi = s.mid = s.lo = make_uint4(0, 0, 0, 0);
+      if (row < nrows) {
+        const char* p = qbase + (int64_t)row * a.sq.r * 4 + pc * 32;
+        s = split_f32x8(ldg16(p), ldg16(p + 16));
+      }
+      char* dst = lds + row * LDSROW + pc * 16;
+      *reinterpret_cast<uint4*>(dst) = s.hi;
+      *reinterpret_cast<uint4*>(dst + PLANE) = s.mid;
+      *reinterpret_cast<uint4*>(dst + 2 * PLANE) = s.lo;
+    }
+    __syncthreads();
+    base = lds;
+    qoff = (lane & 31) * LDSROW + (lane >> 5) * 16;
+  }
+  // Called once per key tile: the operands are the same for every tile, and a compiler that knew it
+  // would keep all of them (12 NG NRB registers) alive across the sweep.  Only the offset is hidden
+  // from it, so that the reads stay LDS reads.
+  __device__ __forceinline__ void per_tile() { asm volatile("" : "+v"(qoff)); }
+  __device__ __forceinline__ Split3 get3(int rb, int c) const {
+    const char* p = base + qoff + rb * 32 * LDSROW + c * 32;
+    Split3 s;
+    s.hi = *reinterpret_cast<const uint4*>(p);
+    s.mid = *reinterpret_cast<const uint4*>(p + PLANE);
+    s.lo = *reinterpret_cast<const uint4*>(p + 2 * PLANE);
+    return s;
+  }
+};
+template <typename T, int RB, int NG, bool QREG> constexpr size_t query_lds_bytes() {
+  if (QREG) return 0;
+  return (size_t)RB * 32 * (NG * 32 + 16) * (sizeof(T) == 4 ? 3 : 1);
+}
+
+// A lane's share of a 32-key tile.  bf16: the chunks are the operands.  f32: the raw chunks are
+// split into pieces once per tile, which frees their registers for the next tile's loads.
+template <typename T, int NG> struct KeyTile;
+template <int NG> struct KeyTile<bf16_t, NG> {
+  uint4 op[NG];
+  __device__ __forceinline__ void load(const char* krow) {
+#pragma unroll
+    for (int c = 0; c < NG; ++c) op[c] = ldg16(krow + c * 32);
+  }
+};
+template <int NG> struct KeyTile<float, NG> {
+  uint4 raw[2 * NG];
+  __device__ __forceinline__ void load(const char* krow) {
+#pragma unroll
+    for (int c = 0; c < NG; ++c) {
+      raw[2 * c] = ldg16(krow + c * 64);
+      raw[2 * c + 1] = ldg16(krow + c * 64 + 16);
+    }
+  }
 };
 
 __device__ __forceinline__ float discount(const AttnArgs& a, int b, int j, double lo, double inv) {
@@ -393,88 +564,121 @@ __device__ __forceinline__ void merge_stat(float& m, float& s, float m2, float s
   m = M;
 }
 
+constexpr float ATT_NEG = -1e30f;
+
+// online (max, sum) update of one row block from the 16 logits a lane holds
+__device__ __forceinline__ void stats_update(f32x16_t& acc, const float (&lam)[16], bool ragged, int tile, int hf, int V,
+                                             float c2, float& m_run, float& s_run) {
+  if (ragged) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (tile * 32 + 8 * (v >> 2) + 4 * hf + (v & 3) >= V) acc[v] = ATT_NEG;
+  }
+  float mx = acc[0];
+#pragma unroll
+  for (int v = 1; v < 16; ++v) mx = fmaxf(mx, acc[v]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32));                  // both halves of the row's 32 keys
+  const float m_new = fmaxf(m_run, mx);
+  float s = s_run * fast_exp2((m_run - m_new) * c2);
+  const float off = -m_new * c2;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) s = fmaf(lam[v], fast_exp2(fmaf(acc[v], c2, off)), s);
+  s_run = s;
+  m_run = m_new;
+}
+
 // Keys are the tile rows here: lane (n, hf) owns text row rb*32 + n and finds, in accumulator
 // register v, its logit against key 8*(v/4) + 4*hf + v%4 of the tile.
-template <typename T, int RB, int CH, bool QREG>
-__global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_stats(AttnArgs a) {
+template <typename T, int RB, int NRB, int NG, bool QREG>
+__device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, int row0, int nrows) {
   constexpr int NR = RB * 32;
-  constexpr bool PREF = CH * RB <= 32;     // next key tile prefetched into a second register set
-  constexpr float NEG = -1e30f;
-  extern __shared__ __align__(16) char lds[];
-  using Q = QueryOps<T, RB, CH, QREG>;
-  float* st_m = reinterpret_cast<float*>(lds + Q::lds_bytes());   // [4][NR]
-  float* st_s = st_m + 4 * NR;                                     // [4][NR]
+  constexpr bool F32 = sizeof(T) == 4;
+  constexpr int GB = group_bytes<T>::value;
+  constexpr bool PREF = !F32 && NG * NRB <= 32;     // bf16: next key tile prefetched into a second register set
+  using Q = QueryOps<T, NRB, NG, QREG>;
+  float* st_m = reinterpret_cast<float*>(lds + query_lds_bytes<T, RB, NG, QREG>());   // [4][NR]
+  float* st_s = st_m + 4 * NR;                                                         // [4][NR]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hf = lane >> 5;
   const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int g = (h * a.Hkv) / a.H;
-  const int len = min(max(a.text_len[b], 0), a.Tmax);
-  const int nrb = (len + 31) >> 5;          // row blocks that hold a valid text row of this image
   Q q;
-  q.init(a, b, h, lane, lds, len);
+  q.init(a, b, h, lane, lds, row0, nrows);
   const double mlo = f64_unkey(a.mmkey[2 * b]), mhi = f64_unkey(a.mmkey[2 * b + 1]);
   const double minv = 1.0 / (mhi - mlo + a.eps);
   const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.kv) + b * a.sk.b + g * a.sk.h) +
-                      hf * 16;
+                      hf * GB;
   const int64_t krow_bytes = a.sk.r * (int64_t)sizeof(T);
   const int ntiles = (a.V + 31) >> 5;
   const int t_end = min(ntiles, (sp + 1) * a.tiles_per_split);
   const float c2 = a.c2;
 
-  float m_run[RB], s_run[RB];
+  float m_run[NRB], s_run[NRB];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) { m_run[rb] = NEG; s_run[rb] = 0.0f; }
+  for (int rb = 0; rb < NRB; ++rb) { m_run[rb] = ATT_NEG; s_run[rb] = 0.0f; }
 
-  uint4 kb[CH], kn[CH];
+  KeyTile<T, NG> kb, kn;
   int tile = sp * a.tiles_per_split + wave;
-  if (tile < t_end) load_key_tile<CH>(kb, kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
+  if (tile < t_end) kb.load(kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
   for (; tile < t_end; tile += 4) {
     const int j = tile * 32 + n;
     const int tnext = tile + 4;
-    if (PREF && tnext < t_end) load_key_tile<CH>(kn, kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+    if (PREF && tnext < t_end) kn.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
     // discount of key n of the tile, then handed to the lanes in accumulator order
     const float lj = j < a.V ? discount(a, b, j, mlo, minv) : 0.0f;
     float lam[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) lam[v] = __shfl(lj, 8 * (v >> 2) + 4 * hf + (v & 3));
     const bool ragged = tile * 32 + 32 > a.V;
+    if constexpr (!F32) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      if (rb >= nrb) continue;               // wave-uniform: nothing but padding in this block
-      f32x16_t acc;
+      for (int rb = 0; rb < NRB; ++rb) {
+        f32x16_t acc;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
-      for (int c = 0; c < CH; ++c) mma32<T>(acc, kb[c], q.get(rb, c));
-      if (ragged) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if (tile * 32 + 8 * (v >> 2) + 4 * hf + (v & 3) >= a.V) acc[v] = NEG;
+        for (int c = 0; c < NG; ++c) mma32<bf16_t>(acc, kb.op[c], q.get(rb, c));
+        stats_update(acc, lam, ragged, tile, hf, a.V, c2, m_run[rb], s_run[rb]);
       }
-      float mx = acc[0];
+      if (tnext < t_end) {
+        if (PREF) {
 #pragma unroll
-      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, acc[v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));                  // both halves of the row's 32 keys
-      const float m_new = fmaxf(m_run[rb], mx);
-      float s = s_run[rb] * fast_exp2((m_run[rb] - m_new) * c2);
-      const float off = -m_new * c2;
+          for (int c = 0; c < NG; ++c) kb.op[c] = kn.op[c];
+        } else {
+          kb.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+        }
+      }
+    } else {
+      // group by group: a key group is split once and meets every row block, whose accumulators
+      // stay alive across the groups; the next tile's rows land in the second register set meanwhile
+      if (tnext < t_end) kn.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+      q.per_tile();
+      f32x16_t acc[NRB], acl[NRB];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s = fmaf(lam[v], fast_exp2(fmaf(acc[v], c2, off)), s);
-      s_run[rb] = s;
-      m_run[rb] = m_new;
-    }
-    if (tnext < t_end) {
-      if (PREF) {
+      for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-        for (int c = 0; c < CH; ++c) kb[c] = kn[c];
-      } else {
-        load_key_tile<CH>(kb, kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+        for (int v = 0; v < 16; ++v) { acc[rb][v] = 0.0f; acl[rb][v] = 0.0f; }
+#pragma unroll
+      for (int c = 0; c < NG; ++c) {
+        const Split3 ks = split_f32x8(kb.raw[2 * c], kb.raw[2 * c + 1]);
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) mma_split(acc[rb], acl[rb], ks, q.get3(rb, c));
+      }
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[rb][v] += acl[rb][v];
+        stats_update(acc[rb], lam, ragged, tile, hf, a.V, c2, m_run[rb], s_run[rb]);
+      }
+      if (tnext < t_end) {
+#pragma unroll
+        for (int c = 0; c < 2 * NG; ++c) kb.raw[c] = kn.raw[c];
       }
     }
   }
   // the two halves of a wave share the row maximum: their sums just add; then the 4 waves
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
+  for (int rb = 0; rb < NRB; ++rb) {
     float s = s_run[rb] + __shfl_xor(s_run[rb], 32);
     if (hf == 0) {
       st_m[wave * NR + rb * 32 + n] = m_run[rb];
@@ -482,7 +686,7 @@ __global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_st
     }
   }
   __syncthreads();
-  if (tid < NR) {
+  if (tid < NRB * 32) {
     float m = st_m[tid], s = st_s[tid];
     for (int w = 1; w < 4; ++w) merge_stat(m, s, st_m[w * NR + tid], st_s[w * NR + tid], c2);
     float* out = a.pstat + ((((int64_t)b * a.H + h) * a.S + sp) * 2) * NR;
@@ -491,96 +695,227 @@ __global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_st
   }
 }
 
+template <typename T, int RB, int NG, bool QREG>
+__global__ __launch_bounds__(256, ((RB <= 2 && NG <= 8 && sizeof(T) == 2) ? 2 : 1)) void k_attn_stats(AttnArgs a) {
+  extern __shared__ __align__(16) char lds[];
+  int row0, nrows;
+  ranking_rows(a, blockIdx.z, row0, nrows);
+  const int nrb = (nrows + 31) >> 5;          // row blocks that hold a valid text row of this image
+  if (nrb <= 1) attn_stats_body<T, RB, 1, NG, QREG>(a, lds, row0, nrows);
+  else if (RB >= 2 && nrb == 2) attn_stats_body<T, RB, (RB >= 2 ? 2 : 1), NG, QREG>(a, lds, row0, nrows);
+  else if (RB >= 3 && nrb == 3) attn_stats_body<T, RB, (RB >= 3 ? 3 : 1), NG, QREG>(a, lds, row0, nrows);
+  else if (RB >= 4) attn_stats_body<T, RB, (RB >= 4 ? 4 : 1), NG, QREG>(a, lds, row0, nrows);
+}
+
+// Row statistics merged over the splits, with the rest of the row (lse_extra) folded in: per text
+// row -max (log2 units) and 1 / denominator; rows that do not rank get (-inf, 0) so that they add
+// nothing.  Threads tid < NR of the workgroup; fin_o / fin_i in LDS.
+__device__ __forceinline__ void final_row_stats(const AttnArgs& a, int b, int h, int NR, int row0, int nrows,
+                                                float* fin_o, float* fin_i) {
+  const int tid = threadIdx.x;
+  if (tid < NR) {
+    const bool row_ok = tid < nrows;
+    float o = -INFINITY, iv = 0.0f;        // 2^(z - inf) = 0: rows that do not rank add nothing
+    if (row_ok) {
+      const float* ps = a.pstat + (((int64_t)b * a.H + h) * a.S * 2) * NR;
+      float m = ps[tid], s = ps[NR + tid];
+      for (int w = 1; w < a.S; ++w) merge_stat(m, s, ps[(w * 2) * NR + tid], ps[(w * 2 + 1) * NR + tid], a.c2);
+      float m2 = m * a.c2;                                           // log2 units from here on
+      if (a.lse_extra != nullptr) {
+        float l2 = a.lse_extra[((int64_t)b * a.H + h) * a.Tmax + row0 + tid] * 1.4426950408889634f;
+        float M = fmaxf(m2, l2);
+        s = s * fast_exp2(m2 - M) + fast_exp2(l2 - M);
+        m2 = M;
+      }
+      o = -m2;
+      iv = 1.0f / s;
+    }
+    fin_o[tid] = o;
+    fin_i[tid] = iv;
+  }
+}
+
 // Queries are the tile rows here: lane (n, hf) owns key n of the tile and finds, in accumulator
 // register v of row block rb, its logit against text row rb*32 + 8*(v/4) + 4*hf + v%4.
-template <typename T, int RB, int CH, bool QREG>
-__global__ __launch_bounds__(256, ((RB <= 2 && CH <= 8) ? 2 : 1)) void k_attn_colsum(AttnArgs a) {
+template <typename T, int RB, int NRB, int NG, bool QREG>
+__device__ __forceinline__ void attn_colsum_body(const AttnArgs& a, char* lds, int row0, int nrows) {
   constexpr int NR = RB * 32;
-  constexpr bool PREF = CH * RB <= 32;
-  extern __shared__ __align__(16) char lds[];
-  using Q = QueryOps<T, RB, CH, QREG>;
-  float* fin_o = reinterpret_cast<float*>(lds + Q::lds_bytes());   // [NR]  -max * c2
-  float* fin_i = fin_o + NR;                                       // [NR]  1 / denominator
+  constexpr bool F32 = sizeof(T) == 4;
+  constexpr int GB = group_bytes<T>::value;
+  constexpr bool PREF = !F32 && NG * NRB <= 32;
+  using Q = QueryOps<T, NRB, NG, QREG>;
+  float* fin_o = reinterpret_cast<float*>(lds + query_lds_bytes<T, RB, NG, QREG>());   // [NR]  -max * c2
+  float* fin_i = fin_o + NR;                                                            // [NR]  1 / denominator
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hf = lane >> 5;
   const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int g = (h * a.Hkv) / a.H;
-  const int len = min(max(a.text_len[b], 0), a.Tmax);
-  const int nrb = (len + 31) >> 5;
   const float c2 = a.c2;
-  // merged row statistics of this (image, head): fixed order over the splits
-  if (tid < NR) {
-    const float* ps = a.pstat + (((int64_t)b * a.H + h) * a.S * 2) * NR;
-    float m = ps[tid], s = ps[NR + tid];
-    for (int w = 1; w < a.S; ++w) merge_stat(m, s, ps[(w * 2) * NR + tid], ps[(w * 2 + 1) * NR + tid], c2);
-    float m2 = m * c2;                                             // log2 units from here on
-    if (a.lse_extra != nullptr && tid < a.Tmax) {
-      float l2 = a.lse_extra[((int64_t)b * a.H + h) * a.Tmax + tid] * 1.4426950408889634f;
-      float M = fmaxf(m2, l2);
-      s = s * fast_exp2(m2 - M) + fast_exp2(l2 - M);
-      m2 = M;
-    }
-    const bool row_ok = tid < len;
-    fin_o[tid] = row_ok ? -m2 : -INFINITY;   // 2^(z - inf) = 0: padded rows add nothing
-    fin_i[tid] = row_ok ? 1.0f / s : 0.0f;
-  }
+  final_row_stats(a, b, h, NR, row0, nrows, fin_o, fin_i);
   Q q;
-  q.init(a, b, h, lane, lds, len);
+  q.init(a, b, h, lane, lds, row0, nrows);
   __syncthreads();
-  float off[RB][16], inv[RB][16];
+  // bf16: the row statistics of the 16 rows a lane meets stay in registers; f32 (whose registers go to
+  // the key pieces and to the accumulators of all row blocks) reads them from LDS after the products
+  constexpr int NST = F32 ? 1 : NRB;
+  float off[NST][16], inv[NST][16];
+  if constexpr (!F32) {
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
+    for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      int row = rb * 32 + mma32_row(v, lane);
-      off[rb][v] = fin_o[row];
-      inv[rb][v] = fin_i[row];
-    }
+      for (int v = 0; v < 16; ++v) {
+        int row = rb * 32 + mma32_row(v, lane);
+        off[rb][v] = fin_o[row];
+        inv[rb][v] = fin_i[row];
+      }
+  }
   const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.kv) + b * a.sk.b + g * a.sk.h) +
-                      hf * 16;
+                      hf * GB;
   const int64_t krow_bytes = a.sk.r * (int64_t)sizeof(T);
   const int ntiles = (a.V + 31) >> 5;
   const int t_end = min(ntiles, (sp + 1) * a.tiles_per_split);
   float* out = a.upart + ((int64_t)b * a.H + h) * a.V;
-  uint4 kb[CH], kn[CH];
+  KeyTile<T, NG> kb, kn;
   int tile = sp * a.tiles_per_split + wave;
-  if (tile < t_end) load_key_tile<CH>(kb, kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
+  if (tile < t_end) kb.load(kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
   for (; tile < t_end; tile += 4) {
     const int j = tile * 32 + n;
     const int tnext = tile + 4;
-    if (PREF && tnext < t_end) load_key_tile<CH>(kn, kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+    if (PREF && tnext < t_end) kn.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
     float u = 0.0f;
+    if constexpr (!F32) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      if (rb >= nrb) continue;               // wave-uniform: padded rows add nothing
-      f32x16_t acc;
+      for (int rb = 0; rb < NRB; ++rb) {
+        f32x16_t acc;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
-      for (int c = 0; c < CH; ++c) mma32<T>(acc, q.get(rb, c), kb[c]);
+        for (int c = 0; c < NG; ++c) mma32<bf16_t>(acc, q.get(rb, c), kb.op[c]);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) u = fmaf(fast_exp2(fmaf(acc[v], c2, off[rb][v])), inv[rb][v], u);
+        for (int v = 0; v < 16; ++v) u = fmaf(fast_exp2(fmaf(acc[v], c2, off[rb][v])), inv[rb][v], u);
+      }
+    } else {
+      if (tnext < t_end) kn.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+      q.per_tile();
+      f32x16_t acc[NRB], acl[NRB];
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { acc[rb][v] = 0.0f; acl[rb][v] = 0.0f; }
+#pragma unroll
+      for (int c = 0; c < NG; ++c) {
+        const Split3 ks = split_f32x8(kb.raw[2 * c], kb.raw[2 * c + 1]);
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) mma_split(acc[rb], acl[rb], q.get3(rb, c), ks);
+      }
+      int fz = 0;
+      asm volatile("" : "+v"(fz));       // re-read per tile rather than kept in 32 NRB registers
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = fz + rb * 32 + mma32_row(v, lane);
+          u = fmaf(fast_exp2(fmaf(acc[rb][v] + acl[rb][v], c2, fin_o[row])), fin_i[row], u);
+        }
+      if (tnext < t_end) {
+#pragma unroll
+        for (int c = 0; c < 2 * NG; ++c) kb.raw[c] = kn.raw[c];
+      }
     }
     u += __shfl_xor(u, 32);
     if (hf == 0 && j < a.V) out[j] = u;
-    if (tnext < t_end) {
-      if (PREF) {
+    if constexpr (!F32) {
+      if (tnext < t_end) {
+        if (PREF) {
 #pragma unroll
-        for (int c = 0; c < CH; ++c) kb[c] = kn[c];
-      } else {
-        load_key_tile<CH>(kb, kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+          for (int c = 0; c < NG; ++c) kb.op[c] = kn.op[c];
+        } else {
+          kb.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+        }
       }
     }
   }
 }
 
+template <typename T, int RB, int NG, bool QREG>
+__global__ __launch_bounds__(256, ((RB <= 2 && NG <= 8 && sizeof(T) == 2) ? 2 : 1)) void k_attn_colsum(AttnArgs a) {
+  extern __shared__ __align__(16) char lds[];
+  int row0, nrows;
+  ranking_rows(a, blockIdx.z, row0, nrows);
+  const int nrb = (nrows + 31) >> 5;
+  if (nrb <= 1) attn_colsum_body<T, RB, 1, NG, QREG>(a, lds, row0, nrows);
+  else if (RB >= 2 && nrb == 2) attn_colsum_body<T, RB, (RB >= 2 ? 2 : 1), NG, QREG>(a, lds, row0, nrows);
+  else if (RB >= 3 && nrb == 3) attn_colsum_body<T, RB, (RB >= 3 ? 3 : 1), NG, QREG>(a, lds, row0, nrows);
+  else if (RB >= 4) attn_colsum_body<T, RB, (RB >= 4 ? 4 : 1), NG, QREG>(a, lds, row0, nrows);
+}
+
 // ------------------------------------------------------------------------------------------
-// k_score: grid (ceil(V/64), B), 256 threads: 64 keys x 4 head groups.
+// The same two reductions from stored logits zlog [B, H, T_eff, V] (accumulator units), for the
+// text rows that rode in the mass sweep.
+// k_rowstats_logits: grid (T_eff, H, B), 256 threads: (max, sum of lambda'_j 2^z) of one row, in the
+// layout k_attn_stats leaves (one split, 32 rows per block).
+// k_colsum_logits: grid (ceil(V / 256), H, B), 256 threads: normalised column sums per key.
 // ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_rowstats_logits(AttnArgs a) {
+  __shared__ float red_m[4], red_s[4];
+  const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int row0, nrows;
+  ranking_rows(a, b, row0, nrows);
+  if (t >= nrows) return;                                   // uniform for the workgroup
+  const double mlo = f64_unkey(a.mmkey[2 * b]), mhi = f64_unkey(a.mmkey[2 * b + 1]);
+  const double minv = 1.0 / (mhi - mlo + a.eps);
+  const float* z = a.zlog + (((int64_t)b * a.H + h) * a.T_eff + t) * a.V;
+  float m = ATT_NEG;
+  for (int j = tid; j < a.V; j += 256) m = fmaxf(m, z[j]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  if (lane == 0) red_m[wave] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+  const float offv = -m * a.c2;
+  float s = 0.0f;
+  for (int j = tid; j < a.V; j += 256) s = fmaf(discount(a, b, j, mlo, minv), fast_exp2(fmaf(z[j], a.c2, offv)), s);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+  if (lane == 0) red_s[wave] = s;
+  __syncthreads();
+  if (tid == 0) {
+    const int NR = ((a.T_eff + 31) >> 5) * 32;
+    float* out = a.pstat + (((int64_t)b * a.H + h) * 2) * NR;     // one split
+    out[t] = m;
+    out[NR + t] = (red_s[0] + red_s[1]) + (red_s[2] + red_s[3]);
+  }
+}
+
+__global__ __launch_bounds__(256) void k_colsum_logits(AttnArgs a) {
+  __shared__ float fin_o[32], fin_i[32];
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  int row0, nrows;
+  ranking_rows(a, b, row0, nrows);
+  final_row_stats(a, b, h, 32, row0, nrows, fin_o, fin_i);
+  __syncthreads();
+  if (j >= a.V) return;
+  const float* z = a.zlog + (((int64_t)b * a.H + h) * a.T_eff) * a.V + j;
+  float u = 0.0f;
+  for (int t = 0; t < nrows; ++t) u = fmaf(fast_exp2(fmaf(z[(int64_t)t * a.V], a.c2, fin_o[t])), fin_i[t], u);
+  a.upart[((int64_t)b * a.H + h) * a.V + j] = u;
+}
+
+// ------------------------------------------------------------------------------------------
+// k_score: grid (ceil(V/64), B), 256 threads: 64 keys x 4 head groups.  rows[b] = text rows that
+// ranked (the divisor of the mean).
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ double rank_count(const int32_t* text_len, int b, int Tmax, int last_only) {
+  const int len = min(max(text_len[b], 0), Tmax);
+  return (double)(last_only ? min(len, 1) : len);
+}
+
 __global__ __launch_bounds__(256) void k_score(const float* __restrict__ upart, const double* __restrict__ s64,
                                                 const unsigned long long* __restrict__ mmkey,
-                                                const int32_t* __restrict__ text_len, int H, int V,
-                                                double lambda_max, double eps, int mask_on,
+                                                const int32_t* __restrict__ text_len, int H, int V, int Tmax,
+                                                int last_only, double lambda_max, double eps, int mask_on,
                                                 float* __restrict__ s_hat, float* __restrict__ score) {
   __shared__ double part[4][64];
   const int b = blockIdx.y, jl = threadIdx.x & 63, hq = threadIdx.x >> 6;
@@ -607,56 +942,61 @@ __global__ __launch_bounds__(256) void k_score(const float* __restrict__ upart, 
     const double sh = (s64[(int64_t)b * V + j] - lo) * (1.0 / (hi - lo + eps));
     const double lam = mask_on ? fmax(lambda_max * sh, eps) : 1.0;
     s_hat[(int64_t)b * V + j] = (float)sh;
-    score[(int64_t)b * V + j] = (float)(lam * u / ((double)H * (double)text_len[b]));
+    score[(int64_t)b * V + j] = (float)(lam * u / ((double)H * rank_count(text_len, b, Tmax, last_only)));
   }
 }
 
 // ------------------------------------------------------------------------------------------
-// k_score_select: grid (B), 1024 threads.  Thread t owns the keys t*ipt .. t*ipt+ipt-1 of its image:
-// it reduces their per-head column sums in the order k_score uses (four interleaved head groups in
-// fp64, then ((0+1)+2)+3), so that score and s_hat come out bit-identical to k_score's, and the
-// workgroup then selects exactly as k_select does.
+// k_score_select: grid (B), 1024 threads, dynamic LDS = V floats when V > 1024.  The threads reduce the
+// per-head column sums of the keys tid, tid + 1024, ... (coalesced) in the order k_score uses (four
+// interleaved head groups in fp64, then ((0+1)+2)+3), so that score and s_hat come out bit-identical to
+// k_score's; the scores change hands through LDS to the blocked layout of the selection (thread t owns
+// keys t*ipt .. t*ipt+ipt-1), and the workgroup then selects exactly as k_select does.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(SEL_THREADS) void k_score_select(const float* __restrict__ upart,
                                                                const double* __restrict__ s64,
                                                                const unsigned long long* __restrict__ mmkey,
                                                                const int32_t* __restrict__ text_len, int H, int V,
-                                                               int k, double lambda_max, double eps, int mask_on,
-                                                               float* __restrict__ s_hat, float* __restrict__ score,
-                                                               int32_t* __restrict__ kept,
+                                                               int k, int Tmax, int last_only, double lambda_max,
+                                                               double eps, int mask_on, float* __restrict__ s_hat,
+                                                               float* __restrict__ score, int32_t* __restrict__ kept,
                                                                int32_t* __restrict__ pruned) {
   __shared__ SelectShared sh;
+  extern __shared__ float sc_lds[];
   const int b = blockIdx.x, tid = threadIdx.x;
   const int ipt = (V + SEL_THREADS - 1) / SEL_THREADS;
   const int i0 = tid * ipt;
   const double lo = f64_unkey(mmkey[2 * b]), hi = f64_unkey(mmkey[2 * b + 1]);
   const double inv = 1.0 / (hi - lo + eps);
-  const double norm = (double)H * (double)text_len[b];
+  const double norm = (double)H * rank_count(text_len, b, Tmax, last_only);
   const float* up = upart + (int64_t)b * H * V;
+  float mine = 0.0f;
+  for (int j = tid; j < V; j += SEL_THREADS) {
+    double part[4] = {0.0, 0.0, 0.0, 0.0};
+    int h = 0;
+    for (; h + 16 <= H; h += 16) {          // 16 loads in flight; head h adds to group h % 4, in order
+      float u[16];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) u[q] = up[(int64_t)(h + q) * V + j];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) part[q & 3] += (double)u[q];
+    }
+    for (; h < H; ++h) part[h & 3] += (double)up[(int64_t)h * V + j];
+    const double usum = ((part[0] + part[1]) + part[2]) + part[3];
+    const double shat = (s64[(int64_t)b * V + j] - lo) * inv;
+    const double lam = mask_on ? fmax(lambda_max * shat, eps) : 1.0;
+    const float sc = (float)(lam * usum / norm);
+    s_hat[(int64_t)b * V + j] = (float)shat;
+    score[(int64_t)b * V + j] = sc;
+    if (ipt > 1) sc_lds[j] = sc;
+    else mine = sc;
+  }
+  if (ipt > 1) __syncthreads();
   uint32_t key[SEL_IPT];
 #pragma unroll
   for (int e = 0; e < SEL_IPT; ++e) {
-    const int j = i0 + e;
-    key[e] = 0u;
-    if (e < ipt && j < V) {
-      double part[4] = {0.0, 0.0, 0.0, 0.0};
-      int h = 0;
-      for (; h + 16 <= H; h += 16) {          // 16 loads in flight; head h adds to group h % 4, in order
-        float u[16];
-#pragma unroll
-        for (int q = 0; q < 16; ++q) u[q] = up[(int64_t)(h + q) * V + j];
-#pragma unroll
-        for (int q = 0; q < 16; ++q) part[q & 3] += (double)u[q];
-      }
-      for (; h < H; ++h) part[h & 3] += (double)up[(int64_t)h * V + j];
-      const double usum = ((part[0] + part[1]) + part[2]) + part[3];
-      const double shat = (s64[(int64_t)b * V + j] - lo) * inv;
-      const double lam = mask_on ? fmax(lambda_max * shat, eps) : 1.0;
-      const float sc = (float)(lam * usum / norm);
-      s_hat[(int64_t)b * V + j] = (float)shat;
-      score[(int64_t)b * V + j] = sc;
-      key[e] = float_key(sc);
-    }
+    const int i = i0 + e;
+    key[e] = (e < ipt && i < V) ? float_key(ipt > 1 ? sc_lds[i] : mine) : 0u;
   }
   int n_keep;
   const uint32_t keep_bits = radix_topk(key, ipt, i0, V, k, sh, &n_keep);
@@ -677,6 +1017,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_score_select(const float* __res
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+static int ranking_rows_max(const asap_params& p) { return p.score_rows == ASAP_ROWS_LAST ? 1 : p.Tmax; }
+
 // Key-range splits of the two text-row sweeps.  Their workgroups run in rounds of as many as fit
 // on the chip at once (1 to 4 per compute unit, by the registers of the instantiation); a round
 // costs the tiles of one split plus a fixed part (start-up, the text queries, the last tiles' tail:
@@ -685,8 +1027,9 @@ __global__ __launch_bounds__(SEL_THREADS) void k_score_select(const float* __res
 // on ties; a split has at least 4 tiles (one per wave).
 static int attn_splits(const asap_params& p) {
   const int ntiles = (p.V + 31) / 32;
-  const int rb = (p.Tmax + 31) / 32, ch = p.d / (p.qk_dtype == ASAP_BF16 ? 16 : 8);
-  const int per_cu = rb * ch <= 4 ? 4 : (rb * ch <= 8 && ch == 8) ? 3 : (rb * ch <= 16 && ch <= 8) ? 2 : 1;
+  const int rb = (ranking_rows_max(p) + 31) / 32, ch = p.d / 16;
+  int per_cu = rb * ch <= 4 ? 4 : (rb * ch <= 8 && ch == 8) ? 3 : (rb * ch <= 16 && ch <= 8) ? 2 : 1;
+  if (p.qk_dtype != ASAP_BF16) per_cu = 1;
   const long slots = 256L * per_cu, groups = (long)p.H * p.B;
   int smax = ntiles / 4;
   if (smax > 16) smax = 16;
@@ -713,26 +1056,45 @@ ScoreWorkspace score_workspace(const asap_params& p) {
   w.q_rows = (p.V + chunks - 1) / chunks;
   w.q_chunks = (p.V + w.q_rows - 1) / w.q_rows;
   w.attn_splits = attn_splits(p);
-  const int NR = ((p.Tmax + 31) / 32) * 32;
+  w.t_eff = ranking_rows_max(p);
+  // Text rows ride in the mass sweep when the rows of one kv head's query heads fit the free rows of
+  // its tile and their logits -- written once, read twice, 12 bytes per row and key -- weigh less than
+  // the two sweeps over the keys they replace.
+  const int G = p.H / p.Hkv, rows = G * w.t_eff;
+  const int row_bytes = p.d * (p.qk_dtype == ASAP_BF16 ? 2 : 4);
+  w.ride = (p.qk_dtype == ASAP_BF16 && rows <= 28 && 12 * rows < 2 * row_bytes) ? 1 : 0;
+  // kv-head groups of the mass sweep: 1 unless the key tiles alone leave most of the chip idle
+  const long tiles = (long)((p.V + 31) / 32) * p.B;
+  w.head_splits = 1;
+  if (tiles < 256) {
+    int want = (int)((512 + tiles - 1) / tiles);
+    for (int hs = p.Hkv; hs >= 1; --hs)
+      if (p.Hkv % hs == 0 && hs <= want) { w.head_splits = hs; break; }
+  }
+  const int NR = ((w.t_eff + 31) / 32) * 32;
+  const int splits = w.ride ? 1 : w.attn_splits;
   size_t off = 0;
   w.off_qpart = off;  off = align256(off + sizeof(double) * p.B * p.H * w.q_chunks * p.d);
   w.off_qbar = off;   off = align256(off + sizeof(double) * p.B * p.Hkv * p.d);
   w.off_qsplit = off; off = align256(off + sizeof(uint16_t) * p.B * p.Hkv * 4 * p.d);
   w.off_s64 = off;    off = align256(off + sizeof(double) * p.B * p.V);
   w.off_mm = off;     off = align256(off + sizeof(double) * p.B * 2);
-  w.off_pstat = off;  off = align256(off + sizeof(float) * (size_t)p.B * p.H * w.attn_splits * 2 * NR);
+  w.off_pstat = off;  off = align256(off + sizeof(float) * (size_t)p.B * p.H * splits * 2 * NR);
   w.off_upart = off;  off = align256(off + sizeof(float) * (size_t)p.B * p.H * p.V);
+  w.off_spart = off;
+  if (w.head_splits > 1) off = align256(off + sizeof(double) * (size_t)w.head_splits * p.B * p.V);
+  w.off_zlog = off;
+  if (w.ride) off = align256(off + sizeof(float) * (size_t)p.B * p.H * w.t_eff * p.V);
   w.total = off;
   return w;
 }
 
-template <typename T, int RB, int CH, bool QREG>
+template <typename T, int RB, int NG, bool QREG>
 static hipError_t launch_attn(const asap_params& p, const AttnArgs& a, hipStream_t st, Timer* tm) {
   constexpr int NR = RB * 32;
-  using Q = QueryOps<T, RB, CH, QREG>;
-  const size_t lds = Q::lds_bytes() + sizeof(float) * 8 * NR;
-  auto k1 = k_attn_stats<T, RB, CH, QREG>;
-  auto k2 = k_attn_colsum<T, RB, CH, QREG>;
+  const size_t lds = query_lds_bytes<T, RB, NG, QREG>() + sizeof(float) * 8 * NR;
+  auto k1 = k_attn_stats<T, RB, NG, QREG>;
+  auto k2 = k_attn_colsum<T, RB, NG, QREG>;
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -746,17 +1108,38 @@ static hipError_t launch_attn(const asap_params& p, const AttnArgs& a, hipStream
   return hipGetLastError();
 }
 
-template <typename T, int CH>
+template <typename T, int NG>
 static hipError_t dispatch_rb(const asap_params& p, const AttnArgs& a, hipStream_t st, Timer* tm) {
-  // queries stay in registers while they need at most 64 VGPRs
-  constexpr bool R1 = CH * 4 <= 64, R2 = CH * 8 <= 64;
-  switch ((p.Tmax + 31) / 32) {
-    case 1: return launch_attn<T, 1, CH, R1>(p, a, st, tm);
-    case 2: return launch_attn<T, 2, CH, R2>(p, a, st, tm);
-    case 3: return launch_attn<T, 3, CH, false>(p, a, st, tm);
-    case 4: return launch_attn<T, 4, CH, false>(p, a, st, tm);
+  // bf16 queries stay in registers while they need at most 64 VGPRs; f32 queries go to LDS as pieces
+  constexpr bool BF = sizeof(T) == 2;
+  constexpr bool R1 = BF && NG * 4 <= 64, R2 = BF && NG * 8 <= 64;
+  switch ((a.T_eff + 31) / 32) {
+    case 1: return launch_attn<T, 1, NG, R1>(p, a, st, tm);
+    case 2: return launch_attn<T, 2, NG, R2>(p, a, st, tm);
+    case 3: return launch_attn<T, 3, NG, false>(p, a, st, tm);
+    case 4: return launch_attn<T, 4, NG, false>(p, a, st, tm);
   }
   return hipErrorInvalidValue;
+}
+
+template <typename T, int NG>
+static hipError_t launch_mass(const asap_params& p, const ScoreWorkspace& w, const void* k_vis, Strides3 kv,
+                              const uint16_t* qsplit, double scale, double* s64, float* s_raw,
+                              unsigned long long* mmkey, double* spart, const RideArgs& ra, hipStream_t st,
+                              Timer* tm) {
+  const int ktiles = (p.V + 31) / 32;
+  const dim3 grid(ktiles, p.B * w.head_splits);
+  const T* kp = static_cast<const T*>(k_vis);
+  if constexpr (sizeof(T) == 2) {
+    if (w.ride) {
+      ASAP_LAUNCH(tm, "k_mass", (k_mass_mfma<T, NG, true>), grid, dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V,
+                  w.head_splits, scale, s64, s_raw, mmkey, spart, ra);
+      return hipGetLastError();
+    }
+  }
+  ASAP_LAUNCH(tm, "k_mass", (k_mass_mfma<T, NG, false>), grid, dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V,
+              w.head_splits, scale, s64, s_raw, mmkey, spart, ra);
+  return hipGetLastError();
 }
 
 template <typename T>
@@ -772,9 +1155,11 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   unsigned long long* mmkey = reinterpret_cast<unsigned long long*>(ws + w.off_mm);
   float* pstat = reinterpret_cast<float*>(ws + w.off_pstat);
   float* upart = reinterpret_cast<float*>(ws + w.off_upart);
+  double* spart = reinterpret_cast<double*>(ws + w.off_spart);
+  float* zlog = reinterpret_cast<float*>(ws + w.off_zlog);
   const int mask_on = p.mask_mode == ASAP_MASK_KEYBIAS;
-  constexpr int E = elem<T>::per16;
-  const int ch = p.d / E / 2;   // 16-byte chunks per half row
+  const int last_only = p.score_rows == ASAP_ROWS_LAST;
+  const int ng = p.d / 16;      // contraction groups of 8 elements per lane half
   const int ktiles = (p.V + 31) / 32;
 
   const int direct = (w.q_chunks == 1 && p.H == p.Hkv) ? 1 : 0;
@@ -784,46 +1169,57 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
     ASAP_LAUNCH(tm, "k_qsplit", k_qsplit, dim3(p.Hkv, p.B), dim3(p.d), 0, st, qpart, qbar, qsplit, p.H, p.Hkv,
                 w.q_chunks, p.d);
   const double scale = 1.0 / ((double)p.H * sqrt((double)p.d));
-  if constexpr (E == 8) {
-    const bf16_t* kp = static_cast<const bf16_t*>(k_vis);
-    if (ch == 8)
-      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<8>, dim3(ktiles, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
-                  s64, s_raw, mmkey);
-    else
-      ASAP_LAUNCH(tm, "k_mass", k_mass_mfma<4>, dim3(ktiles, p.B), dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V, scale,
-                  s64, s_raw, mmkey);
-  } else {
-    ASAP_LAUNCH(tm, "k_mass", k_mass<T>, dim3(ktiles, p.B), dim3(256), sizeof(double) * p.Hkv * p.d, st,
-                static_cast<const T*>(k_vis), kv, qbar, p.Hkv, p.V, p.d, scale, s64, s_raw, mmkey);
-  }
-  hipError_t e = hipGetLastError();
+  RideArgs ra;
+  ra.qt = q_txt; ra.sq = qt; ra.text_len = text_len; ra.zlog = zlog;
+  ra.H = p.H; ra.G = p.H / p.Hkv; ra.T_eff = w.t_eff; ra.Tmax = p.Tmax; ra.last_only = last_only;
+  hipError_t e = ng == 8 ? launch_mass<T, 8>(p, w, k_vis, kv, qsplit, scale, s64, s_raw, mmkey, spart, ra, st, tm)
+                         : launch_mass<T, 4>(p, w, k_vis, kv, qsplit, scale, s64, s_raw, mmkey, spart, ra, st, tm);
   if (e != hipSuccess) return e;
+  if (w.head_splits > 1)
+    ASAP_LAUNCH(tm, "k_mass_finish", k_mass_finish, dim3(p.B), dim3(1024), 0, st, spart, w.head_splits, p.B, p.V,
+                scale, s64, s_raw, mmkey);
 
   AttnArgs a;
   a.qt = q_txt; a.sq = qt; a.kv = k_vis; a.sk = kv; a.s64 = s64; a.mmkey = mmkey; a.text_len = text_len;
-  a.lse_extra = lse_extra; a.pstat = pstat; a.upart = upart;
-  a.H = p.H; a.Hkv = p.Hkv; a.V = p.V; a.Tmax = p.Tmax; a.S = w.attn_splits;
+  a.lse_extra = lse_extra; a.pstat = pstat; a.upart = upart; a.zlog = zlog;
+  a.H = p.H; a.Hkv = p.Hkv; a.V = p.V; a.Tmax = p.Tmax; a.S = w.ride ? 1 : w.attn_splits;
   a.tiles_per_split = (ktiles + a.S - 1) / a.S;
+  a.T_eff = w.t_eff; a.last_only = last_only;
   a.c2 = (float)(1.4426950408889634 / sqrt((double)p.d));
   a.lambda_max = (double)p.lambda_max; a.eps = (double)p.eps; a.mask_on = mask_on;
-  if (ch == 4) {
-    if constexpr (E == 8) e = dispatch_rb<T, 4>(p, a, st, tm);
-    else e = hipErrorInvalidValue;
-  } else if (ch == 8) {
+  if (w.ride) {
+    ASAP_LAUNCH(tm, "k_rowstats_logits", k_rowstats_logits, dim3(w.t_eff, p.H, p.B), dim3(256), 0, st, a);
+    ASAP_LAUNCH(tm, "k_colsum_logits", k_colsum_logits, dim3((p.V + 255) / 256, p.H, p.B), dim3(256), 0, st, a);
+    e = hipGetLastError();
+  } else if (ng == 8) {
     e = dispatch_rb<T, 8>(p, a, st, tm);
-  } else if (ch == 16) {
-    if constexpr (E == 4) e = dispatch_rb<T, 16>(p, a, st, tm);
-    else e = hipErrorInvalidValue;
   } else {
-    e = hipErrorInvalidValue;
+    e = dispatch_rb<T, 4>(p, a, st, tm);
   }
   if (e != hipSuccess) return e;
-  if (kept != nullptr)
-    ASAP_LAUNCH(tm, "k_score_select", k_score_select, dim3(p.B), dim3(SEL_THREADS), 0, st, upart, s64, mmkey,
-                text_len, p.H, p.V, p.k, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score, kept, pruned);
-  else
+  // The selection rides in the launch that finishes the score when the batch gives that launch (one
+  // workgroup per image) enough workgroups to fetch the per-head sums at a reasonable rate; measured
+  // on batches of 4 and 8 it lost to the two separate launches.
+  if (kept != nullptr && p.B < 12) {
     ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
-                p.H, p.V, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
+                p.H, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
+    hipError_t e2 = hipGetLastError();
+    return e2 != hipSuccess ? e2 : launch_select(p, score, kept, pruned, st, tm);
+  }
+  if (kept != nullptr) {
+    const size_t lds = p.V > SEL_THREADS ? sizeof(float) * (size_t)p.V : 0;
+    if (lds > 32 * 1024) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_score_select), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds);
+      if (e != hipSuccess) return e;
+    }
+    ASAP_LAUNCH(tm, "k_score_select", k_score_select, dim3(p.B), dim3(SEL_THREADS), lds, st, upart, s64, mmkey,
+                text_len, p.H, p.V, p.k, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score,
+                kept, pruned);
+  } else {
+    ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
+                p.H, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
+  }
   return hipGetLastError();
 }
 

@@ -9,14 +9,14 @@ from typing import List, Optional
 
 import torch
 
-from .binding import (ASAP_ROUTE_ABSORB, Context, _TORCH_DTYPE, _strides, asap_params, asap_stage_io,
+from .binding import (ASAP_ROUTE_ABSORB, ASAP_ROWS_LAST, Context, _TORCH_DTYPE, _strides, asap_params, asap_stage_io,
                       asap_workspace_bytes, params_from_config)
 
 
 class StageBuffers:
     """Device buffers of one pruning stage (outputs + workspace), allocated once with torch."""
 
-    def __init__(self, p: asap_params, n_layers: int, device="cuda:0", workspace_floor: int = 0):
+    def __init__(self, p: asap_params, n_layers: int, device="cuda:0"):
         B, V, k, D = p.B, p.V, p.k, p.D
         Nout = p.P + p.k + p.Tmax
         f32, i32 = torch.float32, torch.int32
@@ -40,7 +40,7 @@ class StageBuffers:
         kvd = _TORCH_DTYPE[p.kv_dtype]
         self.k_dst = [torch.zeros(B, p.Hkv, Nout, p.d, dtype=kvd, device=dev) for _ in range(n_layers)]
         self.v_dst = [torch.zeros(B, p.Hkv, Nout, p.d, dtype=kvd, device=dev) for _ in range(n_layers)]
-        self.workspace = torch.empty(max(asap_workspace_bytes(p), workspace_floor, 256), dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(max(asap_workspace_bytes(p), 256), dtype=torch.uint8, device=dev)
 
 
 def stage_io(p: asap_params, q: torch.Tensor, k: torch.Tensor, hidden: torch.Tensor, text_len: torch.Tensor,
@@ -107,17 +107,14 @@ class PagedKV:
 def run_stage(ctx: Context, p: asap_params, q: torch.Tensor, k: torch.Tensor, hidden: torch.Tensor,
               text_len: torch.Tensor, k_cache: List[torch.Tensor], v_cache: List[torch.Tensor],
               buf: StageBuffers, lse_extra: Optional[torch.Tensor] = None, stream=None,
-              side_stream=None, paged: Optional[PagedKV] = None, score_with=None) -> StageBuffers:
+              side_stream=None, paged: Optional[PagedKV] = None) -> StageBuffers:
     """The calls of one stage.  q [B,H,N,d], k [B,Hkv,N,d], hidden [B,N,D]; the visual / text blocks
     are passed to the library as strided views.  With a side stream the K/V compaction, which needs
     only the kept set, runs there next to the similarity and merge kernels of the main stream (one
     hand-over between the streams after the selection -- each costs the main stream about 6 us, so
     the rows that depend on nothing are not started earlier on their own); the main stream waits for
     the side stream at the end.  Contiguous caches are compacted by the call that takes the kept
-    list directly; paged caches (`paged`; k_cache / v_cache are then ignored) need asap_positions.
-    score_with = (params, q_txt, text_len): the scoring call takes these instead (ranking by the last
-    text token: params with Tmax = 1, the gathered last rows [B,H,1,d], a text_len of ones); every
-    later call keeps the stage's own params and text lengths."""
+    list directly; paged caches (`paged`; k_cache / v_cache are then ignored) need asap_positions."""
     P, V = p.P, p.V
     q_vis, q_txt, k_vis = q[:, :, P:P + V], q[:, :, P + V:], k[:, :, P:P + V]
     main = torch.cuda.current_stream() if stream is None else stream
@@ -129,13 +126,8 @@ def run_stage(ctx: Context, p: asap_params, q: torch.Tensor, k: torch.Tensor, hi
         ev.record(src)
         dst.wait_event(ev)
 
-    if score_with is None:
-        ctx.asap_score(p, q_vis, q_txt, k_vis, text_len, lse_extra, buf.s_raw, buf.s_hat, buf.score,
-                       buf.workspace, main)
-    else:
-        p_score, q_rows, len_rows = score_with
-        ctx.asap_score(p_score, q_vis, q_rows, k_vis, len_rows, None, buf.s_raw, buf.s_hat, buf.score,
-                       buf.workspace, main)
+    ctx.asap_score(p, q_vis, q_txt, k_vis, text_len, lse_extra, buf.s_raw, buf.s_hat, buf.score,
+                   buf.workspace, main)
     ctx.asap_select(p, buf.score, buf.kept_idx, buf.pruned_idx, buf.workspace, main)
     # with ASAP_ROUTE_ABSORB the kept set is final before the merge
     early = has_kv and side_stream is not None and p.route == ASAP_ROUTE_ABSORB
@@ -171,8 +163,8 @@ class DeviceStage:
     """One batch from synth.make_inputs uploaded to the GPU, with output buffers.  run() is one
     asap_stage call (overlap=True: two streams inside the library); with call_by_call=True, or with
     paged caches, it is the sequence of single calls of run_stage, where the second stream is torch's.
-    last_token=True ranks the visual tokens by the last valid text token's row alone: the scoring
-    call then gets its own params (Tmax = 1) and the gathered last query rows, call by call."""
+    last_token=True ranks the visual tokens by the last valid text token's row alone
+    (score_rows = ASAP_ROWS_LAST in the params; the library picks the row from text_len)."""
 
     def __init__(self, inp: dict, ctx: Optional[Context] = None, lse_extra=None, overlap: bool = True,
                  page_size: Optional[int] = None, call_by_call: bool = False, last_token: bool = False,
@@ -181,6 +173,8 @@ class DeviceStage:
         cfg = inp["cfg"]
         self.cfg = cfg
         self.ctx = ctx or Context(0)
+        if last_token:
+            param_overrides = dict(param_overrides, score_rows=ASAP_ROWS_LAST)
         self.p = params_from_config(cfg, **param_overrides)
         self.q = to_device(inp["q"], cfg.qk_dtype)
         self.k = to_device(inp["k"], cfg.qk_dtype)
@@ -194,21 +188,9 @@ class DeviceStage:
             # the caches become pools of pages; the contiguous copies and destinations are not kept
             self.paged = PagedKV(self.p, self.k_cache, self.v_cache, page_size, seed=cfg.seed)
             self.k_cache, self.v_cache = [], []
-        self.score_with = None
-        floor = 0
-        if last_token:
-            if lse_extra is not None:
-                raise ValueError("last_token and lse_extra are not combined here")
-            p_score = asap_params.from_buffer_copy(self.p)
-            p_score.Tmax = 1
-            rows = (cfg.P + cfg.V + self.text_len.long() - 1)                       # [B] position of the last text token
-            idx = rows.view(-1, 1, 1, 1).expand(-1, self.q.shape[1], 1, self.q.shape[3])
-            q_last = torch.gather(self.q, 2, idx).contiguous()                     # [B,H,1,d]
-            self.score_with = (p_score, q_last, torch.ones_like(self.text_len))
-            floor = asap_workspace_bytes(p_score)
-        self.buf = StageBuffers(self.p, len(self.k_cache), workspace_floor=floor)
+        self.buf = StageBuffers(self.p, len(self.k_cache))
         has_kv = bool(self.k_cache) or self.paged is not None
-        self.call_by_call = call_by_call or self.paged is not None or last_token
+        self.call_by_call = call_by_call or self.paged is not None
         # whether the K/V compaction runs beside the similarity and merge kernels
         self.two_streams = overlap and has_kv and self.p.route == ASAP_ROUTE_ABSORB
         # torch's default-priority second stream, for the call-by-call path only
@@ -219,8 +201,7 @@ class DeviceStage:
     def run_async(self) -> StageBuffers:
         if self.call_by_call:
             return run_stage(self.ctx, self.p, self.q, self.k, self.hidden, self.text_len, self.k_cache,
-                             self.v_cache, self.buf, self.lse_extra, side_stream=self.side_stream, paged=self.paged,
-                             score_with=self.score_with)
+                             self.v_cache, self.buf, self.lse_extra, side_stream=self.side_stream, paged=self.paged)
         self.ctx.asap_stage(self.p, self.io, self.two_streams)
         return self.buf
 

@@ -54,6 +54,7 @@ def test_check_params_accepts_all_benchmark_configs(lib):
     ("B", 0), ("k", 0), ("k", 2305), ("Hkv", 5), ("d", 96), ("D", 4100), ("V", 0), ("V", 20000),
     ("Tmax", 0), ("Tmax", 129), ("P", -1), ("lambda_max", 0.0), ("lambda_max", 1.5), ("eps", 0.0),
     ("merge_weight", -1.0), ("sim_threshold", float("nan")), ("qk_dtype", 7), ("mask_mode", 3), ("route", 2),
+    ("score_rows", 2),
 ])
 def test_check_params_rejects(lib, field, value):
     p = good()
@@ -83,8 +84,8 @@ def test_workspace_size_formula(lib):
 
 
 def test_struct_layout_matches_header(lib):
-    # 9 int32 + 3 enums + 4 floats + 2 enums, all 4 bytes, no padding
-    assert ctypes.sizeof(binding.asap_params) == 18 * 4
+    # 9 int32 + 3 enums + 4 floats + 3 enums, all 4 bytes, no padding
+    assert ctypes.sizeof(binding.asap_params) == 19 * 4
 
 
 def test_header_is_plain_c_and_the_binding_mirrors_its_structs(tmp_path):

@@ -47,9 +47,21 @@ def test_full_row_softmax_with_lse_extra(ctx):
 
 @pytest.mark.parametrize("name", ["S1", "S2", "S4"])
 def test_ranking_by_the_last_text_token(ctx, name):
-    """The scoring call with its own params (Tmax = 1), the gathered last valid query row per image
-    and a text length of one; selection, merge and compaction with the stage's params."""
+    """score_rows = ASAP_ROWS_LAST: the row of the last valid text token ranks alone (it rides in the
+    mass sweep, or takes the one-row sweeps with f32 keys); also with the rest of the row folded in."""
     U.run_and_compare(synth.CONFIGS[name], ctx=ctx, last_token=True)
+    U.run_and_compare(synth.CONFIGS[name], ctx=ctx, last_token=True, lse=True)
+
+
+@pytest.mark.parametrize("base,Tmax,ragged", [("S2", 7, True), ("S2", 8, True), ("S4", 28, False), ("S4", 29, False),
+                                              ("S3", 3, True)])
+def test_few_text_rows_ride_in_the_mass_sweep(ctx, base, Tmax, ragged):
+    """Up to 28 text rows per kv head (bf16) are scored from logits taken in the sweep that computes the
+    masses; one more row, or f32 keys, and the two sweeps over the keys run.  Both sides of the boundary,
+    GQA (4 query heads per kv head x 7 rows) and one head per kv head x 28 rows, ragged lengths."""
+    cfg = dataclasses.replace(synth.CONFIGS[base], Tmax=Tmax, ragged_text=ragged, text_lo=1, name=f"{base}T{Tmax}")
+    U.run_and_compare(cfg, ctx=ctx)
+    U.run_and_compare(cfg, ctx=ctx, lse=True)
 
 
 @pytest.mark.parametrize("base,Tmax,text_lo", [("S1", 24, 3), ("S2", 40, 5), ("S2", 100, 30), ("S0", 128, 20)])
@@ -520,6 +532,20 @@ def test_paper_routing_small(ctx, name, threshold, mu):
         assert all(s["n_sources"] == cfg.k - 1 for s in stats)
     elif name != "S0":
         assert sum(s["n_sources"] for s in stats) > 0, "the case does not exercise any merge"
+
+
+@pytest.mark.parametrize("name,threshold", [("S0", 0.8), ("S1", 0.8), ("S2", 0.85), ("S4", 0.9), ("S2", 0.5)])
+def test_paper_routing_end_to_end_against_the_fp64_oracle(ctx, name, threshold):
+    """The whole stage with the paper's routing against the oracle's whole stage in fp64: same final
+    list, same source sets, same merged rows -- unless the oracle's own numbers show a decision too
+    close to call in f32 (a salience pair within one f32 unit, a cosine within 1e-5 of the threshold).
+    These seeded inputs have no such close call, so agreement has to be exact."""
+    cfg = synth.CONFIGS[name]
+    inp = synth.make_inputs(cfg)
+    st = U.GpuStage(inp, ctx=ctx, route=binding.ASAP_ROUTE_PAPER, sim_threshold=threshold)
+    buf = st.run()
+    res = [U.compare_image_paper_end_to_end(inp, buf, b, threshold) for b in range(cfg.B)]
+    assert all(r["same"] for r in res), [r["close_calls"] for r in res]
 
 
 @pytest.mark.parametrize("V,k,clusters,threshold", [(2, 1, 1, 0.5), (5, 2, 1, 0.5), (64, 32, 2, 0.5), (257, 128, 3, 0.6),
