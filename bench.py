@@ -30,13 +30,28 @@ if ROOT not in sys.path:
 HBM_PEAK = 8.0e12          # B/s, MI355X HBM3E
 MFMA_PEAK = {"bf16": 2.5e15, "f32": 157.3e12}
 
-# HBM bytes per launch read from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
-# (see profiles/); keyed by workload then kernel.  None = not measured for that workload.
-MEASURED_TRAFFIC = {
-    # profiles/bench_C6_hbm_traffic.txt (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0, from the 1 GiB copy)
-    "C6": {"k_qsum": 303.6e6, "k_mass": 307.2e6, "k_attn_stats": 313.1e6, "k_attn_colsum": 315.4e6,
-           "k_score": 5.4e6, "k_select": 0.5e6, "k_sim": 312.9e6, "k_merge": 387.1e6, "k_compact": 439.6e6},
-}
+def measured_traffic(workload: str, kernels) -> tuple:
+    """HBM bytes per launch and kernel as rocprofv3's FETCH_SIZE / WRITE_SIZE counters saw them in an
+    earlier run of this script: read from the committed summary profiles/bench_<workload>_hbm_traffic.txt
+    (its header holds the commands and the calibration against a plain copy).  The figures are only used
+    when that summary lists exactly the kernels this run launched; otherwise (a kernel was added, renamed
+    or dropped since the counters were taken) none is reported.  Returns (dict or None, source, note)."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_hbm_traffic.txt")
+    rel = os.path.relpath(path, ROOT)
+    if not os.path.exists(path):
+        return None, rel, "no counter summary for this workload"
+    table = {}
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 6 and parts[0].startswith("k_"):
+            try:
+                table[parts[0].split("<")[0]] = float(parts[-1]) * 1e6
+            except ValueError:
+                pass
+    if set(table) != set(kernels):
+        return None, rel, ("the summary lists other kernels than this run launched: "
+                           f"only there {sorted(set(table) - set(kernels))}, only here {sorted(set(kernels) - set(table))}")
+    return table, rel, "counter run of an earlier build of the same kernel list, not of this run"
 
 
 def esize(dt: str) -> int:
@@ -55,7 +70,7 @@ def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
     per_kernel = {
         "k_qsum": q_vis,
         "k_qsplit": 8 * B * H * d + 16 * B * Hkv * d,
-        "k_mass": k_vis + 12 * B * V,
+        "k_mass_mfma": k_vis + 12 * B * V,
         "k_attn_stats": k_vis + q_txt + 8 * B * V,
         "k_attn_colsum": k_vis + q_txt + 4 * B * H * V,
         "k_mass_finish": 20 * B * V,
@@ -83,9 +98,19 @@ def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb", lse_ex
     from paper_2603_14549_amd import synth
     try:
         from threadpoolctl import threadpool_info
-        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        pools = threadpool_info()
+        threads = max([i.get("num_threads", 1) for i in pools] or [1])
+        blas = ", ".join(sorted({f"{i.get('internal_api', '?')} {i.get('version', '')}".strip() for i in pools}))
     except Exception:
-        threads = os.cpu_count() or 1
+        threads, blas = os.cpu_count() or 1, "unknown"
+    cpu_model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu_model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
     done, t_total = 0, 0.0
     while t_total < budget_s and done < 16 * cfg.B:
         t0 = time.perf_counter()
@@ -101,6 +126,7 @@ def cpu_baseline(inp, cfg, budget_s: float = 12.0, route: str = "absorb", lse_ex
         t_total += time.perf_counter() - t0
         done += 1
     return {"value": done / t_total, "unit": "images/s", "cores": int(threads), "kind": "oracle",
+            "cpu_model": cpu_model, "os_cpu_count": os.cpu_count(), "blas": blas, "blas_threads": int(threads),
             "sample": f"{done} single-image oracle stages cycling over the {cfg.B} images of workload {cfg.name} "
                       f"(fp64 NumPy, sum-of-queries form of Eq. 2, K/V gather included, {t_total:.1f} s)",
             "ms_per_image": 1e3 * t_total / done}
@@ -156,7 +182,7 @@ def bench_attention(args, cfg):
     out = torch.empty(cfg.B, cfg.H, cfg.N, cfg.d, dtype=stage.q.dtype, device="cuda")
     ws = torch.empty(binding.asap_attention_workspace_bytes(stage.p), dtype=torch.uint8, device="cuda")
     run = lambda: ctx.asap_attention(stage.p, stage.q, stage.k, vals, buf.s_hat, out, ws)
-    steps, warmup = min(args.steps, 10), min(args.warmup, 3)
+    steps, warmup = args.steps, args.warmup
     for _ in range(warmup):
         run()
     torch.cuda.synchronize()
@@ -165,7 +191,7 @@ def bench_attention(args, cfg):
         run()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ctx.asap_timing_enable(64)
+    ctx.asap_timing_enable(min(8192, 4 * steps))
     for _ in range(steps):
         run()
     torch.cuda.synchronize()
@@ -211,6 +237,10 @@ def main():
                          "with asap_compact_kv_paged (0 = contiguous caches, the headline workload)")
     ap.add_argument("--last-token", action="store_true",
                     help="rank the visual tokens by the last text token's row alone (score_rows = ASAP_ROWS_LAST)")
+    ap.add_argument("--rotate", type=int, default=0, metavar="SETS",
+                    help="also time the stage cycling over SETS (>= 2) copies of the inputs and outputs at different "
+                         "addresses, so that no step finds its data in the caches (the small workloads fit the "
+                         "256 MB last-level cache and their default, warm figure profits from it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="accepted for the counter runs documented in profiles/: the 1 GiB device copies that "
@@ -257,6 +287,23 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
     images_per_s = cfg.B * args.steps / elapsed
+
+    rotated = None
+    if args.rotate >= 2:
+        sets = [stage] + [harness.DeviceStage(inp, ctx=ctx, lse_extra=lse_extra, page_size=args.paged_kv or None,
+                                              last_token=args.last_token, **overrides)
+                          for _ in range(args.rotate - 1)]
+        for i in range(args.warmup):
+            sets[i % len(sets)].run_async()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            sets[i % len(sets)].run_async()
+        torch.cuda.synchronize()
+        rot_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        rotated = {"sets": len(sets), "ms_per_step": rot_ms, "images_per_s": cfg.B / (rot_ms * 1e-3),
+                   "note": "same steps cycling over copies of all inputs and outputs at different addresses"}
+        del sets
 
     # second pass of the same K steps with the library's per-kernel HIP events on
     launches_per_step = 18
@@ -340,16 +387,21 @@ def main():
     dominant = max(on_main, key=lambda k: on_main[k][0])
     d_ms, d_n = timing[dominant]
     d_avg_s = 1e-3 * d_ms / d_n
-    traffic = None if paper else MEASURED_TRAFFIC.get(cfg.name, {}).get(dominant)   # measured for the default route
+    variant = paper or args.paged_kv or args.last_token or args.lse_extra       # counters exist for the default run only
+    measured, traffic_source, traffic_note = (None, None, "no counter run for this variant") if variant else \
+        measured_traffic(cfg.name, list(timing))
+    traffic = None if measured is None else measured.get(dominant)
     if dominant == "k_sim" and cfg.V > cfg.k:
         flops = alg["sim_flops"] * args.steps / d_n
         peak = MFMA_PEAK[cfg.h_dtype]
         roofline = {"kernel": dominant, "bound": "mfma", "achieved": flops / d_avg_s / 1e12, "peak": peak / 1e12,
-                    "unit": "TFLOP/s", "frac": flops / d_avg_s / peak, "traffic": traffic}
+                    "unit": "TFLOP/s", "frac": flops / d_avg_s / peak, "traffic": traffic,
+                    "traffic_source": traffic_source, "traffic_note": traffic_note}
     else:
         nbytes = alg["per_kernel"].get(dominant, 0) * args.steps / d_n
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": nbytes / d_avg_s / 1e9, "peak": HBM_PEAK / 1e9,
-                    "unit": "GB/s", "frac": nbytes / d_avg_s / HBM_PEAK, "traffic": traffic}
+                    "unit": "GB/s", "frac": nbytes / d_avg_s / HBM_PEAK, "traffic": traffic,
+                    "traffic_source": traffic_source, "traffic_note": traffic_note}
     sim = timing.get("k_sim")
     sim_roofline = None
     if sim:
@@ -368,12 +420,12 @@ def main():
                       "sum_kernel_us": round(step_kernel_us, 1)}
     # what the memory system really moved per step (counter runs of the default route): the keys are swept
     # three times where the algorithmic figure counts them once
-    measured = MEASURED_TRAFFIC.get(cfg.name)
-    if measured and not paper and not args.paged_kv:
+    if measured:
         moved = sum(measured.get(name, 0.0) * n / args.steps for name, (_, n) in timing.items())
         stage_roofline["traffic_MB"] = round(moved / 1e6, 1)
         stage_roofline["traffic_frac"] = moved / (ms_per_step * 1e-3) / HBM_PEAK
         stage_roofline["traffic_vs_copy"] = moved / (ms_per_step * 1e-3) / copy_bw
+        stage_roofline["traffic_source"] = traffic_source
     stage_roofline["measured_copy_GBps"] = round(copy_bw / 1e9, 1)
 
     out = {
@@ -397,6 +449,8 @@ def main():
         "similarity_gemm": sim_roofline,
         "kernels": kernels,
     }
+    if rotated is not None:
+        out["rotated_inputs"] = rotated
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, cfg, route=args.route, lse_extra=lse_extra,
                                            score_rows="last" if args.last_token else "all")

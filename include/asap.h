@@ -71,7 +71,7 @@ typedef struct {
   int32_t Hkv;      /* key/value heads, H % Hkv == 0; head h reads kv head h*Hkv/H */
   int32_t d;        /* head dim, 64 or 128                                        */
   int32_t D;        /* hidden size, multiple of 64                                */
-  int32_t P;        /* prefix tokens before the image                        >= 0 */
+  int32_t P;        /* prefix tokens before the image, 0 .. 1048576               */
   int32_t V;        /* visual tokens, 1 .. 16384                                  */
   int32_t Tmax;     /* padded text length, 1 .. 128                               */
   int32_t k;        /* visual tokens kept, 1 .. V                                 */

@@ -57,3 +57,28 @@ def build_library(verbose: bool = True) -> str:
 
 if __name__ == "__main__":
     build_library()
+
+
+def build_sanitized_host(out_dir: str) -> str:
+    """The same sources with AddressSanitizer and UndefinedBehaviorSanitizer on the HOST half only (argument
+    checks, workspace sizing, launch-shape choices, the Eq. 7-8 utilities); the device code is compiled as
+    always.  For the CPU-only test that sweeps the host entry points; nothing GPU-side is sanitised or run."""
+    os.makedirs(out_dir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    flags = [f if f != "-O3" else "-O1" for f in FLAGS] + san
+
+    def one(src: str) -> str:
+        obj = os.path.join(out_dir, src.replace(".hip", ".o"))
+        res = subprocess.run([HIPCC, *flags, "-c", os.path.join(CSRC, src), "-o", obj], capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitised host) failed on {src}:\n{res.stderr}")
+        return obj
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+        objs = list(ex.map(one, SOURCES))
+    lib = os.path.join(out_dir, "libasap_san.so")
+    res = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address,undefined",
+                          "-fno-gpu-sanitize", "-o", lib, *objs], capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("link (sanitised host) failed:\n" + res.stderr)
+    return lib

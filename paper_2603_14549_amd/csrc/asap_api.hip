@@ -85,7 +85,7 @@ asap_status check_params(const asap_params* p, char* msg, size_t n) {
   BAD(p->d != 64 && p->d != 128, "d must be 64 or 128");
   BAD((int64_t)p->Hkv * p->d > 8192, "Hkv * d must be <= 8192");
   BAD(p->D < 64 || p->D % 64 != 0 || p->D > 8192, "D must be a multiple of 64 in [64, 8192]");
-  BAD(p->P < 0, "P must be >= 0");
+  BAD(p->P < 0 || p->P > (1 << 20), "P must be in [0, 1048576]");
   BAD(p->V < 1 || p->V > 16384, "V must be in [1, 16384]");
   BAD(p->Tmax < 1 || p->Tmax > 128, "Tmax must be in [1, 128]");
   BAD(p->k < 1 || p->k > p->V, "k must be in [1, V]");

@@ -1132,12 +1132,12 @@ static hipError_t launch_mass(const asap_params& p, const ScoreWorkspace& w, con
   const T* kp = static_cast<const T*>(k_vis);
   if constexpr (sizeof(T) == 2) {
     if (w.ride) {
-      ASAP_LAUNCH(tm, "k_mass", (k_mass_mfma<T, NG, true>), grid, dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V,
+      ASAP_LAUNCH(tm, "k_mass_mfma", (k_mass_mfma<T, NG, true>), grid, dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V,
                   w.head_splits, scale, s64, s_raw, mmkey, spart, ra);
       return hipGetLastError();
     }
   }
-  ASAP_LAUNCH(tm, "k_mass", (k_mass_mfma<T, NG, false>), grid, dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V,
+  ASAP_LAUNCH(tm, "k_mass_mfma", (k_mass_mfma<T, NG, false>), grid, dim3(256), 0, st, kp, kv, qsplit, p.Hkv, p.V,
               w.head_splits, scale, s64, s_raw, mmkey, spart, ra);
   return hipGetLastError();
 }

@@ -52,7 +52,7 @@ def test_check_params_accepts_all_benchmark_configs(lib):
 
 @pytest.mark.parametrize("field,value", [
     ("B", 0), ("k", 0), ("k", 2305), ("Hkv", 5), ("d", 96), ("D", 4100), ("V", 0), ("V", 20000),
-    ("Tmax", 0), ("Tmax", 129), ("P", -1), ("lambda_max", 0.0), ("lambda_max", 1.5), ("eps", 0.0),
+    ("Tmax", 0), ("Tmax", 129), ("P", -1), ("P", (1 << 20) + 1), ("lambda_max", 0.0), ("lambda_max", 1.5), ("eps", 0.0),
     ("merge_weight", -1.0), ("sim_threshold", float("nan")), ("qk_dtype", 7), ("mask_mode", 3), ("route", 2),
     ("score_rows", 2),
 ])
