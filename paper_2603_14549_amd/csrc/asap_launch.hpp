@@ -17,14 +17,15 @@ struct ScoreWorkspace {
   int attn_splits;   // key-range splits of the text-row sweeps
   int t_eff;         // text rows that rank the tokens: Tmax, or 1 with ASAP_ROWS_LAST
   int ride;          // 1: those rows ride in the mass sweep, which leaves their logits (no text-row sweeps)
+  int row_pairs;     // pairs of 32-row blocks of text queries, each with sweep workgroups of its own
   int head_splits;   // kv-head groups of the mass sweep with workgroups of their own (small batches)
   size_t off_qpart;  // double [B,H,q_chunks,d]  partial sums of visual queries
   size_t off_qbar;   // double [B,Hkv,d]         summed visual queries per kv head
   size_t off_qsplit; // bf16   [B,Hkv,4,d]       the same, split into four bf16 pieces per component
   size_t off_s64;    // double [B,V]             raw attention mass before rounding
   size_t off_mm;     // uint64 [B,2]             order-preserving keys of min, max of s per image
-  size_t off_pstat;  // float  [B,H,splits,2,NR] per-split (max, sum) of every text row
-  size_t off_upart;  // float  [B,H,V]           per-head column sums of normalised weights
+  size_t off_pstat;  // float  [B,H,splits,2,NR] per-split (max, sum) of every text row, NR = 64 row_pairs
+  size_t off_upart;  // float  [B,H,row_pairs,V] column sums of normalised weights per head and row pair
   size_t off_spart;  // double [head_splits,B,V] partial masses (head_splits > 1)
   size_t off_zlog;   // float  [B,H,t_eff,V]     raw logits of the riding text rows (ride)
   size_t total;

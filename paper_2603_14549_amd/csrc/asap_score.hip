@@ -90,14 +90,16 @@ __device__ __forceinline__ Split3 split_f32x8(const uint4& c0, const uint4& c1) 
   split_pair(__uint_as_float(c1.z), __uint_as_float(c1.w), s.hi.w, s.mid.w, s.lo.w);
   return s;
 }
-// the six piece products of one contraction group: the small ones into acc_l, smallest first
-__device__ __forceinline__ void mma_split(f32x16_t& acc_h, f32x16_t& acc_l, const Split3& a, const Split3& b) {
-  mma32<bf16_t>(acc_l, a.lo, b.hi);
-  mma32<bf16_t>(acc_l, a.hi, b.lo);
-  mma32<bf16_t>(acc_l, a.mid, b.mid);
-  mma32<bf16_t>(acc_l, a.mid, b.hi);
-  mma32<bf16_t>(acc_l, a.hi, b.mid);
-  mma32<bf16_t>(acc_h, a.hi, b.hi);
+// The six piece products of one contraction group, smallest first, into one accumulator: the small
+// ones land on partial sums of the large ones, i.e. they are rounded at the level the hi.hi products
+// of the row are rounded at anyway (2^-24 of the running sum).
+__device__ __forceinline__ void mma_split(f32x16_t& acc, const Split3& a, const Split3& b) {
+  mma32<bf16_t>(acc, a.lo, b.hi);
+  mma32<bf16_t>(acc, a.hi, b.lo);
+  mma32<bf16_t>(acc, a.mid, b.mid);
+  mma32<bf16_t>(acc, a.mid, b.hi);
+  mma32<bf16_t>(acc, a.hi, b.mid);
+  mma32<bf16_t>(acc, a.hi, b.hi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -413,12 +415,18 @@ __global__ __launch_bounds__(1024) void k_mass_finish(const double* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------
-// Text-row attention sweeps.  grid (S, H, B), 256 threads = 4 waves.
-//   RB = 32-row blocks of text queries the launch provides for (Tmax <= 32 RB); the body is compiled
-//   for every block count NRB <= RB and picked by the image's own text length, so that an image
-//   with few text rows in a padded batch costs what its rows cost.
-//   NG = contraction groups of 8 elements (d = 16 NG); QREG: the queries stay in registers as MFMA
-//   operands (bf16 with at most two row blocks), else in LDS.
+// Text-row attention sweeps.  grid (H * RP * S, B), 256 threads = 4 waves; blockIdx.x = h + H (rp + RP sp).
+//   A workgroup takes one (image, head), one pair rp of 32-row blocks of text queries (64 rows; RP
+//   pairs cover Tmax) and one key-range split sp.  Two row blocks per workgroup keep its registers and
+//   LDS small enough for two workgroups per compute unit, whose waves fill each other's gaps (one
+//   wave's exponentials and operand splitting under the other's matrix instructions); longer text
+//   costs another workgroup per 64 rows, which reads the keys again -- the pairs of one head are
+//   32 ids apart in the launch order, so they run close in time on the same XCD and the second finds
+//   the keys in its L2 -- and an image whose own text ends before a pair starts pays nothing for it
+//   (the workgroup leaves at once).  The body is compiled for one and for two row blocks and picked by
+//   the image's own text length.
+//   NG = contraction groups of 8 elements (d = 16 NG).  bf16 queries stay in registers as MFMA
+//   operands; f32 queries are split into bf16 pieces once and read from LDS.
 // Every wave streams its own 32-key tiles of the split's key range straight from global memory:
 // lane (n, hf) of a tile reads, for group c, the bytes [GB (2c + hf), + GB) of key n (GB = 16 for
 // bf16, 32 for f32) -- the two lanes of a key take contiguous bytes, which halves the cache lines a
@@ -431,10 +439,10 @@ struct AttnArgs {
   const unsigned long long* mmkey;      // [B,2]
   const int32_t* text_len;              // [B]
   const float* lse_extra;               // [B,H,Tmax] or null
-  float* pstat;                         // [B,H,S,2,NR]   partial (max, sum) per text row
-  float* upart;                         // [B,H,V]
+  float* pstat;                         // [B,H,S,2,NR]   partial (max, sum) per text row, NR = 64 RP
+  float* upart;                         // [B,H,RP,V]     column sums per head and row pair
   const float* zlog;                    // [B,H,T_eff,V]  stored logits (k_rowstats_logits / k_colsum_logits)
-  int H, Hkv, V, Tmax, S, tiles_per_split;
+  int H, Hkv, V, Tmax, S, RP, tiles_per_split;
   int T_eff, last_only;                 // rows that rank: all valid text rows, or the last one alone
   float c2;                             // log2(e) / sqrt(d): accumulator units -> log2 units
   double lambda_max, eps;
@@ -448,10 +456,10 @@ __device__ __forceinline__ void ranking_rows(const AttnArgs& a, int b, int& row0
   nrows = a.last_only ? min(len, 1) : len;
 }
 
-// Query operands: registers or LDS.  Operand row m is text row row0 + m; rows at or past nrows
-// (padding of a ragged batch, whatever it holds) are zero operands.
-template <typename T, int NRB, int NG, bool QREG> struct QueryOps;
-template <int NRB, int NG> struct QueryOps<bf16_t, NRB, NG, true> {
+// Query operands: registers (bf16) or LDS (f32, as pieces).  Operand row m is text row row0 + m; rows
+// at or past nrows (padding of a ragged batch, whatever it holds) are zero operands.
+template <typename T, int NRB, int NG> struct QueryOps;
+template <int NRB, int NG> struct QueryOps<bf16_t, NRB, NG> {
   uint4 qa[NRB][NG];
   __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char*, int row0, int nrows) {
     const int m = lane & 31, hf = lane >> 5;
@@ -467,28 +475,8 @@ template <int NRB, int NG> struct QueryOps<bf16_t, NRB, NG, true> {
   }
   __device__ __forceinline__ uint4 get(int rb, int c) const { return qa[rb][c]; }
 };
-template <int NRB, int NG> struct QueryOps<bf16_t, NRB, NG, false> {
-  static constexpr int ROWB = NG * 32, LDSROW = ROWB + 16;
-  const char* qa;
-  __device__ __forceinline__ void init(const AttnArgs& a, int b, int h, int lane, char* lds, int row0, int nrows) {
-    const char* qbase = reinterpret_cast<const char*>(static_cast<const bf16_t*>(a.qt) + b * a.sq.b + h * a.sq.h +
-                                                      (int64_t)row0 * a.sq.r);
-    constexpr int PPR = ROWB / 16;
-    for (int i = threadIdx.x; i < NRB * 32 * PPR; i += 256) {
-      int row = i / PPR, pc = i % PPR;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (row < nrows) v = ldg16(qbase + (int64_t)row * a.sq.r * 2 + pc * 16);
-      *reinterpret_cast<uint4*>(lds + row * LDSROW + pc * 16) = v;
-    }
-    __syncthreads();
-    qa = lds + (lane & 31) * LDSROW + (lane >> 5) * 16;
-  }
-  __device__ __forceinline__ uint4 get(int rb, int c) const {
-    return *reinterpret_cast<const uint4*>(qa + rb * 32 * LDSROW + c * 32);
-  }
-};
 // f32 queries: three bf16 planes in LDS, split once per workgroup
-template <int NRB, int NG> struct QueryOps<float, NRB, NG, false> {
+template <int NRB, int NG> struct QueryOps<float, NRB, NG> {
   static constexpr int ROWB = NG * 32, LDSROW = ROWB + 16, PLANE = NRB * 32 * LDSROW;
   const char* base;     // the workgroup's LDS
   int qoff;             // this lane's operand row and half, as a byte offset
@@ -526,13 +514,14 @@ template <int NRB, int NG> struct QueryOps<float, NRB, NG, false> {
     return s;
   }
 };
-template <typename T, int RB, int NG, bool QREG> constexpr size_t query_lds_bytes() {
-  if (QREG) return 0;
-  return (size_t)RB * 32 * (NG * 32 + 16) * (sizeof(T) == 4 ? 3 : 1);
+// LDS of a sweep workgroup: the f32 query pieces (two row blocks at most), then 8 x 64 floats of statistics
+template <typename T, int NG> constexpr size_t query_lds_bytes() {
+  return sizeof(T) == 4 ? (size_t)64 * (NG * 32 + 16) * 3 : 0;
 }
+constexpr int ATT_ROWS = 64;       // text rows per workgroup
 
-// A lane's share of a 32-key tile.  bf16: the chunks are the operands.  f32: the raw chunks are
-// split into pieces once per tile, which frees their registers for the next tile's loads.
+// A lane's share of a 32-key tile.  bf16: the chunks are the operands.  f32: the raw chunks are split
+// into pieces group by group, and a group's registers take the next tile's chunks as soon as it is split.
 template <typename T, int NG> struct KeyTile;
 template <int NG> struct KeyTile<bf16_t, NG> {
   uint4 op[NG];
@@ -545,10 +534,11 @@ template <int NG> struct KeyTile<float, NG> {
   uint4 raw[2 * NG];
   __device__ __forceinline__ void load(const char* krow) {
 #pragma unroll
-    for (int c = 0; c < NG; ++c) {
-      raw[2 * c] = ldg16(krow + c * 64);
-      raw[2 * c + 1] = ldg16(krow + c * 64 + 16);
-    }
+    for (int c = 0; c < NG; ++c) load_group(krow, c);
+  }
+  __device__ __forceinline__ void load_group(const char* krow, int c) {
+    raw[2 * c] = ldg16(krow + c * 64);
+    raw[2 * c + 1] = ldg16(krow + c * 64 + 16);
   }
 };
 
@@ -587,20 +577,30 @@ __device__ __forceinline__ void stats_update(f32x16_t& acc, const float (&lam)[1
   m_run = m_new;
 }
 
-// Keys are the tile rows here: lane (n, hf) owns text row rb*32 + n and finds, in accumulator
+// (head, row pair, key split) of a sweep workgroup
+struct SweepId { int h, rp, sp, b; };
+__device__ __forceinline__ SweepId sweep_id(const AttnArgs& a) {
+  SweepId w;
+  w.h = blockIdx.x % a.H;
+  const int rest = blockIdx.x / a.H;
+  w.rp = rest % a.RP;
+  w.sp = rest / a.RP;
+  w.b = blockIdx.y;
+  return w;
+}
+
+// Keys are the tile rows here: lane (n, hf) owns text row row0 + rb*32 + n and finds, in accumulator
 // register v, its logit against key 8*(v/4) + 4*hf + v%4 of the tile.
-template <typename T, int RB, int NRB, int NG, bool QREG>
-__device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, int row0, int nrows) {
-  constexpr int NR = RB * 32;
+template <typename T, int NRB, int NG>
+__device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, const SweepId& w, int row0, int nrows) {
   constexpr bool F32 = sizeof(T) == 4;
   constexpr int GB = group_bytes<T>::value;
-  constexpr bool PREF = !F32 && NG * NRB <= 32;     // bf16: next key tile prefetched into a second register set
-  using Q = QueryOps<T, NRB, NG, QREG>;
-  float* st_m = reinterpret_cast<float*>(lds + query_lds_bytes<T, RB, NG, QREG>());   // [4][NR]
-  float* st_s = st_m + 4 * NR;                                                         // [4][NR]
+  using Q = QueryOps<T, NRB, NG>;
+  float* st_m = reinterpret_cast<float*>(lds + query_lds_bytes<T, NG>());   // [4][64]
+  float* st_s = st_m + 4 * ATT_ROWS;                                         // [4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hf = lane >> 5;
-  const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int sp = w.sp, h = w.h, b = w.b;
   const int g = (h * a.Hkv) / a.H;
   Q q;
   q.init(a, b, h, lane, lds, row0, nrows);
@@ -617,13 +617,17 @@ __device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, in
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) { m_run[rb] = ATT_NEG; s_run[rb] = 0.0f; }
 
-  KeyTile<T, NG> kb, kn;
+  KeyTile<T, NG> kb;
   int tile = sp * a.tiles_per_split + wave;
   if (tile < t_end) kb.load(kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
   for (; tile < t_end; tile += 4) {
     const int j = tile * 32 + n;
     const int tnext = tile + 4;
-    if (PREF && tnext < t_end) kn.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+    const char* knext = kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes;
+    KeyTile<T, F32 ? 1 : NG> kn;      // bf16: next key tile prefetched into a second register set, first thing
+    if constexpr (!F32) {
+      if (tnext < t_end) kn.load(knext);
+    }
     // discount of key n of the tile, then handed to the lanes in accumulator order
     const float lj = j < a.V ? discount(a, b, j, mlo, minv) : 0.0f;
     float lam[16];
@@ -641,39 +645,27 @@ __device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, in
         stats_update(acc, lam, ragged, tile, hf, a.V, c2, m_run[rb], s_run[rb]);
       }
       if (tnext < t_end) {
-        if (PREF) {
 #pragma unroll
-          for (int c = 0; c < NG; ++c) kb.op[c] = kn.op[c];
-        } else {
-          kb.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
-        }
+        for (int c = 0; c < NG; ++c) kb.op[c] = kn.op[c];
       }
     } else {
-      // group by group: a key group is split once and meets every row block, whose accumulators
-      // stay alive across the groups; the next tile's rows land in the second register set meanwhile
-      if (tnext < t_end) kn.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+      // group by group: a key group is split once and meets both row blocks, whose accumulators stay
+      // alive across the groups; its registers then take the same group of the next tile
       q.per_tile();
-      f32x16_t acc[NRB], acl[NRB];
+      f32x16_t acc[NRB];
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { acc[rb][v] = 0.0f; acl[rb][v] = 0.0f; }
+        for (int v = 0; v < 16; ++v) acc[rb][v] = 0.0f;
 #pragma unroll
       for (int c = 0; c < NG; ++c) {
         const Split3 ks = split_f32x8(kb.raw[2 * c], kb.raw[2 * c + 1]);
+        if (tnext < t_end) kb.load_group(knext, c);
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) mma_split(acc[rb], acl[rb], ks, q.get3(rb, c));
+        for (int rb = 0; rb < NRB; ++rb) mma_split(acc[rb], ks, q.get3(rb, c));
       }
 #pragma unroll
-      for (int rb = 0; rb < NRB; ++rb) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[rb][v] += acl[rb][v];
-        stats_update(acc[rb], lam, ragged, tile, hf, a.V, c2, m_run[rb], s_run[rb]);
-      }
-      if (tnext < t_end) {
-#pragma unroll
-        for (int c = 0; c < 2 * NG; ++c) kb.raw[c] = kn.raw[c];
-      }
+      for (int rb = 0; rb < NRB; ++rb) stats_update(acc[rb], lam, ragged, tile, hf, a.V, c2, m_run[rb], s_run[rb]);
     }
   }
   // the two halves of a wave share the row maximum: their sums just add; then the 4 waves
@@ -681,45 +673,48 @@ __device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, in
   for (int rb = 0; rb < NRB; ++rb) {
     float s = s_run[rb] + __shfl_xor(s_run[rb], 32);
     if (hf == 0) {
-      st_m[wave * NR + rb * 32 + n] = m_run[rb];
-      st_s[wave * NR + rb * 32 + n] = s;
+      st_m[wave * ATT_ROWS + rb * 32 + n] = m_run[rb];
+      st_s[wave * ATT_ROWS + rb * 32 + n] = s;
     }
   }
   __syncthreads();
   if (tid < NRB * 32) {
     float m = st_m[tid], s = st_s[tid];
-    for (int w = 1; w < 4; ++w) merge_stat(m, s, st_m[w * NR + tid], st_s[w * NR + tid], c2);
-    float* out = a.pstat + ((((int64_t)b * a.H + h) * a.S + sp) * 2) * NR;
+    for (int wv = 1; wv < 4; ++wv) merge_stat(m, s, st_m[wv * ATT_ROWS + tid], st_s[wv * ATT_ROWS + tid], c2);
+    const int NR = ATT_ROWS * a.RP;
+    float* out = a.pstat + ((((int64_t)b * a.H + h) * a.S + sp) * 2) * NR + w.rp * ATT_ROWS;
     out[tid] = m;
     out[NR + tid] = s;
   }
 }
 
-template <typename T, int RB, int NG, bool QREG>
-__global__ __launch_bounds__(256, ((RB <= 2 && NG <= 8 && sizeof(T) == 2) ? 2 : 1)) void k_attn_stats(AttnArgs a) {
+template <typename T, int NG>
+__global__ __launch_bounds__(256, 2) void k_attn_stats(AttnArgs a) {
   extern __shared__ __align__(16) char lds[];
+  const SweepId w = sweep_id(a);
   int row0, nrows;
-  ranking_rows(a, blockIdx.z, row0, nrows);
-  const int nrb = (nrows + 31) >> 5;          // row blocks that hold a valid text row of this image
-  if (nrb <= 1) attn_stats_body<T, RB, 1, NG, QREG>(a, lds, row0, nrows);
-  else if (RB >= 2 && nrb == 2) attn_stats_body<T, RB, (RB >= 2 ? 2 : 1), NG, QREG>(a, lds, row0, nrows);
-  else if (RB >= 3 && nrb == 3) attn_stats_body<T, RB, (RB >= 3 ? 3 : 1), NG, QREG>(a, lds, row0, nrows);
-  else if (RB >= 4) attn_stats_body<T, RB, (RB >= 4 ? 4 : 1), NG, QREG>(a, lds, row0, nrows);
+  ranking_rows(a, w.b, row0, nrows);
+  row0 += w.rp * ATT_ROWS;
+  nrows = min(nrows - w.rp * ATT_ROWS, ATT_ROWS);
+  if (nrows <= 0) return;                      // the image's text ends before this pair of row blocks
+  if (nrows <= 32) attn_stats_body<T, 1, NG>(a, lds, w, row0, nrows);
+  else attn_stats_body<T, 2, NG>(a, lds, w, row0, nrows);
 }
 
 // Row statistics merged over the splits, with the rest of the row (lse_extra) folded in: per text
 // row -max (log2 units) and 1 / denominator; rows that do not rank get (-inf, 0) so that they add
-// nothing.  Threads tid < NR of the workgroup; fin_o / fin_i in LDS.
-__device__ __forceinline__ void final_row_stats(const AttnArgs& a, int b, int h, int NR, int row0, int nrows,
-                                                float* fin_o, float* fin_i) {
+// nothing.  Threads tid < n_local of the workgroup handle rows first + tid of the NR-row layout;
+// row0 = the text row of local row 0; fin_o / fin_i in LDS.
+__device__ __forceinline__ void final_row_stats(const AttnArgs& a, int b, int h, int NR, int first, int n_local,
+                                                int row0, int nrows, float* fin_o, float* fin_i) {
   const int tid = threadIdx.x;
-  if (tid < NR) {
+  if (tid < n_local) {
     const bool row_ok = tid < nrows;
     float o = -INFINITY, iv = 0.0f;        // 2^(z - inf) = 0: rows that do not rank add nothing
     if (row_ok) {
-      const float* ps = a.pstat + (((int64_t)b * a.H + h) * a.S * 2) * NR;
+      const float* ps = a.pstat + (((int64_t)b * a.H + h) * a.S * 2) * NR + first;
       float m = ps[tid], s = ps[NR + tid];
-      for (int w = 1; w < a.S; ++w) merge_stat(m, s, ps[(w * 2) * NR + tid], ps[(w * 2 + 1) * NR + tid], a.c2);
+      for (int wv = 1; wv < a.S; ++wv) merge_stat(m, s, ps[(wv * 2) * NR + tid], ps[(wv * 2 + 1) * NR + tid], a.c2);
       float m2 = m * a.c2;                                           // log2 units from here on
       if (a.lse_extra != nullptr) {
         float l2 = a.lse_extra[((int64_t)b * a.H + h) * a.Tmax + row0 + tid] * 1.4426950408889634f;
@@ -736,27 +731,25 @@ __device__ __forceinline__ void final_row_stats(const AttnArgs& a, int b, int h,
 }
 
 // Queries are the tile rows here: lane (n, hf) owns key n of the tile and finds, in accumulator
-// register v of row block rb, its logit against text row rb*32 + 8*(v/4) + 4*hf + v%4.
-template <typename T, int RB, int NRB, int NG, bool QREG>
-__device__ __forceinline__ void attn_colsum_body(const AttnArgs& a, char* lds, int row0, int nrows) {
-  constexpr int NR = RB * 32;
+// register v of row block rb, its logit against text row row0 + rb*32 + 8*(v/4) + 4*hf + v%4.
+template <typename T, int NRB, int NG>
+__device__ __forceinline__ void attn_colsum_body(const AttnArgs& a, char* lds, const SweepId& w, int row0, int nrows) {
   constexpr bool F32 = sizeof(T) == 4;
   constexpr int GB = group_bytes<T>::value;
-  constexpr bool PREF = !F32 && NG * NRB <= 32;
-  using Q = QueryOps<T, NRB, NG, QREG>;
-  float* fin_o = reinterpret_cast<float*>(lds + query_lds_bytes<T, RB, NG, QREG>());   // [NR]  -max * c2
-  float* fin_i = fin_o + NR;                                                            // [NR]  1 / denominator
+  using Q = QueryOps<T, NRB, NG>;
+  float* fin_o = reinterpret_cast<float*>(lds + query_lds_bytes<T, NG>());   // [64]  -max * c2
+  float* fin_i = fin_o + ATT_ROWS;                                            // [64]  1 / denominator
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hf = lane >> 5;
-  const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int sp = w.sp, h = w.h, b = w.b;
   const int g = (h * a.Hkv) / a.H;
   const float c2 = a.c2;
-  final_row_stats(a, b, h, NR, row0, nrows, fin_o, fin_i);
+  final_row_stats(a, b, h, ATT_ROWS * a.RP, w.rp * ATT_ROWS, NRB * 32, row0, nrows, fin_o, fin_i);
   Q q;
   q.init(a, b, h, lane, lds, row0, nrows);
   __syncthreads();
   // bf16: the row statistics of the 16 rows a lane meets stay in registers; f32 (whose registers go to
-  // the key pieces and to the accumulators of all row blocks) reads them from LDS after the products
+  // the key pieces and to the accumulators) reads them from LDS after the products
   constexpr int NST = F32 ? 1 : NRB;
   float off[NST][16], inv[NST][16];
   if constexpr (!F32) {
@@ -774,16 +767,18 @@ __device__ __forceinline__ void attn_colsum_body(const AttnArgs& a, char* lds, i
   const int64_t krow_bytes = a.sk.r * (int64_t)sizeof(T);
   const int ntiles = (a.V + 31) >> 5;
   const int t_end = min(ntiles, (sp + 1) * a.tiles_per_split);
-  float* out = a.upart + ((int64_t)b * a.H + h) * a.V;
-  KeyTile<T, NG> kb, kn;
+  float* out = a.upart + (((int64_t)b * a.H + h) * a.RP + w.rp) * a.V;
+  KeyTile<T, NG> kb;
   int tile = sp * a.tiles_per_split + wave;
   if (tile < t_end) kb.load(kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
   for (; tile < t_end; tile += 4) {
     const int j = tile * 32 + n;
     const int tnext = tile + 4;
-    if (PREF && tnext < t_end) kn.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
+    const char* knext = kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes;
     float u = 0.0f;
     if constexpr (!F32) {
+      KeyTile<T, NG> kn;
+      if (tnext < t_end) kn.load(knext);
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) {
         f32x16_t acc;
@@ -794,19 +789,23 @@ __device__ __forceinline__ void attn_colsum_body(const AttnArgs& a, char* lds, i
 #pragma unroll
         for (int v = 0; v < 16; ++v) u = fmaf(fast_exp2(fmaf(acc[v], c2, off[rb][v])), inv[rb][v], u);
       }
+      if (tnext < t_end) {
+#pragma unroll
+        for (int c = 0; c < NG; ++c) kb.op[c] = kn.op[c];
+      }
     } else {
-      if (tnext < t_end) kn.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
       q.per_tile();
-      f32x16_t acc[NRB], acl[NRB];
+      f32x16_t acc[NRB];
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { acc[rb][v] = 0.0f; acl[rb][v] = 0.0f; }
+        for (int v = 0; v < 16; ++v) acc[rb][v] = 0.0f;
 #pragma unroll
       for (int c = 0; c < NG; ++c) {
         const Split3 ks = split_f32x8(kb.raw[2 * c], kb.raw[2 * c + 1]);
+        if (tnext < t_end) kb.load_group(knext, c);
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) mma_split(acc[rb], acl[rb], q.get3(rb, c), ks);
+        for (int rb = 0; rb < NRB; ++rb) mma_split(acc[rb], q.get3(rb, c), ks);
       }
       int fz = 0;
       asm volatile("" : "+v"(fz));       // re-read per tile rather than kept in 32 NRB registers
@@ -815,38 +814,32 @@ __device__ __forceinline__ void attn_colsum_body(const AttnArgs& a, char* lds, i
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = fz + rb * 32 + mma32_row(v, lane);
-          u = fmaf(fast_exp2(fmaf(acc[rb][v] + acl[rb][v], c2, fin_o[row])), fin_i[row], u);
+          u = fmaf(fast_exp2(fmaf(acc[rb][v], c2, fin_o[row])), fin_i[row], u);
         }
-      if (tnext < t_end) {
-#pragma unroll
-        for (int c = 0; c < 2 * NG; ++c) kb.raw[c] = kn.raw[c];
-      }
     }
     u += __shfl_xor(u, 32);
     if (hf == 0 && j < a.V) out[j] = u;
-    if constexpr (!F32) {
-      if (tnext < t_end) {
-        if (PREF) {
-#pragma unroll
-          for (int c = 0; c < NG; ++c) kb.op[c] = kn.op[c];
-        } else {
-          kb.load(kbase + (int64_t)min(tnext * 32 + n, a.V - 1) * krow_bytes);
-        }
-      }
-    }
   }
 }
 
-template <typename T, int RB, int NG, bool QREG>
-__global__ __launch_bounds__(256, ((RB <= 2 && NG <= 8 && sizeof(T) == 2) ? 2 : 1)) void k_attn_colsum(AttnArgs a) {
+template <typename T, int NG>
+__global__ __launch_bounds__(256, 2) void k_attn_colsum(AttnArgs a) {
   extern __shared__ __align__(16) char lds[];
+  const SweepId w = sweep_id(a);
   int row0, nrows;
-  ranking_rows(a, blockIdx.z, row0, nrows);
-  const int nrb = (nrows + 31) >> 5;
-  if (nrb <= 1) attn_colsum_body<T, RB, 1, NG, QREG>(a, lds, row0, nrows);
-  else if (RB >= 2 && nrb == 2) attn_colsum_body<T, RB, (RB >= 2 ? 2 : 1), NG, QREG>(a, lds, row0, nrows);
-  else if (RB >= 3 && nrb == 3) attn_colsum_body<T, RB, (RB >= 3 ? 3 : 1), NG, QREG>(a, lds, row0, nrows);
-  else if (RB >= 4) attn_colsum_body<T, RB, (RB >= 4 ? 4 : 1), NG, QREG>(a, lds, row0, nrows);
+  ranking_rows(a, w.b, row0, nrows);
+  row0 += w.rp * ATT_ROWS;
+  nrows = min(nrows - w.rp * ATT_ROWS, ATT_ROWS);
+  if (nrows <= 0) {
+    // the image's text ends before this pair of row blocks: its column sums are zero
+    const int ntiles = (a.V + 31) >> 5;
+    const int j_lo = w.sp * a.tiles_per_split * 32, j_hi = min(a.V, min(ntiles, (w.sp + 1) * a.tiles_per_split) * 32);
+    float* out = a.upart + (((int64_t)w.b * a.H + w.h) * a.RP + w.rp) * a.V;
+    for (int j = j_lo + threadIdx.x; j < j_hi; j += 256) out[j] = 0.0f;
+    return;
+  }
+  if (nrows <= 32) attn_colsum_body<T, 1, NG>(a, lds, w, row0, nrows);
+  else attn_colsum_body<T, 2, NG>(a, lds, w, row0, nrows);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -894,7 +887,7 @@ __global__ __launch_bounds__(256) void k_colsum_logits(AttnArgs a) {
   const int j = blockIdx.x * 256 + threadIdx.x;
   int row0, nrows;
   ranking_rows(a, b, row0, nrows);
-  final_row_stats(a, b, h, 32, row0, nrows, fin_o, fin_i);
+  final_row_stats(a, b, h, 32, 0, 32, row0, nrows, fin_o, fin_i);
   __syncthreads();
   if (j >= a.V) return;
   const float* z = a.zlog + (((int64_t)b * a.H + h) * a.T_eff) * a.V + j;
@@ -914,17 +907,18 @@ __device__ __forceinline__ double rank_count(const int32_t* text_len, int b, int
 
 __global__ __launch_bounds__(256) void k_score(const float* __restrict__ upart, const double* __restrict__ s64,
                                                 const unsigned long long* __restrict__ mmkey,
-                                                const int32_t* __restrict__ text_len, int H, int V, int Tmax,
+                                                const int32_t* __restrict__ text_len, int H, int HV, int V, int Tmax,
                                                 int last_only, double lambda_max, double eps, int mask_on,
                                                 float* __restrict__ s_hat, float* __restrict__ score) {
+  // HV = rows of upart per image: one per head and pair of text-row blocks
   __shared__ double part[4][64];
   const int b = blockIdx.y, jl = threadIdx.x & 63, hq = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + jl;
   double u = 0.0;
   if (j < V) {
-    const float* up = upart + (int64_t)b * H * V + j;
+    const float* up = upart + (int64_t)b * HV * V + j;
     int h = hq;
-    for (; h + 12 < H; h += 16) {
+    for (; h + 12 < HV; h += 16) {
       float u0 = up[(int64_t)h * V], u1 = up[(int64_t)(h + 4) * V], u2 = up[(int64_t)(h + 8) * V],
             u3 = up[(int64_t)(h + 12) * V];
       u += (double)u0;
@@ -932,7 +926,7 @@ __global__ __launch_bounds__(256) void k_score(const float* __restrict__ upart, 
       u += (double)u2;
       u += (double)u3;
     }
-    for (; h < H; h += 4) u += (double)up[(int64_t)h * V];
+    for (; h < HV; h += 4) u += (double)up[(int64_t)h * V];
   }
   part[hq][jl] = u;
   __syncthreads();
@@ -956,8 +950,8 @@ __global__ __launch_bounds__(256) void k_score(const float* __restrict__ upart, 
 __global__ __launch_bounds__(SEL_THREADS) void k_score_select(const float* __restrict__ upart,
                                                                const double* __restrict__ s64,
                                                                const unsigned long long* __restrict__ mmkey,
-                                                               const int32_t* __restrict__ text_len, int H, int V,
-                                                               int k, int Tmax, int last_only, double lambda_max,
+                                                               const int32_t* __restrict__ text_len, int H, int HV,
+                                                               int V, int k, int Tmax, int last_only, double lambda_max,
                                                                double eps, int mask_on, float* __restrict__ s_hat,
                                                                float* __restrict__ score, int32_t* __restrict__ kept,
                                                                int32_t* __restrict__ pruned) {
@@ -969,19 +963,19 @@ __global__ __launch_bounds__(SEL_THREADS) void k_score_select(const float* __res
   const double lo = f64_unkey(mmkey[2 * b]), hi = f64_unkey(mmkey[2 * b + 1]);
   const double inv = 1.0 / (hi - lo + eps);
   const double norm = (double)H * rank_count(text_len, b, Tmax, last_only);
-  const float* up = upart + (int64_t)b * H * V;
+  const float* up = upart + (int64_t)b * HV * V;
   float mine = 0.0f;
   for (int j = tid; j < V; j += SEL_THREADS) {
     double part[4] = {0.0, 0.0, 0.0, 0.0};
     int h = 0;
-    for (; h + 16 <= H; h += 16) {          // 16 loads in flight; head h adds to group h % 4, in order
+    for (; h + 16 <= HV; h += 16) {         // 16 loads in flight; row h adds to group h % 4, in order
       float u[16];
 #pragma unroll
       for (int q = 0; q < 16; ++q) u[q] = up[(int64_t)(h + q) * V + j];
 #pragma unroll
       for (int q = 0; q < 16; ++q) part[q & 3] += (double)u[q];
     }
-    for (; h < H; ++h) part[h & 3] += (double)up[(int64_t)h * V + j];
+    for (; h < HV; ++h) part[h & 3] += (double)up[(int64_t)h * V + j];
     const double usum = ((part[0] + part[1]) + part[2]) + part[3];
     const double shat = (s64[(int64_t)b * V + j] - lo) * inv;
     const double lam = mask_on ? fmax(lambda_max * shat, eps) : 1.0;
@@ -1027,10 +1021,11 @@ static int ranking_rows_max(const asap_params& p) { return p.score_rows == ASAP_
 // on ties; a split has at least 4 tiles (one per wave).
 static int attn_splits(const asap_params& p) {
   const int ntiles = (p.V + 31) / 32;
-  const int rb = (ranking_rows_max(p) + 31) / 32, ch = p.d / 16;
-  int per_cu = rb * ch <= 4 ? 4 : (rb * ch <= 8 && ch == 8) ? 3 : (rb * ch <= 16 && ch <= 8) ? 2 : 1;
-  if (p.qk_dtype != ASAP_BF16) per_cu = 1;
-  const long slots = 256L * per_cu, groups = (long)p.H * p.B;
+  const int rows = ranking_rows_max(p);
+  const int rb = rows > 32 ? 2 : 1, ch = p.d / 16, rp = (rows + 63) / 64;
+  int per_cu = rb * ch <= 4 ? 4 : (rb * ch <= 8 && ch == 8) ? 3 : 2;
+  if (p.qk_dtype != ASAP_BF16) per_cu = 2;
+  const long slots = 256L * per_cu, groups = (long)p.H * p.B * rp;
   int smax = ntiles / 4;
   if (smax > 16) smax = 16;
   if (smax < 1) smax = 1;
@@ -1071,7 +1066,8 @@ ScoreWorkspace score_workspace(const asap_params& p) {
     for (int hs = p.Hkv; hs >= 1; --hs)
       if (p.Hkv % hs == 0 && hs <= want) { w.head_splits = hs; break; }
   }
-  const int NR = ((w.t_eff + 31) / 32) * 32;
+  w.row_pairs = w.ride ? 1 : (w.t_eff + 63) / 64;
+  const int NR = w.ride ? 32 : 64 * w.row_pairs;
   const int splits = w.ride ? 1 : w.attn_splits;
   size_t off = 0;
   w.off_qpart = off;  off = align256(off + sizeof(double) * p.B * p.H * w.q_chunks * p.d);
@@ -1080,7 +1076,7 @@ ScoreWorkspace score_workspace(const asap_params& p) {
   w.off_s64 = off;    off = align256(off + sizeof(double) * p.B * p.V);
   w.off_mm = off;     off = align256(off + sizeof(double) * p.B * 2);
   w.off_pstat = off;  off = align256(off + sizeof(float) * (size_t)p.B * p.H * splits * 2 * NR);
-  w.off_upart = off;  off = align256(off + sizeof(float) * (size_t)p.B * p.H * p.V);
+  w.off_upart = off;  off = align256(off + sizeof(float) * (size_t)p.B * p.H * w.row_pairs * p.V);
   w.off_spart = off;
   if (w.head_splits > 1) off = align256(off + sizeof(double) * (size_t)w.head_splits * p.B * p.V);
   w.off_zlog = off;
@@ -1089,12 +1085,11 @@ ScoreWorkspace score_workspace(const asap_params& p) {
   return w;
 }
 
-template <typename T, int RB, int NG, bool QREG>
+template <typename T, int NG>
 static hipError_t launch_attn(const asap_params& p, const AttnArgs& a, hipStream_t st, Timer* tm) {
-  constexpr int NR = RB * 32;
-  const size_t lds = query_lds_bytes<T, RB, NG, QREG>() + sizeof(float) * 8 * NR;
-  auto k1 = k_attn_stats<T, RB, NG, QREG>;
-  auto k2 = k_attn_colsum<T, RB, NG, QREG>;
+  const size_t lds = query_lds_bytes<T, NG>() + sizeof(float) * 8 * ATT_ROWS;
+  auto k1 = k_attn_stats<T, NG>;
+  auto k2 = k_attn_colsum<T, NG>;
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1103,23 +1098,10 @@ static hipError_t launch_attn(const asap_params& p, const AttnArgs& a, hipStream
                               (int)lds);
     if (e != hipSuccess) return e;
   }
-  ASAP_LAUNCH(tm, "k_attn_stats", k1, dim3(a.S, p.H, p.B), dim3(256), lds, st, a);
-  ASAP_LAUNCH(tm, "k_attn_colsum", k2, dim3(a.S, p.H, p.B), dim3(256), lds, st, a);
+  const dim3 grid(p.H * a.RP * a.S, p.B);
+  ASAP_LAUNCH(tm, "k_attn_stats", k1, grid, dim3(256), lds, st, a);
+  ASAP_LAUNCH(tm, "k_attn_colsum", k2, grid, dim3(256), lds, st, a);
   return hipGetLastError();
-}
-
-template <typename T, int NG>
-static hipError_t dispatch_rb(const asap_params& p, const AttnArgs& a, hipStream_t st, Timer* tm) {
-  // bf16 queries stay in registers while they need at most 64 VGPRs; f32 queries go to LDS as pieces
-  constexpr bool BF = sizeof(T) == 2;
-  constexpr bool R1 = BF && NG * 4 <= 64, R2 = BF && NG * 8 <= 64;
-  switch ((a.T_eff + 31) / 32) {
-    case 1: return launch_attn<T, 1, NG, R1>(p, a, st, tm);
-    case 2: return launch_attn<T, 2, NG, R2>(p, a, st, tm);
-    case 3: return launch_attn<T, 3, NG, false>(p, a, st, tm);
-    case 4: return launch_attn<T, 4, NG, false>(p, a, st, tm);
-  }
-  return hipErrorInvalidValue;
 }
 
 template <typename T, int NG>
@@ -1182,7 +1164,7 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   AttnArgs a;
   a.qt = q_txt; a.sq = qt; a.kv = k_vis; a.sk = kv; a.s64 = s64; a.mmkey = mmkey; a.text_len = text_len;
   a.lse_extra = lse_extra; a.pstat = pstat; a.upart = upart; a.zlog = zlog;
-  a.H = p.H; a.Hkv = p.Hkv; a.V = p.V; a.Tmax = p.Tmax; a.S = w.ride ? 1 : w.attn_splits;
+  a.H = p.H; a.Hkv = p.Hkv; a.V = p.V; a.Tmax = p.Tmax; a.S = w.ride ? 1 : w.attn_splits; a.RP = w.row_pairs;
   a.tiles_per_split = (ktiles + a.S - 1) / a.S;
   a.T_eff = w.t_eff; a.last_only = last_only;
   a.c2 = (float)(1.4426950408889634 / sqrt((double)p.d));
@@ -1192,9 +1174,9 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
     ASAP_LAUNCH(tm, "k_colsum_logits", k_colsum_logits, dim3((p.V + 255) / 256, p.H, p.B), dim3(256), 0, st, a);
     e = hipGetLastError();
   } else if (ng == 8) {
-    e = dispatch_rb<T, 8>(p, a, st, tm);
+    e = launch_attn<T, 8>(p, a, st, tm);
   } else {
-    e = dispatch_rb<T, 4>(p, a, st, tm);
+    e = launch_attn<T, 4>(p, a, st, tm);
   }
   if (e != hipSuccess) return e;
   // The selection rides in the launch that finishes the score when the batch gives that launch (one
@@ -1202,7 +1184,7 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   // on batches of 4 and 8 it lost to the two separate launches.
   if (kept != nullptr && p.B < 12) {
     ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
-                p.H, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
+                p.H, p.H * w.row_pairs, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
     hipError_t e2 = hipGetLastError();
     return e2 != hipSuccess ? e2 : launch_select(p, score, kept, pruned, st, tm);
   }
@@ -1214,11 +1196,11 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
       if (e != hipSuccess) return e;
     }
     ASAP_LAUNCH(tm, "k_score_select", k_score_select, dim3(p.B), dim3(SEL_THREADS), lds, st, upart, s64, mmkey,
-                text_len, p.H, p.V, p.k, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score,
+                text_len, p.H, p.H * w.row_pairs, p.V, p.k, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score,
                 kept, pruned);
   } else {
     ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
-                p.H, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
+                p.H, p.H * w.row_pairs, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
   }
   return hipGetLastError();
 }
