@@ -63,46 +63,6 @@ __device__ __forceinline__ void split_bf16x4(double x, uint16_t* out, int stride
 }
 
 // ------------------------------------------------------------------------------------------
-// Eight consecutive f32 values (two 16-byte chunks) as three bf16x8 operands: hi = rne(x),
-// mid = rne(x - hi), lo = rne(x - hi - mid); the differences are exact, |x - hi - mid - lo| <= 2^-27 |x|.
-// ------------------------------------------------------------------------------------------
-typedef __bf16 sc_bf16x2 __attribute__((ext_vector_type(2)));
-typedef float sc_f32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t pk_bf16(float a, float b) {
-  sc_f32x2 x = {a, b};
-  sc_bf16x2 y = __builtin_convertvector(x, sc_bf16x2);
-  uint32_t u;
-  __builtin_memcpy(&u, &y, 4);
-  return u;
-}
-struct Split3 { uint4 hi, mid, lo; };
-__device__ __forceinline__ void split_pair(float a, float b, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
-  hi = pk_bf16(a, b);
-  const float ra = a - __uint_as_float(hi << 16), rb = b - __uint_as_float(hi & 0xffff0000u);
-  mid = pk_bf16(ra, rb);
-  lo = pk_bf16(ra - __uint_as_float(mid << 16), rb - __uint_as_float(mid & 0xffff0000u));
-}
-__device__ __forceinline__ Split3 split_f32x8(const uint4& c0, const uint4& c1) {
-  Split3 s;
-  split_pair(__uint_as_float(c0.x), __uint_as_float(c0.y), s.hi.x, s.mid.x, s.lo.x);
-  split_pair(__uint_as_float(c0.z), __uint_as_float(c0.w), s.hi.y, s.mid.y, s.lo.y);
-  split_pair(__uint_as_float(c1.x), __uint_as_float(c1.y), s.hi.z, s.mid.z, s.lo.z);
-  split_pair(__uint_as_float(c1.z), __uint_as_float(c1.w), s.hi.w, s.mid.w, s.lo.w);
-  return s;
-}
-// The six piece products of one contraction group, smallest first, into one accumulator: the small
-// ones land on partial sums of the large ones, i.e. they are rounded at the level the hi.hi products
-// of the row are rounded at anyway (2^-24 of the running sum).
-__device__ __forceinline__ void mma_split(f32x16_t& acc, const Split3& a, const Split3& b) {
-  mma32<bf16_t>(acc, a.lo, b.hi);
-  mma32<bf16_t>(acc, a.hi, b.lo);
-  mma32<bf16_t>(acc, a.mid, b.mid);
-  mma32<bf16_t>(acc, a.mid, b.hi);
-  mma32<bf16_t>(acc, a.hi, b.mid);
-  mma32<bf16_t>(acc, a.hi, b.hi);
-}
-
-// ------------------------------------------------------------------------------------------
 // k_qsum: grid (chunks, H, B), 1024 threads.  A row is d elements = LPR 16-byte pieces; thread t
 // keeps piece t % LPR of rows t / LPR + RPI * i.  Block (0, 0, b) also resets the min / max keys.
 // With one chunk and one query head per kv head the block's sums are final (`direct`): it writes

@@ -233,6 +233,56 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
         if (u < PB) load_to_lds16(gb, offb[u < PB ? u : 0], db + u * 32 * SIM_ROWB);
         else if (u < PB + PA) load_to_lds16(ga, offa[u < PB + PA ? u - PB : 0], da + (u - PB) * 32 * SIM_ROWB);
       };
+      if constexpr (sizeof(T) == 4) {
+        // f32: the bf16 matrix instructions take three bf16 pieces per value (hi + mid + lo = the value to
+        // 2^-27) and a product is the sum of the six piece products that matter -- a third of the matrix
+        // time of the f32 instruction.  Two 16-byte chunks make one contraction group of 8 values, so a
+        // step has two groups; every operand is split once per group and meets all its partners.
+        uint4 ra[2][2], rb[NT][2];
+        auto read_group = [&](int gq) {
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) ra[i][u] = *reinterpret_cast<const uint4*>(A + i * 32 * SIM_ROWB + sw[2 * gq + u]);
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) rb[t][u] = *reinterpret_cast<const uint4*>(Bp + t * 32 * SIM_ROWB + sw[2 * gq + u]);
+        };
+        read_group(0);
+#pragma unroll
+        for (int gq = 0; gq < 2; ++gq) {
+          Split3 a3[2], b3[NT];
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            a3[i] = split_f32x8(ra[i][0], ra[i][1]);
+            sumsq16<T>(ra[i][0], ss_a[i]);
+            sumsq16<T>(ra[i][1], ss_a[i]);
+          }
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            b3[t] = split_f32x8(rb[t][0], rb[t][1]);
+            sumsq16<T>(rb[t][0], ss_b[t]);
+            sumsq16<T>(rb[t][1], ss_b[t]);
+          }
+          if (gq == 0) read_group(1);       // the raw registers are free again
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+              // 4 NT slots for the PA + PB loads of the step, issued in their order (all destination
+              // loads before the source loads, as the wait below assumes): two per slot at NT = 1
+              constexpr int PER = (PA + PB + 4 * NT - 1) / (4 * NT);
+              const int u = ((gq * NT + t) * 2 + i) * PER;
+              mma_split(acc[i][t], a3[i], b3[t]);
+#pragma unroll
+              for (int x = 0; x < PER; ++x) load_unit(u + x);
+            }
+        }
+        wait_vmem_but<PA + (NB - 2) * (PA + PB)>();
+        barrier_keep_loads();
+        continue;
+      }
       // LDS operand reads run one contraction slice ahead of the MFMAs that use them
       uint4 a[2][2], bq[2][NT];
       auto load_op = [&](int set, int kk, int u) {      // in the order the MFMAs need them
