@@ -182,7 +182,7 @@ struct RideArgs {
 // spart [HS, B, V] for k_mass_finish.
 // ------------------------------------------------------------------------------------------
 template <typename T, int NG, bool RIDE>
-__global__ __launch_bounds__(256) void k_mass_mfma(const T* __restrict__ kv, Strides3 sk,
+__global__ __launch_bounds__(256, (sizeof(T) == 4 ? 2 : RIDE ? 3 : 1)) void k_mass_mfma(const T* __restrict__ kv, Strides3 sk,
                                                     const uint16_t* __restrict__ qsplit, int Hkv, int V, int HS,
                                                     double scale, double* __restrict__ s64, float* __restrict__ s_raw,
                                                     unsigned long long* __restrict__ mmkey,
@@ -194,6 +194,9 @@ __global__ __launch_bounds__(256) void k_mass_mfma(const T* __restrict__ kv, Str
   constexpr int NC = GB / 16;                         // 16-byte chunks per group and lane
   constexpr bool F32 = GB == 32;
   static_assert(!RIDE || !F32, "text rows ride with bf16 keys only");
+  // one register set for the key rows (reloaded as soon as it is staged) where a second would cost a
+  // workgroup per compute unit: f32 rows, and the kernel that also carries text rows
+  constexpr bool REUSE = F32 || RIDE;
   __shared__ __align__(16) char stage[4][32 * RBY];
   __shared__ double part[4][32];
   __shared__ unsigned long long blk_mm[2];
@@ -267,13 +270,13 @@ __global__ __launch_bounds__(256) void k_mass_mfma(const T* __restrict__ kv, Str
   double sum = 0.0;
   for (; g < g_hi; g += 4) {
     const int gn = g + 4;
-    if (!F32 && gn < g_hi) {
+    if (!REUSE && gn < g_hi) {
 #pragma unroll
       for (int i = 0; i < NL; ++i) kn[i] = ldg16(kbase + gn * headb + roff[i]);
     }
 #pragma unroll
     for (int i = 0; i < NL; ++i) *reinterpret_cast<uint4*>(st + wr[i]) = kb[i];
-    if (F32 && gn < g_hi) {      // 16 registers per row set: the next head's rows reuse this head's
+    if (REUSE && gn < g_hi) {    // the next head's rows reuse this head's registers once those are staged
 #pragma unroll
       for (int i = 0; i < NL; ++i) kb[i] = ldg16(kbase + gn * headb + roff[i]);
     }
@@ -285,12 +288,14 @@ __global__ __launch_bounds__(256) void k_mass_mfma(const T* __restrict__ kv, Str
       for (int c = 0; c < NG; ++c) mma32<bf16_t>(acc, qa[c], *reinterpret_cast<const uint4*>(st + rd[c][0]));
       sum += ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);   // rows 0..3 (lanes < 32)
       if (RIDE) {
-        float* zl = ra.zlog + ((int64_t)(b * ra.H + g * ra.G) * ra.T_eff) * V + j0 + n;
+        // wave-uniform base + 32-bit lane offset: row r of this head group's [G T_eff, V] block, key j0 + n
+        float* zl = ra.zlog + ((int64_t)(b * ra.H + g * ra.G) * ra.T_eff) * V;
+        const uint32_t lane_off = (uint32_t)((4 * hf - 4) * V + j0 + n);      // wraps for hf = 0; the sums below do not
         if (j0 + n < V) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int r = 8 * (v >> 2) + 4 * hf + (v & 3) - 4;
-            if (r >= 0 && r < ride_rows) zl[(int64_t)r * V] = acc[v];
+            if (r >= 0 && r < ride_rows) zl[lane_off + (uint32_t)((8 * (v >> 2) + (v & 3)) * V)] = acc[v];
           }
         }
       }
@@ -314,7 +319,7 @@ __global__ __launch_bounds__(256) void k_mass_mfma(const T* __restrict__ kv, Str
     }
     if (gn < g_hi) {
       load_a(qa, gn);      // small, cached: not worth registers of its own
-      if (!F32) {
+      if (!REUSE) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) kb[i] = kn[i];
       }
