@@ -168,6 +168,55 @@ def bench_library_gemm(args, cfg):
         "gemm_8192_cubed_us": 1e6 * t_big, "gemm_8192_cubed_frac_of_mfma_peak": 2.0 * 8192 ** 3 / t_big / peak}))
 
 
+def bench_front_end(args, cfg):
+    """asap_score_from_hidden (Eq. 2 from the hidden states, the fused front end) against asap_score on the
+    same workload: the whole scoring call both ways, and the kernels of each."""
+    import numpy as np
+    import torch
+    from paper_2603_14549_amd import binding, harness, synth
+    inp = synth.make_inputs(cfg, with_kv=False)
+    ctx = binding.Context(0)
+    st = harness.DeviceStage(inp, ctx=ctx)
+    P, V = cfg.P, cfg.V
+    wq = harness.to_device(synth.quantise(np.ascontiguousarray(inp["Wq"].T), cfg.h_dtype), cfg.h_dtype)
+    ws = torch.empty(binding.asap_front_end_workspace_bytes(st.p), dtype=torch.uint8, device="cuda")
+    q_vis, q_txt, k_vis = st.q[:, :, P:P + V], st.q[:, :, P + V:], st.k[:, :, P:P + V]
+    b = st.buf
+    calls = {
+        "asap_score": lambda: ctx.asap_score(st.p, q_vis, q_txt, k_vis, st.text_len, None, b.s_raw, b.s_hat, b.score,
+                                             b.workspace),
+        "asap_score_from_hidden": lambda: ctx.asap_score_from_hidden(st.p, st.hidden, wq, cfg.rope_theta, None, q_txt,
+                                                                     k_vis, st.text_len, None, b.s_raw, b.s_hat,
+                                                                     b.score, ws),
+    }
+    res = {}
+    for name, run in calls.items():
+        for _ in range(args.warmup):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        ctx.asap_timing_enable(min(8192, 12 * args.steps))
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        timing = ctx.asap_timing_collect()
+        ctx.asap_timing_enable(0)
+        res[name] = {"ms_per_call": ms, "kernels_us": {k: round(1e3 * v[0] / v[1], 1) for k, v in timing.items()}}
+    eh, eq = esize(cfg.h_dtype), esize(cfg.qk_dtype)
+    print(json.dumps({
+        "metric": "scoring call: visual queries given vs taken from the hidden states", "unit": "ms", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "dtype": cfg.h_dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B}, {cfg.V} visual tokens, hidden {cfg.D}, {cfg.H} heads x {cfg.d}"},
+        "bytes_read_visual_queries_MB": cfg.B * cfg.H * cfg.V * cfg.d * eq / 1e6,
+        "bytes_read_visual_hidden_MB": cfg.B * cfg.V * cfg.D * eh / 1e6,
+        "extra_multiply_adds_G": 2.0 * cfg.B * cfg.d * cfg.V * cfg.D / 1e9,
+        **res}))
+
+
 def bench_attention(args, cfg):
     """asap_attention on the workload's shapes: q, k from the generator, random values; one launch set
     (bias, transpose, attention) per step.  Flops = 4 d per (query, key) pair the mask lets through."""
@@ -226,6 +275,9 @@ def main():
     ap.add_argument("--attention", action="store_true",
                     help="measure asap_attention (one layer's forward under the Eq. 4-5 mask) on the workload's "
                          "shapes instead of the pruning stage; prints its own JSON line")
+    ap.add_argument("--front-end", action="store_true",
+                    help="time asap_score_from_hidden (Eq. 2 from the hidden states) against asap_score on the "
+                         "workload; prints its own JSON line")
     ap.add_argument("--library-gemm", action="store_true",
                     help="reference point only: time the vendor GEMM library (torch.bmm) on the similarity "
                          "product's shape with dense operands, and an 8192^3 GEMM; prints its own JSON line")
@@ -263,6 +315,8 @@ def main():
         return bench_attention(args, cfg)
     if args.library_gemm:
         return bench_library_gemm(args, cfg)
+    if args.front_end:
+        return bench_front_end(args, cfg)
     t0 = time.perf_counter()
     inp = synth.make_inputs(cfg)
     gen_s = time.perf_counter() - t0

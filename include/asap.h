@@ -133,6 +133,33 @@ asap_status asap_score(asap_ctx* ctx, const asap_params* p,
                        void* workspace, size_t workspace_bytes, void* stream /* hipStream_t */);
 
 /*
+ * asap_score_from_hidden -- asap_score with the raw mass of Eq. 2 taken from the hidden states instead
+ * of from the visual queries (Sec. 3.1: a query is q_m = R_{Theta,m} W_q x_m, and Eq. 2 only needs the
+ * sum of the visual queries, which is linear in the hidden states): the front end of the stage for a
+ * caller that has not materialised the visual queries.  The rotation pairs coordinates (c, c + d/2) of
+ * every head at angle pos * rope_theta^(-2c/d).
+ *   hidden [B,N,D] h_dtype with element strides hidden_stride[2] (visual rows start at P);
+ *   w_q [H*d, D] h_dtype, contiguous (row e = the weights of query coordinate e, i.e. q = W_q x);
+ *   vis_positions: NULL (visual token i sits at position P + i) or [B,V] int32 position ids (a second
+ *   stage keeps the original ids of its survivors);
+ *   q_txt, k_vis, text_len, lse_extra, the outputs and every rule as for asap_score.
+ * The workspace needs asap_front_end_workspace_bytes(p) bytes, 256-byte aligned.  The trigonometric
+ * weights are taken in fp64 and rounded to f32; token sums run in fp32 over 64 tokens and in fp64 above.
+ * The call reads the visual hidden states (B V D elements) where asap_score reads the visual queries
+ * (B H V d elements) and does 2 d V D more multiply-adds per image: it is there for completeness of
+ * the path, not for speed.
+ */
+size_t      asap_front_end_workspace_bytes(const asap_params* p);
+asap_status asap_score_from_hidden(asap_ctx* ctx, const asap_params* p,
+                                   const void* hidden, const int64_t hidden_stride[2],
+                                   const void* w_q, double rope_theta, const int32_t* vis_positions,
+                                   const void* q_txt, const int64_t q_txt_stride[3],
+                                   const void* k_vis, const int64_t k_vis_stride[3],
+                                   const int32_t* text_len, const float* lse_extra,
+                                   float* s_raw, float* s_hat, float* score,
+                                   void* workspace, size_t workspace_bytes, void* stream /* hipStream_t */);
+
+/*
  * asap_score_static -- asap_score for callers that cannot allocate device memory and have no
  * workspace to hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Arguments, results and checks are those of asap_score without the workspace; the

@@ -24,6 +24,8 @@ order and notation, with no blocking, fusion or reordering:
   stage                     all steps for one image (score_rows="last": ranking by the last text token)
   full_bidirectional_attention   literal N x N Eq. 4-5, brute force, for pins only
   theoretical_flops / flops_ratio   Eq. 7 / Eq. 8 (appendix)
+  rope_rotate / project_queries / summed_visual_queries / attention_mass_from_summed_queries
+                            Sec. 3.1: q_m = R_{Theta,m} W_q x_m, and Eq. 2 taken from the hidden states
 
 Readings taken where the paper is silent (each is listed in the design notes):
 heads are averaged (Eq. 2-4 carry no head index); the selection score is the
@@ -381,3 +383,43 @@ def theoretical_flops(layers: Sequence[int], tokens: Sequence[int], d: int, m: i
 def flops_ratio(layers: Sequence[int], tokens: Sequence[int], v0: int, d: int, m: int) -> float:
     """Eq. 8: Eq. 7 over the unpruned cost of all layers at v0 tokens."""
     return theoretical_flops(layers, tokens, d, m) / (sum(layers) * layer_flops(v0, d, m))
+
+
+# ---------------------------------------------------------------- Sec. 3.1: the RoPE score, and Eq. 2 from hidden states
+def rope_rotate(v: np.ndarray, pos, theta: float = 10000.0) -> np.ndarray:
+    """R_{Theta,m} v of Sec. 3.1 for vectors v [..., n, d] at positions pos [n]: the rotation by angle
+    pos * theta^(-2c/d) of every coordinate pair; pairs are (c, c + d/2), the rotate-half layout of the
+    LLaMA-family backbones the paper prunes (the paper writes R_{Theta,m-n} and leaves the pairing to them)."""
+    d = v.shape[-1]
+    half = d // 2
+    inv_freq = theta ** (-2.0 * np.arange(half, dtype=np.float64) / d)
+    ang = np.asarray(pos, dtype=np.float64)[:, None] * inv_freq[None, :]            # [n, half]
+    c, s = np.cos(ang), np.sin(ang)
+    v1, v2 = v[..., :half], v[..., half:]
+    return np.concatenate([v1 * c - v2 * s, v2 * c + v1 * s], axis=-1)
+
+
+def project_queries(X: np.ndarray, Wq: np.ndarray, pos, H: int, d: int, theta: float = 10000.0) -> np.ndarray:
+    """q_m = R_{Theta,m} W_q x_m (Sec. 3.1).  X [n, D] hidden states, Wq [H*d, D], pos [n] -> Q [H, n, d]."""
+    U = (X @ Wq.T).reshape(X.shape[0], H, d).transpose(1, 0, 2)                      # [H, n, d]
+    return rope_rotate(U, pos, theta)
+
+
+def summed_visual_queries(Xv: np.ndarray, Wq: np.ndarray, pos, H: int, Hkv: int, d: int,
+                          theta: float = 10000.0) -> np.ndarray:
+    """sum over the visual tokens of their queries, per key/value head: the only thing Eq. 2 needs of
+    the visual queries (sum_i W_ij = (sum_i q_i) . k_j / sqrt(d)).  Xv [V, D] -> [Hkv, d]."""
+    Q = project_queries(Xv, Wq, pos, H, d, theta)                                    # [H, V, d]
+    out = np.zeros((Hkv, d), dtype=np.float64)
+    for h in range(H):
+        out[kv_head(h, H, Hkv)] += Q[h].sum(axis=0)
+    return out
+
+
+def attention_mass_from_summed_queries(qbar: np.ndarray, Kv: np.ndarray, H: int) -> np.ndarray:
+    """Eq. 2 from the summed visual queries qbar [Hkv, d] and the visual keys Kv [Hkv, V, d]."""
+    d = Kv.shape[2]
+    s = np.zeros(Kv.shape[1], dtype=np.float64)
+    for g in range(Kv.shape[0]):
+        s += (Kv[g] @ qbar[g]) / math.sqrt(d)
+    return s / H

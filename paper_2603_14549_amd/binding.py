@@ -22,7 +22,7 @@ ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
 ASAP_ROWS_ALL, ASAP_ROWS_LAST = 0, 1
 
 EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
-           "asap_score", "asap_score_static", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv",
+           "asap_score", "asap_score_static", "asap_score_from_hidden", "asap_front_end_workspace_bytes", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv",
            "asap_compact_kv_from_kept", "asap_compact_kv_paged", "asap_stage",
            "asap_timing_enable",
            "asap_timing_collect", "asap_theoretical_flops", "asap_flops_ratio", "asap_attention",
@@ -98,6 +98,11 @@ def load() -> ctypes.CDLL:
     lib.asap_score.restype = ctypes.c_int
     lib.asap_score_static.argtypes = [vp, pp, vp, i64p, vp, i64p, vp, i64p, i32p, f32p, f32p, f32p, f32p, vp]
     lib.asap_score_static.restype = ctypes.c_int
+    lib.asap_front_end_workspace_bytes.argtypes = [pp]
+    lib.asap_front_end_workspace_bytes.restype = ctypes.c_size_t
+    lib.asap_score_from_hidden.argtypes = [vp, pp, vp, i64p, vp, ctypes.c_double, i32p, vp, i64p, vp, i64p, i32p, f32p,
+                                           f32p, f32p, f32p, vp, ctypes.c_size_t, vp]
+    lib.asap_score_from_hidden.restype = ctypes.c_int
     lib.asap_select.argtypes = [vp, pp, f32p, i32p, i32p, vp, ctypes.c_size_t, vp]
     lib.asap_select.restype = ctypes.c_int
     lib.asap_merge.argtypes = [vp, pp, vp, i64p, f32p, f32p, i32p, i32p, i32p, vp, i32p, i32p, i32p, f32p, f32p, i32p,
@@ -158,6 +163,10 @@ def asap_check_params(p: asap_params):
 
 def asap_workspace_bytes(p: asap_params) -> int:
     return int(load().asap_workspace_bytes(ctypes.byref(p)))
+
+
+def asap_front_end_workspace_bytes(p: asap_params) -> int:
+    return int(load().asap_front_end_workspace_bytes(ctypes.byref(p)))
 
 
 def asap_attention_workspace_bytes(p: asap_params) -> int:
@@ -256,6 +265,14 @@ class Context:
             self._h, ctypes.byref(p), _ptr(q_vis), _strides(q_vis, 3), _ptr(q_txt), _strides(q_txt, 3),
             _ptr(k_vis), _strides(k_vis, 3), _ptr(text_len), _ptr(lse_extra), _ptr(s_raw), _ptr(s_hat),
             _ptr(score), _stream(stream)))
+
+    def asap_score_from_hidden(self, p, hidden, w_q, rope_theta, vis_positions, q_txt, k_vis, text_len, lse_extra,
+                               s_raw, s_hat, score, workspace, stream=None):
+        self._check(self._lib.asap_score_from_hidden(
+            self._h, ctypes.byref(p), _ptr(hidden), _strides(hidden, 2), _ptr(w_q), float(rope_theta),
+            _ptr(vis_positions), _ptr(q_txt), _strides(q_txt, 3), _ptr(k_vis), _strides(k_vis, 3), _ptr(text_len),
+            _ptr(lse_extra), _ptr(s_raw), _ptr(s_hat), _ptr(score), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream(stream)))
 
     def asap_select(self, p, score, kept_idx, pruned_idx, workspace, stream=None):
         self._check(self._lib.asap_select(

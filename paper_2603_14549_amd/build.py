@@ -18,7 +18,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB_DIR = os.path.join(PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libasap.so")
 SOURCES = ["asap_api.hip", "asap_score.hip", "asap_select.hip", "asap_sim.hip", "asap_paper.hip", "asap_merge.hip",
-           "asap_compact.hip", "asap_attention.hip"]
+           "asap_compact.hip", "asap_attention.hip", "asap_front.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          # packed-fp32 VALU forms stay off on the test machines

@@ -307,8 +307,53 @@ asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, c
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
   return hip_result(ctx,
                     launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                                 nullptr, nullptr, static_cast<char*>(workspace), static_cast<hipStream_t>(stream), ctx->timer),
+                                 nullptr, nullptr, nullptr, static_cast<char*>(workspace), static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_score launch");
+}
+
+size_t asap_front_end_workspace_bytes(const asap_params* p) {
+  if (check_params(p, nullptr, 0) != ASAP_OK) return 0;
+  return score_workspace(*p).total + front_workspace_bytes(*p);
+}
+
+asap_status asap_score_from_hidden(asap_ctx* ctx, const asap_params* p, const void* hidden,
+                                   const int64_t hidden_stride[2], const void* w_q, double rope_theta,
+                                   const int32_t* vis_positions, const void* q_txt, const int64_t q_txt_stride[3],
+                                   const void* k_vis, const int64_t k_vis_stride[3], const int32_t* text_len,
+                                   const float* lse_extra, float* s_raw, float* s_hat, float* score, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  asap_status st = common_checks(ctx, p);
+  if (st != ASAP_OK) return st;
+  if (!hidden || !w_q || !q_txt || !k_vis || !text_len || !s_raw || !s_hat || !score)
+    return fail(ctx, ASAP_EINVAL, "asap_score_from_hidden: a required pointer is NULL");
+  if (!aligned16(hidden) || !aligned16(w_q) || !aligned16(q_txt) || !aligned16(k_vis))
+    return fail(ctx, ASAP_EINVAL, "asap_score_from_hidden: hidden, w_q, q_txt and k_vis must be 16-byte aligned");
+  if (!(rope_theta > 1.0) || !isfinite(rope_theta))
+    return fail(ctx, ASAP_EINVAL, "asap_score_from_hidden: rope_theta must be finite and > 1");
+  if ((st = check_strides(ctx, "hidden_stride", hidden_stride, 2, 8)) != ASAP_OK) return st;
+  if ((st = check_strides(ctx, "q_txt_stride", q_txt_stride, 3, 8)) != ASAP_OK) return st;
+  if ((st = check_strides(ctx, "k_vis_stride", k_vis_stride, 3, 8)) != ASAP_OK) return st;
+  if (hidden_stride[1] < p->D || q_txt_stride[2] < p->d || k_vis_stride[2] < p->d)
+    return fail(ctx, ASAP_EINVAL, "asap_score_from_hidden: row strides must cover a row");
+  const int64_t esz = dtype_size(p->qk_dtype);
+  if ((st = check_span(ctx, "q_txt", p->Tmax, q_txt_stride[2], esz)) != ASAP_OK) return st;
+  if ((st = check_span(ctx, "k_vis", p->V, k_vis_stride[2], esz)) != ASAP_OK) return st;
+  const size_t need = asap_front_end_workspace_bytes(p);
+  if (!workspace) return fail(ctx, ASAP_EINVAL, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(ctx, ASAP_EINVAL, "workspace is not 256-byte aligned");
+  if (workspace_bytes < need)
+    return fail(ctx, ASAP_EWORKSPACE, "asap_score_from_hidden: workspace of %zu bytes, %zu needed", workspace_bytes, need);
+  char* ws = static_cast<char*>(workspace);
+  FrontArgs fe;
+  fe.hidden = hidden; fe.hsb = hidden_stride[0]; fe.hsr = hidden_stride[1]; fe.wq = w_q; fe.rope_theta = rope_theta;
+  fe.vis_positions = vis_positions; fe.ws = ws + score_workspace(*p).total;
+  Strides3 none{0, 0, 0};
+  Strides3 qt{q_txt_stride[0], q_txt_stride[1], q_txt_stride[2]};
+  Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
+  return hip_result(ctx,
+                    launch_score(*p, nullptr, none, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
+                                 nullptr, nullptr, &fe, ws, static_cast<hipStream_t>(stream), ctx->timer),
+                    "asap_score_from_hidden launch");
 }
 
 asap_status asap_score_static(asap_ctx* ctx, const asap_params* p, const void* q_vis,
@@ -337,7 +382,7 @@ asap_status asap_score_static(asap_ctx* ctx, const asap_params* p, const void* q
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
   return hip_result(ctx,
                     launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                                 nullptr, nullptr, static_cast<char*>(ctx->static_scratch), static_cast<hipStream_t>(stream),
+                                 nullptr, nullptr, nullptr, static_cast<char*>(ctx->static_scratch), static_cast<hipStream_t>(stream),
                                  ctx->timer),
                     "asap_score_static launch");
 }
@@ -524,7 +569,7 @@ asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io*
   char* ws = static_cast<char*>(io->workspace);
   // the selection rides in the launch that finishes the score
   hipError_t e = launch_score(*p, io->q_vis, qv, io->q_txt, qt, io->k_vis, kv, io->text_len, io->lse_extra, io->s_raw,
-                              io->s_hat, io->score, io->kept_idx, io->pruned_idx, ws, main, ctx->timer);
+                              io->s_hat, io->score, io->kept_idx, io->pruned_idx, nullptr, ws, main, ctx->timer);
   bool forked = false;
   if (e == hipSuccess && early) {
     e = hipEventRecord(ctx->ev_fork, main);

@@ -63,12 +63,26 @@ struct Timer {
     ::asap::Timer::end(asap_rec_, st);                                          \
   } while (0)
 
+// Eq. 2 from hidden states (asap_front.hip): the summed visual queries are computed from the hidden
+// states, W_q [H d, D] (h_dtype) and the rotary angles instead of from the visual queries.
+struct FrontArgs {
+  const void* hidden; int64_t hsb, hsr;   // [B,N,D] h_dtype, element strides
+  const void* wq;                         // [H*d, D] h_dtype, contiguous
+  double rope_theta;
+  const int32_t* vis_positions;           // [B,V] position ids of the visual tokens, or null: P + i
+  char* ws;                               // front_workspace_bytes(p)
+};
+size_t front_workspace_bytes(const asap_params& p);
+hipError_t launch_front_end(const asap_params& p, const void* hidden, int64_t hsb, int64_t hsr, const void* wq,
+                            double rope_theta, const int32_t* vis_positions, double* qpart, char* ws, hipStream_t st,
+                            Timer* tm);
+
 // kept != nullptr: the top-k selection runs in the launch that finishes the score (the stage as one
 // call), writing kept [B,k] and pruned [B,V-k] exactly as launch_select would.
 hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
                         const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
-                        float* s_raw, float* s_hat, float* score, int32_t* kept, int32_t* pruned, char* ws,
-                        hipStream_t st, Timer* tm);
+                        float* s_raw, float* s_hat, float* score, int32_t* kept, int32_t* pruned,
+                        const FrontArgs* fe, char* ws, hipStream_t st, Timer* tm);
 
 hipError_t launch_select(const asap_params& p, const float* score, int32_t* kept, int32_t* pruned,
                          hipStream_t st, Timer* tm);

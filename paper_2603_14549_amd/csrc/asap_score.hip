@@ -129,9 +129,10 @@ __global__ __launch_bounds__(1024) void k_qsum(const T* __restrict__ q, Strides3
 // k_qsplit: grid (Hkv, B), d threads.  qbar[b,g,:] = sum over the heads of group g and the chunks;
 // qsplit[b,g,p,:] (p = 0..3) = successive bf16 roundings of what is left of qbar.
 __global__ void k_qsplit(const double* __restrict__ qpart, double* __restrict__ qbar, uint16_t* __restrict__ qsplit,
-                         int H, int Hkv, int nchunk, int d) {
+                         int H, int Hkv, int nchunk, int d, unsigned long long* __restrict__ mmkey) {
   const int g = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
   const int G = H / Hkv;
+  if (g == 0 && c == 0) { mmkey[2 * b] = ~0ull; mmkey[2 * b + 1] = 0ull; }   // also where k_qsum did not run
   double s = 0.0;
   for (int h = g * G; h < (g + 1) * G; ++h)
     for (int ch = 0; ch < nchunk; ++ch) s += qpart[(((int64_t)b * H + h) * nchunk + ch) * d + c];
@@ -1093,7 +1094,7 @@ template <typename T>
 static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt,
                               Strides3 qt, const void* k_vis, Strides3 kv, const int32_t* text_len,
                               const float* lse_extra, float* s_raw, float* s_hat, float* score, int32_t* kept,
-                              int32_t* pruned, char* ws, hipStream_t st, Timer* tm) {
+                              int32_t* pruned, const FrontArgs* fe, char* ws, hipStream_t st, Timer* tm) {
   const ScoreWorkspace w = score_workspace(p);
   double* qpart = reinterpret_cast<double*>(ws + w.off_qpart);
   double* qbar = reinterpret_cast<double*>(ws + w.off_qbar);
@@ -1109,12 +1110,21 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   const int ng = p.d / 16;      // contraction groups of 8 elements per lane half
   const int ktiles = (p.V + 31) / 32;
 
-  const int direct = (w.q_chunks == 1 && p.H == p.Hkv) ? 1 : 0;
-  ASAP_LAUNCH(tm, "k_qsum", k_qsum<T>, dim3(w.q_chunks, p.H, p.B), dim3(1024), 0, st, static_cast<const T*>(q_vis),
-              qv, p.V, p.d, w.q_rows, qpart, mmkey, qbar, qsplit, direct);
-  if (!direct)
-    ASAP_LAUNCH(tm, "k_qsplit", k_qsplit, dim3(p.Hkv, p.B), dim3(p.d), 0, st, qpart, qbar, qsplit, p.H, p.Hkv,
-                w.q_chunks, p.d);
+  if (fe != nullptr) {
+    // the summed visual queries come from the hidden states (asap_front.hip), one chunk per head
+    hipError_t e0 = launch_front_end(p, fe->hidden, fe->hsb, fe->hsr, fe->wq, fe->rope_theta, fe->vis_positions,
+                                     qpart, fe->ws, st, tm);
+    if (e0 != hipSuccess) return e0;
+    ASAP_LAUNCH(tm, "k_qsplit", k_qsplit, dim3(p.Hkv, p.B), dim3(p.d), 0, st, qpart, qbar, qsplit, p.H, p.Hkv, 1, p.d,
+                mmkey);
+  } else {
+    const int direct = (w.q_chunks == 1 && p.H == p.Hkv) ? 1 : 0;
+    ASAP_LAUNCH(tm, "k_qsum", k_qsum<T>, dim3(w.q_chunks, p.H, p.B), dim3(1024), 0, st, static_cast<const T*>(q_vis),
+                qv, p.V, p.d, w.q_rows, qpart, mmkey, qbar, qsplit, direct);
+    if (!direct)
+      ASAP_LAUNCH(tm, "k_qsplit", k_qsplit, dim3(p.Hkv, p.B), dim3(p.d), 0, st, qpart, qbar, qsplit, p.H, p.Hkv,
+                  w.q_chunks, p.d, mmkey);
+  }
   const double scale = 1.0 / ((double)p.H * sqrt((double)p.d));
   RideArgs ra;
   ra.qt = q_txt; ra.sq = qt; ra.text_len = text_len; ra.zlog = zlog;
@@ -1172,13 +1182,13 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
 
 hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
                         const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
-                        float* s_raw, float* s_hat, float* score, int32_t* kept, int32_t* pruned, char* ws,
-                        hipStream_t st, Timer* tm) {
+                        float* s_raw, float* s_hat, float* score, int32_t* kept, int32_t* pruned,
+                        const FrontArgs* fe, char* ws, hipStream_t st, Timer* tm) {
   if (p.qk_dtype == ASAP_BF16)
     return score_typed<bf16_t>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                               kept, pruned, ws, st, tm);
+                               kept, pruned, fe, ws, st, tm);
   return score_typed<float>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score, kept,
-                            pruned, ws, st, tm);
+                            pruned, fe, ws, st, tm);
 }
 
 }  // namespace asap

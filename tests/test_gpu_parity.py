@@ -790,3 +790,83 @@ def test_config5_two_stage(ctx):
         n2 = int(buf2.new_len[b])
         orig = pos[b][p2[b][:n2]]
         assert (np.diff(orig) > 0).all() and n2 == c5b.P + c5b.k + int(inp1["text_len"][b])
+
+
+# ---------------------------------------------------------------- Eq. 2 from hidden states (the front end)
+def _front_end_case(ctx, cfg, own_positions=False):
+    """asap_score_from_hidden against the oracle's own front end in fp64: every visual query projected and
+    rotated (q = R W_q x, Sec. 3.1), summed, Eq. 2 from the sum, then Eq. 3-5 as always.  Same stored
+    hidden states and weights on both sides (W_q in the hidden dtype, row = query coordinate)."""
+    inp = synth.make_inputs(cfg, with_kv=False)
+    st = U.GpuStage(inp, ctx=ctx)
+    P, V, H, Hkv, d, D = cfg.P, cfg.V, cfg.H, cfg.Hkv, cfg.d, cfg.D
+    wq_store = synth.quantise(np.ascontiguousarray(inp["Wq"].T), cfg.h_dtype)            # [H*d, D]
+    wq_dev = U.to_device(wq_store, cfg.h_dtype)
+    Wq = synth.to_f64(wq_store, cfg.h_dtype)
+    pos = None
+    if own_positions:          # as in a second stage: survivors keep scattered original position ids
+        r = np.random.default_rng(cfg.seed + 5)
+        pos = np.stack([np.sort(r.choice(4 * V, size=V, replace=False)) + P for _ in range(cfg.B)]).astype(np.int32)
+    pos_dev = None if pos is None else torch.from_numpy(pos).cuda()
+    p = st.p
+    ws = torch.empty(binding.asap_front_end_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    s_raw, s_hat, score = (torch.full((cfg.B, V), float("nan"), dtype=torch.float32, device="cuda") for _ in range(3))
+    q_txt, k_vis = st.q[:, :, P + V:], st.k[:, :, P:P + V]
+    ctx.asap_score_from_hidden(p, st.hidden, wq_dev, cfg.rope_theta, pos_dev, q_txt, k_vis, st.text_len, None,
+                               s_raw, s_hat, score, ws)
+    torch.cuda.synchronize()
+    u = 2.0 ** -24
+    worst = 0.0
+    for b in range(cfg.B):
+        X = synth.to_f64(inp["hidden"][b], cfg.h_dtype)[P:P + V]
+        K = synth.to_f64(inp["k"][b], cfg.qk_dtype)[:, P:P + V]
+        Qt = synth.to_f64(inp["q"][b], cfg.qk_dtype)[:, P + V:]
+        tl = int(inp["text_len"][b])
+        pv = P + np.arange(V) if pos is None else pos[b]
+        qbar = O.summed_visual_queries(X, Wq, pv, H, Hkv, d, cfg.rope_theta)
+        s_ref = O.attention_mass_from_summed_queries(qbar, K, H)
+        # Error bound from the kernels' arithmetic (u = 2^-24).  A summed query coordinate is two dot
+        # products of a weight row with a trigonometric sum over the tokens: the table entry is one f32
+        # rounding off (u), 64 tokens are added in fp32 (64 u), the sum is stored as f32 (u), and 8 or 4
+        # products of the dot are added in fp32 (8 u): at most 75 u (|w_e| + |w_pair(e)|) . sum_i |x_i|.
+        # Then the mass sweep as for asap_score: (d - 1) u sum |qbar_c k_c| (1.02 for the bf16 pieces), one
+        # rounding of s.
+        absx = np.abs(X).sum(axis=0)
+        wabs = (np.abs(Wq) @ absx).reshape(H, d)
+        dq = 75 * u * (wabs + np.roll(wabs, d // 2, axis=1))                       # [H, d]
+        dq_g = dq.reshape(Hkv, H // Hkv, d).sum(axis=1)
+        scale = 1.0 / (H * math.sqrt(d))
+        bound = (np.einsum("gd,gjd->j", dq_g, np.abs(K)) + 1.02 * (d - 1) * u * np.einsum("gd,gjd->j", np.abs(qbar), np.abs(K))) \
+            * scale + u * np.abs(s_ref) + 1e-300
+        err = np.abs(U.from_device(s_raw[b]) - s_ref)
+        assert (err <= bound).all(), f"s_raw from hidden states: worst {np.max(err / bound):.3g} x bound"
+        # the bound is a worst case (every rounding in the same direction over thousands of terms) and
+        # sits orders of magnitude above what is observed (about 1e-7 of the largest mass): a second,
+        # empirical limit keeps a slip that the bound would hide from passing
+        assert err.max() <= 2e-6 * np.abs(s_ref).max(), f"s_raw from hidden states: {err.max() / np.abs(s_ref).max():.3g} of max |s|"
+        worst = max(worst, float(err.max() / np.abs(s_ref).max()))
+        sh_ref = O.salience(s_ref)
+        rng_s = s_ref.max() - s_ref.min()
+        sh_tol = 4 * bound.max() / rng_s + 2 * u
+        assert np.abs(U.from_device(s_hat[b]) - sh_ref).max() <= sh_tol, "s_hat"
+        A = O.text_visual_attention(Qt, K, O.mask_log_discount(sh_ref), tl)
+        r = O.selection_score(A)
+        lam = np.maximum(sh_ref, 1e-6)
+        e_r = np.abs(U.from_device(score[b]) - r)
+        assert (e_r <= 2e-5 * r + 2 * sh_tol * (r / lam) + 1e-300).all(), "score"
+    return worst
+
+
+@pytest.mark.parametrize("name", ["S0", "S1", "S2", "S3", "S4"])
+def test_mass_from_hidden_states_small(ctx, name):
+    _front_end_case(ctx, synth.CONFIGS[name])
+
+
+def test_mass_from_hidden_states_with_scattered_position_ids(ctx):
+    _front_end_case(ctx, synth.CONFIGS["S2"], own_positions=True)
+    _front_end_case(ctx, synth.CONFIGS["S0"], own_positions=True)
+
+
+def test_mass_from_hidden_states_config2(ctx):
+    worst = _front_end_case(ctx, synth.CONFIGS["C2"])
+    print(f"front end on C2: worst error {worst:.3g} of max |s|")

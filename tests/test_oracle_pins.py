@@ -650,3 +650,47 @@ def test_attention_forward_mask_touches_only_image_rows_and_adds_discounted_futu
         wt[j] = max(lam * s_hat[j - P], 1e-6) * math.exp(w[j])
     want = (wt[:, None] * Vv[h]).sum(0) / wt.sum()
     assert np.allclose(out_bi[h, i], want, rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- Sec. 3.1: RoPE score, Eq. 2 from hidden states
+def test_rope_is_a_rotation_and_the_score_depends_on_the_distance_only():
+    """Sec. 3.1: s(m, n) = x_m^T W_q^T R_{m-n} W_k x_n.  Rotations keep norms; position 0 is the
+    identity; and the score of a query at m with a key at n is the score at (m - n, 0)."""
+    r = rng(70)
+    d = 8
+    q, k = r.standard_normal((1, d)), r.standard_normal((1, d))
+    assert np.allclose(O.rope_rotate(q, [0]), q, rtol=0, atol=0)
+    for m, n in ((5, 2), (100, 97), (3, 0), (2300, 35)):
+        qm, kn = O.rope_rotate(q, [m]), O.rope_rotate(k, [n])
+        assert abs(np.linalg.norm(qm) - np.linalg.norm(q)) < 1e-12
+        ref = O.rope_rotate(q, [m - n]) @ k.T
+        assert abs((qm @ kn.T - ref).item()) < 1e-10 * (1 + abs(ref.item()))
+
+
+def test_rope_pairs_and_frequencies_by_hand():
+    # d = 4, theta = 100: pairs (0, 2) at frequency 1 and (1, 3) at frequency 100^(-1/2) = 0.1
+    v = np.array([[1.0, 2.0, 3.0, 4.0]])
+    out = O.rope_rotate(v, [2.0], theta=100.0)[0]
+    a0, a1 = 2.0 * 1.0, 2.0 * 0.1
+    want = [1.0 * math.cos(a0) - 3.0 * math.sin(a0), 2.0 * math.cos(a1) - 4.0 * math.sin(a1),
+            3.0 * math.cos(a0) + 1.0 * math.sin(a0), 4.0 * math.cos(a1) + 2.0 * math.sin(a1)]
+    np.testing.assert_allclose(out, want, rtol=1e-14)
+
+
+def test_mass_from_hidden_states_equals_the_column_sums_of_the_alignment_matrix():
+    """Eq. 2 from hidden states: project every visual token (q = R W_q x, Sec. 3.1), build W = Q K^T /
+    sqrt(d) and sum its columns (attention_mass, pinned above by the scalar triple loop); the summed
+    queries must give the same masses, GQA included, and the head mapping must matter."""
+    H, Hkv, d, D, V, P = 4, 2, 8, 12, 9, 3
+    r = rng(71)
+    X, Wq, K = r.standard_normal((V, D)), r.standard_normal((H * d, D)), r.standard_normal((Hkv, V, d))
+    pos = P + np.arange(V)
+    Q = O.project_queries(X, Wq, pos, H, d, theta=50.0)
+    assert Q.shape == (H, V, d)
+    # one token by hand: head 1 of token 2 is the rotation of rows d..2d-1 of W_q times x_2
+    np.testing.assert_allclose(Q[1, 2], O.rope_rotate((Wq[d:2 * d] @ X[2])[None, :], [pos[2]], 50.0)[0], rtol=1e-13)
+    qbar = O.summed_visual_queries(X, Wq, pos, H, Hkv, d, theta=50.0)
+    np.testing.assert_allclose(O.attention_mass_from_summed_queries(qbar, K, H), O.attention_mass(Q, K),
+                               rtol=1e-12, atol=1e-13)
+    swapped = qbar[::-1]
+    assert np.abs(O.attention_mass_from_summed_queries(swapped, K, H) - O.attention_mass(Q, K)).max() > 1e-3
