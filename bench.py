@@ -451,6 +451,9 @@ def main():
         roofline = {"kernel": dominant, "bound": "mfma", "achieved": flops / d_avg_s / 1e12, "peak": peak / 1e12,
                     "unit": "TFLOP/s", "frac": flops / d_avg_s / peak, "traffic": traffic,
                     "traffic_source": traffic_source, "traffic_note": traffic_note}
+        if cfg.h_dtype == "f32":
+            roofline["arithmetic"] = "six bf16 matrix products per f32 product (three bf16 pieces per operand)"
+            roofline["issued_frac_of_bf16_peak"] = 6.0 * flops / d_avg_s / MFMA_PEAK["bf16"]
     else:
         nbytes = alg["per_kernel"].get(dominant, 0) * args.steps / d_n
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": nbytes / d_avg_s / 1e9, "peak": HBM_PEAK / 1e9,
@@ -463,6 +466,12 @@ def main():
         sim_roofline = {"bound": "mfma", "achieved": alg["sim_flops"] / s_avg / 1e12,
                         "peak": MFMA_PEAK[cfg.h_dtype] / 1e12, "unit": "TFLOP/s",
                         "frac": alg["sim_flops"] / s_avg / MFMA_PEAK[cfg.h_dtype]}
+    if sim_roofline is not None and cfg.h_dtype == "f32":
+        # the library has no fp32 matrix-core path for this product any more: every f32 operand is cut into
+        # three bf16 pieces and six of the nine piece products are formed on the bf16 matrix cores
+        sim_roofline["arithmetic"] = ("f32 operands as three bf16 pieces, six bf16 matrix products per f32 product; "
+                                      "peak and frac are those of fp32 matrix instructions, the precision delivered")
+        sim_roofline["issued_frac_of_bf16_peak"] = 6.0 * alg["sim_flops"] / s_avg / MFMA_PEAK["bf16"]
     if sim_roofline is not None and sim_alone:
         a_avg = 1e-3 * sim_alone[0] / sim_alone[1]
         sim_roofline["alone"] = {"avg_us": round(1e6 * a_avg, 2), "achieved": alg["sim_flops"] / a_avg / 1e12,
