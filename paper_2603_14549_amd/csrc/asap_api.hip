@@ -307,7 +307,8 @@ asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, c
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
   return hip_result(ctx,
                     launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                                 nullptr, nullptr, nullptr, static_cast<char*>(workspace), static_cast<hipStream_t>(stream), ctx->timer),
+                                 nullptr, nullptr, nullptr, nullptr, static_cast<char*>(workspace), static_cast<hipStream_t>(stream),
+                                 ctx->timer),
                     "asap_score launch");
 }
 
@@ -352,7 +353,7 @@ asap_status asap_score_from_hidden(asap_ctx* ctx, const asap_params* p, const vo
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
   return hip_result(ctx,
                     launch_score(*p, nullptr, none, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                                 nullptr, nullptr, &fe, ws, static_cast<hipStream_t>(stream), ctx->timer),
+                                 nullptr, nullptr, &fe, nullptr, ws, static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_score_from_hidden launch");
 }
 
@@ -382,7 +383,8 @@ asap_status asap_score_static(asap_ctx* ctx, const asap_params* p, const void* q
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
   return hip_result(ctx,
                     launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                                 nullptr, nullptr, nullptr, static_cast<char*>(ctx->static_scratch), static_cast<hipStream_t>(stream),
+                                 nullptr, nullptr, nullptr, nullptr, static_cast<char*>(ctx->static_scratch),
+                                 static_cast<hipStream_t>(stream),
                                  ctx->timer),
                     "asap_score_static launch");
 }
@@ -567,17 +569,31 @@ asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io*
   Strides3 qt{io->q_txt_stride[0], io->q_txt_stride[1], io->q_txt_stride[2]};
   Strides3 kv{io->k_vis_stride[0], io->k_vis_stride[1], io->k_vis_stride[2]};
   char* ws = static_cast<char*>(io->workspace);
-  // the selection rides in the launch that finishes the score
+  // The selection rides in the launch that finishes the score.  That launch keeps B compute units busy
+  // and moves next to nothing, so for large bf16 batches, where the K/V compaction is what the similarity
+  // search waits for, it also takes the K/V rows no selection can change (prefix, valid text); the
+  // second stream then only moves the rows of the kept tokens.
+  const bool fixed_early = early && score_fuses_selection(*p) && p->h_dtype == ASAP_BF16 &&
+                           io->n_layers <= KV_LAYERS_PER_LAUNCH;
+  KvFixedRows fixed;
+  if (fixed_early) {
+    fill_kv_pointers(&fixed.ptrs, io->n_layers, io->k_src, io->v_src, io->k_dst, io->v_dst);
+    fixed.n_bufs = 2 * io->n_layers;
+    fixed.Hkv = p->Hkv; fixed.N = p->P + p->V + p->Tmax; fixed.Nout = p->P + p->k + p->Tmax;
+    fixed.row_bytes = p->d * (p->kv_dtype == ASAP_BF16 ? 2 : 4);
+    fixed.P = p->P; fixed.V = p->V; fixed.k = p->k; fixed.Tmax = p->Tmax;
+  }
   hipError_t e = launch_score(*p, io->q_vis, qv, io->q_txt, qt, io->k_vis, kv, io->text_len, io->lse_extra, io->s_raw,
-                              io->s_hat, io->score, io->kept_idx, io->pruned_idx, nullptr, ws, main, ctx->timer);
+                              io->s_hat, io->score, io->kept_idx, io->pruned_idx, nullptr,
+                              fixed_early ? &fixed : nullptr, ws, main, ctx->timer);
   bool forked = false;
   if (e == hipSuccess && early) {
     e = hipEventRecord(ctx->ev_fork, main);
     if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
     if (e == hipSuccess) {
       forked = true;
-      e = launch_compact_kv(*p, KV_FROM_KEPT, io->n_layers, io->k_src, io->v_src, io->k_dst, io->v_dst, io->kept_idx,
-                            io->text_len, ctx->side, ctx->timer);
+      e = launch_compact_kv(*p, fixed_early ? KV_KEPT_ONLY : KV_FROM_KEPT, io->n_layers, io->k_src, io->v_src,
+                            io->k_dst, io->v_dst, io->kept_idx, io->text_len, ctx->side, ctx->timer);
     }
   }
   if (e == hipSuccess)

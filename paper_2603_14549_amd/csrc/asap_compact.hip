@@ -11,13 +11,18 @@
 
 namespace asap {
 
-constexpr int KV_LAYERS_PER_LAUNCH = 16;
 constexpr int KV_ROWS_PER_THREAD = 4;
 
-struct KvPointers {
-  const char* src[2 * KV_LAYERS_PER_LAUNCH];   // K then V of each layer
-  char* dst[2 * KV_LAYERS_PER_LAUNCH];
-};
+void fill_kv_pointers(KvPointers* ptrs, int n_layers, const void* const* k_src, const void* const* v_src,
+                      void* const* k_dst, void* const* v_dst) {
+  for (int l = 0; l < n_layers; ++l) {
+    ptrs->src[2 * l] = static_cast<const char*>(k_src[l]);
+    ptrs->src[2 * l + 1] = static_cast<const char*>(v_src[l]);
+    ptrs->dst[2 * l] = static_cast<char*>(k_dst[l]);
+    ptrs->dst[2 * l + 1] = static_cast<char*>(v_dst[l]);
+  }
+  for (int l = 2 * n_layers; l < 2 * KV_LAYERS_PER_LAUNCH; ++l) { ptrs->src[l] = nullptr; ptrs->dst[l] = nullptr; }
+}
 
 // Where the source rows come from: the position list of asap_merge / asap_positions, or the kept list
 // and text_len directly (the output order of Fig. 3 written out: prefix | kept | valid text).
@@ -29,7 +34,8 @@ __global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t*
   const int lpr = row_bytes >> 4, rpi = 256 / lpr;
   const int tid = threadIdx.x, piece = tid % lpr, r0 = tid / lpr;
   const int bg = blockIdx.y, b = bg / Hkv;
-  const int n_rows = MODE == KV_BY_POS ? min(len[b], Nout) : P + k + min(len[b], Nout - P - k);
+  const int n_rows = MODE == KV_BY_POS ? min(len[b], Nout) : MODE == KV_KEPT_ONLY ? k
+                                                            : P + k + min(len[b], Nout - P - k);
   const char* src = ptrs.src[blockIdx.z] + (int64_t)bg * N * row_bytes + piece * 16;
   char* dst = ptrs.dst[blockIdx.z] + (int64_t)bg * Nout * row_bytes + piece * 16;
   const int32_t* ix = idx + (int64_t)b * (MODE == KV_BY_POS ? Nout : k);
@@ -39,14 +45,19 @@ __global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t*
   for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
     const int r = base + i * rpi;
     if (r < n_rows) {
-      const int srow = MODE == KV_BY_POS ? ix[r] : r < P ? r : r < P + k ? P + ix[r - P] : r - k + V;
+      const int srow = MODE == KV_BY_POS      ? ix[r]
+                       : MODE == KV_KEPT_ONLY ? P + ix[r]
+                       : r < P                ? r
+                       : r < P + k            ? P + ix[r - P]
+                                              : r - k + V;
       v[i] = ldg16_stream(src + (int64_t)srow * row_bytes);
     }
   }
+  const int shift = MODE == KV_KEPT_ONLY ? P : 0;       // kept slot r is output row P + r
 #pragma unroll
   for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
     const int r = base + i * rpi;
-    if (r < n_rows) stg16_stream(dst + (int64_t)r * row_bytes, v[i]);
+    if (r < n_rows) stg16_stream(dst + (int64_t)(r + shift) * row_bytes, v[i]);
   }
 }
 
@@ -117,22 +128,20 @@ hipError_t launch_compact_kv(const asap_params& p, int mode, int n_layers, const
   const int row_bytes = p.d * (p.kv_dtype == ASAP_BF16 ? 2 : 4);
   const int N = p.P + p.V + p.Tmax, Nout = p.P + p.k + p.Tmax;
   const int rows_per_block = (256 / (row_bytes / 16)) * KV_ROWS_PER_THREAD;
+  const int rows = mode == KV_KEPT_ONLY ? p.k : Nout;
   for (int l0 = 0; l0 < n_layers; l0 += KV_LAYERS_PER_LAUNCH) {
     const int nl = n_layers - l0 < KV_LAYERS_PER_LAUNCH ? n_layers - l0 : KV_LAYERS_PER_LAUNCH;
     KvPointers ptrs;
-    for (int l = 0; l < nl; ++l) {
-      ptrs.src[2 * l] = static_cast<const char*>(k_src[l0 + l]);
-      ptrs.src[2 * l + 1] = static_cast<const char*>(v_src[l0 + l]);
-      ptrs.dst[2 * l] = static_cast<char*>(k_dst[l0 + l]);
-      ptrs.dst[2 * l + 1] = static_cast<char*>(v_dst[l0 + l]);
-    }
-    for (int l = 2 * nl; l < 2 * KV_LAYERS_PER_LAUNCH; ++l) { ptrs.src[l] = nullptr; ptrs.dst[l] = nullptr; }
-    dim3 grid((Nout + rows_per_block - 1) / rows_per_block, p.B * p.Hkv, 2 * nl);
+    fill_kv_pointers(&ptrs, nl, k_src + l0, v_src + l0, k_dst + l0, v_dst + l0);
+    dim3 grid((rows + rows_per_block - 1) / rows_per_block, p.B * p.Hkv, 2 * nl);
     if (mode == KV_BY_POS)
       ASAP_LAUNCH(tm, "k_compact", k_compact<KV_BY_POS>, grid, dim3(256), 0, st, ptrs, idx, len, p.Hkv, N, Nout,
                   row_bytes, p.P, p.V, p.k);
-    else
+    else if (mode == KV_FROM_KEPT)
       ASAP_LAUNCH(tm, "k_compact", k_compact<KV_FROM_KEPT>, grid, dim3(256), 0, st, ptrs, idx, len, p.Hkv, N, Nout,
+                  row_bytes, p.P, p.V, p.k);
+    else
+      ASAP_LAUNCH(tm, "k_compact", k_compact<KV_KEPT_ONLY>, grid, dim3(256), 0, st, ptrs, idx, len, p.Hkv, N, Nout,
                   row_bytes, p.P, p.V, p.k);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -151,13 +160,7 @@ hipError_t launch_compact_kv_paged(const asap_params& p, int n_layers, const voi
   for (int l0 = 0; l0 < n_layers; l0 += KV_LAYERS_PER_LAUNCH) {
     const int nl = n_layers - l0 < KV_LAYERS_PER_LAUNCH ? n_layers - l0 : KV_LAYERS_PER_LAUNCH;
     KvPointers ptrs;
-    for (int l = 0; l < nl; ++l) {
-      ptrs.src[2 * l] = static_cast<const char*>(k_src[l0 + l]);
-      ptrs.src[2 * l + 1] = static_cast<const char*>(v_src[l0 + l]);
-      ptrs.dst[2 * l] = static_cast<char*>(k_dst[l0 + l]);
-      ptrs.dst[2 * l + 1] = static_cast<char*>(v_dst[l0 + l]);
-    }
-    for (int l = 2 * nl; l < 2 * KV_LAYERS_PER_LAUNCH; ++l) { ptrs.src[l] = nullptr; ptrs.dst[l] = nullptr; }
+    fill_kv_pointers(&ptrs, nl, k_src + l0, v_src + l0, k_dst + l0, v_dst + l0);
     dim3 grid((Nout + rows_per_block - 1) / rows_per_block, p.B * p.Hkv, 2 * nl);
     ASAP_LAUNCH(tm, "k_compact_paged", k_compact_paged, grid, dim3(256), 0, st, ptrs, pos_out, new_len, src_table,
                 src_stride, dst_table, dst_stride, page_size, p.Hkv, Nout, row_bytes);

@@ -77,12 +77,35 @@ hipError_t launch_front_end(const asap_params& p, const void* hidden, int64_t hs
                             double rope_theta, const int32_t* vis_positions, double* qpart, char* ws, hipStream_t st,
                             Timer* tm);
 
+// K and V of up to 16 cached layers, K then V of each layer.
+constexpr int KV_LAYERS_PER_LAUNCH = 16;
+struct KvPointers {
+  const char* src[2 * KV_LAYERS_PER_LAUNCH];
+  char* dst[2 * KV_LAYERS_PER_LAUNCH];
+};
+// The K/V rows that survive whatever the selection keeps (Fig. 3: the prefix and the valid text rows),
+// for the launch that moves them while the selection runs.
+struct KvFixedRows {
+  KvPointers ptrs;
+  int n_bufs;                 // 2 * layers
+  int Hkv, N, Nout, row_bytes, P, V, k, Tmax;
+};
+void fill_kv_pointers(KvPointers* ptrs, int n_layers, const void* const* k_src, const void* const* v_src,
+                      void* const* k_dst, void* const* v_dst);
+
+// The selection rides in the launch that finishes the score when the batch gives that launch (one
+// workgroup per image) enough workgroups to fetch the per-head sums at a reasonable rate; measured
+// on batches of 4 and 8 it lost to the two separate launches.
+inline bool score_fuses_selection(const asap_params& p) { return p.B >= 12; }
+
 // kept != nullptr: the top-k selection runs in the launch that finishes the score (the stage as one
-// call), writing kept [B,k] and pruned [B,V-k] exactly as launch_select would.
+// call), writing kept [B,k] and pruned [B,V-k] exactly as launch_select would.  fixed != nullptr (only
+// with kept and score_fuses_selection(p)): further workgroups of that launch copy the K/V rows of the
+// prefix and of the valid text, which depend on no result, while the memory system is otherwise idle.
 hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
                         const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
                         float* s_raw, float* s_hat, float* score, int32_t* kept, int32_t* pruned,
-                        const FrontArgs* fe, char* ws, hipStream_t st, Timer* tm);
+                        const FrontArgs* fe, const KvFixedRows* fixed, char* ws, hipStream_t st, Timer* tm);
 
 hipError_t launch_select(const asap_params& p, const float* score, int32_t* kept, int32_t* pruned,
                          hipStream_t st, Timer* tm);
@@ -111,7 +134,10 @@ hipError_t launch_paper_plan(const asap_params& p, const int32_t* dest, const in
 hipError_t launch_positions(const asap_params& p, const int32_t* kept, const int32_t* text_len, int32_t* pos_out,
                             int32_t* new_len, hipStream_t st, Timer* tm);
 
-enum { KV_BY_POS = 0, KV_FROM_KEPT = 1 };
+// KV_BY_POS: idx = pos_out, len = new_len; KV_FROM_KEPT: idx = kept list, len = text_len, all output
+// rows; KV_KEPT_ONLY: as KV_FROM_KEPT but only the rows of the kept tokens (the others were moved by
+// the launch that took a KvFixedRows).  At most KV_LAYERS_PER_LAUNCH layers per launch.
+enum { KV_BY_POS = 0, KV_FROM_KEPT = 1, KV_KEPT_ONLY = 2 };
 hipError_t launch_compact_kv(const asap_params& p, int mode, int n_layers, const void* const* k_src,
                              const void* const* v_src, void* const* k_dst, void* const* v_dst,
                              const int32_t* idx, const int32_t* len, hipStream_t st, Timer* tm);

@@ -27,7 +27,8 @@
 //   k_score       fixed-order head reduction, times lambda' (Eq. 4) in fp64, mean over heads and
 //                 text rows; also writes s_hat (Eq. 3)
 //   k_score_select  the same followed by the top-k selection of asap_select in one launch (one
-//                 workgroup per image), when the stage runs as one call
+//                 workgroup per image), when the stage runs as one call; k_score_select_kv has further
+//                 workgroups that copy the K/V rows of prefix and text meanwhile
 // f32 queries and keys reach the bf16 matrix instructions as three bf16 pieces each; a logit is the
 // sum of the six piece products that matter (hi.hi, hi.mid, mid.hi, mid.mid, hi.lo, lo.hi: what is
 // left out is below 2^-25 of sum |q_c k_c|, half a unit of the fp32 accumulation itself).
@@ -913,17 +914,16 @@ __global__ __launch_bounds__(256) void k_score(const float* __restrict__ upart, 
 // k_score's; the scores change hands through LDS to the blocked layout of the selection (thread t owns
 // keys t*ipt .. t*ipt+ipt-1), and the workgroup then selects exactly as k_select does.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(SEL_THREADS) void k_score_select(const float* __restrict__ upart,
-                                                               const double* __restrict__ s64,
-                                                               const unsigned long long* __restrict__ mmkey,
-                                                               const int32_t* __restrict__ text_len, int H, int HV,
-                                                               int V, int k, int Tmax, int last_only, double lambda_max,
-                                                               double eps, int mask_on, float* __restrict__ s_hat,
-                                                               float* __restrict__ score, int32_t* __restrict__ kept,
-                                                               int32_t* __restrict__ pruned) {
+__device__ __forceinline__ void score_select_image(const int b, const float* __restrict__ upart,
+                                                   const double* __restrict__ s64,
+                                                   const unsigned long long* __restrict__ mmkey,
+                                                   const int32_t* __restrict__ text_len, int H, int HV, int V, int k,
+                                                   int Tmax, int last_only, double lambda_max, double eps, int mask_on,
+                                                   float* __restrict__ s_hat, float* __restrict__ score,
+                                                   int32_t* __restrict__ kept, int32_t* __restrict__ pruned) {
   __shared__ SelectShared sh;
   extern __shared__ float sc_lds[];
-  const int b = blockIdx.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   const int ipt = (V + SEL_THREADS - 1) / SEL_THREADS;
   const int i0 = tid * ipt;
   const double lo = f64_unkey(mmkey[2 * b]), hi = f64_unkey(mmkey[2 * b + 1]);
@@ -971,6 +971,52 @@ __global__ __launch_bounds__(SEL_THREADS) void k_score_select(const float* __res
       if (keep_bits & (1u << e)) kout[kept_before++] = i;
       else pout[i - kept_before] = i;
     }
+  }
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void k_score_select(const float* __restrict__ upart,
+                                                               const double* __restrict__ s64,
+                                                               const unsigned long long* __restrict__ mmkey,
+                                                               const int32_t* __restrict__ text_len, int H, int HV,
+                                                               int V, int k, int Tmax, int last_only, double lambda_max,
+                                                               double eps, int mask_on, float* __restrict__ s_hat,
+                                                               float* __restrict__ score, int32_t* __restrict__ kept,
+                                                               int32_t* __restrict__ pruned) {
+  score_select_image(blockIdx.x, upart, s64, mmkey, text_len, H, HV, V, k, Tmax, last_only, lambda_max, eps, mask_on,
+                     s_hat, score, kept, pruned);
+}
+
+// k_score_select_kv: grid (B + n_bufs * B * Hkv).  The first B workgroups are k_score_select's.  Each of the
+// others copies, for one (cache buffer, image, kv head), the rows that survive whatever is selected
+// (Fig. 3: prefix rows stay where they are, valid text row t moves from P + V + t to P + k + t): they
+// depend on no result of the stage, and the B selecting workgroups leave the memory system idle.
+// A row is row_bytes / 16 pieces of 16 bytes; two rows per thread are in flight.
+__global__ __launch_bounds__(SEL_THREADS) void k_score_select_kv(
+    const float* __restrict__ upart, const double* __restrict__ s64, const unsigned long long* __restrict__ mmkey,
+    const int32_t* __restrict__ text_len, int H, int HV, int V, int k, int Tmax, int last_only, double lambda_max,
+    double eps, int mask_on, float* __restrict__ s_hat, float* __restrict__ score, int32_t* __restrict__ kept,
+    int32_t* __restrict__ pruned, int B, KvFixedRows fx) {
+  if ((int)blockIdx.x < B) {
+    score_select_image(blockIdx.x, upart, s64, mmkey, text_len, H, HV, V, k, Tmax, last_only, lambda_max, eps,
+                       mask_on, s_hat, score, kept, pruned);
+    return;
+  }
+  const int gid = blockIdx.x - B, groups = B * fx.Hkv;
+  const int buf = gid / groups, bg = gid % groups, b = bg / fx.Hkv;
+  const int lpr = fx.row_bytes >> 4, rpi = SEL_THREADS / lpr;
+  const int tid = threadIdx.x, piece = tid % lpr, r0 = tid / lpr;
+  const int n_fixed = fx.P + min(max(text_len[b], 0), fx.Tmax);
+  const char* src = fx.ptrs.src[buf] + (int64_t)bg * fx.N * fx.row_bytes + piece * 16;
+  char* dst = fx.ptrs.dst[buf] + (int64_t)bg * fx.Nout * fx.row_bytes + piece * 16;
+  for (int r = r0; r < n_fixed; r += 2 * rpi) {
+    const int r2 = r + rpi;
+    const int sa = r < fx.P ? r : r + fx.V, da = r < fx.P ? r : r + fx.k;
+    const int sb = r2 < fx.P ? r2 : r2 + fx.V, db = r2 < fx.P ? r2 : r2 + fx.k;
+    const uint4 va = ldg16_stream(src + (int64_t)sa * fx.row_bytes);
+    uint4 vb = va;
+    if (r2 < n_fixed) vb = ldg16_stream(src + (int64_t)sb * fx.row_bytes);
+    stg16_stream(dst + (int64_t)da * fx.row_bytes, va);
+    if (r2 < n_fixed) stg16_stream(dst + (int64_t)db * fx.row_bytes, vb);
   }
 }
 
@@ -1094,7 +1140,8 @@ template <typename T>
 static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt,
                               Strides3 qt, const void* k_vis, Strides3 kv, const int32_t* text_len,
                               const float* lse_extra, float* s_raw, float* s_hat, float* score, int32_t* kept,
-                              int32_t* pruned, const FrontArgs* fe, char* ws, hipStream_t st, Timer* tm) {
+                              int32_t* pruned, const FrontArgs* fe, const KvFixedRows* fixed, char* ws,
+                              hipStream_t st, Timer* tm) {
   const ScoreWorkspace w = score_workspace(p);
   double* qpart = reinterpret_cast<double*>(ws + w.off_qpart);
   double* qbar = reinterpret_cast<double*>(ws + w.off_qbar);
@@ -1154,10 +1201,7 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
     e = launch_attn<T, 4>(p, a, st, tm);
   }
   if (e != hipSuccess) return e;
-  // The selection rides in the launch that finishes the score when the batch gives that launch (one
-  // workgroup per image) enough workgroups to fetch the per-head sums at a reasonable rate; measured
-  // on batches of 4 and 8 it lost to the two separate launches.
-  if (kept != nullptr && p.B < 12) {
+  if (kept != nullptr && !score_fuses_selection(p)) {
     ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
                 p.H, p.H * w.row_pairs, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
     hipError_t e2 = hipGetLastError();
@@ -1165,14 +1209,20 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
   }
   if (kept != nullptr) {
     const size_t lds = p.V > SEL_THREADS ? sizeof(float) * (size_t)p.V : 0;
+    const void* fn = fixed ? reinterpret_cast<const void*>(k_score_select_kv)
+                           : reinterpret_cast<const void*>(k_score_select);
     if (lds > 32 * 1024) {
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_score_select), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds);
+      e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
     }
-    ASAP_LAUNCH(tm, "k_score_select", k_score_select, dim3(p.B), dim3(SEL_THREADS), lds, st, upart, s64, mmkey,
-                text_len, p.H, p.H * w.row_pairs, p.V, p.k, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score,
-                kept, pruned);
+    if (fixed)
+      ASAP_LAUNCH(tm, "k_score_select_kv", k_score_select_kv, dim3(p.B + fixed->n_bufs * p.B * p.Hkv),
+                  dim3(SEL_THREADS), lds, st, upart, s64, mmkey, text_len, p.H, p.H * w.row_pairs, p.V, p.k, p.Tmax,
+                  last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score, kept, pruned, p.B, *fixed);
+    else
+      ASAP_LAUNCH(tm, "k_score_select", k_score_select, dim3(p.B), dim3(SEL_THREADS), lds, st, upart, s64, mmkey,
+                  text_len, p.H, p.H * w.row_pairs, p.V, p.k, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps,
+                  mask_on, s_hat, score, kept, pruned);
   } else {
     ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
                 p.H, p.H * w.row_pairs, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
@@ -1183,12 +1233,13 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
 hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
                         const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
                         float* s_raw, float* s_hat, float* score, int32_t* kept, int32_t* pruned,
-                        const FrontArgs* fe, char* ws, hipStream_t st, Timer* tm) {
+                        const FrontArgs* fe, const KvFixedRows* fixed, char* ws, hipStream_t st, Timer* tm) {
+  if (fixed && (kept == nullptr || !score_fuses_selection(p))) return hipErrorInvalidValue;
   if (p.qk_dtype == ASAP_BF16)
     return score_typed<bf16_t>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                               kept, pruned, fe, ws, st, tm);
+                               kept, pruned, fe, fixed, ws, st, tm);
   return score_typed<float>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score, kept,
-                            pruned, fe, ws, st, tm);
+                            pruned, fe, fixed, ws, st, tm);
 }
 
 }  // namespace asap

@@ -8,7 +8,8 @@
 //                 hidden dimension is walked in steps of 128 bytes per row, one barrier per step.
 //                 Operands reach LDS by direct global -> LDS loads (no registers in between) that
 //                 every wave issues between its MFMAs; the squared norms of the rows are added up
-//                 from the operands a wave holds, also in the shadow of the MFMAs.
+//                 from the operands a wave holds, also in the shadow of the MFMAs (waves that hold
+//                 the same rows take half of the contraction slices each).
 //                 The source rows are read once, from HBM, so their 128 x 128 B slices go through a
 //                 ring of 4 LDS slots and are asked for three steps ahead; the destination rows are
 //                 shared by all tiles of an image and come from L2, so two slots (one step ahead)
@@ -161,10 +162,15 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
     int r = min(m0 + rr + 32 * i, M - 1);
     offa[i] = (uint32_t)(pruned[(int64_t)b * M + r] * rowb) + piece_off;
   }
-  // Operand reads: byte offset of this lane's chunk kk inside its row
+  // Operand reads: byte offset, inside its row, of the chunk this lane reads at position kk of a step.
+  // Wave w walks the four contraction slices of a step in the order kk ^ w.  The products do not care,
+  // and the sums for the norms can then be shared without a branch: every wave adds up the destination
+  // chunks at positions 0 and 1 and the source chunks at positions 0 and 2; the wave below (w ^ 2, same
+  // destination rows) covers the other two slices of the former, the wave beside (w ^ 1, same source
+  // rows) those of the latter, and the halves meet in LDS after the last step.
   int sw[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) sw[kk] = ((hf * 4 + kk) ^ ((n >> 1) & 7)) * 16;
+  for (int kk = 0; kk < 4; ++kk) sw[kk] = ((hf * 4 + (kk ^ wave)) ^ ((n >> 1) & 7)) * 16;
 
   if (ANCHORED) {            // the barriers of the fill below make these visible
     if (tid < SIM_BM) srow[tid] = s_hat[(int64_t)b * V + pruned[(int64_t)b * M + min(m0 + tid, M - 1)]];
@@ -256,14 +262,15 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
 #pragma unroll
           for (int i = 0; i < 2; ++i) {
             a3[i] = split_f32x8(ra[i][0], ra[i][1]);
-            sumsq16<T>(ra[i][0], ss_a[i]);
-            sumsq16<T>(ra[i][1], ss_a[i]);
+            sumsq16<T>(ra[i][0], ss_a[i]);                 // positions 0 and 2 of the step
           }
 #pragma unroll
           for (int t = 0; t < NT; ++t) {
             b3[t] = split_f32x8(rb[t][0], rb[t][1]);
-            sumsq16<T>(rb[t][0], ss_b[t]);
-            sumsq16<T>(rb[t][1], ss_b[t]);
+            if (gq == 0) {                                 // positions 0 and 1
+              sumsq16<T>(rb[t][0], ss_b[t]);
+              sumsq16<T>(rb[t][1], ss_b[t]);
+            }
           }
           if (gq == 0) read_group(1);       // the raw registers are free again
 #pragma unroll
@@ -298,20 +305,21 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         // After each MFMA: one LDS read for the next contraction slice, one global -> LDS load and a
-        // few dot products for the norms, all in the MFMA's shadow.  Waves that hold the same rows
-        // repeat the sums; wave-dependent branches would cost more.
+        // few dot products for the norms, all in the MFMA's shadow.
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
           __builtin_amdgcn_sched_barrier(0);
           mma32<T>(acc[0][t], a[kk & 1][0], bq[kk & 1][t]);
           if (kk < 3) load_op((kk + 1) & 1, kk + 1, 2 * t);
-          sumsq16<T>(bq[kk & 1][t], ss_b[t]);
+          if (kk < 2) sumsq16<T>(bq[kk & 1][t], ss_b[t]);
           load_unit(kk * 2 * NT + 2 * t);
           __builtin_amdgcn_sched_barrier(0);
           mma32<T>(acc[1][t], a[kk & 1][1], bq[kk & 1][t]);
           if (kk < 3) load_op((kk + 1) & 1, kk + 1, 2 * t + 1);
-          if (t == 0) sumsq16<T>(a[kk & 1][0], ss_a[0]);
-          if (t == 1 || NT == 1) sumsq16<T>(a[kk & 1][1], ss_a[1]);
+          if ((kk & 1) == 0) {
+            if (t == 0) sumsq16<T>(a[kk & 1][0], ss_a[0]);
+            if (t == 1 || NT == 1) sumsq16<T>(a[kk & 1][1], ss_a[1]);
+          }
           load_unit(kk * 2 * NT + 2 * t + 1);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -325,24 +333,31 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
     }
 
     wait_all_vmem();   // the repeated loads of the last steps
-    // the two lane halves hold the two halves of every 128-byte slice
-    if (wn == 0) {
+    // The two lane halves hold the two halves of every 128-byte slice, and the wave beside (source
+    // rows) or below (destination rows) the other two contraction slices of every step: it adds its
+    // half in a second round.
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        float v = ss_a[i].total();
-        v += __shfl_xor(v, 32);
-        if (hf == 0) norm2[wm * 64 + i * 32 + n] = v;
-      }
-    }
-    if (wm == 0) {
+    for (int round = 0; round < 2; ++round) {
+      if (wn == round) {
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        float v = ss_b[t].total();
-        v += __shfl_xor(v, 32);
-        if (hf == 0) normk[wn * (BN / 2) + t * 32 + n] = v;
+        for (int i = 0; i < 2; ++i) {
+          float v = ss_a[i].total();
+          v += __shfl_xor(v, 32);
+          float* o = &norm2[wm * 64 + i * 32 + n];
+          if (hf == 0) *o = round == 0 ? v : *o + v;
+        }
       }
+      if (wm == round) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          float v = ss_b[t].total();
+          v += __shfl_xor(v, 32);
+          float* o = &normk[wn * (BN / 2) + t * 32 + n];
+          if (hf == 0) *o = round == 0 ? v : *o + v;
+        }
+      }
+      __syncthreads();   // round 1: norms visible
     }
-    __syncthreads();   // norms visible
 
     if (ksplit > 1) {
       // this slice's share of the products and of the squared norms; k_sim_reduce adds the slices up
