@@ -297,6 +297,10 @@ def main():
                     help="also time the stage cycling over SETS (>= 2) copies of the inputs and outputs at different "
                          "addresses, so that no step finds its data in the caches (the small workloads fit the "
                          "256 MB last-level cache and their default, warm figure profits from it)")
+    ap.add_argument("--hidden-row-pad", type=int, default=0, metavar="ELEMENTS",
+                    help="store the rows of the input hidden states this many elements further apart than their "
+                         "length (the stage takes strided views; rows a power of two bytes apart all start in the "
+                         "same memory channel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="accepted for the counter runs documented in profiles/: the 1 GiB device copies that "
@@ -332,7 +336,7 @@ def main():
         lse_extra = np.random.default_rng(cfg.seed + 1000).normal(2.0, 2.0, size=(cfg.B, cfg.H, cfg.Tmax)) \
             .astype(np.float32)
     stage = harness.DeviceStage(inp, ctx=ctx, lse_extra=lse_extra, page_size=args.paged_kv or None,
-                                last_token=args.last_token, **overrides)
+                                last_token=args.last_token, hidden_row_pad=args.hidden_row_pad, **overrides)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -349,7 +353,8 @@ def main():
     rotated = None
     if args.rotate >= 2:
         sets = [stage] + [harness.DeviceStage(inp, ctx=ctx, lse_extra=lse_extra, page_size=args.paged_kv or None,
-                                              last_token=args.last_token, **overrides)
+                                              last_token=args.last_token, hidden_row_pad=args.hidden_row_pad,
+                                              **overrides)
                           for _ in range(args.rotate - 1)]
         for i in range(args.warmup):
             sets[i % len(sets)].run_async()

@@ -283,7 +283,10 @@ asap_status asap_compact_kv_from_kept(asap_ctx* ctx, const asap_params* p, int32
  * on first use) ordered after `stream` by an event, next to the similarity and merge kernels, and
  * `stream` waits for it at the end: work enqueued on `stream` after the call sees all outputs.
  * The similarity kernel is bound on chip and the compaction by HBM, which is why the two go well
- * side by side.  Otherwise, and always with ASAP_ROUTE_PAPER (final_idx exists only after the
+ * side by side.  For bf16 hidden states, B >= 12 and n_layers <= 16 the K/V rows that no selection
+ * can change (prefix, valid text; Fig. 3) are copied by further workgroups of the launch that
+ * selects, and the second stream moves the rows of the kept tokens only; the bytes written are the
+ * same either way.  Otherwise, and always with ASAP_ROUTE_PAPER (final_idx exists only after the
  * merge), everything runs on `stream` in order.  One context must not run two stages at once.
  * The calls are capturable into a HIP graph (kernels, event record / wait; no memset, no sync).
  */

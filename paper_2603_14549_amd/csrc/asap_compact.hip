@@ -2,8 +2,9 @@
 // (KV-cache compatibility of the pruning stage).  Pure data movement, bit-exact.
 //
 // k_positions: grid (ceil(Nout / 256), B): the positions the compaction gathers, from the kept set alone.
-// k_compact<MODE>: grid (ceil(Nout / ROWS_PER_BLOCK), B * Hkv, 2 * layers_in_launch), 256 threads; the source
-// rows come from the position list or straight from the kept list (then nothing of asap_merge is needed).
+// k_compact<MODE>: grid (ceil(rows / ROWS_PER_BLOCK), B * Hkv, 2 * layers_in_launch), 256 threads, rows = Nout
+// or, for the kept tokens' rows alone, k; the source rows come from the position list or straight from the
+// kept list (then nothing of asap_merge is needed).
 // k_compact_paged: the same grid for caches kept as pools of pages with one block table per sequence.
 // A row is d elements = LPR 16-byte pieces; LPR consecutive lanes move one row.
 #include "asap_device.hpp"

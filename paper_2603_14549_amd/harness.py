@@ -168,7 +168,7 @@ class DeviceStage:
 
     def __init__(self, inp: dict, ctx: Optional[Context] = None, lse_extra=None, overlap: bool = True,
                  page_size: Optional[int] = None, call_by_call: bool = False, last_token: bool = False,
-                 **param_overrides):
+                 hidden_row_pad: int = 0, **param_overrides):
         import numpy as np
         cfg = inp["cfg"]
         self.cfg = cfg
@@ -179,6 +179,11 @@ class DeviceStage:
         self.q = to_device(inp["q"], cfg.qk_dtype)
         self.k = to_device(inp["k"], cfg.qk_dtype)
         self.hidden = to_device(inp["hidden"], cfg.h_dtype)
+        if hidden_row_pad:       # rows of the hidden states hidden_row_pad elements further apart (a strided view)
+            store = torch.zeros(cfg.B, self.hidden.shape[1], cfg.D + hidden_row_pad, dtype=self.hidden.dtype,
+                                device=self.hidden.device)
+            store[:, :, :cfg.D] = self.hidden
+            self.hidden = store[:, :, :cfg.D]
         self.text_len = torch.from_numpy(inp["text_len"].astype(np.int32)).cuda()
         self.k_cache = [to_device(a, cfg.kv_dtype) for a in inp.get("k_cache", [])]
         self.v_cache = [to_device(a, cfg.kv_dtype) for a in inp.get("v_cache", [])]

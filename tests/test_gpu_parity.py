@@ -339,8 +339,9 @@ def test_positions_and_two_stream_stage(ctx):
     assert bool((st.buf.score == -7.0).all()), "a failed check must launch nothing"
 
 
+@pytest.mark.parametrize("last_token", [False, True])
 @pytest.mark.parametrize("base,kv_dtype,P,layers", [("S2", "bf16", 7, 3), ("S2", "f32", 0, 1), ("S3", "bf16", 33, 16)])
-def test_prefix_and_text_kv_rows_move_with_the_selection(ctx, base, kv_dtype, P, layers):
+def test_prefix_and_text_kv_rows_move_with_the_selection(ctx, base, kv_dtype, P, layers, last_token):
     """Large bf16 batches on two streams: the launch that selects also copies the K/V rows no selection
     can change (prefix, valid text) and the second stream only the kept tokens' rows.  Every byte of
     the compacted caches, rows past new_len included, must equal what the single calls on one stream
@@ -348,8 +349,8 @@ def test_prefix_and_text_kv_rows_move_with_the_selection(ctx, base, kv_dtype, P,
     cfg = dataclasses.replace(synth.CONFIGS[base], B=13, V=300, k=70, P=P, L_kv=layers, kv_dtype=kv_dtype,
                               ragged_text=True, text_lo=1, name=f"fixedkv-{base}-{kv_dtype}")
     inp = synth.make_inputs(cfg)
-    serial = U.GpuStage(inp, ctx=ctx, overlap=False, call_by_call=True).run()
-    fused = U.GpuStage(inp, ctx=ctx, overlap=True)
+    serial = U.GpuStage(inp, ctx=ctx, overlap=False, call_by_call=True, last_token=last_token).run()
+    fused = U.GpuStage(inp, ctx=ctx, overlap=True, last_token=last_token)
     assert fused.two_streams
     for _ in range(2):
         bo = fused.run()
@@ -359,7 +360,7 @@ def test_prefix_and_text_kv_rows_move_with_the_selection(ctx, base, kv_dtype, P,
         for name in ("score", "kept_idx", "pruned_idx", "assign", "pos_out", "new_len"):
             assert torch.equal(getattr(bo, name), getattr(serial, name)), name
     for b in (0, 5, 12):
-        U.compare_image(inp, bo, b, U.oracle_image(inp, b))
+        U.compare_image(inp, bo, b, U.oracle_image(inp, b, score_rows="last" if last_token else "all"))
 
 
 def test_stage_replayed_from_a_captured_graph(ctx):
