@@ -89,6 +89,7 @@ def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
     # not by k_compact (the caller of this function moves the bytes over when it sees that kernel)
     per_kernel["kv_fixed_rows"] = 2 * 2 * n_layers * Hkv * B * (P + T) * d * ek
     per_kernel["k_score_select_kv"] = per_kernel["k_score_select"] + per_kernel["kv_fixed_rows"]
+    per_kernel["k_compact_fixed"] = per_kernel["kv_fixed_rows"]       # deep caches: those rows start at once
     stage = (q_vis + k_vis + q_txt + 12 * B * V) + 12 * B * V + (vis_h + 8 * B * (V - k)) \
         + (vis_h + B * (P + T) * D * eh + out_rows * D * eh) + per_kernel["k_compact"]
     return {"per_kernel": per_kernel, "stage": stage, "sim_flops": 2.0 * B * (V - k) * k * D}
@@ -434,7 +435,7 @@ def main():
         alg["stage"] += (alg["per_kernel"]["k_sim"] - old_sim) + (alg["per_kernel"]["k_merge"] - old_merge) \
             + alg["per_kernel"]["k_paper_plan"]
         alg["sim_flops"] = 2.0 * cfg.B * cfg.k * cfg.k * cfg.D
-    if "k_score_select_kv" in timing:        # the prefix and text rows of K/V went with the selection launch
+    if "k_score_select_kv" in timing or "k_compact_fixed" in timing:     # prefix and text rows of K/V went earlier
         alg["per_kernel"]["k_compact"] -= alg["per_kernel"]["kv_fixed_rows"]
     kernels = {}
     for name, (ms, n) in timing.items():

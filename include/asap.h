@@ -18,7 +18,7 @@
  * allocates nothing on the device, never synchronises the stream and keeps no
  * state between calls except the last error text of a context (and, once
  * asap_stage has been asked for two streams, that context's second stream and
- * two events, released by asap_destroy).
+ * three events, released by asap_destroy).
  * Errors: shapes, dtypes, pointers and workspace size are checked on the host
  * before anything is launched; a failed check launches nothing.  Contents of device
  * buffers (NaNs, text_len outside [1, Tmax]) are not checked.
@@ -283,10 +283,12 @@ asap_status asap_compact_kv_from_kept(asap_ctx* ctx, const asap_params* p, int32
  * on first use) ordered after `stream` by an event, next to the similarity and merge kernels, and
  * `stream` waits for it at the end: work enqueued on `stream` after the call sees all outputs.
  * The similarity kernel is bound on chip and the compaction by HBM, which is why the two go well
- * side by side.  For bf16 hidden states, B >= 12 and n_layers <= 16 the K/V rows that no selection
- * can change (prefix, valid text; Fig. 3) are copied by further workgroups of the launch that
- * selects, and the second stream moves the rows of the kept tokens only; the bytes written are the
- * same either way.  Otherwise, and always with ASAP_ROUTE_PAPER (final_idx exists only after the
+ * side by side.  The K/V rows that no selection can change (prefix, valid text; Fig. 3) do not
+ * wait for it: when the caches are deep (the compaction moves more than four times the bytes of
+ * the hidden states) the second stream starts on them at the beginning of the call, beside the
+ * score kernels; else, for bf16 hidden states, B >= 12 and n_layers <= 16, further workgroups of
+ * the launch that selects copy them.  The second stream then moves the rows of the kept tokens
+ * only; the bytes written are the same in every case.  Otherwise, and always with ASAP_ROUTE_PAPER (final_idx exists only after the
  * merge), everything runs on `stream` in order.  One context must not run two stages at once.
  * The calls are capturable into a HIP graph (kernels, event record / wait; no memset, no sync).
  */

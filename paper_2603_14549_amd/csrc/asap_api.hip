@@ -21,7 +21,7 @@ struct asap_ctx {
   char err[512];
   asap::Timer* timer;   // non-null while kernel timing is on
   hipStream_t side;     // second stream of asap_stage and its fork / join events; made on first use
-  hipEvent_t ev_fork, ev_join;
+  hipEvent_t ev_start, ev_fork, ev_join;
 };
 
 namespace {
@@ -172,7 +172,7 @@ asap_status asap_create(asap_ctx** out_ctx, int device) {
   c->err[0] = 0;
   c->timer = nullptr;
   c->side = nullptr;
-  c->ev_fork = c->ev_join = nullptr;
+  c->ev_start = c->ev_fork = c->ev_join = nullptr;
   *out_ctx = c;
   return ASAP_OK;
 }
@@ -188,11 +188,12 @@ static void drop_timer(asap_ctx* ctx) {
 }
 
 static void drop_stage_resources(asap_ctx* ctx) {
+  if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
   if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
   if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
   if (ctx->side) (void)hipStreamDestroy(ctx->side);
   ctx->side = nullptr;
-  ctx->ev_fork = ctx->ev_join = nullptr;
+  ctx->ev_start = ctx->ev_fork = ctx->ev_join = nullptr;
 }
 
 void asap_destroy(asap_ctx* ctx) {
@@ -530,10 +531,11 @@ asap_status asap_compact_kv_from_kept(asap_ctx* ctx, const asap_params* p, int32
                     "asap_compact_kv_from_kept launch");
 }
 
-// The second stream and the two events of asap_stage, made on first use.
+// The second stream and the three events of asap_stage, made on first use.
 static asap_status stage_resources(asap_ctx* ctx) {
   if (ctx->side) return ASAP_OK;
   hipError_t e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);     // default priority
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_start, hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
   if (e != hipSuccess) {
@@ -569,31 +571,49 @@ asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io*
   Strides3 qt{io->q_txt_stride[0], io->q_txt_stride[1], io->q_txt_stride[2]};
   Strides3 kv{io->k_vis_stride[0], io->k_vis_stride[1], io->k_vis_stride[2]};
   char* ws = static_cast<char*>(io->workspace);
-  // The selection rides in the launch that finishes the score.  That launch keeps B compute units busy
-  // and moves next to nothing, so for large bf16 batches, where the K/V compaction is what the similarity
-  // search waits for, it also takes the K/V rows no selection can change (prefix, valid text); the
-  // second stream then only moves the rows of the kept tokens.
-  const bool fixed_early = early && score_fuses_selection(*p) && p->h_dtype == ASAP_BF16 &&
-                           io->n_layers <= KV_LAYERS_PER_LAUNCH;
+  // The K/V rows that no selection can change (prefix, valid text; Fig. 3) need not wait for it.
+  //  * Deep caches (the compaction moves more than four times the bytes of the hidden states, so it
+  //    outlasts similarity search and merge): the second stream starts on those rows at once, beside
+  //    the score kernels, and takes the kept tokens' rows after the selection.
+  //  * Otherwise, for large bf16 batches: the launch that finishes the score and selects keeps B
+  //    compute units busy and moves next to nothing, so further workgroups of it copy those rows.
+  const int64_t kv_row_bytes = p->d * (p->kv_dtype == ASAP_BF16 ? 2 : 4);
+  const int64_t kv_bytes = 4 * (int64_t)io->n_layers * p->B * p->Hkv * (p->P + p->k + p->Tmax) * kv_row_bytes;
+  const int64_t hidden_bytes = (int64_t)p->B * p->V * p->D * (p->h_dtype == ASAP_BF16 ? 2 : 4);
+  const bool fixed_first = early && kv_bytes > 4 * hidden_bytes;
+  const bool fixed_with_selection = early && !fixed_first && score_fuses_selection(*p) && p->h_dtype == ASAP_BF16 &&
+                                    io->n_layers <= KV_LAYERS_PER_LAUNCH;
+  hipError_t e = hipSuccess;
+  bool forked = false;
+  if (fixed_first) {
+    e = hipEventRecord(ctx->ev_start, main);
+    if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_start, 0);
+    if (e == hipSuccess) {
+      forked = true;
+      e = launch_compact_kv(*p, KV_FIXED_ONLY, io->n_layers, io->k_src, io->v_src, io->k_dst, io->v_dst,
+                            io->kept_idx /* not read in this mode */, io->text_len, ctx->side, ctx->timer);
+    }
+  }
   KvFixedRows fixed;
-  if (fixed_early) {
+  if (fixed_with_selection) {
     fill_kv_pointers(&fixed.ptrs, io->n_layers, io->k_src, io->v_src, io->k_dst, io->v_dst);
     fixed.n_bufs = 2 * io->n_layers;
     fixed.Hkv = p->Hkv; fixed.N = p->P + p->V + p->Tmax; fixed.Nout = p->P + p->k + p->Tmax;
-    fixed.row_bytes = p->d * (p->kv_dtype == ASAP_BF16 ? 2 : 4);
+    fixed.row_bytes = (int)kv_row_bytes;
     fixed.P = p->P; fixed.V = p->V; fixed.k = p->k; fixed.Tmax = p->Tmax;
   }
-  hipError_t e = launch_score(*p, io->q_vis, qv, io->q_txt, qt, io->k_vis, kv, io->text_len, io->lse_extra, io->s_raw,
-                              io->s_hat, io->score, io->kept_idx, io->pruned_idx, nullptr,
-                              fixed_early ? &fixed : nullptr, ws, main, ctx->timer);
-  bool forked = false;
+  if (e == hipSuccess)
+    e = launch_score(*p, io->q_vis, qv, io->q_txt, qt, io->k_vis, kv, io->text_len, io->lse_extra, io->s_raw,
+                     io->s_hat, io->score, io->kept_idx, io->pruned_idx, nullptr,
+                     fixed_with_selection ? &fixed : nullptr, ws, main, ctx->timer);
   if (e == hipSuccess && early) {
     e = hipEventRecord(ctx->ev_fork, main);
     if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
     if (e == hipSuccess) {
       forked = true;
-      e = launch_compact_kv(*p, fixed_early ? KV_KEPT_ONLY : KV_FROM_KEPT, io->n_layers, io->k_src, io->v_src,
-                            io->k_dst, io->v_dst, io->kept_idx, io->text_len, ctx->side, ctx->timer);
+      e = launch_compact_kv(*p, (fixed_first || fixed_with_selection) ? KV_KEPT_ONLY : KV_FROM_KEPT, io->n_layers,
+                            io->k_src, io->v_src, io->k_dst, io->v_dst, io->kept_idx, io->text_len, ctx->side,
+                            ctx->timer);
     }
   }
   if (e == hipSuccess)

@@ -27,38 +27,64 @@ void fill_kv_pointers(KvPointers* ptrs, int n_layers, const void* const* k_src, 
 
 // Where the source rows come from: the position list of asap_merge / asap_positions, or the kept list
 // and text_len directly (the output order of Fig. 3 written out: prefix | kept | valid text).
-// idx = pos_out [B,Nout] and len = new_len (BY_POS); idx = kept list [B,k] and len = text_len (FROM_KEPT).
+// idx = pos_out [B,Nout] and len = new_len (BY_POS); idx = kept list [B,k] and len = text_len (FROM_KEPT,
+// KEPT_ONLY); FIXED_ONLY reads no index list and takes len = text_len.
 template <int MODE>
-__global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t* __restrict__ idx,
-                                                  const int32_t* __restrict__ len, int Hkv, int N, int Nout,
-                                                  int row_bytes, int P, int V, int k) {
+__device__ __forceinline__ void compact_block(const KvPointers& ptrs, const int32_t* __restrict__ idx,
+                                              const int32_t* __restrict__ len, int Hkv, int N, int Nout,
+                                              int row_bytes, int P, int V, int k, int bx, int bg, int bz) {
   const int lpr = row_bytes >> 4, rpi = 256 / lpr;
   const int tid = threadIdx.x, piece = tid % lpr, r0 = tid / lpr;
-  const int bg = blockIdx.y, b = bg / Hkv;
-  const int n_rows = MODE == KV_BY_POS ? min(len[b], Nout) : MODE == KV_KEPT_ONLY ? k
-                                                            : P + k + min(len[b], Nout - P - k);
-  const char* src = ptrs.src[blockIdx.z] + (int64_t)bg * N * row_bytes + piece * 16;
-  char* dst = ptrs.dst[blockIdx.z] + (int64_t)bg * Nout * row_bytes + piece * 16;
+  const int b = bg / Hkv;
+  const int n_rows = MODE == KV_BY_POS      ? min(len[b], Nout)
+                     : MODE == KV_KEPT_ONLY ? k
+                     : MODE == KV_FIXED_ONLY ? P + min(max(len[b], 0), Nout - P - k)
+                                             : P + k + min(len[b], Nout - P - k);
+  const char* src = ptrs.src[bz] + (int64_t)bg * N * row_bytes + piece * 16;
+  char* dst = ptrs.dst[bz] + (int64_t)bg * Nout * row_bytes + piece * 16;
   const int32_t* ix = idx + (int64_t)b * (MODE == KV_BY_POS ? Nout : k);
-  const int base = blockIdx.x * rpi * KV_ROWS_PER_THREAD + r0;
+  const int base = bx * rpi * KV_ROWS_PER_THREAD + r0;
   uint4 v[KV_ROWS_PER_THREAD];
 #pragma unroll
   for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
     const int r = base + i * rpi;
     if (r < n_rows) {
-      const int srow = MODE == KV_BY_POS      ? ix[r]
-                       : MODE == KV_KEPT_ONLY ? P + ix[r]
-                       : r < P                ? r
-                       : r < P + k            ? P + ix[r - P]
-                                              : r - k + V;
+      const int srow = MODE == KV_BY_POS       ? ix[r]
+                       : MODE == KV_KEPT_ONLY  ? P + ix[r]
+                       : MODE == KV_FIXED_ONLY ? (r < P ? r : r + V)
+                       : r < P                 ? r
+                       : r < P + k             ? P + ix[r - P]
+                                               : r - k + V;
       v[i] = ldg16_stream(src + (int64_t)srow * row_bytes);
     }
   }
-  const int shift = MODE == KV_KEPT_ONLY ? P : 0;       // kept slot r is output row P + r
 #pragma unroll
   for (int i = 0; i < KV_ROWS_PER_THREAD; ++i) {
     const int r = base + i * rpi;
-    if (r < n_rows) stg16_stream(dst + (int64_t)(r + shift) * row_bytes, v[i]);
+    // kept slot r is output row P + r; the r-th row that no selection changes is output row r (prefix) or
+    // r + k (text)
+    const int drow = MODE == KV_KEPT_ONLY ? P + r : MODE == KV_FIXED_ONLY ? (r < P ? r : r + k) : r;
+    if (r < n_rows) stg16_stream(dst + (int64_t)drow * row_bytes, v[i]);
+  }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void k_compact(KvPointers ptrs, const int32_t* __restrict__ idx,
+                                                  const int32_t* __restrict__ len, int Hkv, int N, int Nout,
+                                                  int row_bytes, int P, int V, int k) {
+  compact_block<MODE>(ptrs, idx, len, Hkv, N, Nout, row_bytes, P, V, k, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// The rows that no selection changes, for the launch that runs beside the score kernels: a grid of
+// at most two workgroups per compute unit walks the (gx, gy, gz) blocks of k_compact, so that the
+// kernels of the other stream still find room on every compute unit.
+__global__ __launch_bounds__(256) void k_compact_fixed(KvPointers ptrs, const int32_t* __restrict__ len, int Hkv,
+                                                        int N, int Nout, int row_bytes, int P, int V, int k, int gx,
+                                                        int gy, int gz) {
+  const int total = gx * gy * gz;
+  for (int id = blockIdx.x; id < total; id += gridDim.x) {
+    const int bx = id % gx, bg = (id / gx) % gy, bz = id / (gx * gy);
+    compact_block<KV_FIXED_ONLY>(ptrs, len, len, Hkv, N, Nout, row_bytes, P, V, k, bx, bg, bz);
   }
 }
 
@@ -129,7 +155,7 @@ hipError_t launch_compact_kv(const asap_params& p, int mode, int n_layers, const
   const int row_bytes = p.d * (p.kv_dtype == ASAP_BF16 ? 2 : 4);
   const int N = p.P + p.V + p.Tmax, Nout = p.P + p.k + p.Tmax;
   const int rows_per_block = (256 / (row_bytes / 16)) * KV_ROWS_PER_THREAD;
-  const int rows = mode == KV_KEPT_ONLY ? p.k : Nout;
+  const int rows = mode == KV_KEPT_ONLY ? p.k : mode == KV_FIXED_ONLY ? p.P + p.Tmax : Nout;
   for (int l0 = 0; l0 < n_layers; l0 += KV_LAYERS_PER_LAUNCH) {
     const int nl = n_layers - l0 < KV_LAYERS_PER_LAUNCH ? n_layers - l0 : KV_LAYERS_PER_LAUNCH;
     KvPointers ptrs;
@@ -141,9 +167,14 @@ hipError_t launch_compact_kv(const asap_params& p, int mode, int n_layers, const
     else if (mode == KV_FROM_KEPT)
       ASAP_LAUNCH(tm, "k_compact", k_compact<KV_FROM_KEPT>, grid, dim3(256), 0, st, ptrs, idx, len, p.Hkv, N, Nout,
                   row_bytes, p.P, p.V, p.k);
-    else
+    else if (mode == KV_KEPT_ONLY)
       ASAP_LAUNCH(tm, "k_compact", k_compact<KV_KEPT_ONLY>, grid, dim3(256), 0, st, ptrs, idx, len, p.Hkv, N, Nout,
                   row_bytes, p.P, p.V, p.k);
+    else {
+      const long total = (long)grid.x * grid.y * grid.z;
+      ASAP_LAUNCH(tm, "k_compact_fixed", k_compact_fixed, dim3((unsigned)(total < 512 ? total : 512)), dim3(256), 0, st,
+                  ptrs, len, p.Hkv, N, Nout, row_bytes, p.P, p.V, p.k, (int)grid.x, (int)grid.y, (int)grid.z);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

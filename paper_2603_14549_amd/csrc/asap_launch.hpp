@@ -135,9 +135,10 @@ hipError_t launch_positions(const asap_params& p, const int32_t* kept, const int
                             int32_t* new_len, hipStream_t st, Timer* tm);
 
 // KV_BY_POS: idx = pos_out, len = new_len; KV_FROM_KEPT: idx = kept list, len = text_len, all output
-// rows; KV_KEPT_ONLY: as KV_FROM_KEPT but only the rows of the kept tokens (the others were moved by
-// the launch that took a KvFixedRows).  At most KV_LAYERS_PER_LAUNCH layers per launch.
-enum { KV_BY_POS = 0, KV_FROM_KEPT = 1, KV_KEPT_ONLY = 2 };
+// rows; KV_KEPT_ONLY: as KV_FROM_KEPT but only the rows of the kept tokens; KV_FIXED_ONLY: the other
+// rows (prefix, valid text), which need no index list.  The last two together move what KV_FROM_KEPT
+// moves.
+enum { KV_BY_POS = 0, KV_FROM_KEPT = 1, KV_KEPT_ONLY = 2, KV_FIXED_ONLY = 3 };
 hipError_t launch_compact_kv(const asap_params& p, int mode, int n_layers, const void* const* k_src,
                              const void* const* v_src, void* const* k_dst, void* const* v_dst,
                              const int32_t* idx, const int32_t* len, hipStream_t st, Timer* tm);
