@@ -302,6 +302,8 @@ def main():
                     help="store the rows of the input hidden states this many elements further apart than their "
                          "length (the stage takes strided views; rows a power of two bytes apart all start in the "
                          "same memory channel)")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="asap_stage with two_streams = 0: the K/V compaction follows the merge on the caller's stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="accepted for the counter runs documented in profiles/: the 1 GiB device copies that "
@@ -337,7 +339,8 @@ def main():
         lse_extra = np.random.default_rng(cfg.seed + 1000).normal(2.0, 2.0, size=(cfg.B, cfg.H, cfg.Tmax)) \
             .astype(np.float32)
     stage = harness.DeviceStage(inp, ctx=ctx, lse_extra=lse_extra, page_size=args.paged_kv or None,
-                                last_token=args.last_token, hidden_row_pad=args.hidden_row_pad, **overrides)
+                                last_token=args.last_token, hidden_row_pad=args.hidden_row_pad,
+                                overlap=False if args.one_stream else "auto", **overrides)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -355,7 +358,7 @@ def main():
     if args.rotate >= 2:
         sets = [stage] + [harness.DeviceStage(inp, ctx=ctx, lse_extra=lse_extra, page_size=args.paged_kv or None,
                                               last_token=args.last_token, hidden_row_pad=args.hidden_row_pad,
-                                              **overrides)
+                                              overlap=False if args.one_stream else "auto", **overrides)
                           for _ in range(args.rotate - 1)]
         for i in range(args.warmup):
             sets[i % len(sets)].run_async()
@@ -400,7 +403,7 @@ def main():
         n_alone = min(args.steps, 5)
         ctx.asap_timing_enable(launches_per_step * n_alone)
         for _ in range(n_alone):
-            ctx.asap_stage(stage.p, stage.io, False)
+            ctx.asap_stage(stage.p, stage.io, binding.ASAP_STREAMS_ONE)
         torch.cuda.synchronize()
         sim_alone = ctx.asap_timing_collect().get("k_sim")
         ctx.asap_timing_enable(0)

@@ -273,23 +273,31 @@ asap_status asap_compact_kv_from_kept(asap_ctx* ctx, const asap_params* p, int32
                                       void* const* k_dst, void* const* v_dst,
                                       const int32_t* final_idx, const int32_t* text_len, void* stream);
 
+/* Where asap_stage runs the K/V compaction: after the merge on the caller's stream, beside similarity
+ * search and merge on a second stream, or on whichever of the two the sizes favour. */
+typedef enum { ASAP_STREAMS_ONE = 0, ASAP_STREAMS_AUTO = 1, ASAP_STREAMS_TWO = 2 } asap_stream_mode;
+
 /*
  * asap_stage -- the whole stage in one call: asap_score, asap_select, asap_merge and the K/V
  * compaction (asap_compact_kv_from_kept), with the arguments of those calls gathered in one struct
  * (same meaning, layout and checks; every check runs before the first launch).  n_layers = 0 skips
  * the compaction (the four K/V arrays may then be NULL).
- * two_streams != 0 and ASAP_ROUTE_ABSORB: the K/V rows depend on the kept set only, so after the
- * selection the compaction is launched on a second stream of the context (default priority, made
- * on first use) ordered after `stream` by an event, next to the similarity and merge kernels, and
- * `stream` waits for it at the end: work enqueued on `stream` after the call sees all outputs.
- * The similarity kernel is bound on chip and the compaction by HBM, which is why the two go well
- * side by side.  The K/V rows that no selection can change (prefix, valid text; Fig. 3) do not
- * wait for it: when the caches are deep (the compaction moves more than four times the bytes of
- * the hidden states) the second stream starts on them at the beginning of the call, beside the
- * score kernels; else, for bf16 hidden states, B >= 12 and n_layers <= 16, further workgroups of
- * the launch that selects copy them.  The second stream then moves the rows of the kept tokens
- * only; the bytes written are the same in every case.  Otherwise, and always with ASAP_ROUTE_PAPER (final_idx exists only after the
- * merge), everything runs on `stream` in order.  One context must not run two stages at once.
+ * two_streams (asap_stream_mode) and ASAP_ROUTE_ABSORB: the K/V rows depend on the kept set only,
+ * so after the selection the compaction can be launched on a second stream of the context (default
+ * priority, made on first use) ordered after `stream` by an event, next to the similarity and merge
+ * kernels; `stream` waits for it at the end: work enqueued on `stream` after the call sees all
+ * outputs.  The similarity kernel is bound on chip and the compaction by HBM, which is why the two
+ * go well side by side.  ASAP_STREAMS_ONE never does this, ASAP_STREAMS_TWO always, and
+ * ASAP_STREAMS_AUTO when the compaction moves at least 64 MiB (bytes read + written): below that
+ * the two hand-overs between the streams cost more than they save.
+ * The K/V rows that no selection can change (prefix, valid text; Fig. 3) do not wait for the
+ * selection: when the caches are deep (the compaction moves more than four times the bytes of the
+ * hidden states) the second stream starts on them at the beginning of the call, beside the score
+ * kernels; else, for bf16 hidden states, B >= 12 and n_layers <= 16, further workgroups of the
+ * launch that selects copy them.  The second stream then moves the rows of the kept tokens only;
+ * the bytes written are the same in every case.
+ * With ASAP_ROUTE_PAPER (final_idx exists only after the merge) everything runs on `stream` in
+ * order.  Any other value of two_streams: ASAP_EINVAL.  One context must not run two stages at once.
  * The calls are capturable into a HIP graph (kernels, event record / wait; no memset, no sync).
  */
 typedef struct asap_stage_io {

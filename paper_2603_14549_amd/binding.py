@@ -20,6 +20,7 @@ ASAP_F32, ASAP_BF16 = 0, 1
 ASAP_MASK_OFF, ASAP_MASK_KEYBIAS = 0, 1
 ASAP_ROUTE_ABSORB, ASAP_ROUTE_PAPER = 0, 1
 ASAP_ROWS_ALL, ASAP_ROWS_LAST = 0, 1
+ASAP_STREAMS_ONE, ASAP_STREAMS_AUTO, ASAP_STREAMS_TWO = 0, 1, 2
 
 EXPORTS = ["asap_create", "asap_destroy", "asap_last_error", "asap_check_params", "asap_workspace_bytes",
            "asap_score", "asap_score_static", "asap_score_from_hidden", "asap_front_end_workspace_bytes", "asap_select", "asap_merge", "asap_positions", "asap_compact_kv",
@@ -313,8 +314,8 @@ class Context:
             self._h, ctypes.byref(p), n, arr(k_src), arr(v_src), arr(k_dst), arr(v_dst), _ptr(final_idx),
             _ptr(text_len), _stream(stream)))
 
-    def asap_stage(self, p, io: asap_stage_io, two_streams: bool = True, stream=None):
-        self._check(self._lib.asap_stage(self._h, ctypes.byref(p), ctypes.byref(io), 1 if two_streams else 0,
+    def asap_stage(self, p, io: asap_stage_io, two_streams: int = ASAP_STREAMS_AUTO, stream=None):
+        self._check(self._lib.asap_stage(self._h, ctypes.byref(p), ctypes.byref(io), int(two_streams),
                                          _stream(stream)))
 
     def asap_compact_kv_paged(self, p, k_src_pool: Sequence[torch.Tensor], v_src_pool, k_dst_pool, v_dst_pool,

@@ -549,6 +549,8 @@ asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io*
                        void* stream) {
   if (!ctx) return ASAP_EINVAL;
   if (!io) return fail(ctx, ASAP_EINVAL, "asap_stage: io is NULL");
+  if (two_streams < ASAP_STREAMS_ONE || two_streams > ASAP_STREAMS_TWO)
+    return fail(ctx, ASAP_EINVAL, "asap_stage: two_streams = %d is no asap_stream_mode", (int)two_streams);
   // every check of the single calls first: a failed check launches nothing
   asap_status st = score_checks(ctx, p, io->q_vis, io->q_vis_stride, io->q_txt, io->q_txt_stride, io->k_vis,
                                 io->k_vis_stride, io->text_len, io->s_raw, io->s_hat, io->score, io->workspace,
@@ -562,8 +564,14 @@ asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io*
   if (st == ASAP_OK && has_kv)
     st = check_kv_buffers(ctx, p, "asap_stage", io->n_layers, io->k_src, io->v_src, io->k_dst, io->v_dst);
   if (st != ASAP_OK) return st;
-  // with ASAP_ROUTE_ABSORB the kept set is final after the selection: the K/V rows can move while the merge runs
-  const bool early = has_kv && two_streams && p->route == ASAP_ROUTE_ABSORB;
+  // With ASAP_ROUTE_ABSORB the kept set is final after the selection: the K/V rows can move while the merge
+  // runs.  The two hand-overs between the streams cost the caller's stream about as much as copying 64 MB
+  // does (measured: single images and batches of 4 ran 3 to 9 % faster on one stream), so with
+  // ASAP_STREAMS_AUTO smaller compactions stay on the caller's stream.
+  const int64_t kv_row_bytes = p->d * (p->kv_dtype == ASAP_BF16 ? 2 : 4);
+  const int64_t kv_bytes = 4 * (int64_t)io->n_layers * p->B * p->Hkv * (p->P + p->k + p->Tmax) * kv_row_bytes;
+  const bool early = has_kv && p->route == ASAP_ROUTE_ABSORB &&
+                     (two_streams == ASAP_STREAMS_TWO || (two_streams == ASAP_STREAMS_AUTO && kv_bytes >= (64ll << 20)));
   if (early && (st = stage_resources(ctx)) != ASAP_OK) return st;
 
   hipStream_t main = static_cast<hipStream_t>(stream);
@@ -577,8 +585,6 @@ asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io*
   //    the score kernels, and takes the kept tokens' rows after the selection.
   //  * Otherwise, for large bf16 batches: the launch that finishes the score and selects keeps B
   //    compute units busy and moves next to nothing, so further workgroups of it copy those rows.
-  const int64_t kv_row_bytes = p->d * (p->kv_dtype == ASAP_BF16 ? 2 : 4);
-  const int64_t kv_bytes = 4 * (int64_t)io->n_layers * p->B * p->Hkv * (p->P + p->k + p->Tmax) * kv_row_bytes;
   const int64_t hidden_bytes = (int64_t)p->B * p->V * p->D * (p->h_dtype == ASAP_BF16 ? 2 : 4);
   const bool fixed_first = early && kv_bytes > 4 * hidden_bytes;
   const bool fixed_with_selection = early && !fixed_first && score_fuses_selection(*p) && p->h_dtype == ASAP_BF16 &&

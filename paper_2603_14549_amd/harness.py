@@ -9,7 +9,7 @@ from typing import List, Optional
 
 import torch
 
-from .binding import (ASAP_ROUTE_ABSORB, ASAP_ROWS_LAST, Context, _TORCH_DTYPE, _strides, asap_params, asap_stage_io,
+from .binding import (ASAP_ROUTE_ABSORB, ASAP_ROWS_LAST, ASAP_STREAMS_AUTO, ASAP_STREAMS_ONE, ASAP_STREAMS_TWO, Context, _TORCH_DTYPE, _strides, asap_params, asap_stage_io,
                       asap_workspace_bytes, params_from_config)
 
 
@@ -161,12 +161,13 @@ def to_device(arr, dtype: str, device="cuda:0") -> torch.Tensor:
 
 class DeviceStage:
     """One batch from synth.make_inputs uploaded to the GPU, with output buffers.  run() is one
-    asap_stage call (overlap=True: two streams inside the library); with call_by_call=True, or with
+    asap_stage call (overlap=True: two streams inside the library whatever the sizes, "auto": the library
+    chooses, False: one stream); with call_by_call=True, or with
     paged caches, it is the sequence of single calls of run_stage, where the second stream is torch's.
     last_token=True ranks the visual tokens by the last valid text token's row alone
     (score_rows = ASAP_ROWS_LAST in the params; the library picks the row from text_len)."""
 
-    def __init__(self, inp: dict, ctx: Optional[Context] = None, lse_extra=None, overlap: bool = True,
+    def __init__(self, inp: dict, ctx: Optional[Context] = None, lse_extra=None, overlap=True,
                  page_size: Optional[int] = None, call_by_call: bool = False, last_token: bool = False,
                  hidden_row_pad: int = 0, **param_overrides):
         import numpy as np
@@ -197,7 +198,9 @@ class DeviceStage:
         has_kv = bool(self.k_cache) or self.paged is not None
         self.call_by_call = call_by_call or self.paged is not None
         # whether the K/V compaction runs beside the similarity and merge kernels
-        self.two_streams = overlap and has_kv and self.p.route == ASAP_ROUTE_ABSORB
+        self.two_streams = bool(overlap) and has_kv and self.p.route == ASAP_ROUTE_ABSORB
+        self.stream_mode = (ASAP_STREAMS_ONE if not self.two_streams else
+                            ASAP_STREAMS_AUTO if overlap == "auto" else ASAP_STREAMS_TWO)
         # torch's default-priority second stream, for the call-by-call path only
         self.side_stream = torch.cuda.Stream() if (self.call_by_call and overlap and has_kv) else None
         self.io = None if self.call_by_call else stage_io(self.p, self.q, self.k, self.hidden, self.text_len,
@@ -207,7 +210,7 @@ class DeviceStage:
         if self.call_by_call:
             return run_stage(self.ctx, self.p, self.q, self.k, self.hidden, self.text_len, self.k_cache,
                              self.v_cache, self.buf, self.lse_extra, side_stream=self.side_stream, paged=self.paged)
-        self.ctx.asap_stage(self.p, self.io, self.two_streams)
+        self.ctx.asap_stage(self.p, self.io, self.stream_mode)
         return self.buf
 
     def run(self) -> StageBuffers:

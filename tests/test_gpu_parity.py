@@ -305,8 +305,10 @@ def test_positions_and_two_stream_stage(ctx):
     assert serial.side_stream is None
     bs = serial.run()
     variants = [U.GpuStage(inp, ctx=ctx, overlap=True, call_by_call=True), U.GpuStage(inp, ctx=ctx, overlap=True),
-                U.GpuStage(inp, ctx=ctx, overlap=False)]
+                U.GpuStage(inp, ctx=ctx, overlap=False), U.GpuStage(inp, ctx=ctx, overlap="auto")]
     assert variants[0].side_stream is not None and variants[1].two_streams and not variants[2].two_streams
+    assert (variants[1].stream_mode, variants[2].stream_mode, variants[3].stream_mode) == (
+        binding.ASAP_STREAMS_TWO, binding.ASAP_STREAMS_ONE, binding.ASAP_STREAMS_AUTO)
     for both in variants:
         for _ in range(3):
             bo = both.run()
@@ -333,7 +335,10 @@ def test_positions_and_two_stream_stage(ctx):
     st.buf.score.fill_(-7.0)
     torch.cuda.synchronize()
     with pytest.raises(binding.AsapError) as e:
-        ctx.asap_stage(st.p, bad, True)
+        ctx.asap_stage(st.p, bad, binding.ASAP_STREAMS_TWO)
+    assert e.value.status == binding.ASAP_EINVAL
+    with pytest.raises(binding.AsapError) as e:       # no such stream mode
+        ctx.asap_stage(st.p, st.io, 3)
     assert e.value.status == binding.ASAP_EINVAL
     torch.cuda.synchronize()
     assert bool((st.buf.score == -7.0).all()), "a failed check must launch nothing"
