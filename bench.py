@@ -302,6 +302,8 @@ def main():
                     help="store the rows of the input hidden states this many elements further apart than their "
                          "length (the stage takes strided views; rows a power of two bytes apart all start in the "
                          "same memory channel)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time replays of the stage call captured into a HIP graph")
     ap.add_argument("--one-stream", action="store_true",
                     help="asap_stage with two_streams = 0: the K/V compaction follows the merge on the caller's stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -371,6 +373,30 @@ def main():
         rotated = {"sets": len(sets), "ms_per_step": rot_ms, "images_per_s": cfg.B / (rot_ms * 1e-3),
                    "note": "same steps cycling over copies of all inputs and outputs at different addresses"}
         del sets
+
+    graph_replay = None
+    if args.graph and not stage.call_by_call:
+        # the stage records kernels and event record / wait pairs only, so it can be captured; replays are
+        # timed like the eager steps (launch-bound shapes, single images above all, are where it may pay)
+        cap_stream = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(cap_stream):
+            stage.run_async()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=cap_stream):
+                stage.run_async()
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        graph_replay = {"ms_per_step": g_ms, "images_per_s": cfg.B / (g_ms * 1e-3),
+                        "note": "the same stage call captured once into a HIP graph and replayed"}
+        del graph
 
     # second pass of the same K steps with the library's per-kernel HIP events on
     launches_per_step = 18
@@ -529,6 +555,8 @@ def main():
     }
     if rotated is not None:
         out["rotated_inputs"] = rotated
+    if graph_replay is not None:
+        out["graph_replay"] = graph_replay
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, cfg, route=args.route, lse_extra=lse_extra,
                                            score_rows="last" if args.last_token else "all")

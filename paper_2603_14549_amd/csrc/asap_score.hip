@@ -134,9 +134,18 @@ __global__ void k_qsplit(const double* __restrict__ qpart, double* __restrict__ 
   const int g = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
   const int G = H / Hkv;
   if (g == 0 && c == 0) { mmkey[2 * b] = ~0ull; mmkey[2 * b + 1] = 0ull; }   // also where k_qsum did not run
+  // the partials of the group's heads and chunks lie one after the other (head-major): added in that
+  // order, eight loads in flight
+  const double* src = qpart + ((int64_t)b * H + g * G) * nchunk * d + c;
+  const int n = G * nchunk;
   double s = 0.0;
-  for (int h = g * G; h < (g + 1) * G; ++h)
-    for (int ch = 0; ch < nchunk; ++ch) s += qpart[(((int64_t)b * H + h) * nchunk + ch) * d + c];
+  for (int i0 = 0; i0 < n; i0 += 8) {
+    double part[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) part[u] = i0 + u < n ? src[(int64_t)(i0 + u) * d] : 0.0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += part[u];
+  }
   qbar[((int64_t)b * Hkv + g) * d + c] = s;
   split_bf16x4(s, qsplit + ((int64_t)b * Hkv + g) * 4 * d + c, d);
 }
@@ -358,7 +367,13 @@ __global__ __launch_bounds__(1024) void k_mass_finish(const double* __restrict__
   unsigned long long kmin = ~0ull, kmax = 0ull;
   for (int j = tid; j < V; j += 1024) {
     double t = 0.0;
-    for (int q = 0; q < HS; ++q) t += spart[((int64_t)q * B + b) * V + j];
+    for (int q0 = 0; q0 < HS; q0 += 8) {       // eight loads in flight, added in group order
+      double part[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) part[u] = q0 + u < HS ? spart[((int64_t)(q0 + u) * B + b) * V + j] : 0.0;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t += part[u];
+    }
     const double s = t * scale;
     s64[(int64_t)b * V + j] = s;
     s_raw[(int64_t)b * V + j] = (float)s;
