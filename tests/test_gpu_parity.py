@@ -368,10 +368,12 @@ def test_prefix_and_text_kv_rows_move_with_the_selection(ctx, base, kv_dtype, P,
         U.compare_image(inp, bo, b, U.oracle_image(inp, b, score_rows="last" if last_token else "all"))
 
 
-def test_stage_replayed_from_a_captured_graph(ctx):
+@pytest.mark.parametrize("layers", [2, 16])
+def test_stage_replayed_from_a_captured_graph(ctx, layers):
     """asap_stage records only kernels and event record / wait pairs, so it can be captured: every
-    replay, with eager stages and synchronisations in between, gives the eager stage's bits."""
-    cfg = synth.CONFIGS["S2"]
+    replay, with eager stages and synchronisations in between, gives the eager stage's bits.  With 16
+    cached layers the second stream is forked at the start of the call as well (deep caches)."""
+    cfg = dataclasses.replace(synth.CONFIGS["S2"], L_kv=layers, name=f"S2-{layers}-layers")
     inp = synth.make_inputs(cfg)
     st = U.GpuStage(inp, ctx=ctx)
     assert st.two_streams
