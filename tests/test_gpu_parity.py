@@ -749,13 +749,13 @@ def test_config4_gqa_dynamic_resolution(ctx):
 
 def test_config6_target_2304_tokens_batch16(ctx):
     rep = {}
-    U.run_and_compare(synth.CONFIGS["C6"], images=[0, 5, 15], ctx=ctx, report=rep)
+    U.run_and_compare(synth.CONFIGS["C6"], ctx=ctx, report=rep)          # every image against the oracle
     print("C6", rep)
 
 
 def test_config6_invariants_on_every_image(ctx):
-    """What holds at any size, checked on all 16 images of the configuration bench.py times (the oracle
-    comparison above samples three of them): scores are a distribution, the kept set is the top-k of
+    """What holds at any size, checked on all 16 images of the configuration bench.py times, independently
+    of the oracle comparison above: scores are a distribution, the kept set is the top-k of
     the score, the two index lists partition the image, routing targets are kept slots, Eq. 6 conserves
     the merge weight and the weighted sum, positions and lengths follow the kept list, prefix and text
     rows and every K/V row are bit-exact copies."""
