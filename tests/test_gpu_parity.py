@@ -692,41 +692,48 @@ def test_attention_argument_checks_and_strided_inputs(ctx):
     assert torch.equal(out.view(torch.uint8), out2.view(torch.uint8))
 
 
-def test_attention_forward_full_size_sampled_rows(ctx):
-    """asap_attention at the benchmark shape (config 2: N = 2403, 32 heads, bf16) in the launch
-    configuration bench.py --attention times; sampled (head, row) outputs against the row's softmax
-    written out in fp64."""
-    cfg = synth.CONFIGS["C2"]
+@pytest.mark.parametrize("name,images", [("C2", (0,)), ("C6", (0, 7, 15))])
+def test_attention_forward_full_size_sampled_rows(ctx, name, images):
+    """asap_attention at the benchmark shapes (config 2, and its batch of 16 that bench.py --attention
+    times: N = 2403, 32 heads, bf16) in that launch configuration; sampled (image, head, row) outputs
+    against the row's softmax written out in fp64: the rows around every boundary of the mask and of
+    the 256-query workgroups, and seeded random ones."""
+    cfg = synth.CONFIGS[name]
     inp = synth.make_inputs(cfg, with_kv=False)
     st = U.GpuStage(inp, ctx=ctx)
     buf = st.run()
     rng = np.random.default_rng(99)
-    vals = synth.quantise(rng.standard_normal((cfg.B, cfg.Hkv, cfg.N, cfg.d)).astype(np.float32), cfg.qk_dtype)
+    vals = synth.quantise(rng.standard_normal((cfg.B, cfg.Hkv, cfg.N, cfg.d), dtype=np.float32), cfg.qk_dtype)
     v_dev = harness.to_device(vals, cfg.qk_dtype)
     out = torch.empty(cfg.B, cfg.H, cfg.N, cfg.d, dtype=st.q.dtype, device="cuda")
     ws = torch.empty(binding.asap_attention_workspace_bytes(st.p), dtype=torch.uint8, device="cuda")
     ctx.asap_attention(st.p, st.q, st.k, v_dev, buf.s_hat, out, ws)
     torch.cuda.synchronize()
     P, V, N, d = cfg.P, cfg.V, cfg.N, cfg.d
-    s_hat = U.from_device(buf.s_hat[0])
-    bias = np.log(np.maximum(1.0 * s_hat, float(np.float32(1e-6))))
-    Q = synth.to_f64(inp["q"][0], cfg.qk_dtype)
-    K = synth.to_f64(inp["k"][0], cfg.qk_dtype)
-    Vv = synth.to_f64(vals[0], cfg.qk_dtype)
-    got = U.from_device(out[0])
-    rows = [0, 1, 31, 32, P - 1, P, P + 1, P + 63, P + 64, P + 1000, P + V - 2, P + V - 1, P + V, N - 2, N - 1]
-    for h in (0, 7, 31):
-        for i in rows:
-            g = O.kv_head(h, cfg.H, cfg.Hkv)
-            z = K[g] @ Q[h, i] / math.sqrt(d)
-            m = np.full(N, -np.inf)
-            m[:i + 1] = 0.0
-            if P <= i < P + V:
-                m[i + 1:P + V] = bias[i + 1 - P:]
-            z = z + m
-            e = np.exp(z - z.max())
-            ref = (e[:, None] * Vv[g]).sum(0) / e.sum()
-            U.check_rows(got[h, i][None, :], ref[None, :], U.TOL[cfg.qk_dtype], f"head {h} row {i}")
+    edge_rows = [0, 1, 31, 32, P - 1, P, P + 1, P + 63, P + 64, 255, 256, 257, P + 1000, P + V - 2, P + V - 1, P + V,
+                 N - 2, N - 1]
+    pick = np.random.default_rng(100 + cfg.B)
+    for b in images:
+        s_hat = U.from_device(buf.s_hat[b])
+        bias = np.log(np.maximum(1.0 * s_hat, float(np.float32(1e-6))))
+        Q = synth.to_f64(inp["q"][b], cfg.qk_dtype)
+        K = synth.to_f64(inp["k"][b], cfg.qk_dtype)
+        Vv = synth.to_f64(vals[b], cfg.qk_dtype)
+        got = U.from_device(out[b])
+        heads = sorted({0, 7, cfg.H - 1} | set(int(x) for x in pick.integers(0, cfg.H, size=2)))
+        for h in heads:
+            rows = edge_rows + [int(x) for x in pick.integers(0, N, size=6)]
+            for i in rows:
+                g = O.kv_head(h, cfg.H, cfg.Hkv)
+                z = K[g] @ Q[h, i] / math.sqrt(d)
+                m = np.full(N, -np.inf)
+                m[:i + 1] = 0.0
+                if P <= i < P + V:
+                    m[i + 1:P + V] = bias[i + 1 - P:]
+                z = z + m
+                e = np.exp(z - z.max())
+                ref = (e[:, None] * Vv[g]).sum(0) / e.sum()
+                U.check_rows(got[h, i][None, :], ref[None, :], U.TOL[cfg.qk_dtype], f"image {b} head {h} row {i}")
 
 
 def test_config1_llava15_single_image(ctx):
