@@ -229,8 +229,8 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
                       : reinterpret_cast<const char*>(vt + ((int64_t)b * Hkv + g) * D * Npad);
   const int64_t vrow_bytes = sv.r * (int64_t)sizeof(T);
   const char* bg = reinterpret_cast<const char*>(bias2 + (int64_t)b * Npad);
-  auto issue_tile = [&](int t) {
-    const uint32_t st = lds_addr + (uint32_t)(t % NS) * STAGE;
+  auto issue_tile = [&](auto slot_c, int t) {          // tile t goes to ring slot t % NS = slot_c
+    const uint32_t st = lds_addr + (uint32_t)decltype(slot_c)::value * STAGE;
     const int j0 = min(t, ntiles - 1) * 32;
 #pragma unroll
     for (int u = 0; u < (TP + NW - 1) / NW; ++u) {
@@ -285,8 +285,8 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
   const int vtr_base = (4 * hf + src_key) * RB + ((2 * ((lane >> 4) & 1) + ((src16 & 3) >> 1)) << 4) + 8 * (src16 & 1);
 
   // S^T of the wave's queries against key tile t, raw (unscaled) products
-  auto scores = [&](int t, f32x16_t& s) {
-    const char* Kt = lds + (t % NS) * STAGE;
+  auto scores = [&](auto slot_c, f32x16_t& s) {
+    const char* Kt = lds + decltype(slot_c)::value * STAGE;
 #pragma unroll
     for (int v = 0; v < 16; ++v) s[v] = 0.0f;
 #pragma unroll
@@ -303,14 +303,15 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
   // maximum has grown by more than ATT_LAZY (in log2 units), so that the accumulated columns are rescaled
   // a few times per query instead of at most tiles; terms are then at most 2^ATT_LAZY, and the quotient
   // O / l does not depend on the baseline.
-  auto step = [&](int t, f32x16_t& s, f32x16_t& s_next) {
-    const int j0 = t * 32;
+  auto step = [&](auto slot_c, int t, f32x16_t& s, f32x16_t& s_next) {
+    constexpr int SLOT = decltype(slot_c)::value;         // t % NS, known at compile time: the LDS reads of the
+    const int j0 = t * 32;                                // tile then take their slot as an immediate offset
     // the mask, by the kind of tile (a wave-uniform choice; only the few lines that apply it differ)
     const int mode = (j0 + 31 <= i0) ? ATT_PLAIN
                      : (j0 > i0 + 31 && bidir && i0 >= img_lo && i0 + 31 < img_hi) ? ATT_AHEAD : ATT_GENERAL;
     if (mode != ATT_PLAIN) {                   // ATT_PLAIN: raw, the scale goes into the exponent below
       // discounts of this lane's 16 keys, staged with the tile
-      const char* Bt = lds + (t % NS) * STAGE + KTILE + VTILE;
+      const char* Bt = lds + SLOT * STAGE + KTILE + VTILE;
       float kbias[16];
 #pragma unroll
       for (int gq = 0; gq < 4; ++gq) {
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
         }
     }
     const float m_c = m_run * c2;
-    scores(t + 1, s_next);
+    scores(std::integral_constant<int, (SLOT + 1) % NS>{}, s_next);
     float p[16], psum = 0.0f;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -366,7 +367,7 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
 #pragma unroll
     for (int c = 0; c < NPS; ++c) pb[c] = att_pack16<T>(&p[c * E]);
     // O^T += V^T_tile P^T: piece 2c + hf of a values^T row holds the keys this lane half has in P^T
-    const char* Vt = lds + (t % NS) * STAGE + KTILE;
+    const char* Vt = lds + SLOT * STAGE + KTILE;
 #pragma unroll
     for (int c = 0; c < NPS; ++c)
 #pragma unroll
@@ -391,20 +392,28 @@ __global__ __launch_bounds__(64 * ATT_NW) void k_attention(const T* __restrict__
   // it, where it would also wait for the tile requests.
 #pragma unroll
   for (int c = 0; c < CH; ++c) asm volatile("" ::"v"(qa[c].x), "v"(qa[c].y), "v"(qa[c].z), "v"(qa[c].w));
-#pragma unroll
-  for (int t = 0; t <= PD; ++t) issue_tile(t);
+  static_assert(NS % 2 == 0, "the two score buffers swap roles every tile, the ring turns every NS tiles");
+  static_for<PD + 1>([&](auto t_c) { issue_tile(t_c, decltype(t_c)::value); });
   att_wait_tiles((PD - 1) * my_loads);
   barrier_keep_loads();
-  f32x16_t s_cur, s_next;
-  if (my_tiles > 0) scores(0, s_cur);
-  for (int t = 0; t < ntiles; ++t) {
-    issue_tile(t + 1 + PD);
-    if (t < my_tiles) {
-      step(t, s_cur, s_next);
-      s_cur = s_next;
-    }
-    att_wait_tiles((PD - 1) * my_loads);
-    barrier_keep_loads();
+  // The loop runs over whole turns of the ring, so that a tile's slot is a compile-time constant, and
+  // the raw scores alternate between two register sets instead of being copied.
+  f32x16_t s_even, s_odd;
+  if (my_tiles > 0) scores(std::integral_constant<int, 0>{}, s_even);
+  for (int t0 = 0; t0 < ntiles; t0 += NS) {
+    static_for<NS>([&](auto u_c) {
+      constexpr int U = decltype(u_c)::value;
+      const int t = t0 + U;
+      if (t < ntiles) {                        // the same for every wave of the workgroup
+        issue_tile(std::integral_constant<int, (U + 1 + PD) % NS>{}, t + 1 + PD);
+        if (t < my_tiles) {
+          if constexpr (U % 2 == 0) step(u_c, t, s_even, s_odd);
+          else step(u_c, t, s_odd, s_even);
+        }
+        att_wait_tiles((PD - 1) * my_loads);
+        barrier_keep_loads();
+      }
+    });
   }
   wait_all_vmem();                             // the surplus requests of the last iterations
 

@@ -1,6 +1,9 @@
 // Device-side helpers shared by the gfx950 kernels of the pruning stage.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
+#include <utility>
 #include <stdint.h>
 
 namespace asap {
@@ -161,5 +164,16 @@ template <int N> __device__ __forceinline__ void wait_vmem_but() {
 // Workgroup barrier without the release fence of __syncthreads(): that fence would wait for every
 // outstanding load of the wave, also the ones that are meant to stay in flight across the barrier.
 __device__ __forceinline__ void barrier_keep_loads() { asm volatile("s_barrier" ::: "memory"); }
+
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>): a loop whose counter is a
+// compile-time constant inside the body
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 }  // namespace asap
