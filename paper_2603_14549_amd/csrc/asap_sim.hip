@@ -335,28 +335,28 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
     wait_all_vmem();   // the repeated loads of the last steps
     // The two lane halves hold the two halves of every 128-byte slice, and the wave beside (source
     // rows) or below (destination rows) the other two contraction slices of every step: it adds its
-    // half in a second round.
+    // half in a second turn.
 #pragma unroll
-    for (int round = 0; round < 2; ++round) {
-      if (wn == round) {
+    for (int turn = 0; turn < 2; ++turn) {
+      if (wn == turn) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
           float v = ss_a[i].total();
           v += __shfl_xor(v, 32);
           float* o = &norm2[wm * 64 + i * 32 + n];
-          if (hf == 0) *o = round == 0 ? v : *o + v;
+          if (hf == 0) *o = turn == 0 ? v : *o + v;
         }
       }
-      if (wm == round) {
+      if (wm == turn) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
           float v = ss_b[t].total();
           v += __shfl_xor(v, 32);
           float* o = &normk[wn * (BN / 2) + t * 32 + n];
-          if (hf == 0) *o = round == 0 ? v : *o + v;
+          if (hf == 0) *o = turn == 0 ? v : *o + v;
         }
       }
-      __syncthreads();   // round 1: norms visible
+      __syncthreads();   // after the second turn: norms visible
     }
 
     if (ksplit > 1) {
