@@ -345,6 +345,36 @@ def main():
                                 overlap=False if args.one_stream else "auto", **overrides)
     torch.cuda.synchronize()
 
+    # The measurement legs that need no wall clock come first: K steps with the library's per-kernel HIP
+    # events on, and the copy yardstick.  The GPU has idled while the inputs were generated, and for the
+    # first ten milliseconds or so of load after an idle spell this box runs the same steps up to a tenth
+    # slower than it sustains (the per-step times of a cold run show it); the timed pass below should
+    # measure the sustained state also when it is only a few milliseconds long (--steps 20).
+    launches_per_step = 18
+    ctx.asap_timing_enable(min(8192, launches_per_step * args.steps))
+    for _ in range(args.steps):
+        stage.run_async()
+    torch.cuda.synchronize()
+    timing = ctx.asap_timing_collect()
+    ctx.asap_timing_enable(0)
+
+    # what a plain device-to-device copy of 1 GiB reaches on this box (bytes read + bytes written per
+    # second), as a second yardstick beside the nominal peak; with --copy-calibration the copies also
+    # serve to scale the traffic counters of a rocprofv3 run
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_bw = 5 * 2.0 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3)
+    del src, dst
+
+    # W warm-up steps, then exactly K steps on the wall clock
     for _ in range(args.warmup):
         stage.run_async()
     torch.cuda.synchronize()
@@ -398,16 +428,7 @@ def main():
                         "note": "the same stage call captured once into a HIP graph and replayed"}
         del graph
 
-    # second pass of the same K steps with the library's per-kernel HIP events on
-    launches_per_step = 18
-    ctx.asap_timing_enable(min(8192, launches_per_step * args.steps))
-    for _ in range(args.steps):
-        stage.run_async()
-    torch.cuda.synchronize()
-    timing = ctx.asap_timing_collect()
-    ctx.asap_timing_enable(0)
-
-    # third pass: every step bracketed by its own pair of events on the caller's stream (the stage ends
+    # a further pass: every step bracketed by its own pair of events on the caller's stream (the stage ends
     # with the second stream joined), for the spread; the pairs cost a few microseconds per step, which is
     # why `value` comes from the unbracketed pass above
     n_spread = min(args.steps, 200)
@@ -422,7 +443,7 @@ def main():
                    "p90": float(per_step[int(0.9 * (n_spread - 1))]), "steps": n_spread,
                    "note": "per-step event pairs on the caller's stream"}
 
-    # fourth pass, only when the K/V compaction runs beside k_sim: a few steps on one stream with the
+    # last pass, only when the K/V compaction runs beside k_sim: a few steps on one stream with the
     # per-kernel events on, for the duration of k_sim when nothing shares the memory system with it
     sim_alone = None
     if stage.two_streams and not stage.call_by_call:
@@ -433,22 +454,6 @@ def main():
         torch.cuda.synchronize()
         sim_alone = ctx.asap_timing_collect().get("k_sim")
         ctx.asap_timing_enable(0)
-
-    # what a plain device-to-device copy of 1 GiB reaches on this box (bytes read + bytes written per
-    # second), as a second yardstick beside the nominal peak; with --copy-calibration the copies also
-    # serve to scale the traffic counters of a rocprofv3 run
-    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-    dst = torch.empty_like(src)
-    for _ in range(3):
-        dst.copy_(src)
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0.record()
-    for _ in range(5):
-        dst.copy_(src)
-    c1.record()
-    torch.cuda.synchronize()
-    copy_bw = 5 * 2.0 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3)
-    del src, dst
 
     mean_text = float(np.mean(inp["text_len"]))
     alg = algorithmic_bytes(cfg, mean_text, cfg.L_kv)
