@@ -90,6 +90,10 @@ def algorithmic_bytes(cfg, mean_text: float, n_layers: int) -> dict:
     per_kernel["kv_fixed_rows"] = 2 * 2 * n_layers * Hkv * B * (P + T) * d * ek
     per_kernel["k_score_select_kv"] = per_kernel["k_score_select"] + per_kernel["kv_fixed_rows"]
     per_kernel["k_compact_fixed"] = per_kernel["kv_fixed_rows"]       # deep caches: those rows start at once
+    # f32 keys: the first text-row sweep leaves its logits and k_colsum_rows reads them (the caller of
+    # this function adds them to k_attn_stats when it sees that kernel); bytes of work, not compulsory ones
+    per_kernel["stored_logits"] = 4 * B * H * T * V
+    per_kernel["k_colsum_rows"] = per_kernel["stored_logits"] + 4 * B * H * V
     stage = (q_vis + k_vis + q_txt + 12 * B * V) + 12 * B * V + (vis_h + 8 * B * (V - k)) \
         + (vis_h + B * (P + T) * D * eh + out_rows * D * eh) + per_kernel["k_compact"]
     return {"per_kernel": per_kernel, "stage": stage, "sim_flops": 2.0 * B * (V - k) * k * D}
@@ -471,6 +475,8 @@ def main():
         alg["sim_flops"] = 2.0 * cfg.B * cfg.k * cfg.k * cfg.D
     if "k_score_select_kv" in timing or "k_compact_fixed" in timing:     # prefix and text rows of K/V went earlier
         alg["per_kernel"]["k_compact"] -= alg["per_kernel"]["kv_fixed_rows"]
+    if "k_colsum_rows" in timing:
+        alg["per_kernel"]["k_attn_stats"] += alg["per_kernel"]["stored_logits"]
     kernels = {}
     for name, (ms, n) in timing.items():
         avg_us = 1e3 * ms / n

@@ -100,7 +100,9 @@ asap_status asap_check_params(const asap_params* p, char* msg, size_t msg_len);
 
 /* Bytes of device scratch any of the four calls may need for these parameters (one size
  * serves all four).  0 if the parameters are invalid.  The workspace must be 256-byte
- * aligned; its contents are undefined before and after each call. */
+ * aligned; its contents are undefined before and after each call.  With f32 queries and keys it
+ * includes 4 B H Tmax V bytes for the text rows' logits (Eq. 5), which are then formed once instead
+ * of twice, unless that alone would exceed 1 GiB. */
 size_t asap_workspace_bytes(const asap_params* p);
 
 /*
@@ -162,8 +164,10 @@ asap_status asap_score_from_hidden(asap_ctx* ctx, const asap_params* p,
 /*
  * asap_score_static -- asap_score for callers that cannot allocate device memory and have no
  * workspace to hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
- * hipMalloc.  Arguments, results and checks are those of asap_score without the workspace; the
- * scratch is an array of ASAP_STATIC_SCRATCH_BYTES bytes that is part of the library's code object
+ * hipMalloc.  Arguments, results and checks are those of asap_score without the workspace (with f32
+ * keys asap_score keeps the logits of the text rows in its workspace and this call does so only
+ * where the array can hold them; otherwise it forms them a second time, and the scores of the two
+ * calls then differ by rounding, within the tolerance of either); the scratch is an array of ASAP_STATIC_SCRATCH_BYTES bytes that is part of the library's code object
  * (every GPU the library runs on holds its own copy until the process ends; asap_create looks up
  * its address on the context's device).  The call allocates and frees nothing.
  * ASAP_EWORKSPACE if the parameters need more scratch than the array holds (the message names both

@@ -138,8 +138,7 @@ asap_status check_span(asap_ctx* ctx, const char* name, int64_t rows, int64_t ro
   return ASAP_OK;
 }
 
-asap_status check_workspace(asap_ctx* ctx, const asap_params* p, const void* ws, size_t bytes) {
-  size_t need = asap_workspace_bytes(p);
+asap_status check_workspace(asap_ctx* ctx, size_t need, const void* ws, size_t bytes) {
   if (need == 0) return ASAP_OK;
   if (!ws) return fail(ctx, ASAP_EINVAL, "workspace is NULL");
   if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(ctx, ASAP_EINVAL, "workspace is not 256-byte aligned");
@@ -276,7 +275,8 @@ size_t asap_workspace_bytes(const asap_params* p) {
 static asap_status score_checks(asap_ctx* ctx, const asap_params* p, const void* q_vis,
                                 const int64_t q_vis_stride[3], const void* q_txt, const int64_t q_txt_stride[3],
                                 const void* k_vis, const int64_t k_vis_stride[3], const int32_t* text_len,
-                                float* s_raw, float* s_hat, float* score, void* workspace, size_t workspace_bytes) {
+                                float* s_raw, float* s_hat, float* score, void* workspace, size_t workspace_bytes,
+                                size_t workspace_need) {
   asap_status st = common_checks(ctx, p);
   if (st != ASAP_OK) return st;
   if (!q_vis || !q_txt || !k_vis || !text_len || !s_raw || !s_hat || !score)
@@ -292,7 +292,7 @@ static asap_status score_checks(asap_ctx* ctx, const asap_params* p, const void*
   if ((st = check_span(ctx, "q_vis", p->V, q_vis_stride[2], esz)) != ASAP_OK) return st;
   if ((st = check_span(ctx, "q_txt", p->Tmax, q_txt_stride[2], esz)) != ASAP_OK) return st;
   if ((st = check_span(ctx, "k_vis", p->V, k_vis_stride[2], esz)) != ASAP_OK) return st;
-  return check_workspace(ctx, p, workspace, workspace_bytes);
+  return check_workspace(ctx, workspace_need, workspace, workspace_bytes);
 }
 
 asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, const int64_t q_vis_stride[3],
@@ -301,15 +301,15 @@ asap_status asap_score(asap_ctx* ctx, const asap_params* p, const void* q_vis, c
                        float* s_raw, float* s_hat, float* score, void* workspace, size_t workspace_bytes,
                        void* stream) {
   asap_status st = score_checks(ctx, p, q_vis, q_vis_stride, q_txt, q_txt_stride, k_vis, k_vis_stride, text_len,
-                                s_raw, s_hat, score, workspace, workspace_bytes);
+                                s_raw, s_hat, score, workspace, workspace_bytes, asap_workspace_bytes(p));
   if (st != ASAP_OK) return st;
   Strides3 qv{q_vis_stride[0], q_vis_stride[1], q_vis_stride[2]};
   Strides3 qt{q_txt_stride[0], q_txt_stride[1], q_txt_stride[2]};
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
   return hip_result(ctx,
                     launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                                 nullptr, nullptr, nullptr, nullptr, static_cast<char*>(workspace), static_cast<hipStream_t>(stream),
-                                 ctx->timer),
+                                 nullptr, nullptr, nullptr, nullptr, static_cast<char*>(workspace), ~size_t(0),
+                                 static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_score launch");
 }
 
@@ -354,7 +354,8 @@ asap_status asap_score_from_hidden(asap_ctx* ctx, const asap_params* p, const vo
   Strides3 kv{k_vis_stride[0], k_vis_stride[1], k_vis_stride[2]};
   return hip_result(ctx,
                     launch_score(*p, nullptr, none, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                                 nullptr, nullptr, &fe, nullptr, ws, static_cast<hipStream_t>(stream), ctx->timer),
+                                 nullptr, nullptr, &fe, nullptr, ws, ~size_t(0), static_cast<hipStream_t>(stream),
+                                 ctx->timer),
                     "asap_score_from_hidden launch");
 }
 
@@ -367,7 +368,7 @@ asap_status asap_score_static(asap_ctx* ctx, const asap_params* p, const void* q
   char msg[128];
   asap_status st = check_params(p, msg, sizeof(msg));
   if (st != ASAP_OK) return fail(ctx, st, "invalid parameters: %s", msg);
-  const size_t need = score_workspace(*p).total;
+  const size_t need = score_workspace(*p, ASAP_STATIC_SCRATCH_BYTES).total;
   if (need > (size_t)ASAP_STATIC_SCRATCH_BYTES)
     return fail(ctx, ASAP_EWORKSPACE,
                 "asap_score_static: these parameters need %zu bytes of scratch, the built-in array holds %zu; "
@@ -377,7 +378,7 @@ asap_status asap_score_static(asap_ctx* ctx, const asap_params* p, const void* q
     return fail(ctx, ASAP_EHIP, "asap_score_static: address of the built-in scratch array: %s",
                 hipGetErrorString(ctx->static_scratch_err));
   st = score_checks(ctx, p, q_vis, q_vis_stride, q_txt, q_txt_stride, k_vis, k_vis_stride, text_len, s_raw, s_hat,
-                    score, ctx->static_scratch, ASAP_STATIC_SCRATCH_BYTES);
+                    score, ctx->static_scratch, ASAP_STATIC_SCRATCH_BYTES, need);
   if (st != ASAP_OK) return st;
   Strides3 qv{q_vis_stride[0], q_vis_stride[1], q_vis_stride[2]};
   Strides3 qt{q_txt_stride[0], q_txt_stride[1], q_txt_stride[2]};
@@ -385,8 +386,7 @@ asap_status asap_score_static(asap_ctx* ctx, const asap_params* p, const void* q
   return hip_result(ctx,
                     launch_score(*p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
                                  nullptr, nullptr, nullptr, nullptr, static_cast<char*>(ctx->static_scratch),
-                                 static_cast<hipStream_t>(stream),
-                                 ctx->timer),
+                                 ASAP_STATIC_SCRATCH_BYTES, static_cast<hipStream_t>(stream), ctx->timer),
                     "asap_score_static launch");
 }
 
@@ -440,7 +440,7 @@ static asap_status merge_checks(asap_ctx* ctx, const asap_params* p, const void*
     const char* b1 = b0 + (int64_t)p->B * (p->P + p->k + p->Tmax) * p->D * esz;
     if (a0 < b1 && b0 < a1) return fail(ctx, ASAP_EINVAL, "asap_merge: out_hidden overlaps hidden");
   }
-  return check_workspace(ctx, p, workspace, workspace_bytes);
+  return check_workspace(ctx, asap_workspace_bytes(p), workspace, workspace_bytes);
 }
 
 asap_status asap_merge(asap_ctx* ctx, const asap_params* p, const void* hidden, const int64_t hidden_stride[2],
@@ -554,7 +554,7 @@ asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io*
   // every check of the single calls first: a failed check launches nothing
   asap_status st = score_checks(ctx, p, io->q_vis, io->q_vis_stride, io->q_txt, io->q_txt_stride, io->k_vis,
                                 io->k_vis_stride, io->text_len, io->s_raw, io->s_hat, io->score, io->workspace,
-                                io->workspace_bytes);
+                                io->workspace_bytes, asap_workspace_bytes(p));
   if (st == ASAP_OK) st = select_checks(ctx, p, io->score, io->kept_idx, io->pruned_idx);
   if (st == ASAP_OK)
     st = merge_checks(ctx, p, io->hidden, io->hidden_stride, io->s_raw, io->s_hat, io->text_len, io->kept_idx,
@@ -611,7 +611,7 @@ asap_status asap_stage(asap_ctx* ctx, const asap_params* p, const asap_stage_io*
   if (e == hipSuccess)
     e = launch_score(*p, io->q_vis, qv, io->q_txt, qt, io->k_vis, kv, io->text_len, io->lse_extra, io->s_raw,
                      io->s_hat, io->score, io->kept_idx, io->pruned_idx, nullptr,
-                     fixed_with_selection ? &fixed : nullptr, ws, main, ctx->timer);
+                     fixed_with_selection ? &fixed : nullptr, ws, ~size_t(0), main, ctx->timer);
   if (e == hipSuccess && early) {
     e = hipEventRecord(ctx->ev_fork, main);
     if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);

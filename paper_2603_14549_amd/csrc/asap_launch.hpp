@@ -19,6 +19,7 @@ struct ScoreWorkspace {
   int ride;          // 1: those rows ride in the mass sweep, which leaves their logits (no text-row sweeps)
   int row_pairs;     // pairs of 32-row blocks of text queries, each with sweep workgroups of its own
   int head_splits;   // kv-head groups of the mass sweep with workgroups of their own (small batches)
+  int store_logits;  // 1: the first text-row sweep leaves its logits and the column sums read those
   size_t off_qpart;  // double [B,H,q_chunks,d]  partial sums of visual queries
   size_t off_qbar;   // double [B,Hkv,d]         summed visual queries per kv head
   size_t off_qsplit; // bf16   [B,Hkv,4,d]       the same, split into four bf16 pieces per component
@@ -27,10 +28,13 @@ struct ScoreWorkspace {
   size_t off_pstat;  // float  [B,H,splits,2,NR] per-split (max, sum) of every text row, NR = 64 row_pairs
   size_t off_upart;  // float  [B,H,row_pairs,V] column sums of normalised weights per head and row pair
   size_t off_spart;  // double [head_splits,B,V] partial masses (head_splits > 1)
-  size_t off_zlog;   // float  [B,H,t_eff,V]     raw logits of the riding text rows (ride)
+  size_t off_zlog;   // float  [B,H,t_eff,V]     raw logits of the ranking rows (ride, store_logits)
   size_t total;
 };
-ScoreWorkspace score_workspace(const asap_params& p);
+// budget: the bytes the caller can give; optional parts of the workspace (the stored logits) are
+// planned only if the whole then fits.
+constexpr size_t STORED_LOGITS_MAX_BYTES = size_t(1) << 30;
+ScoreWorkspace score_workspace(const asap_params& p, size_t budget = ~size_t(0));
 
 struct Strides3 { int64_t b, h, r; };
 
@@ -102,10 +106,12 @@ inline bool score_fuses_selection(const asap_params& p) { return p.B >= 12; }
 // call), writing kept [B,k] and pruned [B,V-k] exactly as launch_select would.  fixed != nullptr (only
 // with kept and score_fuses_selection(p)): further workgroups of that launch copy the K/V rows of the
 // prefix and of the valid text, which depend on no result, while the memory system is otherwise idle.
+// ws_budget: the budget score_workspace planned ws with (~0 for workspaces sized by asap_workspace_bytes).
 hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
                         const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
                         float* s_raw, float* s_hat, float* score, int32_t* kept, int32_t* pruned,
-                        const FrontArgs* fe, const KvFixedRows* fixed, char* ws, hipStream_t st, Timer* tm);
+                        const FrontArgs* fe, const KvFixedRows* fixed, char* ws, size_t ws_budget,
+                        hipStream_t st, Timer* tm);
 
 hipError_t launch_select(const asap_params& p, const float* score, int32_t* kept, int32_t* pruned,
                          hipStream_t st, Timer* tm);

@@ -423,7 +423,7 @@ struct AttnArgs {
   const float* lse_extra;               // [B,H,Tmax] or null
   float* pstat;                         // [B,H,S,2,NR]   partial (max, sum) per text row, NR = 64 RP
   float* upart;                         // [B,H,RP,V]     column sums per head and row pair
-  const float* zlog;                    // [B,H,T_eff,V]  stored logits (k_rowstats_logits / k_colsum_logits)
+  float* zlog;                          // [B,H,T_eff,V]  stored logits (k_rowstats_logits / k_colsum_logits / k_colsum_rows)
   int H, Hkv, V, Tmax, S, RP, tiles_per_split;
   int T_eff, last_only;                 // rows that rank: all valid text rows, or the last one alone
   float c2;                             // log2(e) / sqrt(d): accumulator units -> log2 units
@@ -466,6 +466,7 @@ template <int NRB, int NG> struct QueryOps<float, NRB, NG> {
     const char* qbase = reinterpret_cast<const char*>(static_cast<const float*>(a.qt) + b * a.sq.b + h * a.sq.h +
                                                       (int64_t)row0 * a.sq.r);
     constexpr int PPR = ROWB / 16;         // groups of 8 elements per row
+#pragma unroll
     for (int i = threadIdx.x; i < NRB * 32 * PPR; i += 256) {
       int row = i / PPR, pc = i % PPR;
       Split3 s;
@@ -524,9 +525,12 @@ template <int NG> struct KeyTile<float, NG> {
   }
 };
 
-__device__ __forceinline__ float discount(const AttnArgs& a, int b, int j, double lo, double inv) {
+__device__ __forceinline__ float discount_of(const AttnArgs& a, double s, double lo, double inv) {
   if (!a.mask_on) return 1.0f;
-  return (float)fmax(a.lambda_max * ((a.s64[(int64_t)b * a.V + j] - lo) * inv), a.eps);
+  return (float)fmax(a.lambda_max * ((s - lo) * inv), a.eps);
+}
+__device__ __forceinline__ float discount(const AttnArgs& a, int b, int j, double lo, double inv) {
+  return discount_of(a, a.mask_on ? a.s64[(int64_t)b * a.V + j] : 0.0, lo, inv);
 }
 
 // merge of two (max, sum) pairs kept in accumulator units with scale c2
@@ -573,7 +577,9 @@ __device__ __forceinline__ SweepId sweep_id(const AttnArgs& a) {
 
 // Keys are the tile rows here: lane (n, hf) owns text row row0 + rb*32 + n and finds, in accumulator
 // register v, its logit against key 8*(v/4) + 4*hf + v%4 of the tile.
-template <typename T, int NRB, int NG>
+// STORE: the logits of the ranking rows are also left in zlog (row t of an image's ranking rows,
+// accumulator units), so that the column sums need no second sweep over the keys.
+template <typename T, int NRB, int NG, bool STORE>
 __device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, const SweepId& w, int row0, int nrows) {
   constexpr bool F32 = sizeof(T) == 4;
   constexpr int GB = group_bytes<T>::value;
@@ -584,24 +590,52 @@ __device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, co
   const int n = lane & 31, hf = lane >> 5;
   const int sp = w.sp, h = w.h, b = w.b;
   const int g = (h * a.Hkv) / a.H;
-  Q q;
-  q.init(a, b, h, lane, lds, row0, nrows);
-  const double mlo = f64_unkey(a.mmkey[2 * b]), mhi = f64_unkey(a.mmkey[2 * b + 1]);
-  const double minv = 1.0 / (mhi - mlo + a.eps);
   const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.kv) + b * a.sk.b + g * a.sk.h) +
                       hf * GB;
   const int64_t krow_bytes = a.sk.r * (int64_t)sizeof(T);
   const int ntiles = (a.V + 31) >> 5;
   const int t_end = min(ntiles, (sp + 1) * a.tiles_per_split);
   const float c2 = a.c2;
+  // the first key tile and its masses are asked for before the queries, so that the waits overlap
+  KeyTile<T, NG> kb;
+  int tile = sp * a.tiles_per_split + wave;
+  if (tile < t_end) kb.load(kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
+  const double* s64 = a.s64 + (int64_t)b * a.V;
+  double sj = (a.mask_on && tile < t_end) ? s64[min(tile * 32 + n, a.V - 1)] : 0.0;
+  Q q;
+  q.init(a, b, h, lane, lds, row0, nrows);
+  const double mlo = f64_unkey(a.mmkey[2 * b]), mhi = f64_unkey(a.mmkey[2 * b + 1]);
+  const double minv = 1.0 / (mhi - mlo + a.eps);
 
   float m_run[NRB], s_run[NRB];
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) { m_run[rb] = ATT_NEG; s_run[rb] = 0.0f; }
+  // where this lane's text rows start in zlog, at the lane's first key of a tile
+  float* zrow[NRB];
+  const bool zvec = (a.V & 3) == 0;            // rows of zlog start on 16-byte boundaries
+  if constexpr (STORE) {
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+      zrow[rb] = rb * 32 + n < nrows
+                     ? a.zlog + (((int64_t)b * a.H + h) * a.T_eff + w.rp * ATT_ROWS + rb * 32 + n) * a.V + 4 * hf
+                     : nullptr;
+  }
+  auto store_logits = [&](const f32x16_t& acc, int rb, int tile, bool ragged) {
+    if (zrow[rb] == nullptr) return;
+    float* z = zrow[rb] + tile * 32;
+    if (zvec && !ragged) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(z + 8 * q) = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int o = 8 * (v >> 2) + (v & 3);
+        if (tile * 32 + 4 * hf + o < a.V) z[o] = acc[v];
+      }
+    }
+  };
 
-  KeyTile<T, NG> kb;
-  int tile = sp * a.tiles_per_split + wave;
-  if (tile < t_end) kb.load(kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
   for (; tile < t_end; tile += 4) {
     const int j = tile * 32 + n;
     const int tnext = tile + 4;
@@ -610,8 +644,10 @@ __device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, co
     if constexpr (!F32) {
       if (tnext < t_end) kn.load(knext);
     }
-    // discount of key n of the tile, then handed to the lanes in accumulator order
-    const float lj = j < a.V ? discount(a, b, j, mlo, minv) : 0.0f;
+    // discount of key n of the tile (its mass was asked for a tile ago), then handed to the lanes in
+    // accumulator order
+    const float lj = j < a.V ? discount_of(a, sj, mlo, minv) : 0.0f;
+    if (a.mask_on && tnext < t_end) sj = s64[min(tnext * 32 + n, a.V - 1)];
     float lam[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) lam[v] = __shfl(lj, 8 * (v >> 2) + 4 * hf + (v & 3));
@@ -624,6 +660,7 @@ __device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, co
         for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
         for (int c = 0; c < NG; ++c) mma32<bf16_t>(acc, kb.op[c], q.get(rb, c));
+        if constexpr (STORE) store_logits(acc, rb, tile, ragged);
         stats_update(acc, lam, ragged, tile, hf, a.V, c2, m_run[rb], s_run[rb]);
       }
       if (tnext < t_end) {
@@ -647,7 +684,10 @@ __device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, co
         for (int rb = 0; rb < NRB; ++rb) mma_split(acc[rb], ks, q.get3(rb, c));
       }
 #pragma unroll
-      for (int rb = 0; rb < NRB; ++rb) stats_update(acc[rb], lam, ragged, tile, hf, a.V, c2, m_run[rb], s_run[rb]);
+      for (int rb = 0; rb < NRB; ++rb) {
+        if constexpr (STORE) store_logits(acc[rb], rb, tile, ragged);
+        stats_update(acc[rb], lam, ragged, tile, hf, a.V, c2, m_run[rb], s_run[rb]);
+      }
     }
   }
   // the two halves of a wave share the row maximum: their sums just add; then the 4 waves
@@ -670,7 +710,7 @@ __device__ __forceinline__ void attn_stats_body(const AttnArgs& a, char* lds, co
   }
 }
 
-template <typename T, int NG>
+template <typename T, int NG, bool STORE>
 __global__ __launch_bounds__(256, 2) void k_attn_stats(AttnArgs a) {
   extern __shared__ __align__(16) char lds[];
   const SweepId w = sweep_id(a);
@@ -679,8 +719,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_stats(AttnArgs a) {
   row0 += w.rp * ATT_ROWS;
   nrows = min(nrows - w.rp * ATT_ROWS, ATT_ROWS);
   if (nrows <= 0) return;                      // the image's text ends before this pair of row blocks
-  if (nrows <= 32) attn_stats_body<T, 1, NG>(a, lds, w, row0, nrows);
-  else attn_stats_body<T, 2, NG>(a, lds, w, row0, nrows);
+  if (nrows <= 32) attn_stats_body<T, 1, NG, STORE>(a, lds, w, row0, nrows);
+  else attn_stats_body<T, 2, NG, STORE>(a, lds, w, row0, nrows);
 }
 
 // Row statistics merged over the splits, with the rest of the row (lse_extra) folded in: per text
@@ -726,6 +766,15 @@ __device__ __forceinline__ void attn_colsum_body(const AttnArgs& a, char* lds, c
   const int sp = w.sp, h = w.h, b = w.b;
   const int g = (h * a.Hkv) / a.H;
   const float c2 = a.c2;
+  const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.kv) + b * a.sk.b + g * a.sk.h) +
+                      hf * GB;
+  const int64_t krow_bytes = a.sk.r * (int64_t)sizeof(T);
+  const int ntiles = (a.V + 31) >> 5;
+  const int t_end = min(ntiles, (sp + 1) * a.tiles_per_split);
+  // the first key tile is asked for before the statistics and the queries, so that the waits overlap
+  KeyTile<T, NG> kb;
+  int tile = sp * a.tiles_per_split + wave;
+  if (tile < t_end) kb.load(kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
   final_row_stats(a, b, h, ATT_ROWS * a.RP, w.rp * ATT_ROWS, NRB * 32, row0, nrows, fin_o, fin_i);
   Q q;
   q.init(a, b, h, lane, lds, row0, nrows);
@@ -744,15 +793,7 @@ __device__ __forceinline__ void attn_colsum_body(const AttnArgs& a, char* lds, c
         inv[rb][v] = fin_i[row];
       }
   }
-  const char* kbase = reinterpret_cast<const char*>(static_cast<const T*>(a.kv) + b * a.sk.b + g * a.sk.h) +
-                      hf * GB;
-  const int64_t krow_bytes = a.sk.r * (int64_t)sizeof(T);
-  const int ntiles = (a.V + 31) >> 5;
-  const int t_end = min(ntiles, (sp + 1) * a.tiles_per_split);
   float* out = a.upart + (((int64_t)b * a.H + h) * a.RP + w.rp) * a.V;
-  KeyTile<T, NG> kb;
-  int tile = sp * a.tiles_per_split + wave;
-  if (tile < t_end) kb.load(kbase + (int64_t)min(tile * 32 + n, a.V - 1) * krow_bytes);
   for (; tile < t_end; tile += 4) {
     const int j = tile * 32 + n;
     const int tnext = tile + 4;
@@ -876,6 +917,70 @@ __global__ __launch_bounds__(256) void k_colsum_logits(AttnArgs a) {
   float u = 0.0f;
   for (int t = 0; t < nrows; ++t) u = fmaf(fast_exp2(fmaf(z[(int64_t)t * a.V], a.c2, fin_o[t])), fin_i[t], u);
   a.upart[((int64_t)b * a.H + h) * a.V + j] = u;
+}
+
+// Column sums from the logits k_attn_stats<.., true> left: grid (ceil(V / 256), H, B), 256 threads.
+// A lane takes four neighbouring keys, the four waves take the ranking rows t = wave, wave + 4, ...
+// (256 at a time: their statistics sit in LDS), and the waves' partial sums are added in wave order.
+// upart then has one row per head.
+__global__ __launch_bounds__(256) void k_colsum_rows(AttnArgs a) {
+  __shared__ float fin_o[256], fin_i[256];
+  __shared__ float4 part[4][64];
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j0 = blockIdx.x * 256 + lane * 4;
+  int row0, nrows;
+  ranking_rows(a, b, row0, nrows);
+  const int NR = ATT_ROWS * a.RP;
+  const bool vec = (a.V & 3) == 0;
+  const float* z = a.zlog + (((int64_t)b * a.H + h) * a.T_eff) * a.V + j0;
+  const float c2 = a.c2;
+  float4 u = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  for (int first = 0; first < nrows; first += 256) {
+    if (first) __syncthreads();
+    final_row_stats(a, b, h, NR, first, min(256, NR - first), row0 + first, nrows - first, fin_o, fin_i);
+    __syncthreads();
+    const int nl = min(256, nrows - first);
+    if (j0 < a.V) {
+#pragma unroll 4
+      for (int t = wave; t < nl; t += 4) {
+        const float* zr = z + (int64_t)(first + t) * a.V;
+        float4 x;
+        if (vec) {
+          x = *reinterpret_cast<const float4*>(zr);
+        } else {
+          x.x = zr[0];
+          x.y = j0 + 1 < a.V ? zr[1] : 0.0f;
+          x.z = j0 + 2 < a.V ? zr[2] : 0.0f;
+          x.w = j0 + 3 < a.V ? zr[3] : 0.0f;
+        }
+        const float o = fin_o[t], iv = fin_i[t];
+        u.x = fmaf(fast_exp2(fmaf(x.x, c2, o)), iv, u.x);
+        u.y = fmaf(fast_exp2(fmaf(x.y, c2, o)), iv, u.y);
+        u.z = fmaf(fast_exp2(fmaf(x.z, c2, o)), iv, u.z);
+        u.w = fmaf(fast_exp2(fmaf(x.w, c2, o)), iv, u.w);
+      }
+    }
+  }
+  part[wave][lane] = u;
+  __syncthreads();
+  if (wave == 0 && j0 < a.V) {
+    float4 r = part[0][lane];
+#pragma unroll
+    for (int wv = 1; wv < 4; ++wv) {
+      const float4 q = part[wv][lane];
+      r.x += q.x; r.y += q.y; r.z += q.z; r.w += q.w;
+    }
+    float* out = a.upart + ((int64_t)b * a.H + h) * a.V + j0;
+    if (vec) {
+      *reinterpret_cast<float4*>(out) = r;
+    } else {
+      out[0] = r.x;
+      if (j0 + 1 < a.V) out[1] = r.y;
+      if (j0 + 2 < a.V) out[2] = r.z;
+      if (j0 + 3 < a.V) out[3] = r.w;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1069,7 +1174,7 @@ static int attn_splits(const asap_params& p) {
   return best;
 }
 
-ScoreWorkspace score_workspace(const asap_params& p) {
+ScoreWorkspace score_workspace(const asap_params& p, size_t budget) {
   ScoreWorkspace w;
   // rows per k_qsum block: whole image span unless that leaves the chip short of blocks
   int chunks = (512 + p.B * p.H - 1) / (p.B * p.H);
@@ -1094,6 +1199,12 @@ ScoreWorkspace score_workspace(const asap_params& p) {
       if (p.Hkv % hs == 0 && hs <= want) { w.head_splits = hs; break; }
   }
   w.row_pairs = w.ride ? 1 : (w.t_eff + 63) / 64;
+  // f32 keys: the first text-row sweep leaves its logits (4 bytes per ranking row and key, never more
+  // than the key sweeps they replace at 512 bytes per key and 64 rows) and the column sums read them
+  // back instead of sweeping the keys and forming the products again, as long as the workspace stays
+  // moderate.
+  const size_t zlog_bytes = sizeof(float) * (size_t)p.B * p.H * w.t_eff * p.V;
+  w.store_logits = (!w.ride && p.qk_dtype != ASAP_BF16 && zlog_bytes <= STORED_LOGITS_MAX_BYTES) ? 1 : 0;
   const int NR = w.ride ? 32 : 64 * w.row_pairs;
   const int splits = w.ride ? 1 : w.attn_splits;
   size_t off = 0;
@@ -1107,15 +1218,31 @@ ScoreWorkspace score_workspace(const asap_params& p) {
   w.off_spart = off;
   if (w.head_splits > 1) off = align256(off + sizeof(double) * (size_t)w.head_splits * p.B * p.V);
   w.off_zlog = off;
-  if (w.ride) off = align256(off + sizeof(float) * (size_t)p.B * p.H * w.t_eff * p.V);
+  if (w.store_logits && align256(off + zlog_bytes) > budget) w.store_logits = 0;
+  if (w.ride || w.store_logits) off = align256(off + zlog_bytes);
   w.total = off;
   return w;
 }
 
 template <typename T, int NG>
-static hipError_t launch_attn(const asap_params& p, const AttnArgs& a, hipStream_t st, Timer* tm) {
+static hipError_t launch_attn(const asap_params& p, const AttnArgs& a, bool store_logits, hipStream_t st,
+                              Timer* tm) {
   const size_t lds = query_lds_bytes<T, NG>() + sizeof(float) * 8 * ATT_ROWS;
-  auto k1 = k_attn_stats<T, NG>;
+  const dim3 grid(p.H * a.RP * a.S, p.B);
+  if constexpr (sizeof(T) == 4) {
+    if (store_logits) {
+      auto ks = k_attn_stats<T, NG, true>;
+      if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ks),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+      }
+      ASAP_LAUNCH(tm, "k_attn_stats", ks, grid, dim3(256), lds, st, a);
+      ASAP_LAUNCH(tm, "k_colsum_rows", k_colsum_rows, dim3((p.V + 255) / 256, p.H, p.B), dim3(256), 0, st, a);
+      return hipGetLastError();
+    }
+  }
+  auto k1 = k_attn_stats<T, NG, false>;
   auto k2 = k_attn_colsum<T, NG>;
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
@@ -1125,7 +1252,6 @@ static hipError_t launch_attn(const asap_params& p, const AttnArgs& a, hipStream
                               (int)lds);
     if (e != hipSuccess) return e;
   }
-  const dim3 grid(p.H * a.RP * a.S, p.B);
   ASAP_LAUNCH(tm, "k_attn_stats", k1, grid, dim3(256), lds, st, a);
   ASAP_LAUNCH(tm, "k_attn_colsum", k2, grid, dim3(256), lds, st, a);
   return hipGetLastError();
@@ -1156,8 +1282,8 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
                               Strides3 qt, const void* k_vis, Strides3 kv, const int32_t* text_len,
                               const float* lse_extra, float* s_raw, float* s_hat, float* score, int32_t* kept,
                               int32_t* pruned, const FrontArgs* fe, const KvFixedRows* fixed, char* ws,
-                              hipStream_t st, Timer* tm) {
-  const ScoreWorkspace w = score_workspace(p);
+                              size_t ws_budget, hipStream_t st, Timer* tm) {
+  const ScoreWorkspace w = score_workspace(p, ws_budget);
   double* qpart = reinterpret_cast<double*>(ws + w.off_qpart);
   double* qbar = reinterpret_cast<double*>(ws + w.off_qbar);
   uint16_t* qsplit = reinterpret_cast<uint16_t*>(ws + w.off_qsplit);
@@ -1211,14 +1337,15 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
     ASAP_LAUNCH(tm, "k_colsum_logits", k_colsum_logits, dim3((p.V + 255) / 256, p.H, p.B), dim3(256), 0, st, a);
     e = hipGetLastError();
   } else if (ng == 8) {
-    e = launch_attn<T, 8>(p, a, st, tm);
+    e = launch_attn<T, 8>(p, a, w.store_logits != 0, st, tm);
   } else {
-    e = launch_attn<T, 4>(p, a, st, tm);
+    e = launch_attn<T, 4>(p, a, w.store_logits != 0, st, tm);
   }
   if (e != hipSuccess) return e;
+  const int u_rows = p.H * (w.store_logits ? 1 : w.row_pairs);     // rows of upart per image
   if (kept != nullptr && !score_fuses_selection(p)) {
     ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
-                p.H, p.H * w.row_pairs, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
+                p.H, u_rows, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
     hipError_t e2 = hipGetLastError();
     return e2 != hipSuccess ? e2 : launch_select(p, score, kept, pruned, st, tm);
   }
@@ -1232,15 +1359,15 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
     }
     if (fixed)
       ASAP_LAUNCH(tm, "k_score_select_kv", k_score_select_kv, dim3(p.B + fixed->n_bufs * p.B * p.Hkv),
-                  dim3(SEL_THREADS), lds, st, upart, s64, mmkey, text_len, p.H, p.H * w.row_pairs, p.V, p.k, p.Tmax,
+                  dim3(SEL_THREADS), lds, st, upart, s64, mmkey, text_len, p.H, u_rows, p.V, p.k, p.Tmax,
                   last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score, kept, pruned, p.B, *fixed);
     else
       ASAP_LAUNCH(tm, "k_score_select", k_score_select, dim3(p.B), dim3(SEL_THREADS), lds, st, upart, s64, mmkey,
-                  text_len, p.H, p.H * w.row_pairs, p.V, p.k, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps,
+                  text_len, p.H, u_rows, p.V, p.k, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps,
                   mask_on, s_hat, score, kept, pruned);
   } else {
     ASAP_LAUNCH(tm, "k_score", k_score, dim3((p.V + 63) / 64, p.B), dim3(256), 0, st, upart, s64, mmkey, text_len,
-                p.H, p.H * w.row_pairs, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
+                p.H, u_rows, p.V, p.Tmax, last_only, (double)p.lambda_max, (double)p.eps, mask_on, s_hat, score);
   }
   return hipGetLastError();
 }
@@ -1248,13 +1375,14 @@ static hipError_t score_typed(const asap_params& p, const void* q_vis, Strides3 
 hipError_t launch_score(const asap_params& p, const void* q_vis, Strides3 qv, const void* q_txt, Strides3 qt,
                         const void* k_vis, Strides3 kv, const int32_t* text_len, const float* lse_extra,
                         float* s_raw, float* s_hat, float* score, int32_t* kept, int32_t* pruned,
-                        const FrontArgs* fe, const KvFixedRows* fixed, char* ws, hipStream_t st, Timer* tm) {
+                        const FrontArgs* fe, const KvFixedRows* fixed, char* ws, size_t ws_budget, hipStream_t st,
+                        Timer* tm) {
   if (fixed && (kept == nullptr || !score_fuses_selection(p))) return hipErrorInvalidValue;
   if (p.qk_dtype == ASAP_BF16)
     return score_typed<bf16_t>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score,
-                               kept, pruned, fe, fixed, ws, st, tm);
+                               kept, pruned, fe, fixed, ws, ws_budget, st, tm);
   return score_typed<float>(p, q_vis, qv, q_txt, qt, k_vis, kv, text_len, lse_extra, s_raw, s_hat, score, kept,
-                            pruned, fe, fixed, ws, st, tm);
+                            pruned, fe, fixed, ws, ws_budget, st, tm);
 }
 
 }  // namespace asap

@@ -1,10 +1,12 @@
 """asap_score_static, the scoring call that allocates nothing and takes no workspace (its scratch is
 an array inside the library), against asap_score on the same inputs: two calls in a row on one
 context, the second on a smaller batch, so that whatever the first call left in the shared array
-is there when the second runs.  Both calls launch the same kernels, so the three outputs must agree
-bit for bit (which is inside every tolerance of the parity rules); the second call's result is also
-compared with the fp64 oracle.  Parameters whose scratch exceeds the array are refused before
-anything is launched."""
+is there when the second runs.  Both calls launch the same kernels there, so the three outputs must
+agree bit for bit (which is inside every tolerance of the parity rules); the second call's result is
+also compared with the fp64 oracle.  With f32 keys asap_score stores the text rows' logits in its
+workspace when that stays moderate; where the built-in array cannot hold them the static call sweeps
+the keys a second time instead, and the two agree within the parity rules, not bit for bit.
+Parameters whose scratch exceeds the array are refused before anything is launched."""
 import numpy as np
 import pytest
 import torch
@@ -43,6 +45,22 @@ def _score_both_ways(ctx, cfg):
     return inp, out
 
 
+def _against_the_oracle(cfg, inp, outs):
+    """The rules of the parity tests: salience within what the observed mass error allows through Eq. 3,
+    scores 2e-5 relative away from the image's least salient keys."""
+    for b in range(cfg.B):
+        ref = O.stage(synth.to_f64(inp["q"][b], cfg.qk_dtype), synth.to_f64(inp["k"][b], cfg.qk_dtype),
+                      synth.to_f64(inp["hidden"][b], cfg.h_dtype), int(inp["text_len"][b]), cfg.P, cfg.V,
+                      cfg.Tmax, cfg.k)
+        s_raw, s_hat = outs[0][b].astype(np.float64), outs[1][b].astype(np.float64)
+        sh_tol = U.salience_tolerance(s_raw, s_hat, ref)
+        assert np.abs(s_hat - ref["s_hat"]).max() <= sh_tol
+        r = ref["score"]
+        lam = np.maximum(ref["s_hat"], 1e-6)
+        err = np.abs(outs[2][b] - r)
+        assert (err <= 2e-5 * r + 2 * max(sh_tol, 2e-7) * (r / lam) + 1e-300).all()
+
+
 def test_static_scratch_scoring_matches_the_workspace_call_twice_in_a_row():
     ctx = binding.Context(0)
     # S2: two images, 461 visual tokens (ragged last key tile), GQA, ragged text; then S0: 72 tokens, f32
@@ -52,19 +70,24 @@ def test_static_scratch_scoring_matches_the_workspace_call_twice_in_a_row():
         for a, b, what in zip(out["static"], out["workspace"], ("s_raw", "s_hat", "score")):
             assert np.isfinite(a).all(), (name, what)
             assert (a.view(np.uint32) == b.view(np.uint32)).all(), (name, what)
-        # and against the oracle, by the rules of the parity tests (salience within what the observed mass
-        # error allows through Eq. 3, scores 2e-5 relative away from the image's least salient keys)
-        for b in range(cfg.B):
-            ref = O.stage(synth.to_f64(inp["q"][b], cfg.qk_dtype), synth.to_f64(inp["k"][b], cfg.qk_dtype),
-                          synth.to_f64(inp["hidden"][b], cfg.h_dtype), int(inp["text_len"][b]), cfg.P, cfg.V,
-                          cfg.Tmax, cfg.k)
-            s_raw, s_hat = out["static"][0][b].astype(np.float64), out["static"][1][b].astype(np.float64)
-            sh_tol = U.salience_tolerance(s_raw, s_hat, ref)
-            assert np.abs(s_hat - ref["s_hat"]).max() <= sh_tol
-            r = ref["score"]
-            lam = np.maximum(ref["s_hat"], 1e-6)
-            err = np.abs(out["static"][2][b] - r)
-            assert (err <= 2e-5 * r + 2 * max(sh_tol, 2e-7) * (r / lam) + 1e-300).all()
+        _against_the_oracle(cfg, inp, out["static"])
+    ctx.close()
+
+
+def test_static_scratch_too_small_for_the_stored_logits_of_f32_keys():
+    """Three images of C3's shape (f32, 576 visual tokens, up to 128 text rows): 28 MB of logits, which
+    asap_score keeps in its workspace and the 16 MiB array cannot hold.  Mass and salience do not depend
+    on that and agree bit for bit; the scores of both calls are held to the oracle."""
+    ctx = binding.Context(0)
+    cfg = synth.shrink(synth.CONFIGS["C3"], B=3)
+    p = binding.params_from_config(cfg)
+    assert binding.asap_workspace_bytes(p) > 16 << 20
+    inp, out = _score_both_ways(ctx, cfg)
+    for a, b, what in zip(out["static"][:2], out["workspace"][:2], ("s_raw", "s_hat")):
+        assert (a.view(np.uint32) == b.view(np.uint32)).all(), what
+    assert np.isfinite(out["static"][2]).all() and np.isfinite(out["workspace"][2]).all()
+    _against_the_oracle(cfg, inp, out["static"])
+    _against_the_oracle(cfg, inp, out["workspace"])
     ctx.close()
 
 
