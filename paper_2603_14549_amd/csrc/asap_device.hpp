@@ -110,6 +110,19 @@ __device__ __forceinline__ void mma_split(f32x16_t& acc, const Split3& a, const 
   mma32<bf16_t>(acc, a.hi, b.hi);
 }
 
+// The same products one at a time: product P (0..5, in the order of mma_split) of a group.  A caller
+// that walks P in its outer loop and the accumulators in its inner loop adds the same terms in the same
+// order per accumulator, with independent matrix instructions next to each other.
+template <int P> __device__ __forceinline__ void mma_split_term(f32x16_t& acc, const Split3& a, const Split3& b) {
+  static_assert(P >= 0 && P < 6, "six piece products");
+  if constexpr (P == 0) mma32<bf16_t>(acc, a.lo, b.hi);
+  else if constexpr (P == 1) mma32<bf16_t>(acc, a.hi, b.lo);
+  else if constexpr (P == 2) mma32<bf16_t>(acc, a.mid, b.mid);
+  else if constexpr (P == 3) mma32<bf16_t>(acc, a.mid, b.hi);
+  else if constexpr (P == 4) mma32<bf16_t>(acc, a.hi, b.mid);
+  else mma32<bf16_t>(acc, a.hi, b.hi);
+}
+
 // row of the 32x32 tile held in accumulator register v of lane l
 __device__ __forceinline__ int mma32_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 

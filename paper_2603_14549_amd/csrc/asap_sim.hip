@@ -2,7 +2,8 @@
 // stage, (pruned rows) x (kept rows)^T over the hidden dimension, on the matrix cores, with the
 // row arg-max fused into the epilogue.
 //
-//   k_sim<T, NT>  workgroup tile BM = 128 source rows x BN = 64*NT destination rows, 256 threads =
+//   k_sim<T, NT>  (bf16 hidden states)
+//                 workgroup tile BM = 128 source rows x BN = 64*NT destination rows, 256 threads =
 //                 4 waves (2 x 2 over the tile, each 64 x 32*NT = 2 x NT MFMA tiles of 32 x 32), one
 //                 wave per SIMD so that a wave may use the whole 512-entry register file.  The
 //                 hidden dimension is walked in steps of 128 bytes per row, one barrier per step.
@@ -29,6 +30,9 @@
 //                 Launches of at most 128 workgroups also cut the hidden dimension into slices
 //                 with workgroups of their own, which leave raw partial products and partial
 //                 squared norms instead of a row winner.
+//   k_sim_f32<NT> (f32 hidden states) the same tile, grid and epilogue; every value is cut into three
+//                 bf16 pieces once per workgroup on its way global memory -> registers -> LDS, and the
+//                 waves multiply finished pieces (six piece products per pair of values)
 //   k_sim_finish  largest key of a row -> assign, best_sim (threshold and source norm applied here)
 //   k_sim_reduce  sums the slices of a split launch, then the same scaling, predicate and arg-max
 #include "asap_device.hpp"
@@ -88,6 +92,154 @@ __device__ __forceinline__ int rowmin16(int x) {
   x = min(x, (int)dpp_u32<0x122>((uint32_t)x));
   x = min(x, (int)dpp_u32<0x121>((uint32_t)x));
   return x;
+}
+
+// What a workgroup knows about its tile once the products are done, and where the results go.
+struct SimTile {
+  int b, B, M, k, V;
+  int m0, n0;                 // first source row, first destination column
+  int pass, ptiles, mt;       // destination tile, their count, source tile
+  int ks, ksplit;             // slice of the hidden dimension
+  float threshold;
+  const int32_t* kept;
+  const float* s_hat;
+  int32_t* assign;
+  float* best_sim;
+  unsigned long long* best_key;
+  float* src_norm2;
+  float* dots;
+  float* kept_norm2;
+};
+
+// Epilogue of a 128 x 64 NT tile held as 2 x NT accumulators per wave (waves 2 x 2 over the tile):
+// norm2 [128] / normk [64 NT] hold the squared norms of its rows / columns (this slice's share),
+// part [2][128] is LDS scratch, srow [128] the salience of the source rows (ANCHORED).  The caller
+// has put a barrier after the writes of norm2, normk and srow.
+template <int NT, bool ANCHORED>
+__device__ __forceinline__ void sim_tile_epilogue(f32x16_t (&acc)[2][NT], const float* norm2, const float* normk,
+                                                  uint2* part, const float* srow, const SimTile& T_) {
+  constexpr int BN = 64 * NT;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 31;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int b = T_.b, B = T_.B, M = T_.M, k = T_.k, V = T_.V, m0 = T_.m0, n0 = T_.n0, pass = T_.pass;
+  const int ptiles = T_.ptiles, mt = T_.mt, ks = T_.ks, ksplit = T_.ksplit;
+  const float threshold = T_.threshold;
+  const int32_t* __restrict__ kept = T_.kept;
+  const float* __restrict__ s_hat = T_.s_hat;
+  float run_v = -INFINITY;   // best of this workgroup's destination tile (threads < BM)
+  int run_c = 0;
+  {
+    if (ksplit > 1) {
+      // this slice's share of the products and of the squared norms; k_sim_reduce adds the slices up
+      const int64_t img = (int64_t)ks * B + b;
+      if (pass == 0 && tid < SIM_BM && m0 + tid < M) T_.src_norm2[img * M + m0 + tid] = norm2[tid];
+      if (mt == 0)
+        for (int c = tid; c < BN; c += 256)        // BN may exceed the workgroup size
+          if (n0 + c < k) T_.kept_norm2[img * k + n0 + c] = normk[c];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * 64 + i * 32 + mma32_row(v, lane);
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            const int col = n0 + wn * (BN / 2) + t * 32 + n;
+            if (row < M && col < k) T_.dots[(img * M + row) * k + col] = acc[i][t][v];
+          }
+        }
+      return;
+    }
+
+    // Row arg-max of dot / |x_j| over this pass's destinations (|x_i| > 0 does not move it).
+    // A lane first takes the best of its NT columns of a row (columns past k get -inf), then the 32
+    // lanes that share the row agree on the maximum and on the smallest column that reaches it.
+    float invk[NT], bias[NT];
+    int colv[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int cl = wn * (BN / 2) + t * 32 + n;
+      colv[t] = n0 + cl;
+      const bool valid = colv[t] < k;
+      invk[t] = valid ? 1.0f / fmaxf(sqrtf(normk[cl]), 1e-8f) : 0.0f;
+      bias[t] = valid ? 0.0f : -INFINITY;
+    }
+    float scol[NT];            // ANCHORED: salience of this lane's destination columns
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      scol[t] = (ANCHORED && colv[t] < k) ? s_hat[(int64_t)b * V + kept[(int64_t)b * k + colv[t]]] : 0.0f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      // stage by stage over the 16 rows a lane holds, so that the cross-lane exchanges of
+      // different rows overlap instead of waiting for one another
+      float bv[16], mv[16], ov[16];
+      int bc[16], mc[16], oc[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float c[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) c[t] = fmaf(acc[i][t][v], invk[t], bias[t]);
+        if (ANCHORED) {
+          const int rloc = wm * 64 + i * 32 + mma32_row(v, lane);
+          const float sr_ = srow[rloc];
+          const int rslot = m0 + rloc;
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            const bool stronger = (scol[t] > sr_) | ((scol[t] == sr_) & (colv[t] < rslot));
+            c[t] = stronger ? c[t] : -INFINITY;
+          }
+        }
+        bv[v] = c[0];
+#pragma unroll
+        for (int t = 1; t < NT; ++t) bv[v] = fmaxf(bv[v], c[t]);
+        bc[v] = 0x7fffffff;
+#pragma unroll
+        for (int t = NT - 1; t >= 0; --t) bc[v] = (c[t] == bv[v]) ? colv[t] : bc[v];   // columns ascend with t
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mv[v] = rowmax16(bv[v]);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) ov[v] = __shfl_xor(mv[v], 16);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        mv[v] = fmaxf(mv[v], ov[v]);
+        mc[v] = rowmin16(bv[v] == mv[v] ? bc[v] : 0x7fffffff);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oc[v] = __shfl_xor(mc[v], 16);
+      if (n == 0) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          part[wn * SIM_BM + wm * 64 + i * 32 + mma32_row(v, lane)] =
+              make_uint2(__float_as_uint(mv[v]), (uint32_t)min(mc[v], oc[v]));
+      }
+    }
+    __syncthreads();
+    if (tid < SIM_BM) {
+      uint2 p0 = part[tid], p1 = part[SIM_BM + tid];
+      float v0 = __uint_as_float(p0.x), v1 = __uint_as_float(p1.x);
+      int c0 = (int)p0.y, c1 = (int)p1.y;
+      if (v1 > v0 || (v1 == v0 && c1 < c0)) { v0 = v1; c0 = c1; }
+      run_v = v0;
+      run_c = c0;
+    }
+  }
+  if (tid < SIM_BM && m0 + tid < M) {
+    const int64_t o = (int64_t)b * M + m0 + tid;
+    if (ptiles == 1) {
+      float c = run_v / fmaxf(sqrtf(norm2[tid]), 1e-8f);
+      T_.best_sim[o] = c;
+      T_.assign[o] = (c > threshold) ? run_c : -1;
+    } else {
+      // several destination tiles per source row: every tile leaves its best as a 64-bit key (value,
+      // then the inverted column so that equal values keep the smaller column); k_sim_finish takes the
+      // largest key of a row and turns it into assign / best_sim
+      const unsigned long long key = ((unsigned long long)float_key(run_v) << 32) | (0xFFFFFFFFu - (uint32_t)run_c);
+      T_.best_key[(int64_t)pass * ((int64_t)B * M) + o] = key;
+      if (pass == 0) T_.src_norm2[o] = norm2[tid];
+    }
+  }
 }
 
 // ANCHORED (the routing inside the kept set, Sec. 4.2): the source rows are the kept tokens too
@@ -175,9 +327,6 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
   if (ANCHORED) {            // the barriers of the fill below make these visible
     if (tid < SIM_BM) srow[tid] = s_hat[(int64_t)b * V + pruned[(int64_t)b * M + min(m0 + tid, M - 1)]];
   }
-  float run_v = -INFINITY;   // best of this workgroup's destination tile (threads < BM)
-  int run_c = 0;
-
   {
     const int n0 = pass * BN;
 #pragma unroll
@@ -239,57 +388,6 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
         if (u < PB) load_to_lds16(gb, offb[u < PB ? u : 0], db + u * 32 * SIM_ROWB);
         else if (u < PB + PA) load_to_lds16(ga, offa[u < PB + PA ? u - PB : 0], da + (u - PB) * 32 * SIM_ROWB);
       };
-      if constexpr (sizeof(T) == 4) {
-        // f32: the bf16 matrix instructions take three bf16 pieces per value (hi + mid + lo = the value to
-        // 2^-27) and a product is the sum of the six piece products that matter -- a third of the matrix
-        // time of the f32 instruction.  Two 16-byte chunks make one contraction group of 8 values, so a
-        // step has two groups; every operand is split once per group and meets all its partners.
-        uint4 ra[2][2], rb[NT][2];
-        auto read_group = [&](int gq) {
-#pragma unroll
-          for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) ra[i][u] = *reinterpret_cast<const uint4*>(A + i * 32 * SIM_ROWB + sw[2 * gq + u]);
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) rb[t][u] = *reinterpret_cast<const uint4*>(Bp + t * 32 * SIM_ROWB + sw[2 * gq + u]);
-        };
-        read_group(0);
-#pragma unroll
-        for (int gq = 0; gq < 2; ++gq) {
-          Split3 a3[2], b3[NT];
-#pragma unroll
-          for (int i = 0; i < 2; ++i) {
-            a3[i] = split_f32x8(ra[i][0], ra[i][1]);
-            sumsq16<T>(ra[i][0], ss_a[i]);                 // positions 0 and 2 of the step
-          }
-#pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            b3[t] = split_f32x8(rb[t][0], rb[t][1]);
-            if (gq == 0) {                                 // positions 0 and 1
-              sumsq16<T>(rb[t][0], ss_b[t]);
-              sumsq16<T>(rb[t][1], ss_b[t]);
-            }
-          }
-          if (gq == 0) read_group(1);       // the raw registers are free again
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-              // 4 NT slots for the PA + PB loads of the step, issued in their order (all destination
-              // loads before the source loads, as the wait below assumes): two per slot at NT = 1
-              constexpr int PER = (PA + PB + 4 * NT - 1) / (4 * NT);
-              const int u = ((gq * NT + t) * 2 + i) * PER;
-              mma_split(acc[i][t], a3[i], b3[t]);
-#pragma unroll
-              for (int x = 0; x < PER; ++x) load_unit(u + x);
-            }
-        }
-        wait_vmem_but<PA + (NB - 2) * (PA + PB)>();
-        barrier_keep_loads();
-        continue;
-      }
       // LDS operand reads run one contraction slice ahead of the MFMAs that use them
       uint4 a[2][2], bq[2][NT];
       auto load_op = [&](int set, int kk, int u) {      // in the order the MFMAs need them
@@ -359,115 +457,255 @@ __global__ __launch_bounds__(256) void k_sim(const T* __restrict__ xv, int64_t s
       __syncthreads();   // after the second turn: norms visible
     }
 
-    if (ksplit > 1) {
-      // this slice's share of the products and of the squared norms; k_sim_reduce adds the slices up
-      const int64_t img = (int64_t)ks * B + b;
-      if (pass == 0 && tid < SIM_BM && m0 + tid < M) src_norm2[img * M + m0 + tid] = norm2[tid];
-      if (mt == 0)
-        for (int c = tid; c < BN; c += 256)        // BN may exceed the workgroup size
-          if (n0 + c < k) kept_norm2[img * k + n0 + c] = normk[c];
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = m0 + wm * 64 + i * 32 + mma32_row(v, lane);
-#pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            const int col = n0 + wn * (BN / 2) + t * 32 + n;
-            if (row < M && col < k) dots[(img * M + row) * k + col] = acc[i][t][v];
-          }
-        }
-      return;
-    }
+    SimTile tile;
+    tile.b = b; tile.B = B; tile.M = M; tile.k = k; tile.V = V; tile.m0 = m0; tile.n0 = n0; tile.pass = pass;
+    tile.ptiles = ptiles; tile.mt = mt; tile.ks = ks; tile.ksplit = ksplit; tile.threshold = threshold;
+    tile.kept = kept; tile.s_hat = s_hat; tile.assign = assign; tile.best_sim = best_sim; tile.best_key = best_key;
+    tile.src_norm2 = src_norm2; tile.dots = dots; tile.kept_norm2 = kept_norm2;
+    sim_tile_epilogue<NT, ANCHORED>(acc, norm2, normk, part, srow, tile);
+  }
+}
 
-    // Row arg-max of dot / |x_j| over this pass's destinations (|x_i| > 0 does not move it).
-    // A lane first takes the best of its NT columns of a row (columns past k get -inf), then the 32
-    // lanes that share the row agree on the maximum and on the smallest column that reaches it.
-    float invk[NT], bias[NT];
-    int colv[NT];
+// f32 hidden states.  The bf16 matrix instructions take three bf16 pieces per value (hi + mid + lo =
+// the value to 2^-27) and a product is the sum of the six piece products that matter -- a third of
+// the matrix time of the f32 instruction.  Cutting a value into its pieces costs about five vector
+// instructions, and a wave that issues those for every operand it multiplies (its 64 source and 32 NT
+// destination rows, which the wave beside or below cuts again) is bound by its own instruction stream,
+// not by the matrix cores.  So here every value is cut exactly once per workgroup: the rows travel
+// global memory -> registers (asked for two steps ahead) -> pieces -> LDS, each thread cutting 8
+// consecutive values of 2 + NT rows per step, and the waves read finished pieces as operands.  LDS
+// holds the pieces of two steps (one being multiplied, one being written); one barrier per step.
+//   LDS row of a step: 208 bytes = hi | mid | lo planes of 64 bytes (32 values x 2 bytes) + 16 bytes
+//   of padding: 16 consecutive rows then start in 16 different groups of 4 banks.
+// Tile, waves, grid order, slices of the hidden dimension and epilogue are those of k_sim.
+constexpr int SIMF_ROWP = 208;
+constexpr int SIMF_MAX_NT = 4;      // 2 x (128 + 256) rows x 208 bytes = 156 KiB
+template <int NT, bool ANCHORED>
+__global__ __launch_bounds__(256) void k_sim_f32(const float* __restrict__ xv, int64_t sb, int64_t sr, int D,
+                                                  const int32_t* __restrict__ pruned,
+                                                  const int32_t* __restrict__ kept, const float* __restrict__ s_hat,
+                                                  int V, int B, int M, int k, int mtiles, int ptiles, int spread,
+                                                  int vmt, float threshold, int32_t* __restrict__ assign,
+                                                  float* __restrict__ best_sim,
+                                                  unsigned long long* __restrict__ best_key,
+                                                  float* __restrict__ src_norm2, int ksplit,
+                                                  float* __restrict__ dots, float* __restrict__ kept_norm2) {
+  constexpr int BN = 64 * NT;
+  constexpr int ROWS = SIM_BM + BN;              // rows of a step in LDS: sources, then destinations
+  constexpr int NJ = ROWS / 64;                  // rows a thread cuts per step (8 values of each)
+  constexpr int STAGE = ROWS * SIMF_ROWP;
+  extern __shared__ __align__(16) char lds[];
+  // the epilogue's arrays take the place of the pieces once the last step is through
+  float* norm2 = reinterpret_cast<float*>(lds);                  // [BM]
+  float* normk = norm2 + SIM_BM;                                 // [BN]
+  uint2* part = reinterpret_cast<uint2*>(normk + BN);            // [2][BM]
+  float* srow = reinterpret_cast<float*>(part + 2 * SIM_BM);     // [BM]
+
+  const int xcd = blockIdx.x % NUM_XCD, slot_p = blockIdx.x / NUM_XCD;
+  const int pass = slot_p % ptiles, ks = (slot_p / ptiles) % ksplit, slot = slot_p / (ptiles * ksplit);
+  const int vb = (slot / vmt) * NUM_XCD + xcd;
+  const int b = vb / spread;
+  const int mt = vb % spread + spread * (slot % vmt);
+  if (b >= B || mt >= mtiles) return;
+  const int m0 = mt * SIM_BM, n0 = pass * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 31, hf = lane >> 5;
+  const int wm = wave >> 1, wn = wave & 1;
+  const char* xb = reinterpret_cast<const char*>(xv + b * sb);
+  const int64_t rowb = sr * (int64_t)sizeof(float);
+  const int steps = (D * (int)sizeof(float)) / SIM_ROWB / ksplit;     // ksplit divides the step count
+  const int step_lo = ks * steps;
+  const int rot = (mt + 16 * (slot / vmt)) % steps;                   // see k_sim
+  auto step_base = [&](int s) __attribute__((always_inline)) {
+    int sr_ = s + rot;
+    if (sr_ >= steps) sr_ -= steps;
+    return xb + (int64_t)(step_lo + sr_) * SIM_ROWB;
+  };
+
+  // Cutting: thread (lr, g4) takes the values 8 g4 .. 8 g4 + 7 of the step for rows lr + 64 j.
+  const int lr = tid >> 2, g4 = tid & 3;
+  uint32_t off[NJ];           // byte offsets from the image base (an image spans < 4 GiB)
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int cl = wn * (BN / 2) + t * 32 + n;
-      colv[t] = n0 + cl;
-      const bool valid = colv[t] < k;
-      invk[t] = valid ? 1.0f / fmaxf(sqrtf(normk[cl]), 1e-8f) : 0.0f;
-      bias[t] = valid ? 0.0f : -INFINITY;
-    }
-    float scol[NT];            // ANCHORED: salience of this lane's destination columns
+  for (int j = 0; j < NJ; ++j) {
+    const int row = lr + 64 * j;
+    const int idx = row < SIM_BM ? pruned[(int64_t)b * M + min(m0 + row, M - 1)]
+                                 : kept[(int64_t)b * k + min(n0 + row - SIM_BM, k - 1)];
+    off[j] = (uint32_t)(idx * rowb) + g4 * 32;
+  }
+  const int wr = lr * SIMF_ROWP + g4 * 16;        // where the thread's pieces of row lr go (+ 64 j rows)
+  // Operands: lane (n, hf) reads the values 16 kb + 8 hf .. + 7 of its rows for contraction block kb.
+  const int rd_a = (wm * 64 + n) * SIMF_ROWP + hf * 16;
+  const int rd_b = (SIM_BM + wn * (BN / 2) + n) * SIMF_ROWP + hf * 16;
+
+  f32x16_t acc[2][NT];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int t = 0; t < NT; ++t)
-      scol[t] = (ANCHORED && colv[t] < k) ? s_hat[(int64_t)b * V + kept[(int64_t)b * k + colv[t]]] : 0.0f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][t][v] = 0.0f;
+  SumSq4 ss[NJ];              // squared norms of the thread's share of its rows
+
+  uint4 raw[2][NJ][2];        // the values of two steps on their way
+  auto fetch = [&](uint4 (&r)[NJ][2], int s) __attribute__((always_inline)) {
+    const char* g = step_base(s);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      r[j][0] = ldg16(g + off[j]);
+      r[j][1] = ldg16(g + off[j] + 16);
+    }
+  };
+  auto cut = [&](const uint4 (&r)[NJ][2], char* stage) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const Split3 p3 = split_f32x8(r[j][0], r[j][1]);
+      sumsq16<float>(r[j][0], ss[j]);
+      sumsq16<float>(r[j][1], ss[j]);
+      char* dst = stage + wr + j * 64 * SIMF_ROWP;
+      *reinterpret_cast<uint4*>(dst) = p3.hi;
+      *reinterpret_cast<uint4*>(dst + 64) = p3.mid;
+      *reinterpret_cast<uint4*>(dst + 128) = p3.lo;
+    }
+  };
+  // The same cut in NJ x 11 units, for a schedule written out by hand: per row of the thread, 8 units
+  // that take one value pair through one of the two phases of split_pair, 2 units of squared norms,
+  // and the unit that stores the three pieces and asks for the row's values two steps on (gnext: where
+  // that step starts), so that every load has almost two steps to arrive.  The pieces under way live
+  // in p3, r0, r1.
+  constexpr int CUT_UNITS = NJ * 11;
+  Split3 p3;
+  float r0 = 0.0f, r1 = 0.0f;
+  auto cut_unit = [&](auto uc, uint4 (&r)[NJ][2], char* stage, const char* gnext) __attribute__((always_inline)) {
+    constexpr int U = decltype(uc)::value;
+    constexpr int J = U / 11, R = U % 11;
+    if constexpr (R < 8) {
+      constexpr int Q = R / 2;
+      auto put = [](uint4& v, uint32_t x) __attribute__((always_inline)) {
+        if constexpr (Q == 0) v.x = x;
+        else if constexpr (Q == 1) v.y = x;
+        else if constexpr (Q == 2) v.z = x;
+        else v.w = x;
+      };
+      if constexpr (R % 2 == 0) {
+        const uint4& c = r[J][Q / 2];
+        const float a = __uint_as_float(Q % 2 == 0 ? c.x : c.z), b = __uint_as_float(Q % 2 == 0 ? c.y : c.w);
+        const uint32_t hi = pk_bf16(a, b);
+        r0 = a - __uint_as_float(hi << 16);
+        r1 = b - __uint_as_float(hi & 0xffff0000u);
+        put(p3.hi, hi);
+      } else {
+        const uint32_t mid = pk_bf16(r0, r1);
+        put(p3.mid, mid);
+        put(p3.lo, pk_bf16(r0 - __uint_as_float(mid << 16), r1 - __uint_as_float(mid & 0xffff0000u)));
+      }
+    } else if constexpr (R < 10) {
+      sumsq16<float>(r[J][R - 8], ss[J]);
+    } else {
+      char* dst = stage + wr + J * 64 * SIMF_ROWP;
+      *reinterpret_cast<uint4*>(dst) = p3.hi;
+      *reinterpret_cast<uint4*>(dst + 64) = p3.mid;
+      *reinterpret_cast<uint4*>(dst + 128) = p3.lo;
+      r[J][0] = ldg16(gnext + off[J]);
+      r[J][1] = ldg16(gnext + off[J] + 16);
+    }
+  };
+  // Operand pieces of contraction block kb (16 values) of the stage
+  Split3 a3[2], b3[NT];
+  auto operands = [&](const char* stage, int kb) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      // stage by stage over the 16 rows a lane holds, so that the cross-lane exchanges of
-      // different rows overlap instead of waiting for one another
-      float bv[16], mv[16], ov[16];
-      int bc[16], mc[16], oc[16];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float c[NT];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) c[t] = fmaf(acc[i][t][v], invk[t], bias[t]);
-        if (ANCHORED) {
-          const int rloc = wm * 64 + i * 32 + mma32_row(v, lane);
-          const float sr_ = srow[rloc];
-          const int rslot = m0 + rloc;
-#pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            const bool stronger = (scol[t] > sr_) | ((scol[t] == sr_) & (colv[t] < rslot));
-            c[t] = stronger ? c[t] : -INFINITY;
-          }
-        }
-        bv[v] = c[0];
-#pragma unroll
-        for (int t = 1; t < NT; ++t) bv[v] = fmaxf(bv[v], c[t]);
-        bc[v] = 0x7fffffff;
-#pragma unroll
-        for (int t = NT - 1; t >= 0; --t) bc[v] = (c[t] == bv[v]) ? colv[t] : bc[v];   // columns ascend with t
-      }
-#pragma unroll
-      for (int v = 0; v < 16; ++v) mv[v] = rowmax16(bv[v]);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) ov[v] = __shfl_xor(mv[v], 16);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        mv[v] = fmaxf(mv[v], ov[v]);
-        mc[v] = rowmin16(bv[v] == mv[v] ? bc[v] : 0x7fffffff);
-      }
-#pragma unroll
-      for (int v = 0; v < 16; ++v) oc[v] = __shfl_xor(mc[v], 16);
-      if (n == 0) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          part[wn * SIM_BM + wm * 64 + i * 32 + mma32_row(v, lane)] =
-              make_uint2(__float_as_uint(mv[v]), (uint32_t)min(mc[v], oc[v]));
-      }
+      const char* p = stage + rd_a + i * 32 * SIMF_ROWP + kb * 32;
+      a3[i].hi = *reinterpret_cast<const uint4*>(p);
+      a3[i].mid = *reinterpret_cast<const uint4*>(p + 64);
+      a3[i].lo = *reinterpret_cast<const uint4*>(p + 128);
     }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const char* p = stage + rd_b + t * 32 * SIMF_ROWP + kb * 32;
+      b3[t].hi = *reinterpret_cast<const uint4*>(p);
+      b3[t].mid = *reinterpret_cast<const uint4*>(p + 64);
+      b3[t].lo = *reinterpret_cast<const uint4*>(p + 128);
+    }
+  };
+  // A step, slot by slot and in this order (the compiler moves nothing across a slot's end): one piece
+  // product -- product by product over the 2 NT accumulators, so that neighbouring matrix instructions
+  // never wait for one another -- and that slot's share of the cut of the next step's values, a few
+  // vector instructions that run in the matrix instruction's shadow.  CUT = false: the last step.
+  constexpr int SLOTS = 24 * NT;
+  auto multiply = [&](auto do_cut, const char* stage, uint4 (&r)[NJ][2], char* next_stage, const char* gnext) __attribute__((always_inline)) {
+    constexpr bool CUT = decltype(do_cut)::value;
+    static_for<SLOTS>([&](auto sc) __attribute__((always_inline)) {
+      constexpr int S = decltype(sc)::value;
+      constexpr int KB = S / (12 * NT), P = (S % (12 * NT)) / (2 * NT), t = (S % (2 * NT)) / 2, i = S % 2;
+      if constexpr (S % (12 * NT) == 0) operands(stage, KB);
+      mma_split_term<P>(acc[i][t], a3[i], b3[t]);
+      if constexpr (CUT) {
+        constexpr int U0 = S * CUT_UNITS / SLOTS, U1 = (S + 1) * CUT_UNITS / SLOTS;
+        static_for<U1 - U0>([&](auto k) __attribute__((always_inline)) {
+          cut_unit(std::integral_constant<int, U0 + decltype(k)::value>{}, r, next_stage, gnext);
+        });
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
+  // Step s multiplies the pieces in stage s % 2 while the values of step s + 1 (asked for during step
+  // s - 1) are cut into the other stage, row by row; each row's registers then ask for step s + 3.
+  // Nothing in a step
+  // is conditional (past the end the registers ask for the last step again, and the last step, which
+  // has nothing to cut, stands alone after the loop): the waits the compiler places before the first
+  // use of a value then leave the younger set of loads in flight.  Two steps per turn, so that each
+  // register set keeps its role.
+  const int last = steps - 1;
+  fetch(raw[0], 0);
+  fetch(raw[1], min(1, last));
+  cut(raw[0], lds);
+  fetch(raw[0], min(2, last));
+  __syncthreads();
+  auto step = [&](auto parity, int s) __attribute__((always_inline)) {
+    constexpr int CUR = decltype(parity)::value;
+    multiply(std::true_type{}, lds + CUR * STAGE, raw[CUR ^ 1], lds + (CUR ^ 1) * STAGE,
+             step_base(min(s + 3, last)));
     __syncthreads();
-    if (tid < SIM_BM) {
-      uint2 p0 = part[tid], p1 = part[SIM_BM + tid];
-      float v0 = __uint_as_float(p0.x), v1 = __uint_as_float(p1.x);
-      int c0 = (int)p0.y, c1 = (int)p1.y;
-      if (v1 > v0 || (v1 == v0 && c1 < c0)) { v0 = v1; c0 = c1; }
-      run_v = v0;
-      run_c = c0;
+  };
+  int s = 0;
+  for (; s + 2 < steps; s += 2) {
+    step(std::integral_constant<int, 0>{}, s);
+    step(std::integral_constant<int, 1>{}, s + 1);
+  }
+  if (s + 2 == steps) {
+    step(std::integral_constant<int, 0>{}, s);
+    multiply(std::false_type{}, lds + STAGE, raw[0], lds, xb);
+  } else {
+    multiply(std::false_type{}, lds, raw[1], lds + STAGE, xb);
+  }
+  __syncthreads();
+
+  // squared norms: the four threads of a row add up their shares
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    float v = ss[j].total();
+    v += __shfl_xor(v, 1);
+    v += __shfl_xor(v, 2);
+    const int row = lr + 64 * j;
+    if (g4 == 0) {
+      if (row < SIM_BM) norm2[row] = v;
+      else normk[row - SIM_BM] = v;
     }
   }
-  if (tid < SIM_BM && m0 + tid < M) {
-    const int64_t o = (int64_t)b * M + m0 + tid;
-    if (ptiles == 1) {
-      float c = run_v / fmaxf(sqrtf(norm2[tid]), 1e-8f);
-      best_sim[o] = c;
-      assign[o] = (c > threshold) ? run_c : -1;
-    } else {
-      // several destination tiles per source row: every tile leaves its best as a 64-bit key (value,
-      // then the inverted column so that equal values keep the smaller column); k_sim_finish takes the
-      // largest key of a row and turns it into assign / best_sim
-      const unsigned long long key = ((unsigned long long)float_key(run_v) << 32) | (0xFFFFFFFFu - (uint32_t)run_c);
-      best_key[(int64_t)pass * ((int64_t)B * M) + o] = key;
-      if (pass == 0) src_norm2[o] = norm2[tid];
-    }
+  if (ANCHORED) {
+    if (tid < SIM_BM) srow[tid] = s_hat[(int64_t)b * V + pruned[(int64_t)b * M + min(m0 + tid, M - 1)]];
   }
+  __syncthreads();
+
+  SimTile tile;
+  tile.b = b; tile.B = B; tile.M = M; tile.k = k; tile.V = V; tile.m0 = m0; tile.n0 = n0; tile.pass = pass;
+  tile.ptiles = ptiles; tile.mt = mt; tile.ks = ks; tile.ksplit = ksplit; tile.threshold = threshold;
+  tile.kept = kept; tile.s_hat = s_hat; tile.assign = assign; tile.best_sim = best_sim; tile.best_key = best_key;
+  tile.src_norm2 = src_norm2; tile.dots = dots; tile.kept_norm2 = kept_norm2;
+  sim_tile_epilogue<NT, ANCHORED>(acc, norm2, normk, part, srow, tile);
 }
 
 // grid (ceil(n / 256)): the largest key over the destination tiles of a row -> assign, best_sim
@@ -589,8 +827,14 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
                                 int M, const int32_t* kept, const float* s_hat, int32_t* assign, float* best_sim,
                                 char* ws, hipStream_t st, Timer* tm) {
   constexpr int BN = 64 * NT;
-  const size_t lds = (size_t)(sim_na(NT) * SIM_BM + sim_nb(NT) * BN) * SIM_ROWB + sizeof(float) * (6 * SIM_BM + BN);
-  auto kern = k_sim<T, NT, ANCHORED>;
+  constexpr bool F32 = sizeof(T) == 4;
+  static_assert(!F32 || NT <= SIMF_MAX_NT, "two steps of f32 pieces must fit LDS");
+  const size_t lds = F32 ? (size_t)2 * (SIM_BM + BN) * SIMF_ROWP
+                         : (size_t)(sim_na(NT) * SIM_BM + sim_nb(NT) * BN) * SIM_ROWB + sizeof(float) * (6 * SIM_BM + BN);
+  auto kern = [] {
+    if constexpr (F32) return k_sim_f32<NT, ANCHORED>;
+    else return k_sim<T, NT, ANCHORED>;
+  }();
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -632,9 +876,10 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
 static int pick_nt(const asap_params& p, int M) {
   const long mt = (M + SIM_BM - 1) / SIM_BM;
   const long steps = p.D * (p.h_dtype == ASAP_BF16 ? 2 : 4) / SIM_ROWB;
-  int best_nt = 5;
+  const int nt_max = p.h_dtype == ASAP_BF16 ? 5 : SIMF_MAX_NT;
+  int best_nt = nt_max;
   long best_cost = -1;
-  for (int nt = 5; nt >= 1; --nt) {
+  for (int nt = nt_max; nt >= 1; --nt) {
     const long bn = 64 * nt, passes = (p.k + bn - 1) / bn;
     const long ks = pick_ksplit(p, M, nt);
     const long wgs = (long)p.B * mt * passes * ks, rounds = (wgs + 255) / 256;
@@ -656,7 +901,11 @@ static hipError_t sim_typed(const asap_params& p, const void* hidden, int64_t hs
     case 2: return launch_sim_nt<T, 2, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, ws, st, tm);
     case 3: return launch_sim_nt<T, 3, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, ws, st, tm);
     case 4: return launch_sim_nt<T, 4, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, ws, st, tm);
-    default: return launch_sim_nt<T, 5, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, ws, st, tm);
+    default:
+      if constexpr (sizeof(T) == 2)
+        return launch_sim_nt<T, 5, ANCHORED>(p, xv, hsb, hsr, srcs, M, kept, s_hat, assign, best_sim, ws, st, tm);
+      else
+        return hipErrorInvalidValue;        // pick_nt stays below for f32
   }
 }
 
