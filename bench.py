@@ -456,18 +456,21 @@ def main():
         for _ in range(n_alone):
             ctx.asap_stage(stage.p, stage.io, binding.ASAP_STREAMS_ONE)
         torch.cuda.synchronize()
-        sim_alone = ctx.asap_timing_collect().get("k_sim")
+        alone = ctx.asap_timing_collect()
+        sim_alone = alone.get("k_sim") or alone.get("k_sim_f32")
         ctx.asap_timing_enable(0)
 
     mean_text = float(np.mean(inp["text_len"]))
     alg = algorithmic_bytes(cfg, mean_text, cfg.L_kv)
+    sim_name = "k_sim_f32" if "k_sim_f32" in timing else "k_sim"      # f32 hidden states have a kernel of their own
+    alg["per_kernel"]["k_sim_f32"] = alg["per_kernel"]["k_sim"]
     if paper:
         # kept x kept search; the merge reads the k final rows and the rows they absorb (counted from the run)
         eh = esize(cfg.h_dtype)
         n_src = int((stage.buf.assign.flatten()[:cfg.B * cfg.k] >= 0).sum())
         kept_rows = cfg.B * cfg.k * cfg.D * eh
         old_sim, old_merge = alg["per_kernel"]["k_sim"], alg["per_kernel"]["k_merge"]
-        alg["per_kernel"]["k_sim"] = kept_rows + 8 * cfg.B * cfg.k
+        alg["per_kernel"]["k_sim"] = alg["per_kernel"]["k_sim_f32"] = kept_rows + 8 * cfg.B * cfg.k
         alg["per_kernel"]["k_merge"] = old_merge - cfg.B * cfg.V * cfg.D * eh + kept_rows + n_src * cfg.D * eh
         alg["per_kernel"]["k_paper_plan"] = 12 * cfg.B * cfg.k + 4 * cfg.B * cfg.V
         alg["stage"] += (alg["per_kernel"]["k_sim"] - old_sim) + (alg["per_kernel"]["k_merge"] - old_merge) \
@@ -497,7 +500,7 @@ def main():
     measured, traffic_source, traffic_note = (None, None, "no counter run for this variant") if variant else \
         measured_traffic(cfg.name, list(timing))
     traffic = None if measured is None else measured.get(dominant)
-    if dominant == "k_sim" and cfg.V > cfg.k:
+    if dominant == sim_name and cfg.V > cfg.k:
         flops = alg["sim_flops"] * args.steps / d_n
         peak = MFMA_PEAK[cfg.h_dtype]
         roofline = {"kernel": dominant, "bound": "mfma", "achieved": flops / d_avg_s / 1e12, "peak": peak / 1e12,
@@ -511,7 +514,7 @@ def main():
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": nbytes / d_avg_s / 1e9, "peak": HBM_PEAK / 1e9,
                     "unit": "GB/s", "frac": nbytes / d_avg_s / HBM_PEAK, "traffic": traffic,
                     "traffic_source": traffic_source, "traffic_note": traffic_note}
-    sim = timing.get("k_sim")
+    sim = timing.get(sim_name)
     sim_roofline = None
     if sim:
         s_avg = 1e-3 * sim[0] / sim[1]

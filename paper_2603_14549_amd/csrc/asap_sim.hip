@@ -847,11 +847,12 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
   const int groups = (p.B * spread + NUM_XCD - 1) / NUM_XCD;
   const int n = p.B * M;
   const int ksplit = pick_ksplit(p, M, NT);
+  const char* label = F32 ? "k_sim_f32" : "k_sim";
   if (ksplit > 1) {
     float* dots = reinterpret_cast<float*>(ws);                                       // [ksplit][B][M][k]
     float* nsrc = reinterpret_cast<float*>(ws + align256(sizeof(float) * ksplit * (size_t)n * p.k));
     float* nkept = reinterpret_cast<float*>(reinterpret_cast<char*>(nsrc) + align256(sizeof(float) * ksplit * (size_t)n));
-    ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * vmt * ptiles * ksplit), dim3(256), lds, st, xv, sb, sr, p.D,
+    ASAP_LAUNCH(tm, label, kern, dim3(NUM_XCD * groups * vmt * ptiles * ksplit), dim3(256), lds, st, xv, sb, sr, p.D,
                 srcs, kept, s_hat, p.V, p.B, M, p.k, mtiles, ptiles, spread, vmt, p.sim_threshold, assign, best_sim,
                 static_cast<unsigned long long*>(nullptr), nsrc, ksplit, dots, nkept);
     ASAP_LAUNCH(tm, "k_sim_reduce", k_sim_reduce<ANCHORED>, dim3((M + 3) / 4, p.B), dim3(256), 0, st, dots, nsrc, nkept,
@@ -860,7 +861,7 @@ static hipError_t launch_sim_nt(const asap_params& p, const T* xv, int64_t sb, i
   }
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(ws);               // [ptiles][B*M]
   float* norms = reinterpret_cast<float*>(ws + align256(sizeof(unsigned long long) * (size_t)n * ptiles));
-  ASAP_LAUNCH(tm, "k_sim", kern, dim3(NUM_XCD * groups * vmt * ptiles), dim3(256), lds, st, xv, sb, sr, p.D, srcs,
+  ASAP_LAUNCH(tm, label, kern, dim3(NUM_XCD * groups * vmt * ptiles), dim3(256), lds, st, xv, sb, sr, p.D, srcs,
               kept, s_hat, p.V, p.B, M, p.k, mtiles, ptiles, spread, vmt, p.sim_threshold, assign, best_sim, keys,
               norms, 1, static_cast<float*>(nullptr), static_cast<float*>(nullptr));
   if (ptiles > 1)

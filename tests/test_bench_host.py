@@ -63,7 +63,7 @@ def test_measured_traffic_is_only_quoted_for_the_kernels_the_summary_lists(tmp_p
 
 def test_the_committed_counter_summaries_name_the_kernels_of_their_workloads():
     c6 = ["k_qsum", "k_mass_mfma", "k_attn_stats", "k_attn_colsum", "k_score_select_kv", "k_compact", "k_sim", "k_merge"]
-    c3 = ["k_qsum", "k_mass_mfma", "k_attn_stats", "k_attn_colsum", "k_score_select", "k_compact", "k_sim",
+    c3 = ["k_qsum", "k_mass_mfma", "k_attn_stats", "k_colsum_rows", "k_score_select", "k_compact", "k_sim_f32",
           "k_sim_reduce", "k_merge"]
     for workload, kernels in (("C6", c6), ("C3", c3)):
         table, _, note = bench.measured_traffic(workload, kernels)
