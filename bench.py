@@ -306,6 +306,10 @@ def main():
                     help="store the rows of the input hidden states this many elements further apart than their "
                          "length (the stage takes strided views; rows a power of two bytes apart all start in the "
                          "same memory channel)")
+    ap.add_argument("--in-flight", type=int, default=0, metavar="BATCHES",
+                    help="also time BATCHES (>= 2) independent copies of the batch in flight at once, each with a "
+                         "context and a stream of its own (a serving loop that does not wait for one batch before "
+                         "it submits the next); reported beside `value`, which stays one batch at a time")
     ap.add_argument("--graph", action="store_true",
                     help="also time replays of the stage call captured into a HIP graph")
     ap.add_argument("--one-stream", action="store_true",
@@ -407,6 +411,33 @@ def main():
         rotated = {"sets": len(sets), "ms_per_step": rot_ms, "images_per_s": cfg.B / (rot_ms * 1e-3),
                    "note": "same steps cycling over copies of all inputs and outputs at different addresses"}
         del sets
+
+    in_flight = None
+    if args.in_flight >= 2:
+        copies = [stage] + [harness.DeviceStage(inp, ctx=binding.Context(0), lse_extra=lse_extra,
+                                                page_size=args.paged_kv or None, last_token=args.last_token,
+                                                hidden_row_pad=args.hidden_row_pad,
+                                                overlap=False if args.one_stream else "auto", **overrides)
+                            for _ in range(args.in_flight - 1)]
+        lanes = [torch.cuda.Stream() for _ in copies]       # default priority
+
+        def submit(rounds):
+            for _ in range(rounds):
+                for st, lane in zip(copies, lanes):
+                    with torch.cuda.stream(lane):
+                        st.run_async()
+        torch.cuda.synchronize()
+        submit(max(args.warmup // len(copies), 2))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rounds = max(args.steps // len(copies), 1)
+        submit(rounds)
+        torch.cuda.synchronize()
+        f_ms = 1e3 * (time.perf_counter() - t0) / (rounds * len(copies))
+        in_flight = {"batches": len(copies), "ms_per_batch": f_ms, "images_per_s": cfg.B / (f_ms * 1e-3),
+                     "note": "independent batches submitted round-robin to streams and contexts of their own; "
+                             "their kernels share the GPU as the hardware schedules them"}
+        del copies[1:]
 
     graph_replay = None
     if args.graph and not stage.call_by_call:
@@ -571,6 +602,8 @@ def main():
         out["rotated_inputs"] = rotated
     if graph_replay is not None:
         out["graph_replay"] = graph_replay
+    if in_flight is not None:
+        out["in_flight"] = in_flight
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, cfg, route=args.route, lse_extra=lse_extra,
                                            score_rows="last" if args.last_token else "all")
